@@ -1,0 +1,3 @@
+"""Seeded synthetic input generators (shared by oracle tests and GPU tests)."""
+from .graphs import (CONFIGS, CONFIG_ORDER, Workload, build, make_config,
+                     power_law_degrees, random_csr, sample_columns)
