@@ -1,0 +1,182 @@
+/*
+ * sptir.h - C ABI of the hyb(c,k) composable-format SpMM library for gfx950.
+ *
+ * The operations follow the SpMM problem statement of the paper (arXiv
+ * 2207.04606): A is sparse in CSR with int32 indices and float32 values, X and
+ * Y are dense row-major float32 (the SpMM script of Appendix A), and
+ *     Y[i,k] = sum_j A[i,j] * X[j,k]                  (Section 4.2.1).
+ * A is first decomposed into the parameterised composable format hyb(c,k) of
+ * Section 4.2.1: c column partitions of width w = ceil(n_cols / c); in every
+ * partition the row pieces of length l with 2^(i-1) < l <= 2^i form ELL bucket
+ * i (i = 0..k), padded to width 2^i.  Row pieces longer than 2^k, on which the
+ * paper is silent, are kept unpadded in a CSR remainder per partition.
+ *
+ * All pointers named "device" are GPU global-memory addresses of the current
+ * HIP device; everything else is host memory.  No function throws or aborts;
+ * every failure is reported through sptir_status_t and leaves the out
+ * parameters untouched.  The library is not re-entrant per hyb object: calls
+ * that use the same object must be ordered by the caller.
+ */
+#ifndef SPTIR_H_
+#define SPTIR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPTIR_OK = 0,
+  SPTIR_ERR_INVALID_ARG = 1, /* null pointer, negative size, parameter out of range, X/Y alias */
+  SPTIR_ERR_UNSORTED = 2,    /* column ids of a row not strictly ascending, or outside [0, n_cols) */
+  SPTIR_ERR_OVERFLOW = 3,    /* a count does not fit the index type of its array */
+  SPTIR_ERR_ALLOC = 4,       /* the allocator returned NULL */
+  SPTIR_ERR_HIP = 5,         /* a HIP runtime call failed; see sptir_last_hip_error() */
+  SPTIR_ERR_UNSUPPORTED = 6  /* valid request this build cannot serve (e.g. misaligned X/Y) */
+} sptir_status_t;
+
+/*
+ * CSR input (axes I = dense_fixed(m), J = sparse_variable(I, (n, nnz), (indptr,
+ * indices)) of Appendix A).  All three arrays are device pointers, borrowed for
+ * the duration of the call, never written and never freed by the library.
+ */
+typedef struct {
+  int32_t n_rows;
+  int32_t n_cols;
+  int64_t nnz;            /* must equal indptr[n_rows] and be < 2^31 */
+  const int32_t* indptr;  /* device, [n_rows + 1], indptr[0] == 0, non-decreasing */
+  const int32_t* indices; /* device, [nnz], strictly ascending inside a row, in [0, n_cols) */
+  const float* values;    /* device, [nnz] */
+} sptir_csr_t;
+
+/* Opaque handle of a decomposed matrix; owns its device arrays. */
+typedef struct sptir_hyb sptir_hyb_t;
+
+/*
+ * The flat hyb arrays, in the canonical layout that is compared bit for bit
+ * with the CPU oracle.  B = c*(k+1) buckets, bucket id b = p*(k+1) + i for
+ * partition p and width 2^i; empty buckets are kept.
+ *   BUCKET_ROW_PTR  int64 [B+1]  prefix of ELL rows per bucket
+ *   BUCKET_SLOT_PTR int64 [B+1]  prefix of stored slots per bucket (rows * 2^i)
+ *   ELL_ROW         int32 [R]    row id of every ELL row, ascending inside a bucket
+ *   ELL_COL         int32 [S]    global column ids, row-major inside a bucket
+ *                                (slot = slot_ptr[b] + q*2^i + j, the flattening
+ *                                rule of Section 3.4.1); a pad repeats the last
+ *                                real column of its row piece
+ *   ELL_VAL         float [S]    values in CSR order; pads are +0.0f
+ *   REM_PART_PTR    int32 [c+1]  prefix of remainder pieces per partition
+ *   REM_ROW         int32 [M]    row id of every remainder piece, ascending inside a partition
+ *   REM_PTR         int64 [M+1]  prefix of piece lengths
+ *   REM_COL         int32 [T]    global column ids
+ *   REM_VAL         float [T]
+ */
+typedef enum {
+  SPTIR_HYB_BUCKET_ROW_PTR = 0,
+  SPTIR_HYB_BUCKET_SLOT_PTR = 1,
+  SPTIR_HYB_ELL_ROW = 2,
+  SPTIR_HYB_ELL_COL = 3,
+  SPTIR_HYB_ELL_VAL = 4,
+  SPTIR_HYB_REM_PART_PTR = 5,
+  SPTIR_HYB_REM_ROW = 6,
+  SPTIR_HYB_REM_PTR = 7,
+  SPTIR_HYB_REM_COL = 8,
+  SPTIR_HYB_REM_VAL = 9,
+  SPTIR_HYB_N_ARRAYS = 10
+} sptir_hyb_array_id;
+
+typedef struct {
+  int32_t n_rows, n_cols;
+  int32_t n_col_parts;      /* c */
+  int32_t max_bucket_log2;  /* k */
+  int32_t part_width;       /* w = ceil(n_cols / c) */
+  int32_t n_buckets;        /* B = c*(k+1) */
+  int64_t nnz;              /* true non-zeros of A */
+  int64_t n_ell_rows;       /* R */
+  int64_t n_ell_slots;      /* S, pads included */
+  int64_t n_pad_slots;      /* S + T - nnz */
+  int64_t n_rem_pieces;     /* M */
+  int64_t n_rem_nnz;        /* T */
+  int64_t n_work_items;     /* wavefront work items one sptir_spmm launch walks */
+  int32_t item_slots;       /* stored slots per work item */
+  int32_t reserved;
+  int64_t device_bytes;     /* device memory the handle owns */
+} sptir_hyb_info_t;
+
+/*
+ * Device allocator hook.  alloc(bytes, ctx, stream) returns a device pointer
+ * aligned to at least 256 bytes, or NULL; free_(ptr, ctx) releases it.  The
+ * default (both NULL) is hipMalloc / hipFree.  The hook is process-global and
+ * must not be changed while a hyb object allocated through it is alive.
+ */
+typedef void* (*sptir_alloc_fn)(size_t bytes, void* ctx, void* stream);
+typedef void (*sptir_free_fn)(void* ptr, void* ctx);
+sptir_status_t sptir_set_allocator(sptir_alloc_fn alloc, sptir_free_fn free_, void* ctx);
+
+/*
+ * Format decomposition CSR -> hyb(c,k) on the GPU (Section 4.2.1 bucketing
+ * rule; the "copy to the new format" step of Section 3.2.1 done once, as
+ * pre-processing).  Runs a validation pass, a per-(row, partition) length
+ * histogram, scans, and a stable scatter, all on `stream`
+ * (a hipStream_t passed as void*; NULL is the default stream), and synchronises
+ * that stream before returning.
+ *   n_col_parts     c >= 1
+ *   max_bucket_log2 0 <= k <= 30; ELL widths are 1, 2, ..., 2^k
+ * On success *out receives a handle to release with sptir_hyb_destroy.
+ * Errors: INVALID_ARG (null pointers, bad sizes, indptr not a non-decreasing
+ * prefix ending at nnz), UNSORTED, OVERFLOW (nnz >= 2^31, or more than 2^31-1
+ * ELL rows / remainder pieces), ALLOC, HIP.
+ */
+sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
+                               void* stream, sptir_hyb_t** out);
+
+/* The paper's rule of thumb for k (Section 4.2.1): ceil(log2(nnz / n_rows)), clamped to [0, 30]. */
+int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows);
+
+/*
+ * Y = A * X on the hyb decomposition (SpMM equation of Section 4.2.1; Y is
+ * overwritten, rows without non-zeros become 0, as the init block of the
+ * Appendix A script prescribes).
+ *   X  device, [n_cols, feat] row-major float32, read only
+ *   Y  device, [n_rows, feat] row-major float32, must not overlap X
+ *   feat >= 1
+ * Only enqueues work on `stream` (no synchronisation, no allocation).
+ * Contributions of different column partitions are combined with float atomic
+ * adds, so the low-order bits of Y may differ between runs.  A pad slot
+ * multiplies X by +0.0f: X must be finite.
+ * Errors: INVALID_ARG, HIP.
+ */
+sptir_status_t sptir_spmm(const sptir_hyb_t* hyb, const float* X, float* Y, int32_t feat, void* stream);
+
+/*
+ * Y = A * X straight from CSR, one pass, no decomposition: the "no-hyb"
+ * variant that Section 4.2.1 compares hyb against.  Same argument meaning as
+ * sptir_spmm; the CSR arrays are device pointers and are assumed valid (they
+ * are not re-validated).  Only enqueues work on `stream`.
+ */
+sptir_status_t sptir_spmm_csr(const sptir_csr_t* csr, const float* X, float* Y, int32_t feat, void* stream);
+
+/* Releases the handle and its device arrays.  NULL is accepted. */
+sptir_status_t sptir_hyb_destroy(sptir_hyb_t* hyb);
+
+/* Fills *out with sizes and parameters of the decomposition. */
+sptir_status_t sptir_hyb_info(const sptir_hyb_t* hyb, sptir_hyb_info_t* out);
+
+/*
+ * Borrowed device pointer and element count of one canonical array
+ * (sptir_hyb_array_id); valid until sptir_hyb_destroy.  An empty array
+ * reports *n_elems == 0 and may report a NULL pointer.
+ */
+sptir_status_t sptir_hyb_array(const sptir_hyb_t* hyb, int32_t which, const void** dev_ptr, int64_t* n_elems);
+
+/* Static description of a status code. */
+const char* sptir_status_string(sptir_status_t status);
+
+/* Text of the last HIP error this thread saw inside the library ("" if none). */
+const char* sptir_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPTIR_H_ */

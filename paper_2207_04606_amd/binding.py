@@ -1,0 +1,262 @@
+"""ctypes binding of libsptir.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/sptir.h).
+PyTorch supplies device memory (tensors) and streams; all computation happens
+inside the HIP library.  There is no CPU fallback: if the library is missing
+or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch  # imported before the library so that both share torch's HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsptir.so")
+
+SPTIR_OK = 0
+ARRAY_IDS = {"bucket_row_ptr": 0, "bucket_slot_ptr": 1, "ell_row": 2, "ell_col": 3, "ell_val": 4,
+             "rem_part_ptr": 5, "rem_row": 6, "rem_ptr": 7, "rem_col": 8, "rem_val": 9}
+ARRAY_DTYPES = {"bucket_row_ptr": np.int64, "bucket_slot_ptr": np.int64, "ell_row": np.int32,
+                "ell_col": np.int32, "ell_val": np.float32, "rem_part_ptr": np.int32,
+                "rem_row": np.int32, "rem_ptr": np.int64, "rem_col": np.int32, "rem_val": np.float32}
+
+
+class SptirError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        detail = sptir_status_string(status)
+        if status == 5:
+            detail += ": " + _lib.sptir_last_hip_error().decode()
+        super().__init__(f"{where}: {detail} (status {status})")
+
+
+class _Csr(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
+                ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("values", ctypes.c_void_p)]
+
+
+class _Info(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32), ("n_col_parts", ctypes.c_int32),
+                ("max_bucket_log2", ctypes.c_int32), ("part_width", ctypes.c_int32),
+                ("n_buckets", ctypes.c_int32), ("nnz", ctypes.c_int64), ("n_ell_rows", ctypes.c_int64),
+                ("n_ell_slots", ctypes.c_int64), ("n_pad_slots", ctypes.c_int64),
+                ("n_rem_pieces", ctypes.c_int64), ("n_rem_nnz", ctypes.c_int64),
+                ("n_work_items", ctypes.c_int64), ("item_slots", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
+
+
+_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p)
+_FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
+
+_lib = None
+_hip = None
+
+EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_default_bucket_log2", "sptir_spmm",
+                    "sptir_spmm_csr", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
+                    "sptir_status_string", "sptir_last_hip_error")
+
+
+def load_library(path: str | None = None):
+    """Loads libsptir.so (built beforehand by paper_2207_04606_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is not built; run `python -m paper_2207_04606_amd.build` first")
+    lib = ctypes.CDLL(path)
+    lib.sptir_set_allocator.restype = ctypes.c_int
+    lib.sptir_set_allocator.argtypes = [_ALLOC_FN, _FREE_FN, ctypes.c_void_p]
+    lib.sptir_hyb_build.restype = ctypes.c_int
+    lib.sptir_hyb_build.argtypes = [ctypes.POINTER(_Csr), ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                    ctypes.POINTER(ctypes.c_void_p)]
+    lib.sptir_default_bucket_log2.restype = ctypes.c_int32
+    lib.sptir_default_bucket_log2.argtypes = [ctypes.c_int64, ctypes.c_int32]
+    lib.sptir_spmm.restype = ctypes.c_int
+    lib.sptir_spmm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+    lib.sptir_spmm_csr.restype = ctypes.c_int
+    lib.sptir_spmm_csr.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                   ctypes.c_void_p]
+    lib.sptir_hyb_destroy.restype = ctypes.c_int
+    lib.sptir_hyb_destroy.argtypes = [ctypes.c_void_p]
+    lib.sptir_hyb_info.restype = ctypes.c_int
+    lib.sptir_hyb_info.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Info)]
+    lib.sptir_hyb_array.restype = ctypes.c_int
+    lib.sptir_hyb_array.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p),
+                                    ctypes.POINTER(ctypes.c_int64)]
+    lib.sptir_status_string.restype = ctypes.c_char_p
+    lib.sptir_status_string.argtypes = [ctypes.c_int]
+    lib.sptir_last_hip_error.restype = ctypes.c_char_p
+    lib.sptir_last_hip_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _hip_runtime():
+    """The HIP runtime torch already loaded (for device-to-host copies of raw pointers)."""
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"))
+        _hip.hipMemcpy.restype = ctypes.c_int
+        _hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    return _hip
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev(t: torch.Tensor, dtype, what: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a CUDA/HIP tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t
+
+
+def _csr_struct(n_rows, n_cols, indptr, indices, values):
+    _dev(indptr, torch.int32, "indptr"); _dev(indices, torch.int32, "indices"); _dev(values, torch.float32, "values")
+    if indptr.numel() != n_rows + 1 or indices.numel() != values.numel():
+        raise ValueError("CSR array sizes do not match")
+    return _Csr(n_rows, n_cols, indices.numel(), indptr.data_ptr(), indices.data_ptr() or None,
+                values.data_ptr() or None)
+
+
+def sptir_status_string(status: int) -> str:
+    return load_library().sptir_status_string(status).decode()
+
+
+def sptir_default_bucket_log2(nnz: int, n_rows: int) -> int:
+    return int(load_library().sptir_default_bucket_log2(nnz, n_rows))
+
+
+class Hyb:
+    """Owner of a sptir_hyb_t handle."""
+
+    def __init__(self, handle):
+        self._h = ctypes.c_void_p(handle)
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise RuntimeError("hyb object already destroyed")
+        return self._h
+
+    def destroy(self):
+        sptir_hyb_destroy(self)
+
+    def __del__(self):
+        try:
+            if self._h and _lib is not None:
+                _lib.sptir_hyb_destroy(self._h)
+                self._h = ctypes.c_void_p(None)
+        except Exception:
+            pass
+
+
+def sptir_hyb_build(n_rows: int, n_cols: int, indptr, indices, values, n_col_parts: int,
+                    max_bucket_log2: int, stream=None) -> Hyb:
+    lib = load_library()
+    csr = _csr_struct(n_rows, n_cols, indptr, indices, values)
+    out = ctypes.c_void_p(None)
+    st = lib.sptir_hyb_build(ctypes.byref(csr), n_col_parts, max_bucket_log2, _stream_ptr(stream), ctypes.byref(out))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_hyb_build")
+    return Hyb(out.value)
+
+
+def sptir_hyb_destroy(hyb: Hyb) -> None:
+    if hyb._h:
+        st = load_library().sptir_hyb_destroy(hyb._h)
+        hyb._h = ctypes.c_void_p(None)
+        if st != SPTIR_OK:
+            raise SptirError(st, "sptir_hyb_destroy")
+
+
+def sptir_hyb_info(hyb: Hyb) -> dict:
+    info = _Info()
+    st = load_library().sptir_hyb_info(hyb.handle, ctypes.byref(info))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_hyb_info")
+    return {name: getattr(info, name) for name, _ in _Info._fields_ if name != "reserved"}
+
+
+def sptir_hyb_array(hyb: Hyb, name: str) -> np.ndarray:
+    """Host copy (numpy) of one canonical hyb array."""
+    ptr = ctypes.c_void_p(None)
+    n = ctypes.c_int64(0)
+    st = load_library().sptir_hyb_array(hyb.handle, ARRAY_IDS[name], ctypes.byref(ptr), ctypes.byref(n))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_hyb_array")
+    out = np.empty(n.value, dtype=ARRAY_DTYPES[name])
+    if n.value:
+        torch.cuda.synchronize()
+        rc = _hip_runtime().hipMemcpy(out.ctypes.data, ptr, out.nbytes, 2)  # hipMemcpyDeviceToHost
+        if rc != 0:
+            raise RuntimeError(f"hipMemcpy failed with {rc}")
+    return out
+
+
+def sptir_spmm(hyb: Hyb, X, Y, stream=None) -> None:
+    """Y[n_rows, feat] = A @ X[n_cols, feat]; Y is overwritten."""
+    _dev(X, torch.float32, "X"); _dev(Y, torch.float32, "Y")
+    if X.dim() != 2 or Y.dim() != 2 or X.shape[1] != Y.shape[1]:
+        raise ValueError("X and Y must be 2-D with the same number of columns")
+    info = sptir_hyb_info(hyb)
+    if X.shape[0] != info["n_cols"] or Y.shape[0] != info["n_rows"]:
+        raise ValueError("X / Y row counts do not match the matrix")
+    st = load_library().sptir_spmm(hyb.handle, X.data_ptr() or None, Y.data_ptr() or None, X.shape[1],
+                                   _stream_ptr(stream))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_spmm")
+
+
+def sptir_spmm_csr(n_rows: int, n_cols: int, indptr, indices, values, X, Y, stream=None) -> None:
+    _dev(X, torch.float32, "X"); _dev(Y, torch.float32, "Y")
+    if X.dim() != 2 or Y.dim() != 2 or X.shape[1] != Y.shape[1]:
+        raise ValueError("X and Y must be 2-D with the same number of columns")
+    if X.shape[0] != n_cols or Y.shape[0] != n_rows:
+        raise ValueError("X / Y row counts do not match the matrix")
+    csr = _csr_struct(n_rows, n_cols, indptr, indices, values)
+    st = load_library().sptir_spmm_csr(ctypes.byref(csr), X.data_ptr() or None, Y.data_ptr() or None, X.shape[1],
+                                       _stream_ptr(stream))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_spmm_csr")
+
+
+# ------------------------------------------------------------ allocator hook
+_torch_blocks: dict[int, torch.Tensor] = {}
+
+
+@_ALLOC_FN
+def _torch_alloc(nbytes, ctx, stream):
+    try:
+        t = torch.empty(max(int(nbytes), 1), dtype=torch.uint8, device="cuda")
+    except Exception:
+        return None
+    _torch_blocks[t.data_ptr()] = t
+    return t.data_ptr()
+
+
+@_FREE_FN
+def _torch_free(ptr, ctx):
+    _torch_blocks.pop(ptr, None)
+
+
+def sptir_set_allocator(use_torch: bool) -> None:
+    """Routes the library's device allocations through torch's caching allocator
+    (True) or back to hipMalloc/hipFree (False)."""
+    lib = load_library()
+    if use_torch:
+        st = lib.sptir_set_allocator(_torch_alloc, _torch_free, None)
+    else:
+        st = lib.sptir_set_allocator(ctypes.cast(None, _ALLOC_FN), ctypes.cast(None, _FREE_FN), None)
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_set_allocator")

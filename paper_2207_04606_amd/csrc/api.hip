@@ -1,0 +1,130 @@
+// Handle management, allocator hook and status strings of the C ABI.
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+
+#include "sptir_internal.h"
+
+namespace sptir {
+
+static std::mutex g_alloc_mu;
+static sptir_alloc_fn g_alloc = nullptr;
+static sptir_free_fn g_free = nullptr;
+static void* g_alloc_ctx = nullptr;
+static thread_local char g_hip_error[512] = "";
+
+void* default_alloc(size_t bytes, void*, void*) {
+  void* p = nullptr;
+  if (hipMalloc(&p, bytes ? bytes : 1) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  return p;
+}
+
+void default_free(void* p, void*) {
+  if (p) (void)hipFree(p);
+}
+
+void current_allocator(sptir_alloc_fn* a, sptir_free_fn* f, void** ctx) {
+  std::lock_guard<std::mutex> lock(g_alloc_mu);
+  if (g_alloc && g_free) {
+    *a = g_alloc; *f = g_free; *ctx = g_alloc_ctx;
+  } else {
+    *a = default_alloc; *f = default_free; *ctx = nullptr;
+  }
+}
+
+sptir_status_t note_hip_error(hipError_t e, const char* what) {
+  snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+  (void)hipGetLastError();  // clear the sticky-less error slot
+  return SPTIR_ERR_HIP;
+}
+
+}  // namespace sptir
+
+extern "C" {
+
+sptir_status_t sptir_set_allocator(sptir_alloc_fn alloc, sptir_free_fn free_, void* ctx) {
+  if ((alloc == nullptr) != (free_ == nullptr)) return SPTIR_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(sptir::g_alloc_mu);
+  sptir::g_alloc = alloc;
+  sptir::g_free = free_;
+  sptir::g_alloc_ctx = ctx;
+  return SPTIR_OK;
+}
+
+sptir_status_t sptir_hyb_destroy(sptir_hyb_t* h) {
+  if (!h) return SPTIR_OK;
+  void* ptrs[] = {h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_part_ptr, h->rem_ptr,
+                  h->row_ids, h->cols, h->vals, h->items};
+  for (void* p : ptrs)
+    if (p) h->free_(p, h->alloc_ctx);
+  delete h;
+  return SPTIR_OK;
+}
+
+sptir_status_t sptir_hyb_info(const sptir_hyb_t* h, sptir_hyb_info_t* out) {
+  if (!h || !out) return SPTIR_ERR_INVALID_ARG;
+  sptir_hyb_info_t o;
+  memset(&o, 0, sizeof(o));
+  o.n_rows = h->n_rows; o.n_cols = h->n_cols;
+  o.n_col_parts = h->c; o.max_bucket_log2 = h->k; o.part_width = h->w;
+  o.n_buckets = (int32_t)h->B;
+  o.nnz = h->nnz;
+  o.n_ell_rows = h->R; o.n_ell_slots = h->S;
+  o.n_pad_slots = h->S + h->T - h->nnz;
+  o.n_rem_pieces = h->M; o.n_rem_nnz = h->T;
+  o.n_work_items = h->n_items; o.item_slots = h->item_slots;
+  o.device_bytes = (int64_t)h->device_bytes;
+  *out = o;
+  return SPTIR_OK;
+}
+
+sptir_status_t sptir_hyb_array(const sptir_hyb_t* h, int32_t which, const void** dev_ptr, int64_t* n_elems) {
+  if (!h || !dev_ptr || !n_elems) return SPTIR_ERR_INVALID_ARG;
+  const void* p = nullptr;
+  int64_t n = 0;
+  switch (which) {
+    case SPTIR_HYB_BUCKET_ROW_PTR: p = h->bucket_row_ptr; n = h->B + 1; break;
+    case SPTIR_HYB_BUCKET_SLOT_PTR: p = h->bucket_slot_ptr; n = h->B + 1; break;
+    case SPTIR_HYB_ELL_ROW: p = h->row_ids; n = h->R; break;
+    case SPTIR_HYB_ELL_COL: p = h->cols; n = h->S; break;
+    case SPTIR_HYB_ELL_VAL: p = h->vals; n = h->S; break;
+    case SPTIR_HYB_REM_PART_PTR: p = h->rem_part_ptr; n = h->c + 1; break;
+    case SPTIR_HYB_REM_ROW: p = h->row_ids + h->R; n = h->M; break;
+    case SPTIR_HYB_REM_PTR: p = h->rem_ptr; n = h->M + 1; break;
+    case SPTIR_HYB_REM_COL: p = h->cols + h->S; n = h->T; break;
+    case SPTIR_HYB_REM_VAL: p = h->vals + h->S; n = h->T; break;
+    default: return SPTIR_ERR_INVALID_ARG;
+  }
+  *dev_ptr = n ? p : nullptr;
+  *n_elems = n;
+  return SPTIR_OK;
+}
+
+const char* sptir_status_string(sptir_status_t s) {
+  switch (s) {
+    case SPTIR_OK: return "ok";
+    case SPTIR_ERR_INVALID_ARG: return "invalid argument";
+    case SPTIR_ERR_UNSORTED: return "column ids not strictly ascending inside a row, or out of range";
+    case SPTIR_ERR_OVERFLOW: return "a count overflows its index type";
+    case SPTIR_ERR_ALLOC: return "device allocation failed";
+    case SPTIR_ERR_HIP: return "HIP runtime error";
+    case SPTIR_ERR_UNSUPPORTED: return "unsupported request";
+  }
+  return "unknown status";
+}
+
+const char* sptir_last_hip_error(void) { return sptir::g_hip_error; }
+
+int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows) {
+  if (n_rows <= 0 || nnz <= 0) return 0;
+  // smallest k with 2^k * n_rows >= nnz, i.e. ceil(log2(nnz / n_rows))
+  int32_t k = 0;
+  while (k < 30 && ((int64_t)n_rows << k) < nnz) ++k;
+  return k;
+}
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+"""The C-ABI library loads and exports every symbol include/sptir.h declares
+(no compute calls, so no GPU needed)."""
+import ctypes
+import os
+import re
+
+import paper_2207_04606_amd as sptir
+from paper_2207_04606_amd import build as sptir_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sptir.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sptir_[a-z0-9_]+)\s*\(", text)) - {"sptir_alloc_fn", "sptir_free_fn"})
+
+
+def test_library_exports_every_declared_symbol():
+    if sptir_build.is_stale():
+        sptir_build.build()
+    lib = sptir.load_library()
+    names = declared_functions()
+    assert len(names) >= 10
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in sptir.h but not exported"
+        assert name in sptir.EXPORTED_SYMBOLS
+
+
+def test_host_only_entry_points():
+    assert sptir.sptir_status_string(0) == "ok"
+    assert "ascending" in sptir.sptir_status_string(2)
+    # k = ceil(log2(nnz / n)) (section 4.2.1)
+    assert sptir.sptir_default_bucket_log2(10556, 2708) == 2
+    assert sptir.sptir_default_bucket_log2(114615892, 232965) == 9
+    assert sptir.sptir_default_bucket_log2(8, 8) == 0
+    assert sptir.sptir_default_bucket_log2(9, 8) == 1
+    assert sptir.sptir_default_bucket_log2(0, 8) == 0
+
+
+def test_null_arguments_are_rejected_without_a_gpu():
+    lib = sptir.load_library()
+    assert lib.sptir_hyb_build(None, 1, 1, None, None) == 1
+    assert lib.sptir_hyb_info(None, None) == 1
+    assert lib.sptir_hyb_destroy(None) == 0
+    assert lib.sptir_spmm(None, None, None, 4, None) == 1

@@ -1,0 +1,268 @@
+"""GPU parity tests: every call goes through the C ABI (ctypes binding) and is
+compared with the CPU oracle on the same seeded inputs.  hyb arrays must match
+bit for bit; Y within 1e-5 of the oracle, normalised by sum_j |a_ij x_jk|."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_helpers import assert_y_close, fetch_hyb, upload
+from hyb_checks import assert_same_hyb, load_golden
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hyb_2_2_example.txt")
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def build_both(sptir, w, c, k):
+    d = upload(w)
+    hyb = sptir.sptir_hyb_build(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, c, k)
+    got, info = fetch_hyb(sptir, hyb)
+    want = oracle.hyb_build(w.n_rows, w.n_cols, w.indptr, w.indices, w.values, c, k)
+    return d, hyb, got, want, info
+
+
+def ragged_workload(seed, n_rows, n_cols, feat, max_deg, empty_frac=0.15, long_rows=0):
+    rng = np.random.default_rng(seed)
+    deg = np.minimum(rng.geometric(0.15, n_rows), max_deg)
+    deg[rng.random(n_rows) < empty_frac] = 0
+    for r in rng.choice(n_rows, size=long_rows, replace=False):
+        deg[r] = rng.integers(max_deg // 2, max_deg + 1)
+    return workloads.random_csr(n_rows, n_cols, np.minimum(deg, n_cols), seed, feat)
+
+
+# ------------------------------------------------------------------- builder
+
+def test_hyb_golden_example(gpu_lib):
+    g = load_golden(GOLDEN)
+    ints = lambda key: np.array(g[key], dtype=np.int32)
+    w = workloads.Workload("golden", 5, 12, ints("indptr"), ints("indices"), np.array(g["values"], np.float32),
+                           np.ones((12, 1), np.float32), 1, 2, 2)
+    d, hyb, got, want, info = build_both(gpu_lib, w, 2, 2)
+    assert_same_hyb(got, want)
+    for name in ("ell_row", "ell_col", "rem_col", "bucket_slot_ptr"):
+        assert np.array_equal(getattr(got, name), np.array(g[name], dtype=getattr(got, name).dtype))
+    Y = torch.empty(5, 1, device="cuda")
+    gpu_lib.sptir_spmm(hyb, d.X, Y)
+    assert np.array_equal(Y.cpu().numpy().ravel(), np.array(g["y_ones"], np.float32))
+
+
+@pytest.mark.parametrize("seed,n_rows,n_cols,c,k", [
+    (0, 300, 300, 1, 0), (1, 777, 513, 1, 5), (2, 1000, 1200, 2, 2), (3, 1025, 999, 3, 1),
+    (4, 2500, 2500, 4, 6), (5, 513, 4000, 7, 3), (6, 3000, 64, 16, 2), (7, 255, 700, 100, 3),
+    (8, 256, 300, 2, 30), (9, 257, 5000, 5, 9), (10, 1, 50, 2, 2), (11, 4097, 4097, 16, 11)])
+def test_hyb_bit_exact_ragged(gpu_lib, seed, n_rows, n_cols, c, k):
+    say(f"[hyb ragged] seed={seed} n_rows={n_rows} n_cols={n_cols} c={c} k={k}")
+    w = ragged_workload(seed, n_rows, n_cols, 8, max_deg=min(n_cols, 600), long_rows=min(5, n_rows))
+    d, hyb, got, want, info = build_both(gpu_lib, w, c, k)
+    assert_same_hyb(got, want)
+    assert info["nnz"] == w.nnz and info["n_pad_slots"] == want.ell_col.size + want.rem_col.size - w.nnz
+
+
+def test_hyb_edge_cases(gpu_lib):
+    sptir = gpu_lib
+    # no non-zeros at all
+    w = workloads.random_csr(7, 9, np.zeros(7, np.int64), 0, 4)
+    d, hyb, got, want, info = build_both(sptir, w, 3, 2)
+    assert_same_hyb(got, want)
+    Y = torch.full((7, 4), 5.0, device="cuda")
+    sptir.sptir_spmm(hyb, d.X, Y)
+    assert (Y == 0).all()
+    # zero rows
+    w0 = workloads.Workload("z", 0, 5, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32),
+                            np.ones((5, 3), np.float32), 3, 1, 1)
+    d, hyb, got, want, info = build_both(sptir, w0, 2, 1)
+    assert_same_hyb(got, want)
+    # a full row (every column) and maximum-length pieces
+    deg = np.array([64, 0, 64, 1, 33], dtype=np.int64)
+    wf = workloads.random_csr(5, 64, deg, 3, 5)
+    for c, k in ((1, 6), (1, 5), (2, 5), (4, 3), (64, 0), (3, 0)):
+        d, hyb, got, want, info = build_both(sptir, wf, c, k)
+        assert_same_hyb(got, want)
+
+
+def test_hyb_build_is_deterministic(gpu_lib):
+    w = workloads.make_config("small")
+    d = upload(w)
+    a = gpu_lib.sptir_hyb_build(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 4, 4)
+    b = gpu_lib.sptir_hyb_build(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 4, 4)
+    ga, _ = fetch_hyb(gpu_lib, a)
+    gb, _ = fetch_hyb(gpu_lib, b)
+    assert_same_hyb(ga, gb)
+
+
+def test_hyb_build_through_torch_allocator(gpu_lib):
+    w = workloads.make_config("tiny")
+    gpu_lib.sptir_set_allocator(True)
+    try:
+        d, hyb, got, want, info = build_both(gpu_lib, w, 2, 3)
+        assert_same_hyb(got, want)
+        hyb.destroy()
+    finally:
+        gpu_lib.sptir_set_allocator(False)
+
+
+def test_error_paths(gpu_lib):
+    sptir = gpu_lib
+    dev = "cuda"
+    t = lambda a, dt: torch.tensor(a, dtype=dt, device=dev)
+    vals = t([1.0, 1.0], torch.float32)
+    cases = [
+        ([0, 2], [2, 1], 2),      # descending columns
+        ([0, 2], [1, 1], 2),      # duplicate column
+        ([0, 2], [0, 4], 2),      # column out of range
+        ([0, 2], [-1, 1], 2),     # negative column
+        ([1, 2], [0, 1], 1),      # indptr[0] != 0
+        ([0, 1], [0, 1], 1),      # indptr[-1] != nnz
+    ]
+    for indptr, indices, status in cases:
+        with pytest.raises(sptir.SptirError) as e:
+            sptir.sptir_hyb_build(1, 4, t(indptr, torch.int32), t(indices, torch.int32), vals, 1, 1)
+        assert e.value.status == status, (indptr, indices)
+    # decreasing indptr over two rows
+    with pytest.raises(sptir.SptirError) as e:
+        sptir.sptir_hyb_build(2, 4, t([0, 2, 1], torch.int32), t([0, 1], torch.int32), vals, 1, 1)
+    assert e.value.status == 1
+    ok = (t([0, 2], torch.int32), t([0, 1], torch.int32), vals)
+    for c, k in ((0, 1), (1, -1), (1, 31)):
+        with pytest.raises(sptir.SptirError) as e:
+            sptir.sptir_hyb_build(1, 4, *ok, c, k)
+        assert e.value.status == 1
+    hyb = sptir.sptir_hyb_build(1, 4, *ok, 1, 1)
+    X = torch.ones(4, 8, device=dev)
+    with pytest.raises(sptir.SptirError) as e:      # Y overlapping X
+        sptir.sptir_spmm(hyb, X, X[:1])
+    assert e.value.status == 1
+    # two rows that are legal only because the descent sits on a row boundary
+    h2 = sptir.sptir_hyb_build(2, 4, t([0, 1, 2], torch.int32), t([3, 0], torch.int32), vals, 1, 1)
+    assert sptir.sptir_hyb_info(h2)["nnz"] == 2
+
+
+# ---------------------------------------------------------------------- SpMM
+
+@pytest.mark.parametrize("feat", [1, 3, 4, 8, 16, 30, 32, 33, 64, 100, 128, 130, 256, 288])
+def test_spmm_feature_widths(gpu_lib, feat):
+    say(f"[spmm feat] feat={feat}")
+    w = ragged_workload(100 + feat, 1500, 1700, feat, max_deg=900, long_rows=6)
+    for c, k in ((1, 3), (3, 5), (4, 10)):
+        d, hyb, got, want, info = build_both(gpu_lib, w, c, k)
+        Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+        gpu_lib.sptir_spmm(hyb, d.X, Y)
+        Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+        assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"feat={feat} c={c} k={k}")
+
+
+def test_spmm_unaligned_views(gpu_lib):
+    w = ragged_workload(7, 400, 500, 12, max_deg=300, long_rows=3)
+    d = upload(w)
+    hyb = gpu_lib.sptir_hyb_build(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 2, 4)
+    Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+    for shift in (1, 2):     # X and Y start 4 or 8 bytes past a 16-byte boundary
+        xb = torch.empty(w.X.size + 4, device="cuda")
+        yb = torch.empty(w.n_rows * 12 + 4, device="cuda")
+        X = xb[shift:shift + w.X.size].view(w.n_cols, 12); X.copy_(d.X)
+        Y = yb[shift:shift + w.n_rows * 12].view(w.n_rows, 12)
+        gpu_lib.sptir_spmm(hyb, X, Y)
+        assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"shift={shift}")
+
+
+def test_spmm_identity_and_ones(gpu_lib):
+    n, feat = 1000, 64
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((n, feat)).astype(np.float32)
+    dev = "cuda"
+    indptr = torch.arange(n + 1, dtype=torch.int32, device=dev)
+    indices = torch.arange(n, dtype=torch.int32, device=dev)
+    hyb = gpu_lib.sptir_hyb_build(n, n, indptr, indices, torch.ones(n, device=dev), 4, 2)
+    Y = torch.empty(n, feat, device=dev)
+    Xd = torch.from_numpy(X).to(dev)
+    gpu_lib.sptir_spmm(hyb, Xd, Y)
+    assert torch.equal(Y, Xd)                     # A = I gives Y = X exactly
+    w = ragged_workload(5, 800, 900, 32, max_deg=700, long_rows=4)
+    w.values[:] = 1.0
+    d = upload(w)
+    hyb = gpu_lib.sptir_hyb_build(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 3, 4)
+    Y = torch.empty(w.n_rows, 32, device=dev)
+    gpu_lib.sptir_spmm(hyb, torch.ones(w.n_cols, 32, device=dev), Y)
+    deg = np.diff(w.indptr).astype(np.float32)     # unit values, X = 1: exactly the degrees
+    assert np.array_equal(Y.cpu().numpy(), np.repeat(deg[:, None], 32, 1))
+
+
+@pytest.mark.parametrize("name", ["tiny", "small", "medium"])
+def test_named_configs_full(gpu_lib, name):
+    say(f"[config] {name}")
+    w = workloads.make_config(name)
+    d, hyb, got, want, info = build_both(gpu_lib, w, w.n_col_parts, w.max_bucket_log2)
+    assert_same_hyb(got, want)
+    Y = torch.empty(w.n_rows, w.feat, device="cuda")
+    gpu_lib.sptir_spmm(hyb, d.X, Y)
+    Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+    worst = assert_y_close(Y.cpu().numpy(), Yr, Sr, what=name)
+    say(f"[config] {name}: nnz={w.nnz} pads={info['n_pad_slots']} rem_nnz={info['n_rem_nnz']} max_err={worst:.2e}")
+    # the no-hyb CSR kernel on the same input
+    Y2 = torch.empty_like(Y)
+    gpu_lib.sptir_spmm_csr(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, d.X, Y2)
+    assert_y_close(Y2.cpu().numpy(), Yr, Sr, what=name + " csr")
+
+
+@pytest.mark.parametrize("name", ["protein", "social"])
+def test_named_configs_full_size_sampled(gpu_lib, name):
+    """Full-size graphs in the launch configuration bench.py times: hyb arrays
+    bit-exact in full, Y on a sample of rows the oracle evaluates one by one
+    (the highest-degree rows, the first and last rows, and random rows)."""
+    say(f"[config] {name}: generating")
+    w = workloads.make_config(name)
+    say(f"[config] {name}: building on GPU and in the oracle")
+    d, hyb, got, want, info = build_both(gpu_lib, w, w.n_col_parts, w.max_bucket_log2)
+    assert_same_hyb(got, want)
+    del got, want
+    Y = torch.empty(w.n_rows, w.feat, device="cuda")
+    gpu_lib.sptir_spmm(hyb, d.X, Y)
+    torch.cuda.synchronize()
+    deg = np.diff(w.indptr)
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([np.argsort(deg)[-64:], np.argsort(deg)[:64], [0, w.n_rows - 1],
+                                     rng.choice(w.n_rows, 6000, replace=False)])).astype(np.int32)
+    say(f"[config] {name}: oracle on {rows.size} sampled rows")
+    Yr, Sr = oracle.spmm_csr_rows(rows, w.indptr, w.indices, w.values, w.X)
+    Yg = Y[torch.from_numpy(rows.astype(np.int64)).cuda()].cpu().numpy()
+    worst = assert_y_close(Yg, Yr, Sr, what=name)
+    # property that holds at any size: column sums, sum_i Y[i,:] = sum_j (sum_i a_ij) X[j,:]
+    colw = np.bincount(w.indices, weights=w.values.astype(np.float64), minlength=w.n_cols)
+    want_sum = colw @ w.X.astype(np.float64)
+    abs_sum = np.bincount(w.indices, weights=np.abs(w.values.astype(np.float64)), minlength=w.n_cols) @ np.abs(
+        w.X.astype(np.float64))
+    got_sum = Y.double().sum(0).cpu().numpy()
+    assert (np.abs(got_sum - want_sum) <= 1e-5 * abs_sum).all()
+    say(f"[config] {name}: nnz={w.nnz} pads={info['n_pad_slots']} rem_nnz={info['n_rem_nnz']} "
+        f"items={info['n_work_items']} max_err={worst:.2e}")
+
+
+def test_spmm_csr_ragged(gpu_lib):
+    for feat in (5, 32, 96):
+        w = ragged_workload(50 + feat, 1200, 1500, feat, max_deg=1000, long_rows=5)
+        d = upload(w)
+        Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+        gpu_lib.sptir_spmm_csr(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, d.X, Y)
+        Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+        assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"csr feat={feat}")
+
+
+def test_spmm_on_side_stream_and_repeat(gpu_lib):
+    w = workloads.make_config("small")
+    d, hyb, got, want, info = build_both(gpu_lib, w, 2, 6)
+    Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+    s = torch.cuda.Stream()
+    Y = torch.empty(w.n_rows, w.feat, device="cuda")
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        for _ in range(3):                       # Y is overwritten, not accumulated
+            gpu_lib.sptir_spmm(hyb, d.X, Y, stream=s)
+    s.synchronize()
+    assert_y_close(Y.cpu().numpy(), Yr, Sr, what="side stream")
