@@ -98,8 +98,10 @@ typedef struct {
   int64_t n_pad_slots;      /* S + T - nnz */
   int64_t n_rem_pieces;     /* M */
   int64_t n_rem_nnz;        /* T */
-  int64_t n_work_items;     /* wavefront work items one sptir_spmm launch walks */
-  int32_t item_slots;       /* stored slots per work item */
+  int64_t n_work_items;     /* chunk descriptors one sptir_spmm call walks */
+  int32_t item_slots;       /* stored slots per chunk */
+  int32_t row_block;        /* rows of Y one workgroup accumulates on chip */
+  int32_t n_phases;         /* kernel launches per sptir_spmm (groups of column partitions) */
   int32_t reserved;
   int64_t device_bytes;     /* device memory the handle owns */
 } sptir_hyb_info_t;
@@ -142,8 +144,8 @@ int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows);
  *   Y  device, [n_rows, feat] row-major float32, must not overlap X
  *   feat >= 1
  * Only enqueues work on `stream` (no synchronisation, no allocation).
- * Contributions of different column partitions are combined with float atomic
- * adds, so the low-order bits of Y may differ between runs.  A pad slot
+ * Partial sums of a row meet in on-chip float atomic adds whose order is not
+ * fixed, so the low-order bits of Y may differ between runs.  A pad slot
  * multiplies X by +0.0f: X must be finite.
  * Errors: INVALID_ARG, HIP.
  */

@@ -45,6 +45,7 @@ class _Info(ctypes.Structure):
                 ("n_ell_slots", ctypes.c_int64), ("n_pad_slots", ctypes.c_int64),
                 ("n_rem_pieces", ctypes.c_int64), ("n_rem_nnz", ctypes.c_int64),
                 ("n_work_items", ctypes.c_int64), ("item_slots", ctypes.c_int32),
+                ("row_block", ctypes.c_int32), ("n_phases", ctypes.c_int32),
                 ("reserved", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
 
 
@@ -185,7 +186,7 @@ def sptir_hyb_info(hyb: Hyb) -> dict:
     st = load_library().sptir_hyb_info(hyb.handle, ctypes.byref(info))
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_hyb_info")
-    return {name: getattr(info, name) for name, _ in _Info._fields_ if name != "reserved"}
+    return {name: getattr(info, name) for name, _ in _Info._fields_}
 
 
 def sptir_hyb_array(hyb: Hyb, name: str) -> np.ndarray:

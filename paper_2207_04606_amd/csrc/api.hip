@@ -58,7 +58,7 @@ sptir_status_t sptir_set_allocator(sptir_alloc_fn alloc, sptir_free_fn free_, vo
 sptir_status_t sptir_hyb_destroy(sptir_hyb_t* h) {
   if (!h) return SPTIR_OK;
   void* ptrs[] = {h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_part_ptr, h->rem_ptr,
-                  h->row_ids, h->cols, h->vals, h->items};
+                  h->row_ids, h->row_len, h->cols, h->vals, h->chunks, h->rb_chunk_ptr};
   for (void* p : ptrs)
     if (p) h->free_(p, h->alloc_ctx);
   delete h;
@@ -76,7 +76,8 @@ sptir_status_t sptir_hyb_info(const sptir_hyb_t* h, sptir_hyb_info_t* out) {
   o.n_ell_rows = h->R; o.n_ell_slots = h->S;
   o.n_pad_slots = h->S + h->T - h->nnz;
   o.n_rem_pieces = h->M; o.n_rem_nnz = h->T;
-  o.n_work_items = h->n_items; o.item_slots = h->item_slots;
+  o.n_work_items = h->n_chunks; o.item_slots = sptir::kChunkSlots; o.row_block = 1 << h->log2_row_block;
+  o.n_phases = h->n_phases;
   o.device_bytes = (int64_t)h->device_bytes;
   *out = o;
   return SPTIR_OK;

@@ -12,6 +12,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <new>
 #include <vector>
 
 #include "sptir_internal.h"
@@ -26,7 +27,6 @@ struct BuildShape {
   int32_t n_rows, n_cols, c, k, w;
   int32_t nb;  // bins per partition = k + 2
   int32_t NB;  // row blocks = ceil(n_rows / 256)
-  int32_t item_slots;
 };
 
 // first position q in [lo, hi) whose column is >= bound
@@ -91,16 +91,15 @@ __global__ void k_validate_elems(int64_t nnz, int32_t n_cols, const int32_t* __r
 // --------------------------------------------------------------------- count
 // counts   [c][nb][NB] int32 : pieces of each bin per row block
 // rem_nnz  [c][NB]     int64 : non-zeros sent to the remainder per row block
-// rem_items[c][NB]     int64 : SpMM work items those pieces will need
 __global__ __launch_bounds__(kBuildBlock) void k_count(BuildShape s, const int32_t* __restrict__ indptr,
                                                        const int32_t* __restrict__ indices, int32_t* counts,
-                                                       int64_t* rem_nnz, int64_t* rem_items) {
+                                                       int64_t* rem_nnz) {
   __shared__ int hist[kMaxBins];
-  __shared__ unsigned long long sum_nnz, sum_items;
+  __shared__ unsigned long long sum_nnz;
   int tid = threadIdx.x;
   int p = blockIdx.x / s.NB, rb = blockIdx.x % s.NB;
   if (tid < kMaxBins) hist[tid] = 0;
-  if (tid == 0) { sum_nnz = 0; sum_items = 0; }
+  if (tid == 0) sum_nnz = 0;
   __syncthreads();
   int r = rb * kBuildBlock + tid;
   if (r < s.n_rows) {
@@ -109,18 +108,12 @@ __global__ __launch_bounds__(kBuildBlock) void k_count(BuildShape s, const int32
     if (l > 0) {
       int bin = bin_of_length(l, s.k);
       atomicAdd(&hist[bin], 1);
-      if (bin == s.k + 1) {
-        atomicAdd(&sum_nnz, (unsigned long long)l);
-        atomicAdd(&sum_items, (unsigned long long)((l + s.item_slots - 1) / s.item_slots));
-      }
+      if (bin == s.k + 1) atomicAdd(&sum_nnz, (unsigned long long)l);
     }
   }
   __syncthreads();
   if (tid < s.nb) counts[((int64_t)p * s.nb + tid) * s.NB + rb] = hist[tid];
-  if (tid == 0) {
-    rem_nnz[(int64_t)p * s.NB + rb] = (int64_t)sum_nnz;
-    rem_items[(int64_t)p * s.NB + rb] = (int64_t)sum_items;
-  }
+  if (tid == 0) rem_nnz[(int64_t)p * s.NB + rb] = (int64_t)sum_nnz;
 }
 
 // ---------------------------------------------------------------------- scan
@@ -178,17 +171,15 @@ struct ScatterArgs {
   const float* values;
   const int32_t* counts;       // scanned: rank of the block's first piece of each bin
   const int64_t* rem_nnz;      // scanned
-  const int64_t* rem_items;    // scanned
   const int64_t* bucket_row_ptr;
   const int64_t* bucket_slot_ptr;
   const int32_t* rem_part_ptr;
   const int64_t* rem_nnz_base;   // [c] first remainder nnz of each partition
-  const int64_t* rem_item_base;  // [c] absolute index of the partition's first remainder work item
   int32_t* row_ids;
   int32_t* cols;
   float* vals;
   int64_t* rem_ptr;
-  WorkItem* items;
+  int32_t* row_len;  // [R+M] real (unpadded) length of every ELL row and remainder piece
   int64_t R, S, M, T;
 };
 
@@ -233,13 +224,11 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
   int rank_in_wave = __popcll(peers & ((1ull << lane) - 1ull));
   if (bin >= 0 && rank_in_wave == 0) wave_cnt[wave][bin] = __popcll(peers);
 
-  // remainder pieces also need running sums of their lengths and work items
+  // remainder pieces also need the running sum of their lengths
   bool is_rem = (bin == s.k + 1);
   long long my_nnz = is_rem ? l : 0;
-  long long my_items = is_rem ? (l + s.item_slots - 1) / s.item_slots : 0;
   long long tot;
   long long nnz_before = block_exclusive_scan<long long>(my_nnz, wave_sums, &tot);
-  long long items_before = block_exclusive_scan<long long>(my_items, wave_sums, &tot);
   // (block_exclusive_scan synchronises the workgroup, so wave_cnt is complete here)
   // Lanes without a piece stay alive with width 0: the wide copies below need all 64 lanes.
   int width = 0;
@@ -252,24 +241,16 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
       int64_t b = (int64_t)p * (s.k + 1) + bin;
       width = 1 << bin;
       a.row_ids[a.bucket_row_ptr[b] + q] = r;
+      a.row_len[a.bucket_row_ptr[b] + q] = l;
       dst = a.bucket_slot_ptr[b] + q * width;
     } else {
       int64_t m = (int64_t)a.rem_part_ptr[p] + q;
       int64_t t0 = a.rem_nnz_base[p] + a.rem_nnz[(int64_t)p * s.NB + rb] + nnz_before;
       a.row_ids[a.R + m] = r;
+      a.row_len[a.R + m] = l;
       a.rem_ptr[m] = t0;
       width = l;
       dst = a.S + t0;
-      // the piece's SpMM work items: item_slots non-zeros each, one row
-      int64_t it = a.rem_item_base[p] + a.rem_items[(int64_t)p * s.NB + rb] + items_before;
-      for (int off = 0; off < l; off += s.item_slots, ++it) {
-        int cnt = min(s.item_slots, l - off);
-        WorkItem w;
-        w.slot0 = dst + off;
-        w.row0 = (int32_t)(a.R + m);
-        w.meta = (uint32_t)kRemLog2W | ((uint32_t)cnt << 6);
-        a.items[it] = w;
-      }
     }
   }
   // short pieces are copied by their own lane, long ones by the whole wave
@@ -285,29 +266,145 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
   }
 }
 
-// ELL work items: bucket b contributes ceil(slots_b / item_slots) items, stored
-// from items[item_base[b]]; item_prefix is the dense prefix used to map a
-// thread to its bucket.
-__global__ void k_make_ell_items(int32_t B, int32_t k, int32_t item_slots, const int64_t* __restrict__ item_prefix,
-                                 const int64_t* __restrict__ item_base, const int64_t* __restrict__ bucket_row_ptr,
-                                 const int64_t* __restrict__ bucket_slot_ptr, WorkItem* items) {
-  int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (u >= item_prefix[B]) return;
-  int lo = 0, hi = B;  // last b with item_prefix[b] <= u
-  while (hi - lo > 1) {
-    int mid = (lo + hi) >> 1;
-    if (item_prefix[mid] <= u) lo = mid; else hi = mid;
+// ------------------------------------------------------- SpMM work-item list
+// The SpMM kernel keeps the Y rows of one row block (row_block consecutive
+// rows) in LDS, and walks the stored slots in chunks of kChunkSlots.  A chunk
+// descriptor never crosses a row-block boundary.  Rows ascend inside every
+// bucket and inside every partition's remainder, hence the rows of a bin that
+// fall into row block j are one contiguous run; a "cell" is that run for one
+// (phase, row block, partition, bin).  Cells are numbered
+//   ((phase * n_rb + rb) * ppg + p_local) * nb + bin,   p = phase * ppg + p_local,
+// and their chunks are laid out in that order, so the chunks of one (phase, row
+// block) are contiguous and sweep the column partitions in ascending order.
+// Rows of width < 64 are packed 64/width to a chunk.  A wider row (and a
+// remainder piece) takes ceil(len / 64) chunks for its len real entries:
+// chunks that would hold nothing but pads are never emitted.
+struct CellShape {
+  int32_t c, k, nb;
+  int32_t log2_rb, n_rb, ppg, n_phases;
+  int64_t R;
+};
+
+// bin_rb_ptr[(p*nb + bin)*(n_rb+1) + j] = first position in row_ids of bin
+// (p, bin) whose row id is >= j * row_block (absolute index into row_ids)
+__global__ void k_cell_bounds(CellShape cs, const int64_t* __restrict__ bucket_row_ptr,
+                              const int32_t* __restrict__ rem_part_ptr, const int32_t* __restrict__ row_ids,
+                              int32_t* bin_rb_ptr) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t per_bin = (int64_t)cs.n_rb + 1;
+  if (t >= (int64_t)cs.c * cs.nb * per_bin) return;
+  int j = (int)(t % per_bin);
+  int pb = (int)(t / per_bin);
+  int p = pb / cs.nb, bin = pb % cs.nb;
+  int64_t lo, hi;
+  if (bin <= cs.k) {
+    int64_t b = (int64_t)p * (cs.k + 1) + bin;
+    lo = bucket_row_ptr[b]; hi = bucket_row_ptr[b + 1];
+  } else {
+    lo = cs.R + rem_part_ptr[p]; hi = cs.R + rem_part_ptr[p + 1];
   }
-  int b = lo, i = b % (k + 1);
-  int64_t j = u - item_prefix[b];
-  int64_t off = j * item_slots;
-  int64_t slots = bucket_slot_ptr[b + 1] - bucket_slot_ptr[b];
-  int64_t cnt = slots - off < item_slots ? slots - off : item_slots;
-  WorkItem w;
-  w.slot0 = bucket_slot_ptr[b] + off;
-  w.row0 = (int32_t)(bucket_row_ptr[b] + (off >> i));
-  w.meta = (uint32_t)i | ((uint32_t)cnt << 6);
-  items[item_base[b] + j] = w;
+  int64_t bound = (int64_t)j << cs.log2_rb;
+  while (lo < hi) {
+    int64_t mid = lo + ((hi - lo) >> 1);
+    if ((int64_t)row_ids[mid] < bound) lo = mid + 1; else hi = mid;
+  }
+  bin_rb_ptr[t] = (int32_t)lo;
+}
+
+struct CellRef {
+  int phase, rb, p, bin;
+  int32_t q_lo, q_hi;  // run of rows in row_ids
+};
+
+__device__ __forceinline__ bool decode_cell(const CellShape& cs, int64_t cell, const int32_t* __restrict__ bin_rb_ptr,
+                                            CellRef* r) {
+  r->bin = (int)(cell % cs.nb);
+  int64_t t = cell / cs.nb;
+  int pl = (int)(t % cs.ppg);
+  t /= cs.ppg;
+  r->rb = (int)(t % cs.n_rb);
+  r->phase = (int)(t / cs.n_rb);
+  r->p = r->phase * cs.ppg + pl;
+  r->q_lo = r->q_hi = 0;
+  if (r->p >= cs.c) return false;
+  const int32_t* ptr = bin_rb_ptr + ((int64_t)r->p * cs.nb + r->bin) * ((int64_t)cs.n_rb + 1) + r->rb;
+  r->q_lo = ptr[0];
+  r->q_hi = ptr[1];
+  return r->q_hi > r->q_lo;
+}
+
+__device__ __forceinline__ int chunks_of_length(int len) { return (len + kChunkSlots - 1) / kChunkSlots; }
+
+__global__ void k_cell_chunk_counts(CellShape cs, int64_t n_cells, const int32_t* __restrict__ bin_rb_ptr,
+                                    const int32_t* __restrict__ row_len, long long* cell_chunks) {
+  int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (cell >= n_cells) return;
+  CellRef r;
+  long long n = 0;
+  if (decode_cell(cs, cell, bin_rb_ptr, &r)) {
+    if (r.bin <= cs.k && (1 << r.bin) < kChunkSlots) {
+      int rows_per_chunk = kChunkSlots >> r.bin;
+      n = (r.q_hi - r.q_lo + rows_per_chunk - 1) / rows_per_chunk;
+    } else {
+      for (int32_t q = r.q_lo; q < r.q_hi; ++q) n += chunks_of_length(row_len[q]);
+    }
+  }
+  cell_chunks[cell] = n;
+}
+
+__global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t* __restrict__ bin_rb_ptr,
+                                   const long long* __restrict__ cell_first_chunk,
+                                   const int32_t* __restrict__ row_len, const int64_t* __restrict__ bucket_row_ptr,
+                                   const int64_t* __restrict__ bucket_slot_ptr, const int64_t* __restrict__ rem_ptr,
+                                   int64_t S, Chunk* chunks, int64_t* rb_chunk_ptr) {
+  int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (cell >= n_cells) return;
+  CellRef r;
+  bool any = decode_cell(cs, cell, bin_rb_ptr, &r);
+  int64_t it = cell_first_chunk[cell];
+  const int64_t group_first_cell = cell - cell % ((int64_t)cs.ppg * cs.nb);
+  const int64_t list_begin = cell_first_chunk[group_first_cell];  // first chunk of this (phase, row block)
+  if (cell == group_first_cell) rb_chunk_ptr[(int64_t)r.phase * cs.n_rb + r.rb] = it;
+  if (!any) return;
+  // A wave carries the partial sum of a row that continues in its next chunk;
+  // it must hand it over at the end of every group of kChunksPerTurn chunks,
+  // because the next group belongs to another wave.
+  auto emit = [&](int64_t slot0, int32_t row0, int lw, int count, bool row_ends) {
+    bool turn_ends = ((it - list_begin) % kChunksPerTurn) == kChunksPerTurn - 1;
+    Chunk ck;
+    ck.slot0 = slot0;
+    ck.row0 = row0;
+    ck.meta = (uint32_t)lw | ((uint32_t)count << 6) | ((row_ends || turn_ends) ? (1u << 13) : 0u);
+    chunks[it++] = ck;
+  };
+  if (r.bin <= cs.k) {
+    int64_t b = (int64_t)r.p * (cs.k + 1) + r.bin;
+    int64_t width = (int64_t)1 << r.bin;
+    int64_t first_slot = bucket_slot_ptr[b] + ((int64_t)r.q_lo - bucket_row_ptr[b]) * width;
+    if (width < kChunkSlots) {  // several whole rows per chunk
+      int rows_per_chunk = kChunkSlots >> r.bin;
+      for (int32_t q = r.q_lo; q < r.q_hi; q += rows_per_chunk) {
+        int rows = r.q_hi - q < rows_per_chunk ? r.q_hi - q : rows_per_chunk;
+        emit(first_slot + ((int64_t)(q - r.q_lo) << r.bin), q, r.bin, rows << r.bin, true);
+      }
+    } else {  // a row takes one chunk per 64 real entries
+      for (int32_t q = r.q_lo; q < r.q_hi; ++q) {
+        int len = row_len[q];
+        int64_t row_slot = first_slot + (int64_t)(q - r.q_lo) * width;
+        for (int off = 0; off < len; off += kChunkSlots)
+          emit(row_slot + off, q, kRowLog2W, len - off < kChunkSlots ? len - off : kChunkSlots,
+               off + kChunkSlots >= len);
+      }
+    }
+  } else {
+    for (int32_t q = r.q_lo; q < r.q_hi; ++q) {
+      int64_t begin = rem_ptr[q - cs.R];
+      int len = row_len[q];
+      for (int off = 0; off < len; off += kChunkSlots)
+        emit(S + begin + off, q, kRowLog2W, len - off < kChunkSlots ? len - off : kChunkSlots,
+             off + kChunkSlots >= len);
+    }
+  }
 }
 
 // --------------------------------------------------------------- host helpers
@@ -321,11 +418,40 @@ struct Blob {  // bump allocator over one device allocation
   }
 };
 
-int item_slots_setting() {
-  const char* e = getenv("SPTIR_ITEM_SLOTS");
-  long v = e ? atol(e) : 1024;
-  if (v < 64 || v > 65536 || (v & (v - 1))) v = 1024;
-  return (int)v;
+// Tuning knobs (environment, read when a hyb object is built):
+//   SPTIR_ROW_BLOCK        rows of Y a workgroup keeps in LDS (power of two, 32..1024)
+//   SPTIR_PARTS_PER_PHASE  column partitions swept per SpMM launch (default: chosen from the sizes)
+int log2_row_block_setting(int32_t n_rows) {
+  const char* e = getenv("SPTIR_ROW_BLOCK");
+  long v = e ? atol(e) : 0;
+  if (v < 32 || v > 1024 || (v & (v - 1))) {
+    // enough row blocks to fill 256 CUs several times over, else smaller blocks
+    v = 256;
+    while (v > 64 && n_rows / v < 512) v >>= 1;
+  }
+  int l = 0;
+  while ((1L << l) < v) ++l;
+  return l;
+}
+
+// Column partitions swept by one SpMM launch.  Sweeping them one (or a few)
+// at a time keeps the gathered slice of X inside an XCD's 4 MB L2 (the reason
+// section 4.2.1 gives for column partitioning) but costs a read-modify-write
+// of Y per extra launch, so it only pays when rows are long: with P launches
+// the extra Y traffic is 2*(P-1) lines per row and tile, against one X line
+// per stored slot served from L2 instead of from memory (about 4x faster).
+int parts_per_phase_setting(int32_t c, int32_t w, int32_t n_rows, int64_t slots) {
+  const char* e = getenv("SPTIR_PARTS_PER_PHASE");
+  long v = e ? atol(e) : 0;
+  if (v >= 1 && v <= c) return (int)v;
+  const double slice_bytes = (double)w * 128.0;               // one 32-float tile of a partition's X rows
+  long fit = (long)(2.5 * 1024 * 1024 / (slice_bytes > 1 ? slice_bytes : 1));
+  if (fit < 1) fit = 1;
+  if (fit >= c) return c;
+  long phases = (c + fit - 1) / fit;
+  const double slots_per_row = n_rows > 0 ? (double)slots / n_rows : 0.0;
+  if (slots_per_row < 2.5 * (double)(phases - 1)) return c;   // Y traffic would outweigh the L2 hits
+  return (int)fit;
 }
 
 }  // namespace
@@ -348,7 +474,6 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
   s.w = (int32_t)(((int64_t)csr->n_cols + n_col_parts - 1) / n_col_parts);
   s.nb = s.k + 2;
   s.NB = (s.n_rows + kBuildBlock - 1) / kBuildBlock;
-  s.item_slots = item_slots_setting();
   const int64_t n_pair_blocks = (int64_t)s.NB * s.c;
   if (n_pair_blocks > 0x7FFFFFFF) return SPTIR_ERR_OVERFLOW;
   const int64_t B = (int64_t)s.c * (s.k + 1);
@@ -357,28 +482,25 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
   sptir_alloc_fn alloc; sptir_free_fn free_; void* actx;
   current_allocator(&alloc, &free_, &actx);
 
-  // ---- temporary device storage (one blob)
+  // ---- temporary device storage: one blob now, a second one once the cell count is known
+  const size_t nbk = (size_t)(s.NB ? s.NB : 1);
   Blob tmp;
   const size_t o_flags = tmp.reserve(4 * sizeof(unsigned long long));
-  const size_t o_counts = tmp.reserve(sizeof(int32_t) * (size_t)s.c * s.nb * (size_t)(s.NB ? s.NB : 1));
-  const size_t o_rnnz = tmp.reserve(sizeof(int64_t) * (size_t)s.c * (size_t)(s.NB ? s.NB : 1));
-  const size_t o_ritems = tmp.reserve(sizeof(int64_t) * (size_t)s.c * (size_t)(s.NB ? s.NB : 1));
+  const size_t o_counts = tmp.reserve(sizeof(int32_t) * (size_t)s.c * s.nb * nbk);
+  const size_t o_rnnz = tmp.reserve(sizeof(int64_t) * (size_t)s.c * nbk);
   const size_t o_tot_bins = tmp.reserve(sizeof(int32_t) * (size_t)s.c * s.nb);
   const size_t o_tot_rnnz = tmp.reserve(sizeof(int64_t) * (size_t)s.c);
-  const size_t o_tot_ritems = tmp.reserve(sizeof(int64_t) * (size_t)s.c);
   const size_t o_rnnz_base = tmp.reserve(sizeof(int64_t) * (size_t)s.c);
-  const size_t o_ritem_base = tmp.reserve(sizeof(int64_t) * (size_t)s.c);
-  const size_t o_item_prefix = tmp.reserve(sizeof(int64_t) * (size_t)(B + 1));
-  const size_t o_item_base = tmp.reserve(sizeof(int64_t) * (size_t)(B + 1));
   tmp.base = (char*)alloc(tmp.size, actx, stream);
   if (!tmp.base) return SPTIR_ERR_ALLOC;
+  Blob tmp2;
 
   sptir_hyb* h = new (std::nothrow) sptir_hyb();
   if (!h) { free_(tmp.base, actx); return SPTIR_ERR_ALLOC; }
   memset(h, 0, sizeof(*h));
   h->alloc = alloc; h->free_ = free_; h->alloc_ctx = actx;
   h->n_rows = s.n_rows; h->n_cols = s.n_cols; h->c = s.c; h->k = s.k; h->w = s.w;
-  h->nnz = csr->nnz; h->B = B; h->item_slots = s.item_slots;
+  h->nnz = csr->nnz; h->B = B;
 
   // every exit after this point goes through `fail`
   sptir_status_t st = SPTIR_OK;
@@ -392,14 +514,9 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
     unsigned long long* d_flags = (unsigned long long*)(tmp.base + o_flags);
     int32_t* d_counts = (int32_t*)(tmp.base + o_counts);
     int64_t* d_rnnz = (int64_t*)(tmp.base + o_rnnz);
-    int64_t* d_ritems = (int64_t*)(tmp.base + o_ritems);
     int32_t* d_tot_bins = (int32_t*)(tmp.base + o_tot_bins);
     int64_t* d_tot_rnnz = (int64_t*)(tmp.base + o_tot_rnnz);
-    int64_t* d_tot_ritems = (int64_t*)(tmp.base + o_tot_ritems);
     int64_t* d_rnnz_base = (int64_t*)(tmp.base + o_rnnz_base);
-    int64_t* d_ritem_base = (int64_t*)(tmp.base + o_ritem_base);
-    int64_t* d_item_prefix = (int64_t*)(tmp.base + o_item_prefix);
-    int64_t* d_item_base = (int64_t*)(tmp.base + o_item_base);
 
     // ---- validation of the CSR input
     unsigned long long flags[4] = {0, 0, 0, 0};
@@ -417,71 +534,83 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
       int32_t first = 0;
       BUILD_HIP(hipMemcpyAsync(&first, csr->indptr, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
       BUILD_HIP(hipStreamSynchronize(stream));
-      if (first != 0) flags[0] = 1;
+      if (first != 0 || csr->nnz != 0) flags[0] = 1;
     }
     if (flags[0]) { st = SPTIR_ERR_INVALID_ARG; goto fail; }
     if (flags[1] || flags[2] != flags[3]) { st = SPTIR_ERR_UNSORTED; goto fail; }
 
     // ---- histogram and scans
     std::vector<int32_t> tot_bins((size_t)s.c * s.nb, 0);
-    std::vector<int64_t> tot_rnnz((size_t)s.c, 0), tot_ritems((size_t)s.c, 0);
+    std::vector<int64_t> tot_rnnz((size_t)s.c, 0);
     if (s.NB > 0) {
       hipLaunchKernelGGL(k_count, dim3((unsigned)n_pair_blocks), dim3(kBuildBlock), 0, stream, s, csr->indptr,
-                         csr->indices, d_counts, d_rnnz, d_ritems);
+                         csr->indices, d_counts, d_rnnz);
       hipLaunchKernelGGL(k_scan_sequences<int32_t>, dim3((unsigned)(s.c * s.nb)), dim3(kBuildBlock), 0, stream,
                          d_counts, s.NB, d_tot_bins);
       hipLaunchKernelGGL(k_scan_sequences<long long>, dim3((unsigned)s.c), dim3(kBuildBlock), 0, stream,
                          (long long*)d_rnnz, s.NB, (long long*)d_tot_rnnz);
-      hipLaunchKernelGGL(k_scan_sequences<long long>, dim3((unsigned)s.c), dim3(kBuildBlock), 0, stream,
-                         (long long*)d_ritems, s.NB, (long long*)d_tot_ritems);
       BUILD_HIP(hipGetLastError());
       BUILD_HIP(hipMemcpyAsync(tot_bins.data(), d_tot_bins, sizeof(int32_t) * tot_bins.size(),
                                hipMemcpyDeviceToHost, stream));
       BUILD_HIP(hipMemcpyAsync(tot_rnnz.data(), d_tot_rnnz, sizeof(int64_t) * s.c, hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipMemcpyAsync(tot_ritems.data(), d_tot_ritems, sizeof(int64_t) * s.c, hipMemcpyDeviceToHost,
-                               stream));
       BUILD_HIP(hipStreamSynchronize(stream));
     }
 
     // ---- sizes and the small prefix arrays (host)
     std::vector<int64_t> row_ptr((size_t)B + 1, 0), slot_ptr((size_t)B + 1, 0);
-    std::vector<int64_t> item_prefix((size_t)B + 1, 0), item_base((size_t)B + 1, 0);
     std::vector<int32_t> rem_part_ptr((size_t)s.c + 1, 0);
-    std::vector<int64_t> rnnz_base((size_t)s.c, 0), ritem_base((size_t)s.c, 0);
-    int64_t M = 0, T = 0, n_items = 0;
+    std::vector<int64_t> rnnz_base((size_t)s.c, 0);
+    int64_t M = 0, T = 0;
     for (int32_t p = 0; p < s.c; ++p) {
       for (int32_t i = 0; i <= s.k; ++i) {
         int64_t b = (int64_t)p * (s.k + 1) + i;
         int64_t rows = tot_bins[(size_t)p * s.nb + i];
-        int64_t slots = rows << i;
         row_ptr[b + 1] = row_ptr[b] + rows;
-        slot_ptr[b + 1] = slot_ptr[b] + slots;
-        int64_t its = (slots + s.item_slots - 1) / s.item_slots;
-        item_prefix[b + 1] = item_prefix[b] + its;
-        item_base[b] = n_items;
-        n_items += its;
+        slot_ptr[b + 1] = slot_ptr[b] + (rows << i);
       }
       rnnz_base[p] = T;
-      ritem_base[p] = n_items;
       M += tot_bins[(size_t)p * s.nb + s.k + 1];
       T += tot_rnnz[p];
-      n_items += tot_ritems[p];
       if (M > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
       rem_part_ptr[p + 1] = (int32_t)M;
     }
-    h->R = row_ptr[B]; h->S = slot_ptr[B]; h->M = M; h->T = T; h->n_items = n_items;
+    h->R = row_ptr[B]; h->S = slot_ptr[B]; h->M = M; h->T = T;
     if (h->R + h->M > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
 
-    // ---- the handle's device arrays
+    // ---- launch shape of the SpMM: row blocks and phases
+    CellShape cs;
+    cs.c = s.c; cs.k = s.k; cs.nb = s.nb; cs.R = h->R;
+    cs.log2_rb = log2_row_block_setting(s.n_rows);
+    cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
+    cs.ppg = parts_per_phase_setting(s.c, s.w, s.n_rows, h->S + h->T);
+    cs.n_phases = (s.c + cs.ppg - 1) / cs.ppg;
+    h->log2_row_block = cs.log2_rb; h->n_row_blocks = cs.n_rb;
+    h->parts_per_phase = cs.ppg; h->n_phases = cs.n_phases;
+    const int64_t n_cells = (int64_t)cs.n_phases * cs.n_rb * cs.ppg * cs.nb;
+    const int64_t n_bounds = (int64_t)s.c * s.nb * ((int64_t)cs.n_rb + 1);
+    if (n_cells > 0x7FFFFFFF || n_bounds > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
+    const size_t o_bounds = tmp2.reserve(sizeof(int32_t) * (size_t)(n_bounds ? n_bounds : 1));
+    const size_t o_cell_chunks = tmp2.reserve(sizeof(long long) * (size_t)(n_cells ? n_cells : 1));
+    const size_t o_cell_total = tmp2.reserve(sizeof(long long));
+    tmp2.base = (char*)alloc(tmp2.size, actx, stream);
+    if (!tmp2.base) { st = SPTIR_ERR_ALLOC; goto fail; }
+    int32_t* d_bounds = (int32_t*)(tmp2.base + o_bounds);
+    long long* d_cell_chunks = (long long*)(tmp2.base + o_cell_chunks);
+    long long* d_cell_total = (long long*)(tmp2.base + o_cell_total);
+
+    // ---- the handle's device arrays (the chunk list follows further down)
     struct { void** p; size_t bytes; } wanted[] = {
         {(void**)&h->bucket_row_ptr, sizeof(int64_t) * (size_t)(B + 1)},
         {(void**)&h->bucket_slot_ptr, sizeof(int64_t) * (size_t)(B + 1)},
         {(void**)&h->rem_part_ptr, sizeof(int32_t) * (size_t)(s.c + 1)},
         {(void**)&h->rem_ptr, sizeof(int64_t) * (size_t)(M + 1)},
-        {(void**)&h->row_ids, sizeof(int32_t) * (size_t)(h->R + M)},
-        {(void**)&h->cols, sizeof(int32_t) * (size_t)(h->S + T)},
-        {(void**)&h->vals, sizeof(float) * (size_t)(h->S + T)},
-        {(void**)&h->items, sizeof(WorkItem) * (size_t)n_items},
+        // (row_ids, cols and vals end in kChunkSlots spare zero entries: the SpMM kernel
+        //  reads whole 64-slot chunks, the last one of an array may be shorter)
+        {(void**)&h->row_ids, sizeof(int32_t) * (size_t)(h->R + M + kChunkSlots)},
+        {(void**)&h->row_len, sizeof(int32_t) * (size_t)(h->R + M)},
+        {(void**)&h->cols, sizeof(int32_t) * (size_t)(h->S + T + kChunkSlots)},
+        {(void**)&h->vals, sizeof(float) * (size_t)(h->S + T + kChunkSlots)},
+        {(void**)&h->rb_chunk_ptr, sizeof(int64_t) * ((size_t)cs.n_phases * cs.n_rb + 1)},
     };
     for (auto& wnt : wanted) {
       size_t bytes = wnt.bytes ? wnt.bytes : 16;
@@ -489,6 +618,9 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
       if (!*wnt.p) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += bytes;
     }
+    BUILD_HIP(hipMemsetAsync(h->row_ids + h->R + M, 0, sizeof(int32_t) * kChunkSlots, stream));
+    BUILD_HIP(hipMemsetAsync(h->cols + h->S + T, 0, sizeof(int32_t) * kChunkSlots, stream));
+    BUILD_HIP(hipMemsetAsync(h->vals + h->S + T, 0, sizeof(float) * kChunkSlots, stream));
     BUILD_HIP(hipMemcpyAsync(h->bucket_row_ptr, row_ptr.data(), sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice,
                              stream));
     BUILD_HIP(hipMemcpyAsync(h->bucket_slot_ptr, slot_ptr.data(), sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice,
@@ -496,42 +628,64 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
     BUILD_HIP(hipMemcpyAsync(h->rem_part_ptr, rem_part_ptr.data(), sizeof(int32_t) * (s.c + 1),
                              hipMemcpyHostToDevice, stream));
     BUILD_HIP(hipMemcpyAsync(d_rnnz_base, rnnz_base.data(), sizeof(int64_t) * s.c, hipMemcpyHostToDevice, stream));
-    BUILD_HIP(hipMemcpyAsync(d_ritem_base, ritem_base.data(), sizeof(int64_t) * s.c, hipMemcpyHostToDevice, stream));
-    BUILD_HIP(hipMemcpyAsync(d_item_prefix, item_prefix.data(), sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice,
-                             stream));
-    BUILD_HIP(hipMemcpyAsync(d_item_base, item_base.data(), sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice,
-                             stream));
 
-    // ---- stable scatter and work-item list
+    // ---- stable scatter
     if (s.NB > 0) {
       ScatterArgs a;
       a.indptr = csr->indptr; a.indices = csr->indices; a.values = csr->values;
-      a.counts = d_counts; a.rem_nnz = d_rnnz; a.rem_items = d_ritems;
+      a.counts = d_counts; a.rem_nnz = d_rnnz;
       a.bucket_row_ptr = h->bucket_row_ptr; a.bucket_slot_ptr = h->bucket_slot_ptr;
-      a.rem_part_ptr = h->rem_part_ptr; a.rem_nnz_base = d_rnnz_base; a.rem_item_base = d_ritem_base;
-      a.row_ids = h->row_ids; a.cols = h->cols; a.vals = h->vals; a.rem_ptr = h->rem_ptr; a.items = h->items;
+      a.rem_part_ptr = h->rem_part_ptr; a.rem_nnz_base = d_rnnz_base;
+      a.row_ids = h->row_ids; a.cols = h->cols; a.vals = h->vals; a.rem_ptr = h->rem_ptr; a.row_len = h->row_len;
       a.R = h->R; a.S = h->S; a.M = M; a.T = T;
       hipLaunchKernelGGL(k_scatter, dim3((unsigned)n_pair_blocks), dim3(kBuildBlock), 0, stream, s, a);
     } else {
       int64_t zero = 0;
       BUILD_HIP(hipMemcpyAsync(h->rem_ptr, &zero, sizeof(int64_t), hipMemcpyHostToDevice, stream));
     }
-    if (item_prefix[B] > 0) {
-      int64_t blocks = (item_prefix[B] + 255) / 256;
-      if (blocks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
-      hipLaunchKernelGGL(k_make_ell_items, dim3((unsigned)blocks), dim3(256), 0, stream, (int32_t)B, s.k,
-                         s.item_slots, d_item_prefix, d_item_base, h->bucket_row_ptr, h->bucket_slot_ptr, h->items);
+    BUILD_HIP(hipGetLastError());
+
+    // ---- chunk descriptors, grouped by (phase, row block)
+    long long n_chunks = 0;
+    if (n_cells > 0) {
+      hipLaunchKernelGGL(k_cell_bounds, dim3((unsigned)((n_bounds + 255) / 256)), dim3(256), 0, stream, cs,
+                         h->bucket_row_ptr, h->rem_part_ptr, h->row_ids, d_bounds);
+      hipLaunchKernelGGL(k_cell_chunk_counts, dim3((unsigned)((n_cells + 255) / 256)), dim3(256), 0, stream, cs,
+                         n_cells, d_bounds, h->row_len, d_cell_chunks);
+      hipLaunchKernelGGL(k_scan_sequences<long long>, dim3(1), dim3(kBuildBlock), 0, stream, d_cell_chunks,
+                         (int32_t)n_cells, d_cell_total);
+      BUILD_HIP(hipGetLastError());
+      BUILD_HIP(hipMemcpyAsync(&n_chunks, d_cell_total, sizeof(long long), hipMemcpyDeviceToHost, stream));
+      BUILD_HIP(hipStreamSynchronize(stream));
+    }
+    h->n_chunks = n_chunks;
+    {
+      size_t bytes = sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1);
+      h->chunks = (Chunk*)alloc(bytes, actx, stream);
+      if (!h->chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += bytes;
+    }
+    if (n_cells > 0)
+      hipLaunchKernelGGL(k_cell_fill_chunks, dim3((unsigned)((n_cells + 255) / 256)), dim3(256), 0, stream, cs,
+                         n_cells, d_bounds, d_cell_chunks, h->row_len, h->bucket_row_ptr, h->bucket_slot_ptr,
+                         h->rem_ptr, h->S, h->chunks, h->rb_chunk_ptr);
+    {
+      int64_t total = n_chunks;
+      BUILD_HIP(hipMemcpyAsync(h->rb_chunk_ptr + (size_t)cs.n_phases * cs.n_rb, &total, sizeof(int64_t),
+                               hipMemcpyHostToDevice, stream));
     }
     BUILD_HIP(hipGetLastError());
     BUILD_HIP(hipStreamSynchronize(stream));
   }
   free_(tmp.base, actx);
+  if (tmp2.base) free_(tmp2.base, actx);
   *out = h;
   return SPTIR_OK;
 
 fail:
   (void)hipStreamSynchronize(stream);
   free_(tmp.base, actx);
+  if (tmp2.base) free_(tmp2.base, actx);
   sptir_hyb_destroy(h);
   return st;
 #undef BUILD_HIP

@@ -2,27 +2,34 @@
 // 2207.04606), and the single-pass CSR variant the paper calls "no-hyb".
 //
 // Mapping (gfx950, wave64).  The feature dimension is cut into tiles of
-// LG*VEC floats (32 floats = one 128-byte line of X by default).  A wavefront
-// owns one work item (a run of up to item_slots stored slots of one ELL bucket
-// or of one remainder piece) for one feature tile.  Its 64 lanes form 64/LG
-// lane groups; a group covers the tile with VEC floats per lane, so one wave
-// load instruction gathers 64/LG different rows of X, each as one contiguous
-// 128-byte read.  The stored (column, value) pairs are read 64 at a time, one
-// per lane, and handed to the groups by cross-lane reads; partial sums stay in
-// registers and leave the wave once per ELL row through float atomic adds
-// (different column partitions contribute to the same row of Y).
+// LG*VEC floats (32 floats = one 128-byte line of X by default).  A workgroup
+// owns one (row block, feature tile): it keeps that tile of the row block's Y
+// rows in LDS, walks every work item of the row block (all column partitions,
+// all ELL buckets, the remainder) and finally writes the Y tile once with
+// plain coalesced stores.  Y therefore needs no zero fill and no global
+// atomics, and rows without non-zeros come out as 0 (the init block of the
+// SpMM script in appendix A).
 //
-// Workgroup -> (item, tile): consecutive workgroup ids are dealt round-robin to
-// the 8 XCDs, each with a private L2.  Tiles are therefore bound to
-// blockIdx.x % 8 where the tile count allows it, so that an XCD's L2 only ever
-// holds its own feature tile of the X slice of the column partition in flight.
+// A wavefront takes work items from the workgroup's list one at a time.  Its
+// 64 lanes form 64/LG lane groups; a group covers the tile with VEC floats per
+// lane, so one wave load instruction gathers 64/LG different rows of X, each
+// as one contiguous 128-byte read.  Stored (column, value, row) triples are
+// read one per lane, a chunk of slots at a time, and handed to the groups by
+// cross-lane reads.  The loop is software pipelined: the gathers of chunk n+1
+// are in flight while chunk n is multiplied, the triples of chunk n+2 are
+// being fetched.  Partial sums stay in registers (section 4.2.1 names this as
+// what a CSR code generator misses) and go to LDS once per ELL row.
+//
+// Workgroup -> (row block, tile): consecutive workgroup ids are dealt
+// round-robin to the 8 XCDs, each with a private L2.  Tiles are bound to
+// blockIdx.x % 8 where the tile count allows it, so an XCD's L2 only ever holds
+// its own feature tile of X; the items of a row block sweep the column
+// partitions in ascending order, which keeps the X slice in flight L2-sized
+// (the purpose section 4.2.1 gives for column partitioning).
 #include "sptir_internal.h"
 
 namespace sptir {
 namespace {
-
-constexpr int kWavesPerBlock = 4;
-constexpr int kSpmmBlock = 64 * kWavesPerBlock;
 
 template <int VEC> struct Vec;
 template <> struct Vec<4> { using type = float4; };
@@ -37,160 +44,438 @@ __device__ __forceinline__ void load_vec(float (&x)[VEC], const float* p) {
   else { x[0] = v; }
 }
 
+template <int VEC>
+__device__ __forceinline__ void store_vec(float* p, const float (&x)[VEC]) {
+  if constexpr (VEC == 4) *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+  else if constexpr (VEC == 2) *reinterpret_cast<float2*>(p) = make_float2(x[0], x[1]);
+  else *p = x[0];
+}
+
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v >> 1); }
+
+// Lane geometry of one wavefront.
+template <int VEC, int LG>
+struct Shape {
+  static constexpr int kGroups = 64 / LG;            // lane groups = X rows gathered per load
+  static constexpr int kSteps = LG < 8 ? LG : 8;     // slots a group takes from one chunk
+  static constexpr int kChunk = kGroups * kSteps;    // slots per chunk (<= 64: one per lane)
+  static constexpr int kTile = VEC * LG;             // floats per feature tile
+  static constexpr int kLog2Steps = ilog2(kSteps);
+  static constexpr int kLog2Chunk = ilog2(kChunk);
+};
+
+// LDS position of feature (fl*VEC + e) of local row r.  Lane fl of a group
+// owns features fl*VEC .. fl*VEC+VEC-1; storing component e of all lanes side
+// by side, and rotating rows against each other, spreads a flush over banks.
+template <int VEC, int LG>
+__device__ __forceinline__ int lds_index(int r, int fl, int e) {
+  constexpr int T = VEC * LG;
+  return r * T + ((e * LG + fl + r * LG) & (T - 1));
+}
+
+// Adds a finished row sum into the workgroup's Y tile.
+template <int VEC, int LG>
+struct LdsSink {
+  float* tile;     // [row_block][kTile] in LDS
+  int rb_first;    // first row of the row block
+  int fl;
+  bool f_active;
+  __device__ __forceinline__ void operator()(int row_id, bool valid, const float (&acc)[VEC]) const {
+    if (valid && f_active) {
+      int r = row_id - rb_first;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) atomicAdd(&tile[lds_index<VEC, LG>(r, fl, e)], acc[e]);
+    }
+  }
+};
+
+// Stores a finished row straight to Y (a row owned by exactly one wavefront).
+template <int VEC, int LG>
+struct DirectSink {
+  float* y;  // Y + row*feat + f0
+  bool f_active;
+  __device__ __forceinline__ void operator()(int, bool valid, const float (&acc)[VEC]) const {
+    if (valid && f_active) store_vec<VEC>(y, acc);
+  }
+};
+
+// Walks `count` stored slots cp/vp[0..count) for this lane's feature offset.
+// Slot o belongs to the row whose id is rp[o >> lw] (WITH_ROWS) and is handled
+// by lane group (o % kChunk) / kSteps.  Finished row sums go to `sink`.
+template <int VEC, int LG, bool WITH_ROWS, typename Sink>
+__device__ __forceinline__ void walk_slots(const int32_t* __restrict__ cp, const float* __restrict__ vp,
+                                           const int32_t* __restrict__ rp, const float* __restrict__ Xf,
+                                           int feat, int lw, int count, int lane, bool f_active, const Sink& sink) {
+  using S = Shape<VEC, LG>;
+  constexpr int UB = S::kSteps, CS = S::kChunk;
+  if (count <= 0) return;
+  const int g = lane / LG;
+  const int src0 = g * UB;  // lane that fetched slot (g*UB) of the chunk
+  const int nch = (count + CS - 1) >> S::kLog2Chunk;
+  const int width_mask = (lw < 31) ? ((1 << lw) - 1) : 0x7FFFFFFF;
+
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+
+  // one (column, value, row id) triple per lane and chunk
+  auto fetch = [&](int ch, int& c, float& v, int& rid) {
+    int o = (ch << S::kLog2Chunk) + lane;
+    bool ok = (CS == 64 || lane < CS) && o < count;
+    int oc = o < count ? o : count - 1;
+    c = cp[oc];
+    float vv = vp[oc];
+    v = ok ? vv : 0.f;
+    if constexpr (WITH_ROWS) rid = rp[oc >> lw]; else rid = 0;
+  };
+  auto issue = [&](int c_reg, float (&x)[UB][VEC]) {
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      int c = __shfl(c_reg, src0 + u, 64);
+      if (f_active) load_vec<VEC>(x[u], Xf + (size_t)c * (size_t)feat);
+      else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) x[u][e] = 0.f;
+      }
+    }
+  };
+  auto consume = [&](int ch, float v_reg, int rid_reg, const float (&x)[UB][VEC]) {
+    const int chunk0 = ch << S::kLog2Chunk;
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      float v = __shfl(v_reg, src0 + u, 64);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v, x[u][e], acc[e]);
+      // rows no wider than a group's share end inside the group: no cross-lane sum
+      if (lw <= S::kLog2Steps && ((u + 1) & width_mask) == 0) {
+        int rid = __shfl(rid_reg, src0 + u, 64);
+        sink(rid, chunk0 + src0 + u < count, acc);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+      }
+    }
+    if (lw > S::kLog2Steps) {
+      // a wider row spans several lane groups and, beyond a chunk, several chunks
+      bool row_done = (ch == nch - 1) || lw < S::kLog2Chunk || (((ch + 1) << S::kLog2Chunk) & width_mask) == 0;
+      if (row_done) {
+        const int groups = (lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));  // groups per row
+        for (int d = 1; d < groups; d <<= 1) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], d * LG, 64);
+        }
+        const int g_first = g & ~(groups - 1);
+        int rid = __shfl(rid_reg, g_first * UB, 64);
+        sink(rid, g == g_first && chunk0 + g_first * UB < count, acc);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+      }
+    }
+  };
+
+  // software pipeline: x0 / x1 hold the gathers of two consecutive chunks
+  float x0[UB][VEC], x1[UB][VEC];
+  int c_a = 0, c_b = 0, c_p = 0, r_a = 0, r_b = 0, r_p = 0;
+  float v_a = 0.f, v_b = 0.f, v_p = 0.f;
+  fetch(0, c_a, v_a, r_a);
+  if (nch > 1) fetch(1, c_b, v_b, r_b);
+  issue(c_a, x0);
+  if (nch > 2) fetch(2, c_p, v_p, r_p);
+  if (nch > 1) issue(c_b, x1);
+  for (int ch = 0; ch < nch; ch += 2) {
+    consume(ch, v_a, r_a, x0);
+    if (ch + 2 < nch) {
+      c_a = c_p; v_a = v_p; r_a = r_p;
+      if (ch + 3 < nch) fetch(ch + 3, c_p, v_p, r_p);
+      issue(c_a, x0);
+    }
+    if (ch + 1 < nch) {
+      consume(ch + 1, v_b, r_b, x1);
+      if (ch + 3 < nch) {
+        c_b = c_p; v_b = v_p; r_b = r_p;
+        if (ch + 4 < nch) fetch(ch + 4, c_p, v_p, r_p);
+        issue(c_b, x1);
+      }
+    }
+  }
+}
+
 enum TileMap : int {
   kMapTilesPerXcd = 0,  // n_tiles multiple of 8: XCD x owns tiles x, x+8, ...
-  kMapXcdsPerTile = 1,  // n_tiles in {1,2,4}: 8/n_tiles XCDs share a tile, split the items
+  kMapXcdsPerTile = 1,  // n_tiles in {1,2,4}: 8/n_tiles XCDs share a tile, split the units
   kMapPlain = 2         // any other tile count: tile = id % n_tiles
 };
 
+// workgroup id -> (unit, feature tile); units are row blocks (hyb) or groups of rows (CSR)
+__device__ __forceinline__ void decode_block(int map_mode, int map_param, int n_tiles, int64_t* unit, int* tile) {
+  unsigned bid = blockIdx.x;
+  if (map_mode == kMapTilesPerXcd) {
+    unsigned q = bid >> 3, x = bid & 7;
+    *tile = (int)(x + 8 * (q % (unsigned)map_param));
+    *unit = q / (unsigned)map_param;
+  } else if (map_mode == kMapXcdsPerTile) {
+    unsigned q = bid >> 3, x = bid & 7;
+    *tile = (int)(x % (unsigned)n_tiles);
+    *unit = (int64_t)q * map_param + x / (unsigned)n_tiles;
+  } else {
+    *tile = (int)(bid % (unsigned)n_tiles);
+    *unit = bid / (unsigned)n_tiles;
+  }
+}
+
 struct SpmmArgs {
-  const WorkItem* items;
-  int64_t n_items;
+  const Chunk* chunks;
+  const int64_t* rb_chunk_ptr;  // this phase's [n_row_blocks + 1]
   const int32_t* row_ids;
   const int32_t* cols;
   const float* vals;
   const float* X;
   float* Y;
+  int32_t n_rows;
+  int32_t n_row_blocks;
+  int32_t log2_row_block;
   int32_t feat;
   int32_t n_tiles;
   int32_t map_mode;
   int32_t map_param;
+  int32_t accumulate;  // 0: Y tile is overwritten, 1: added to (a later phase)
 };
 
-// Walks `count` stored slots starting at cols/vals[slot0] for the feature
-// offset f0 of this lane.  Slot o belongs to output row (row0 + (o >> lw)).
-// DIRECT: the caller guarantees a single row that no other wave touches, so
-// the result is stored instead of added, and row0 is the row of Y itself.
-template <int VEC, int LG, bool DIRECT>
-__device__ __forceinline__ void walk_item(const int32_t* __restrict__ cols, const float* __restrict__ vals,
-                                          const int32_t* __restrict__ row_ids, const float* __restrict__ X,
-                                          float* __restrict__ Y, int feat, int64_t slot0, int row0, int lw,
-                                          int count, int lane, int f0, bool f_active) {
-  constexpr int LOG2LG = (LG == 1) ? 0 : (LG == 2) ? 1 : (LG == 4) ? 2 : (LG == 8) ? 3 : (LG == 16) ? 4
-                                     : (LG == 32) ? 5 : 6;
-  constexpr int UB = LG < 8 ? LG : 8;  // gathers issued back to back before their FMAs
-  const int group_base = lane & ~(LG - 1);
-  const float* Xf = X + f0;
+
+constexpr int kHybWaves = 4;
+constexpr int kHybBlock = 64 * kHybWaves;
+
+// One wavefront's walk over its share of a row block's chunk list.
+//
+// The unit of the pipeline is a "step": kChunk = kGroups*kSteps slots of a
+// 64-slot chunk (the whole chunk when a lane group is 8 lanes wide).  A chunk's
+// (column, value, row id) triples are fetched one per lane, four chunks ahead,
+// and parked in a small per-wave LDS ring; from there every lane group reads
+// the kSteps columns / values it needs with wide LDS reads (all lanes of a
+// group read the same address, which LDS broadcasts).  While step u is
+// multiplied, the X gathers of steps u+1 and u+2 are in flight.  The
+// steady-state loop body holds no conditional memory operation, so that the
+// compiler's wait counters stay exact; the last steps are peeled.
+//
+// The lane groups that share a row add their partial sums up with cross-lane
+// reads; one of them adds the row sum into the workgroup's LDS tile of Y (float
+// LDS atomics: other wavefronts may be working on the same row).
+template <int VEC, int LG, bool IDX32>
+struct HybWalker {
+  using S = Shape<VEC, LG>;
+  static constexpr int UB = S::kSteps, CS = S::kChunk;
+  static constexpr int SUB = kChunkSlots / CS;  // steps per chunk descriptor
+  static constexpr int LOG2SUB = ilog2(SUB);
+  static constexpr int kRing = 4;               // chunks parked in LDS per wave
+  static constexpr int kStageInts = 3 * kChunkSlots;
+
+  struct Fetched {  // one chunk in flight from memory: a triple per lane, the chunk's facts
+    int col;
+    float val;
+    int rid;
+    int meta;
+  };
+
+  const SpmmArgs& a;
+  const Chunk* list;  // chunk list of this (phase, row block)
+  int n_chunks;       // chunks of this wave
+  int wave, lane, g;
+  int* ring;          // this wave's LDS ring: kRing x [cols | vals | row ids]
+  unsigned row_bytes, lane_bytes;  // bytes per row of X, byte offset of this lane's features
+  LdsSink<VEC, LG> sink;
   float acc[VEC];
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
 
-  const int nch = (count + 63) >> 6;
-  const int32_t* cp = cols + slot0;
-  const float* vp = vals + slot0;
-  int o = lane;
-  int oc = o < count ? o : count - 1;
-  int next_col = nch > 0 ? cp[oc] : 0;
-  float next_val = (nch > 0 && o < count) ? vp[oc] : 0.f;
+  // local chunk number -> position in the row block's list (turns of kChunksPerTurn chunks, dealt round-robin)
+  __device__ __forceinline__ int list_pos(int k) const {
+    return ((k / kChunksPerTurn) * kHybWaves + wave) * kChunksPerTurn + (k % kChunksPerTurn);
+  }
 
-  for (int ch = 0; ch < nch; ++ch) {
-    const int my_col = next_col;
-    const float my_val = next_val;
-    if (ch + 1 < nch) {  // fetch the next 64 (column, value) pairs early
-      o = ((ch + 1) << 6) + lane;
-      oc = o < count ? o : count - 1;
-      next_col = cp[oc];
-      next_val = o < count ? vp[oc] : 0.f;
-    }
+  __device__ __forceinline__ void fetch(int k, Fetched& f) const {
+    k = k < n_chunks ? k : n_chunks - 1;
+    const Chunk ck = list[list_pos(k)];
+    const int lw = (int)(ck.meta & 63u);
+    const int count = (int)((ck.meta >> 6) & 127u);
+    // (the arrays end in kChunkSlots spare entries, so lanes past `count` read valid memory)
+    f.col = a.cols[ck.slot0 + lane];
+    float v = a.vals[ck.slot0 + lane];
+    f.val = lane < count ? v : 0.f;
+    f.rid = a.row_ids[ck.row0 + (lane >> lw)];
+    f.meta = (int)ck.meta;
+  }
+
+  __device__ __forceinline__ int* stage(int k) const { return ring + (k & (kRing - 1)) * kStageInts; }
+
+  __device__ __forceinline__ void park(int k, const Fetched& f) const {
+    int* st = stage(k);
+    st[lane] = f.col;
+    st[kChunkSlots + lane] = __float_as_int(f.val);
+    st[2 * kChunkSlots + lane] = f.rid;
+  }
+
+  // gathers of step u: the UB rows of X this lane group multiplies in that step
+  __device__ __forceinline__ void issue(int u, float (&x)[UB][VEC]) const {
+    const int* st = stage(u >> LOG2SUB) + (u & (SUB - 1)) * CS + g * UB;
+    int c[UB];
 #pragma unroll
-    for (int ub = 0; ub < LG; ub += UB) {
-      float x[UB][VEC];
+    for (int j = 0; j < UB; ++j) c[j] = st[j];
 #pragma unroll
-      for (int u = 0; u < UB; ++u) {
-        int c = __shfl(my_col, group_base | (ub + u), 64);
-        if (f_active) load_vec<VEC>(x[u], Xf + (size_t)c * (size_t)feat);
-        else {
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) x[u][e] = 0.f;
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < UB; ++u) {
-        float v = __shfl(my_val, group_base | (ub + u), 64);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v, x[u][e], acc[e]);
-        if constexpr (!DIRECT) {
-          // rows no wider than a lane group end inside the group: no cross-lane sum
-          if (lw <= LOG2LG && (((ub + u + 1) & ((1 << lw) - 1)) == 0)) {
-            int o_last = (ch << 6) + group_base + ub + u;
-            if (f_active && o_last < count) {
-              int r = row_ids[row0 + (o_last >> lw)];
-              float* y = Y + (size_t)r * (size_t)feat + f0;
-#pragma unroll
-              for (int e = 0; e < VEC; ++e) unsafeAtomicAdd(y + e, acc[e]);
-            }
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-          }
-        }
-      }
-    }
-    if (DIRECT || lw > LOG2LG) {
-      // a wider row spans several lane groups (and, from 64 slots on, several chunks)
-      bool row_done = (ch == nch - 1) || (!DIRECT && (lw < 6 || ((((unsigned)(ch + 1)) << 6) & ((1u << lw) - 1u)) == 0));
-      if (row_done) {
-        const int span = (DIRECT || lw >= 6) ? 64 : (1 << lw);  // lanes that share the row
-        for (int d = LG; d < span; d <<= 1) {
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], d, 64);
-        }
-        int o_first = (ch << 6) + (lane & ~(span - 1));
-        if (f_active && (lane & (span - 1)) < LG && (DIRECT || o_first < count)) {
-          if constexpr (DIRECT) {
-            float* y = Y + (size_t)row0 * (size_t)feat + f0;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) y[e] = acc[e];
-          } else {
-            int r = row_ids[row0 + (o_first >> lw)];
-            float* y = Y + (size_t)r * (size_t)feat + f0;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) unsafeAtomicAdd(y + e, acc[e]);
-          }
-        }
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    for (int j = 0; j < UB; ++j) {
+      if constexpr (IDX32) {
+        // column ids are below 2^24 here, so the 24-bit multiply is exact
+        unsigned off = __umul24((unsigned)c[j], row_bytes) + lane_bytes;
+        load_vec<VEC>(x[j], reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.X) + off));
+      } else {
+        load_vec<VEC>(x[j], reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.X) +
+                                                            (size_t)c[j] * row_bytes + lane_bytes));
       }
     }
   }
-  if constexpr (DIRECT) {
-    if (nch == 0 && f_active && lane < LG) {  // empty row: Y row is zero
-      float* y = Y + (size_t)row0 * (size_t)feat + f0;
+
+  __device__ __forceinline__ void consume(int u, int meta, const float (&x)[UB][VEC]) {
+    const int lw = meta & 63, count = (meta >> 6) & 127;
+    const bool hand_over = (meta >> 13) & 1;
+    const int sub = u & (SUB - 1);
+    const int first = sub * CS + g * UB;  // this group's first slot of the chunk
+    const int* st = stage(u >> LOG2SUB);
+    float v[UB];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) y[e] = 0.f;
+    for (int j = 0; j < UB; ++j) v[j] = __int_as_float(st[kChunkSlots + first + j]);
+    if (lw < S::kLog2Steps) {
+      // several rows inside the group's share: hand each one over as it ends
+      int rid[UB];
+#pragma unroll
+      for (int j = 0; j < UB; ++j) rid[j] = st[2 * kChunkSlots + first + j];
+      const int width_mask = (1 << lw) - 1;
+#pragma unroll
+      for (int j = 0; j < UB; ++j) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
+        if (((j + 1) & width_mask) == 0) {
+          sink(rid[j], first + j < count, acc);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+        }
+      }
+      return;
     }
+    // the group's share lies inside one row, which `groups` neighbouring lane groups share
+    const bool one_row_chunk = lw >= 6;
+#pragma unroll
+    for (int j = 0; j < UB; ++j)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
+    if (one_row_chunk && !(hand_over && sub == SUB - 1)) return;  // the row goes on: keep the sums in registers
+    const int groups = (one_row_chunk || lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));
+    if (!one_row_chunk && lw >= S::kLog2Chunk && (((sub + 1) * CS) & ((1 << lw) - 1)) != 0) return;  // row spans steps
+    for (int d = 1; d < groups; d <<= 1) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], d * LG, 64);
+    }
+    const int g_first = g & ~(groups - 1);
+    // (a row cut into several chunks keeps its partial sums in registers in between,
+    //  so for a one-row chunk even groups past `count` take part; its row id sits in slot 0)
+    const int rid = st[2 * kChunkSlots + (one_row_chunk ? 0 : sub * CS + g_first * UB)];
+    sink(rid, g == g_first && (one_row_chunk || sub * CS + g_first * UB < count), acc);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
   }
-}
 
-// workgroup id -> (group of kWavesPerBlock consecutive units, feature tile)
-__device__ __forceinline__ void decode_block(int map_mode, int map_param, int n_tiles, int64_t* group, int* tile) {
-  unsigned bid = blockIdx.x;
-  if (map_mode == kMapTilesPerXcd) {
-    unsigned q = bid >> 3, x = bid & 7;
-    *tile = (int)(x + 8 * (q % (unsigned)map_param));
-    *group = q / (unsigned)map_param;
-  } else if (map_mode == kMapXcdsPerTile) {
-    unsigned q = bid >> 3, x = bid & 7;
-    *tile = (int)(x % (unsigned)n_tiles);
-    *group = (int64_t)q * map_param + x / (unsigned)n_tiles;
-  } else {
-    *tile = (int)(bid % (unsigned)n_tiles);
-    *group = bid / (unsigned)n_tiles;
+  __device__ __forceinline__ void run() {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    if (n_chunks <= 0) return;
+    const int n_steps = n_chunks * SUB;
+    // chunks 0..3 are fetched at once; 0..2 are parked, 3 stays in registers for the first loop step
+    Fetched f0, f1, f2, fp;
+    fetch(0, f0); fetch(1, f1); fetch(2, f2); fetch(3, fp);
+    park(0, f0); park(1, f1); park(2, f2);
+    int m0 = f0.meta, m1 = f1.meta, m2 = f2.meta, m3 = 0;  // facts of chunks k, k+1, k+2, k+3 (k = chunk of step u)
+    float xa[UB][VEC], xb[UB][VEC];
+    issue(0, xa);
+    issue(n_steps > 1 ? 1 : 0, xb);
+    // one step; `x` holds the gathers of step u and is refilled with those of step u+2
+    auto step = [&](int u, float (&x)[UB][VEC]) {
+      if (SUB == 1 || (u & (SUB - 1)) == 0) {  // first step of chunk k: chunk k+3 arrives, chunk k+4 is requested
+        const int k = u >> LOG2SUB;
+        park(k + 3, fp);
+        m3 = fp.meta;
+        fetch(k + 4, fp);
+      }
+      consume(u, m0, x);
+      issue(u + 2, x);
+      if (SUB == 1 || (u & (SUB - 1)) == SUB - 1) { m0 = m1; m1 = m2; m2 = m3; }
+    };
+    int u = 0;
+    for (; u + 3 < n_steps; u += 2) {
+      step(u, xa);
+      step(u + 1, xb);
+    }
+    // 1..3 steps left; the gathers of steps u and u+1 are in flight
+    const int left = n_steps - u;
+    auto last = [&](int uu, float (&x)[UB][VEC]) {
+      consume(uu, m0, x);
+      if (SUB == 1 || (uu & (SUB - 1)) == SUB - 1) { m0 = m1; m1 = m2; m2 = m3; }
+    };
+    if (SUB > 1 && (u & (SUB - 1)) == 0) { park((u >> LOG2SUB) + 3, fp); m3 = fp.meta; }
+    last(u, xa);
+    if (left == 3) issue(u + 2, xa);
+    if (left >= 2) last(u + 1, xb);
+    if (left == 3) last(u + 2, xa);
   }
-}
+};
 
-template <int VEC, int LG>
-__global__ __launch_bounds__(kSpmmBlock) void k_spmm_hyb(SpmmArgs a) {
-  int64_t group;
-  int tile;
-  decode_block(a.map_mode, a.map_param, a.n_tiles, &group, &tile);
-  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const int64_t item = group * kWavesPerBlock + wave;
-  if (item >= a.n_items) return;
-  const WorkItem it = a.items[item];
-  const int lane = threadIdx.x & 63;
-  const int f0 = tile * (LG * VEC) + (lane & (LG - 1)) * VEC;
-  walk_item<VEC, LG, false>(a.cols, a.vals, a.row_ids, a.X, a.Y, a.feat, it.slot0, it.row0, (int)(it.meta & 63u),
-                            (int)(it.meta >> 6), lane, f0, f0 < a.feat);
+template <int VEC, int LG, bool IDX32>
+__global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
+  using S = Shape<VEC, LG>;
+  using W = HybWalker<VEC, LG, IDX32>;
+  extern __shared__ float smem[];  // [row_block][kTile] tile of Y, then the waves' chunk rings
+  float* tile = smem;
+  int64_t rb;
+  int tile_id;
+  decode_block(a.map_mode, a.map_param, a.n_tiles, &rb, &tile_id);
+  if (rb >= a.n_row_blocks) return;
+  const int row_block = 1 << a.log2_row_block;
+  const int rb_first = (int)(rb << a.log2_row_block);
+  const int rows_here = min(row_block, a.n_rows - rb_first);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int fl = lane & (LG - 1);
+  const int f0 = tile_id * S::kTile + fl * VEC;
+  const bool f_active = f0 < a.feat;
+  int* ring = reinterpret_cast<int*>(smem + row_block * S::kTile) + wave * (W::kRing * W::kStageInts);
+
+  for (int i = tid; i < rows_here * S::kTile; i += kHybBlock) tile[i] = 0.f;
+  __syncthreads();
+
+  const int64_t c0 = a.rb_chunk_ptr[rb];
+  const int n_list = (int)(a.rb_chunk_ptr[rb + 1] - c0);
+  // this wave's chunks: turns wave, wave + kHybWaves, ... of kChunksPerTurn chunks each
+  const int n_turns = (n_list + kChunksPerTurn - 1) / kChunksPerTurn;
+  int my_turns = n_turns > wave ? (n_turns - wave + kHybWaves - 1) / kHybWaves : 0;
+  int my_chunks = my_turns * kChunksPerTurn;
+  if (my_turns > 0 && (n_turns - 1) % kHybWaves == wave) my_chunks -= n_turns * kChunksPerTurn - n_list;
+
+  const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
+  W wk{a, a.chunks + c0, my_chunks, wave, lane, lane / LG, ring, (unsigned)a.feat * 4u, (unsigned)f_read * 4u,
+       LdsSink<VEC, LG>{tile, rb_first, fl, f_active}, {}};
+  wk.run();
+  __syncthreads();
+
+  // write the tile: a lane group per row, one 128-byte line per group
+  const int g = tid / LG;
+  for (int r = g; r < rows_here; r += kHybBlock / LG) {
+    if (!f_active) continue;
+    float out[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) out[e] = tile[lds_index<VEC, LG>(r, fl, e)];
+    float* y = a.Y + (size_t)(rb_first + r) * (size_t)a.feat + f0;
+    if (a.accumulate) {
+      float old[VEC];
+      load_vec<VEC>(old, y);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) out[e] += old[e];
+    }
+    store_vec<VEC>(y, out);
+  }
 }
 
 struct CsrArgs {
@@ -206,32 +491,35 @@ struct CsrArgs {
   int32_t map_param;
 };
 
+constexpr int kCsrWaves = 4;
+
 // no-hyb: one wavefront per (row, feature tile); the row is walked whole
 template <int VEC, int LG>
-__global__ __launch_bounds__(kSpmmBlock) void k_spmm_csr(CsrArgs a) {
-  int64_t group;
-  int tile;
-  decode_block(a.map_mode, a.map_param, a.n_tiles, &group, &tile);
+__global__ __launch_bounds__(64 * kCsrWaves) void k_spmm_csr(CsrArgs a) {
+  using S = Shape<VEC, LG>;
+  int64_t unit;
+  int tile_id;
+  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const int64_t row = group * kWavesPerBlock + wave;
+  const int64_t row = unit * kCsrWaves + wave;
   if (row >= a.n_rows) return;
   const int begin = a.indptr[row], end = a.indptr[row + 1];
   const int lane = threadIdx.x & 63;
-  const int f0 = tile * (LG * VEC) + (lane & (LG - 1)) * VEC;
-  walk_item<VEC, LG, true>(a.indices, a.values, nullptr, a.X, a.Y, a.feat, begin, (int)row, kRemLog2W, end - begin,
-                           lane, f0, f0 < a.feat);
-}
-
-__global__ void k_fill_zero_f4(float4* p, int64_t n4) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  int64_t step = (int64_t)gridDim.x * blockDim.x;
-  for (; i < n4; i += step) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-}
-
-__global__ void k_fill_zero_f1(float* p, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  int64_t step = (int64_t)gridDim.x * blockDim.x;
-  for (; i < n; i += step) p[i] = 0.f;
+  const int f0 = tile_id * S::kTile + (lane & (LG - 1)) * VEC;
+  const bool f_active = f0 < a.feat;
+  float* y = a.Y + (size_t)row * (size_t)a.feat + f0;
+  if (end == begin) {  // empty row
+    if (f_active && lane < LG) {
+      float zero[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) zero[e] = 0.f;
+      store_vec<VEC>(y, zero);
+    }
+    return;
+  }
+  DirectSink<VEC, LG> sink{y, f_active};
+  walk_slots<VEC, LG, false>(a.indices + begin, a.values + begin, nullptr, a.X + f0, a.feat, kRowLog2W, end - begin,
+                             lane, f_active, sink);
 }
 
 // launch geometry shared by both SpMM entry points
@@ -247,32 +535,39 @@ bool plan(int64_t n_units, int feat, const void* X, const void* Y, Geometry* g) 
   else { g->vec = 1; g->lg = 32; }
   int tf = g->vec * g->lg;
   g->n_tiles = (feat + tf - 1) / tf;
-  int64_t groups = (n_units + kWavesPerBlock - 1) / kWavesPerBlock;
   if (g->n_tiles % 8 == 0) {
     g->map_mode = kMapTilesPerXcd; g->map_param = g->n_tiles / 8;
-    g->grid = groups * g->n_tiles;
+    g->grid = n_units * g->n_tiles;
   } else if (8 % g->n_tiles == 0) {
     g->map_mode = kMapXcdsPerTile; g->map_param = 8 / g->n_tiles;
-    g->grid = 8 * ((groups + g->map_param - 1) / g->map_param);
+    g->grid = 8 * ((n_units + g->map_param - 1) / g->map_param);
   } else {
     g->map_mode = kMapPlain; g->map_param = 0;
-    g->grid = groups * g->n_tiles;
+    g->grid = n_units * g->n_tiles;
   }
   return g->grid <= 0x7FFFFFFF;
-}
-
-template <typename Args, typename K4_8, typename K4_4, typename K2, typename K1>
-void launch_by_shape(const Geometry& g, hipStream_t stream, const Args& a, K4_8 k48, K4_4 k44, K2 k2, K1 k1) {
-  dim3 grid((unsigned)g.grid), block(kSpmmBlock);
-  if (g.vec == 4 && g.lg == 8) hipLaunchKernelGGL(k48, grid, block, 0, stream, a);
-  else if (g.vec == 4) hipLaunchKernelGGL(k44, grid, block, 0, stream, a);
-  else if (g.vec == 2) hipLaunchKernelGGL(k2, grid, block, 0, stream, a);
-  else hipLaunchKernelGGL(k1, grid, block, 0, stream, a);
 }
 
 bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
   return a0 < b0 + nb && b0 < a0 + na;
+}
+
+template <int VEC, int LG, bool IDX32>
+void launch_hyb_one(const Geometry& g, size_t lds_bytes, hipStream_t stream, const SpmmArgs& a) {
+  static bool raised = false;  // row blocks of 1024 rows need more than the default 64 KB of dynamic LDS
+  if (!raised && lds_bytes > 48 * 1024) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_hyb<VEC, LG, IDX32>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
+    raised = true;
+  }
+  hipLaunchKernelGGL((k_spmm_hyb<VEC, LG, IDX32>), dim3((unsigned)g.grid), dim3(kHybBlock), lds_bytes, stream, a);
+}
+
+template <int VEC, int LG>
+void launch_hyb(const Geometry& g, size_t lds_bytes, hipStream_t stream, const SpmmArgs& a, bool idx32) {
+  if (idx32) launch_hyb_one<VEC, LG, true>(g, lds_bytes, stream, a);
+  else launch_hyb_one<VEC, LG, false>(g, lds_bytes, stream, a);
 }
 
 }  // namespace
@@ -288,24 +583,22 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
   hipStream_t stream = (hipStream_t)stream_;
   if (h->n_rows == 0) return SPTIR_OK;
 
-  // Y starts at zero (init block of the SpMM script, appendix A); a fill kernel
-  // rather than a memset so that the call can be captured into a HIP graph
-  const int64_t n_y = (int64_t)h->n_rows * feat;
-  if (((uintptr_t)Y & 15) == 0 && n_y % 4 == 0) {
-    int64_t n4 = n_y / 4;
-    unsigned blocks = (unsigned)((n4 + 255) / 256 < 8192 ? (n4 + 255) / 256 : 8192);
-    hipLaunchKernelGGL(k_fill_zero_f4, dim3(blocks), dim3(256), 0, stream, (float4*)Y, n4);
-  } else {
-    unsigned blocks = (unsigned)((n_y + 255) / 256 < 8192 ? (n_y + 255) / 256 : 8192);
-    hipLaunchKernelGGL(k_fill_zero_f1, dim3(blocks), dim3(256), 0, stream, Y, n_y);
-  }
-  if (h->n_items > 0) {
-    Geometry g;
-    if (!plan(h->n_items, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
-    SpmmArgs a;
-    a.items = h->items; a.n_items = h->n_items; a.row_ids = h->row_ids; a.cols = h->cols; a.vals = h->vals;
-    a.X = X; a.Y = Y; a.feat = feat; a.n_tiles = g.n_tiles; a.map_mode = g.map_mode; a.map_param = g.map_param;
-    launch_by_shape(g, stream, a, k_spmm_hyb<4, 8>, k_spmm_hyb<4, 4>, k_spmm_hyb<2, 16>, k_spmm_hyb<1, 32>);
+  Geometry g;
+  if (!plan(h->n_row_blocks, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
+  SpmmArgs a;
+  a.chunks = h->chunks; a.row_ids = h->row_ids; a.cols = h->cols; a.vals = h->vals;
+  a.X = X; a.Y = Y; a.n_rows = h->n_rows; a.n_row_blocks = h->n_row_blocks; a.log2_row_block = h->log2_row_block;
+  a.feat = feat; a.n_tiles = g.n_tiles; a.map_mode = g.map_mode; a.map_param = g.map_param;
+  const size_t lds_bytes = sizeof(float) * ((size_t)g.vec * g.lg << h->log2_row_block) +
+                           sizeof(int) * kHybWaves * 4 * 3 * kChunkSlots;  // Y tile + the waves' chunk rings
+  const bool idx32 = h->n_cols < (1 << 24) && x_bytes < ((size_t)1 << 32);
+  for (int phase = 0; phase < h->n_phases; ++phase) {
+    a.rb_chunk_ptr = h->rb_chunk_ptr + (size_t)phase * h->n_row_blocks;
+    a.accumulate = phase > 0;
+    if (g.vec == 4 && g.lg == 8) launch_hyb<4, 8>(g, lds_bytes, stream, a, idx32);
+    else if (g.vec == 4) launch_hyb<4, 4>(g, lds_bytes, stream, a, idx32);
+    else if (g.vec == 2) launch_hyb<2, 16>(g, lds_bytes, stream, a, idx32);
+    else launch_hyb<1, 32>(g, lds_bytes, stream, a, idx32);
   }
   SPTIR_HIP(hipGetLastError());
   return SPTIR_OK;
@@ -320,12 +613,16 @@ extern "C" sptir_status_t sptir_spmm_csr(const sptir_csr_t* csr, const float* X,
   if (x_bytes && y_bytes && overlaps(X, x_bytes, Y, y_bytes)) return SPTIR_ERR_INVALID_ARG;
   if (csr->n_rows == 0) return SPTIR_OK;
   Geometry g;
-  if (!plan(csr->n_rows, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
+  if (!plan(((int64_t)csr->n_rows + kCsrWaves - 1) / kCsrWaves, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
   CsrArgs a;
   a.indptr = csr->indptr; a.indices = csr->indices; a.values = csr->values; a.X = X; a.Y = Y;
   a.n_rows = csr->n_rows; a.feat = feat; a.n_tiles = g.n_tiles; a.map_mode = g.map_mode; a.map_param = g.map_param;
-  launch_by_shape(g, (hipStream_t)stream_, a, k_spmm_csr<4, 8>, k_spmm_csr<4, 4>, k_spmm_csr<2, 16>,
-                  k_spmm_csr<1, 32>);
+  dim3 grid((unsigned)g.grid), block(64 * kCsrWaves);
+  hipStream_t stream = (hipStream_t)stream_;
+  if (g.vec == 4 && g.lg == 8) hipLaunchKernelGGL((k_spmm_csr<4, 8>), grid, block, 0, stream, a);
+  else if (g.vec == 4) hipLaunchKernelGGL((k_spmm_csr<4, 4>), grid, block, 0, stream, a);
+  else if (g.vec == 2) hipLaunchKernelGGL((k_spmm_csr<2, 16>), grid, block, 0, stream, a);
+  else hipLaunchKernelGGL((k_spmm_csr<1, 32>), grid, block, 0, stream, a);
   SPTIR_HIP(hipGetLastError());
   return SPTIR_OK;
 }

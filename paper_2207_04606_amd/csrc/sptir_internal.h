@@ -9,19 +9,22 @@
 
 namespace sptir {
 
-// One wavefront's share of an SpMM launch: `count` consecutive stored slots of
-// the fused (cols, vals) arrays starting at `slot0`.  Slot o of the item
-// belongs to row_ids[row0 + (o >> log2w)]; for an ELL bucket log2w is the
-// bucket's i (section 4.2.1: width 2^i), for a piece of the CSR remainder it
-// is 31 so that the whole item is one row.
-struct WorkItem {
+// The SpMM kernel walks the stored slots in chunks of kChunkSlots consecutive
+// slots of the fused (cols, vals) arrays, starting at `slot0`.  Slot o of the
+// chunk belongs to row_ids[row0 + (o >> log2w)]: for an ELL bucket narrower
+// than a chunk log2w is the bucket's i (section 4.2.1: width 2^i, so a chunk
+// packs 64 / 2^i whole rows); a chunk cut from a wider row or from a piece of
+// the CSR remainder holds one row only and carries log2w = kRowLog2W.
+struct Chunk {
   int64_t slot0;
   int32_t row0;
-  uint32_t meta;  // bits 0..5 log2w, bits 6..31 count
+  uint32_t meta;  // bits 0..5 log2w, bits 6..12 count (1..64), bit 13: hand the row's partial sum over after this chunk
 };
-static_assert(sizeof(WorkItem) == 16, "WorkItem must stay 16 bytes");
+static_assert(sizeof(Chunk) == 16, "Chunk must stay 16 bytes");
 
-constexpr int kRemLog2W = 31;
+constexpr int kChunkSlots = 64;
+constexpr int kRowLog2W = 31;
+constexpr int kChunksPerTurn = 8;  // consecutive chunks one wavefront takes before the next wavefront's turn
 constexpr int kBuildBlock = 256;  // rows per workgroup in the builder kernels
 
 }  // namespace sptir
@@ -40,9 +43,14 @@ struct sptir_hyb {
   int32_t* row_ids;          // device [R+M]
   int32_t* cols;             // device [S+T]
   float* vals;               // device [S+T]
-  sptir::WorkItem* items;    // device [n_items]
-  int64_t n_items;
-  int32_t item_slots;
+  int32_t* row_len;          // device [R+M], real length of every ELL row / remainder piece
+  sptir::Chunk* chunks;      // device [n_chunks], grouped by (phase, row block)
+  int64_t* rb_chunk_ptr;     // device [n_phases * n_row_blocks + 1], first chunk of each group
+  int64_t n_chunks;
+  int32_t log2_row_block;    // rows of Y one workgroup accumulates in LDS (power of two)
+  int32_t n_row_blocks;
+  int32_t parts_per_phase;   // column partitions swept by one SpMM launch
+  int32_t n_phases;
   size_t device_bytes;
   sptir_alloc_fn alloc;
   sptir_free_fn free_;
