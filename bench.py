@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""SpMM throughput of the hyb(c,k) path on one MI355X.
+
+One "step" is one sptir_spmm call (Y = A X on the decomposed matrix, every
+launch it enqueues) with A, X and Y resident in HBM.  The format conversion
+(sptir_hyb_build) is pre-processing of a stationary matrix, as in the paper,
+and is timed separately.  The workload is the largest graph of the benchmark
+set (232,965 rows, ~114.6M non-zeros, hyb(16, 11)) at the metric's feature
+size 128; the same graph at its as-written feature size 256 and the four
+smaller configurations are reported in extra keys of the same JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+GATHER_PEAK_GBS = 39300.0  # 256 CUs x 64 B/clk x 2.4 GHz vector-memory return path (measured ~38.7 TB/s)
+
+
+def bytes_min(nnz, n_rows, n_cols, feat):
+    """Minimal-traffic byte model: every true non-zero's column and value once, X once, Y once."""
+    return 8.0 * nnz + 4.0 * n_cols * feat + 4.0 * n_rows * feat
+
+
+def time_spmm(sptir, torch, hyb, X, Y, steps, warmup):
+    for _ in range(warmup):
+        sptir.sptir_spmm(hyb, X, Y)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        sptir.sptir_spmm(hyb, X, Y)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    event_ms = e0.elapsed_time(e1) / steps
+    return wall_ms, event_ms
+
+
+def time_cold(sptir, torch, hyb, X, Y, reps, scratch):
+    """Per-step time with the caches flushed before every step (outside the timed region)."""
+    times = []
+    for _ in range(reps):
+        scratch.add_(1.0)            # 1 GiB read + write: evicts L2 and the 256 MB Infinity Cache
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        sptir.sptir_spmm(hyb, X, Y)
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1))
+    times.sort()
+    return times[len(times) // 2]
+
+
+def upload(torch, w):
+    dev = torch.device("cuda:0")
+    return (torch.from_numpy(w.indptr).to(dev), torch.from_numpy(w.indices).to(dev),
+            torch.from_numpy(w.values).to(dev))
+
+
+def read_traffic(key):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if one covers `key`."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == key:
+            return float(parts[1])
+    return None
+
+
+def cpu_baseline(oracle, np, w, X_host, feat, budget_s=12.0):
+    """The fp64 oracle, untuned, on a bounded sample of rows of the same workload."""
+    rng = np.random.default_rng(1)
+    rows = rng.permutation(w.n_rows).astype(np.int32)
+    deg = np.diff(w.indptr)
+    probe = rows[:2000]
+    t0 = time.perf_counter()
+    oracle.spmm_csr_rows(probe, w.indptr, w.indices, w.values, X_host)
+    dt = max(time.perf_counter() - t0, 1e-4)
+    rate = deg[probe].sum() / dt                       # non-zeros per second
+    want_nnz = rate * budget_s
+    csum = np.cumsum(deg[rows])
+    n_sel = int(min(w.n_rows, max(2000, np.searchsorted(csum, want_nnz))))
+    sel = rows[:n_sel]
+    t0 = time.perf_counter()
+    Yr, Sr = oracle.spmm_csr_rows(sel, w.indptr, w.indices, w.values, X_host)
+    dt = time.perf_counter() - t0
+    nnz_sel = int(deg[sel].sum())
+    return dict(value=2.0 * nnz_sel * feat / dt / 1e9, unit="GFLOP/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"{n_sel} random rows ({nnz_sel} non-zeros) of the same graph and X, feat={feat}, "
+                       f"{dt:.1f} s, fp64, OpenMP over rows"), sel, Yr, Sr
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-extras", action="store_true", help="only the headline workload (for profiling runs)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM bytes) to scale profiler byte counters")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (every box has one); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2207_04606_amd as sptir
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    sptir.load_library()   # no fallback: raises if the HIP library is not built
+    dev = torch.device("cuda:0")
+
+    if args.copy_calibration:
+        src = torch.ones(256 * 1024 * 1024, device=dev)   # 1 GiB written by the fill kernel
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)                      # 1 GiB read + 1 GiB written by one elementwise kernel
+        torch.cuda.synchronize()
+        del src, dst
+
+    # ---------------------------------------------------------------- headline
+    w = workloads.make_config("social")
+    indptr, indices, values = upload(torch, w)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    hyb = sptir.sptir_hyb_build(w.n_rows, w.n_cols, indptr, indices, values, w.n_col_parts, w.max_bucket_log2)
+    torch.cuda.synchronize()
+    build_first_ms = (time.perf_counter() - t0) * 1e3
+    t0 = time.perf_counter()
+    hyb2 = sptir.sptir_hyb_build(w.n_rows, w.n_cols, indptr, indices, values, w.n_col_parts, w.max_bucket_log2)
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) * 1e3
+    hyb2.destroy()
+    info = sptir.sptir_hyb_info(hyb)
+
+    results = {}
+    X_host_128 = None
+    for feat in (128, 256):
+        if feat == 256 and args.no_extras:
+            continue
+        if feat == w.feat:
+            Xh = w.X
+        else:
+            Xh = np.random.Generator(np.random.PCG64(7)).standard_normal((w.n_cols, feat), dtype=np.float32)
+        if feat == 128:
+            X_host_128 = Xh
+        X = torch.from_numpy(Xh).to(dev)
+        Y = torch.empty(w.n_rows, feat, device=dev)
+        wall_ms, event_ms = time_spmm(sptir, torch, hyb, X, Y, args.steps, args.warmup)
+        flops = 2.0 * w.nnz * feat
+        bmin = bytes_min(w.nnz, w.n_rows, w.n_cols, feat)
+        results[feat] = dict(wall_ms=wall_ms, event_ms=event_ms, gflops=flops / wall_ms / 1e6,
+                             bmin_gbs=bmin / event_ms / 1e6, bmin=bmin,
+                             gather_gbs=(info["n_ell_slots"] + info["n_rem_nnz"]) * feat * 4.0 / event_ms / 1e6,
+                             Y=Y if feat == 128 else None)
+        if feat == 256:
+            del X, Y
+    head = results[128]
+
+    out = {
+        "metric": "SpMM GFLOP/s and achieved HBM GB/s (% of peak) at feat=128, 1 MI355X",
+        "value": round(head["gflops"], 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["wall_ms"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "largest graph of the set (social-like: 232,965 rows, %d non-zeros, power-law "
+                               "degrees, values 1/deg) decomposed as hyb(c=16, k=11), X 232,965 x 128 fp32 N(0,1); "
+                               "Y = A X per step" % w.nnz,
+                   "n_rows": w.n_rows, "nnz": w.nnz, "feat": 128, "n_col_parts": w.n_col_parts,
+                   "max_bucket_log2": w.max_bucket_log2, "stored_slots": info["n_ell_slots"] + info["n_rem_nnz"],
+                   "pad_slots": info["n_pad_slots"], "kernel_launches_per_step": info["n_phases"],
+                   "row_block": info["row_block"]},
+        "hbm_gbs_min_model": round(head["bmin_gbs"], 1),
+        "hbm_pct_of_peak": round(100.0 * head["bmin_gbs"] / HBM_PEAK_GBS, 2),
+        "hyb_build_ms": round(build_ms, 3), "hyb_build_first_call_ms": round(build_first_ms, 3),
+    }
+    # dominant kernel: k_spmm_hyb, launched once per phase; events bracket all launches of a step
+    per_launch_ms = head["event_ms"] / info["n_phases"]
+    per_launch_bytes = head["bmin"] / info["n_phases"]
+    out["roofline"] = {
+        "bound": "hbm", "achieved": round(per_launch_bytes / per_launch_ms / 1e6, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(per_launch_bytes / per_launch_ms / 1e6 / HBM_PEAK_GBS, 4),
+        "traffic": read_traffic("social_feat128"),
+        "kernel": "k_spmm_hyb<4, 8, true>", "launches_per_step": info["n_phases"],
+        "avg_launch_ms": round(per_launch_ms, 4), "algorithmic_bytes_per_launch": per_launch_bytes,
+        # the path is a cache-served gather, not an HBM stream: each stored slot pulls feat*4 bytes of X
+        # through the vector-memory return path, whose peak is 64 B/clk/CU
+        "binding_roof": {"name": "vector-memory gather (L2 -> VGPR)", "achieved_gbs": round(head["gather_gbs"], 1),
+                         "peak_gbs": GATHER_PEAK_GBS, "frac": round(head["gather_gbs"] / GATHER_PEAK_GBS, 4)},
+    }
+
+    # ------------------------------------------------- CPU oracle beside it
+    if not args.no_cpu:
+        import oracle
+        base, sel, Yr, Sr = cpu_baseline(oracle, np, w, X_host_128, 128)
+        out["cpu_baseline"] = base
+        Yg = head["Y"][torch.from_numpy(sel.astype(np.int64)).to(dev)].cpu().numpy().astype(np.float64)
+        nz = Sr > 0
+        out["max_normalised_error_vs_oracle"] = float((np.abs(Yg - Yr)[nz] / Sr[nz]).max())
+    head["Y"] = None
+
+    if not args.no_extras:
+        r256 = results[256]
+        out["as_written_feat256"] = {"gflops": round(r256["gflops"], 1), "ms_per_step": round(r256["wall_ms"], 4),
+                                     "hbm_gbs_min_model": round(r256["bmin_gbs"], 1),
+                                     "gather_gbs": round(r256["gather_gbs"], 1)}
+        scratch = torch.zeros(256 * 1024 * 1024, device=dev)
+        X = torch.from_numpy(X_host_128).to(dev)
+        Y = torch.empty(w.n_rows, 128, device=dev)
+        out["cold_ms_per_step"] = round(time_cold(sptir, torch, hyb, X, Y, 10, scratch), 4)
+        del X, Y
+        hyb.destroy()
+        del indptr, indices, values
+        others = []
+        for name in ("tiny", "small", "medium", "protein"):
+            wc = workloads.make_config(name)
+            ip, ix, va = upload(torch, wc)
+            t0 = time.perf_counter()
+            hc = sptir.sptir_hyb_build(wc.n_rows, wc.n_cols, ip, ix, va, wc.n_col_parts, wc.max_bucket_log2)
+            torch.cuda.synchronize()
+            b_ms = (time.perf_counter() - t0) * 1e3
+            X = torch.from_numpy(wc.X).to(dev)
+            Y = torch.empty(wc.n_rows, wc.feat, device=dev)
+            wall_ms, event_ms = time_spmm(sptir, torch, hc, X, Y, 100, 10)
+            cold = time_cold(sptir, torch, hc, X, Y, 10, scratch)
+            bm = bytes_min(wc.nnz, wc.n_rows, wc.n_cols, wc.feat)
+            others.append({"config": name, "nnz": wc.nnz, "feat": wc.feat,
+                           "gflops": round(2.0 * wc.nnz * wc.feat / wall_ms / 1e6, 1),
+                           "ms_per_step": round(wall_ms, 4), "cold_ms_per_step": round(cold, 4),
+                           "hbm_gbs_min_model_cold": round(bm / cold / 1e6, 1), "hyb_build_ms": round(b_ms, 3)})
+            hc.destroy()
+        out["other_configs"] = others
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
