@@ -407,6 +407,37 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
   }
 }
 
+// ------------------------------------------------------------ chunk stream
+// What the SpMM kernel actually reads: the chunks re-tiled into fixed records,
+// in list order, so that the address of every record follows from its list
+// position alone (no dependent descriptor load inside the gather loop):
+//   stream[q*192 +   0.. 63]  column ids   (slots past `count` repeat the last real column)
+//   stream[q*192 +  64..127]  values       (slots past `count` hold +0.0f)
+//   stream[q*192 + 128..191]  per slot: row relative to the first row of the row block in bits 0..15,
+//                             the chunk's log2w in bits 16..21, its hand-over flag in bit 22;
+//                             slots past `count` hold -1
+// One wavefront per chunk; reads the canonical arrays through the descriptor.
+__global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chunk* __restrict__ chunks,
+                                                     const int32_t* __restrict__ row_ids,
+                                                     const int32_t* __restrict__ cols, const float* __restrict__ vals,
+                                                     int32_t log2_rb, int32_t* stream) {
+  int64_t q = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (q >= n_chunks) return;
+  int lane = threadIdx.x & 63;
+  const Chunk ck = chunks[q];
+  const int lw = (int)(ck.meta & 63u), count = (int)((ck.meta >> 6) & 127u);
+  const int hand_over = (int)((ck.meta >> 13) & 1u);
+  const int o = lane < count ? lane : count - 1;
+  int32_t col = cols[ck.slot0 + o];
+  float val = vals[ck.slot0 + o];
+  int32_t rid = row_ids[ck.row0 + (o >> lw)];
+  int32_t* rec = stream + q * (3 * kChunkSlots);
+  rec[lane] = col;
+  rec[kChunkSlots + lane] = lane < count ? __float_as_int(val) : 0;
+  rec[2 * kChunkSlots + lane] =
+      lane < count ? ((rid & ((1 << log2_rb) - 1)) | (lw << 16) | (hand_over << 22)) : -1;
+}
+
 // --------------------------------------------------------------- host helpers
 struct Blob {  // bump allocator over one device allocation
   char* base = nullptr;
@@ -494,6 +525,7 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
   tmp.base = (char*)alloc(tmp.size, actx, stream);
   if (!tmp.base) return SPTIR_ERR_ALLOC;
   Blob tmp2;
+  void* tmp_chunks = nullptr;
 
   sptir_hyb* h = new (std::nothrow) sptir_hyb();
   if (!h) { free_(tmp.base, actx); return SPTIR_ERR_ALLOC; }
@@ -661,14 +693,23 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
     h->n_chunks = n_chunks;
     {
       size_t bytes = sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1);
-      h->chunks = (Chunk*)alloc(bytes, actx, stream);
-      if (!h->chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
+      tmp_chunks = alloc(bytes, actx, stream);  // descriptors are only needed until the stream is packed
+      if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
+      bytes = sizeof(int32_t) * 3 * kChunkSlots * (size_t)(n_chunks ? n_chunks : 1);
+      h->stream = (int32_t*)alloc(bytes, actx, stream);
+      if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += bytes;
     }
     if (n_cells > 0)
       hipLaunchKernelGGL(k_cell_fill_chunks, dim3((unsigned)((n_cells + 255) / 256)), dim3(256), 0, stream, cs,
                          n_cells, d_bounds, d_cell_chunks, h->row_len, h->bucket_row_ptr, h->bucket_slot_ptr,
-                         h->rem_ptr, h->S, h->chunks, h->rb_chunk_ptr);
+                         h->rem_ptr, h->S, (Chunk*)tmp_chunks, h->rb_chunk_ptr);
+    if (n_chunks > 0) {
+      int64_t blocks = (n_chunks + 3) / 4;
+      if (blocks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
+      hipLaunchKernelGGL(k_pack_stream, dim3((unsigned)blocks), dim3(256), 0, stream, (int64_t)n_chunks,
+                         (const Chunk*)tmp_chunks, h->row_ids, h->cols, h->vals, cs.log2_rb, h->stream);
+    }
     {
       int64_t total = n_chunks;
       BUILD_HIP(hipMemcpyAsync(h->rb_chunk_ptr + (size_t)cs.n_phases * cs.n_rb, &total, sizeof(int64_t),
@@ -679,6 +720,7 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
   }
   free_(tmp.base, actx);
   if (tmp2.base) free_(tmp2.base, actx);
+  if (tmp_chunks) free_(tmp_chunks, actx);
   *out = h;
   return SPTIR_OK;
 
@@ -686,6 +728,7 @@ fail:
   (void)hipStreamSynchronize(stream);
   free_(tmp.base, actx);
   if (tmp2.base) free_(tmp2.base, actx);
+  if (tmp_chunks) free_(tmp_chunks, actx);
   sptir_hyb_destroy(h);
   return st;
 #undef BUILD_HIP

@@ -73,21 +73,44 @@ __device__ __forceinline__ int lds_index(int r, int fl, int e) {
   return r * T + ((e * LG + fl + r * LG) & (T - 1));
 }
 
-// Adds a finished row sum into the workgroup's Y tile.
+// Adds a finished row sum into the workgroup's Y tile; r is the row relative to the row block.
 template <int VEC, int LG>
 struct LdsSink {
   float* tile;     // [row_block][kTile] in LDS
-  int rb_first;    // first row of the row block
   int fl;
   bool f_active;
-  __device__ __forceinline__ void operator()(int row_id, bool valid, const float (&acc)[VEC]) const {
+  __device__ __forceinline__ void operator()(int r, bool valid, const float (&acc)[VEC]) const {
     if (valid && f_active) {
-      int r = row_id - rb_first;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) atomicAdd(&tile[lds_index<VEC, LG>(r, fl, e)], acc[e]);
     }
   }
 };
+
+// acc[i] += acc of the lane DIST lanes above (only lanes whose partner exists need the result)
+template <int DIST, int VEC>
+__device__ __forceinline__ void add_from_above(float (&acc)[VEC]) {
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    float other;
+    if constexpr (DIST == 8)        // same 16-lane row: DPP row shift left by 8
+      other = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(acc[e]), 0x108, 0xF, 0xF, true));
+    else if constexpr (DIST == 16)  // neighbouring rows of the same half: swizzle lane ^ 16
+      other = __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(acc[e]), 0x401F));
+    else
+      other = __shfl_down(acc[e], DIST, 64);
+    acc[e] += other;
+  }
+}
+
+// sums the partial sums of `groups` (1, 2, 4, ... kGroups) neighbouring lane groups into the first of them
+template <int VEC, int LG>
+__device__ __forceinline__ void sum_groups(float (&acc)[VEC], int groups) {
+  if (groups >= 2) add_from_above<LG, VEC>(acc);
+  if constexpr (LG <= 16) { if (groups >= 4) add_from_above<2 * LG, VEC>(acc); }
+  if constexpr (LG <= 8) { if (groups >= 8) add_from_above<4 * LG, VEC>(acc); }
+  if constexpr (LG <= 4) { if (groups >= 16) add_from_above<8 * LG, VEC>(acc); }
+}
 
 // Stores a finished row straight to Y (a row owned by exactly one wavefront).
 template <int VEC, int LG>
@@ -223,11 +246,8 @@ __device__ __forceinline__ void decode_block(int map_mode, int map_param, int n_
 }
 
 struct SpmmArgs {
-  const Chunk* chunks;
+  const int32_t* stream;        // chunk records: [cols | vals | local rows] x 64
   const int64_t* rb_chunk_ptr;  // this phase's [n_row_blocks + 1]
-  const int32_t* row_ids;
-  const int32_t* cols;
-  const float* vals;
   const float* X;
   float* Y;
   int32_t n_rows;
@@ -240,46 +260,44 @@ struct SpmmArgs {
   int32_t accumulate;  // 0: Y tile is overwritten, 1: added to (a later phase)
 };
 
-
 constexpr int kHybWaves = 4;
 constexpr int kHybBlock = 64 * kHybWaves;
 
 // One wavefront's walk over its share of a row block's chunk list.
 //
 // The unit of the pipeline is a "step": kChunk = kGroups*kSteps slots of a
-// 64-slot chunk (the whole chunk when a lane group is 8 lanes wide).  A chunk's
-// (column, value, row id) triples are fetched one per lane, four chunks ahead,
-// and parked in a small per-wave LDS ring; from there every lane group reads
-// the kSteps columns / values it needs with wide LDS reads (all lanes of a
-// group read the same address, which LDS broadcasts).  While step u is
+// 64-slot chunk (the whole chunk when a lane group is 8 lanes wide).  A chunk
+// is a fixed 768-byte record of the stream whose address follows from its list
+// position, so nothing in the loop waits for a descriptor.  Its (column,
+// value, row) triples are requested one per lane, six chunks ahead, and parked
+// three steps later in a small per-wave LDS ring; from there every lane group
+// reads the kSteps columns / values it needs with wide LDS reads (all lanes of
+// a group read the same address, which LDS broadcasts).  While step u is
 // multiplied, the X gathers of steps u+1 and u+2 are in flight.  The
 // steady-state loop body holds no conditional memory operation, so that the
 // compiler's wait counters stay exact; the last steps are peeled.
 //
 // The lane groups that share a row add their partial sums up with cross-lane
-// reads; one of them adds the row sum into the workgroup's LDS tile of Y (float
-// LDS atomics: other wavefronts may be working on the same row).
+// moves; the leading group adds the row sum into the workgroup's LDS tile of Y
+// (float LDS atomics: other wavefronts may be working on the same row).
 template <int VEC, int LG, bool IDX32>
 struct HybWalker {
   using S = Shape<VEC, LG>;
   static constexpr int UB = S::kSteps, CS = S::kChunk;
-  static constexpr int SUB = kChunkSlots / CS;  // steps per chunk descriptor
+  static constexpr int SUB = kChunkSlots / CS;  // steps per chunk
   static constexpr int LOG2SUB = ilog2(SUB);
   static constexpr int kRing = 4;               // chunks parked in LDS per wave
-  static constexpr int kStageInts = 3 * kChunkSlots;
+  static constexpr int kRecord = 3 * kChunkSlots;
 
-  struct Fetched {  // one chunk in flight from memory: a triple per lane, the chunk's facts
-    int col;
-    float val;
-    int rid;
-    int meta;
+  struct Fetched {  // one chunk on its way from memory: a (column, value, row word) triple per lane
+    int col, val, row;
   };
 
   const SpmmArgs& a;
-  const Chunk* list;  // chunk list of this (phase, row block)
-  int n_chunks;       // chunks of this wave
+  const int32_t* records;  // stream of this (phase, row block)
+  int n_chunks;            // chunks of this wave
   int wave, lane, g;
-  int* ring;          // this wave's LDS ring: kRing x [cols | vals | row ids]
+  int* ring;               // this wave's LDS ring: kRing x [cols | vals | rows]
   unsigned row_bytes, lane_bytes;  // bytes per row of X, byte offset of this lane's features
   LdsSink<VEC, LG> sink;
   float acc[VEC];
@@ -291,32 +309,50 @@ struct HybWalker {
 
   __device__ __forceinline__ void fetch(int k, Fetched& f) const {
     k = k < n_chunks ? k : n_chunks - 1;
-    const Chunk ck = list[list_pos(k)];
-    const int lw = (int)(ck.meta & 63u);
-    const int count = (int)((ck.meta >> 6) & 127u);
-    // (the arrays end in kChunkSlots spare entries, so lanes past `count` read valid memory)
-    f.col = a.cols[ck.slot0 + lane];
-    float v = a.vals[ck.slot0 + lane];
-    f.val = lane < count ? v : 0.f;
-    f.rid = a.row_ids[ck.row0 + (lane >> lw)];
-    f.meta = (int)ck.meta;
+    const int q = list_pos(k);
+    const int32_t* rec = records + (size_t)q * kRecord;
+    f.col = rec[lane];
+    f.val = rec[kChunkSlots + lane];
+    f.row = rec[2 * kChunkSlots + lane];
   }
 
-  __device__ __forceinline__ int* stage(int k) const { return ring + (k & (kRing - 1)) * kStageInts; }
+  __device__ __forceinline__ int* stage(int k) const { return ring + (k & (kRing - 1)) * kRecord; }
 
-  __device__ __forceinline__ void park(int k, const Fetched& f) const {
+  // returns the chunk's facts (wave-uniform; slot 0 is always a real slot): log2w | hand-over << 6
+  __device__ __forceinline__ int park(int k, const Fetched& f) const {
     int* st = stage(k);
     st[lane] = f.col;
-    st[kChunkSlots + lane] = __float_as_int(f.val);
-    st[2 * kChunkSlots + lane] = f.rid;
+    st[kChunkSlots + lane] = f.val;
+    st[2 * kChunkSlots + lane] = f.row < 0 ? -1 : (f.row & 0xFFFF);
+    return __builtin_amdgcn_readfirstlane(f.row) >> 16;
   }
 
-  // gathers of step u: the UB rows of X this lane group multiplies in that step
-  __device__ __forceinline__ void issue(int u, float (&x)[UB][VEC]) const {
-    const int* st = stage(u >> LOG2SUB) + (u & (SUB - 1)) * CS + g * UB;
-    int c[UB];
+  // first slot of this lane group in step u, as an offset into the chunk's record
+  __device__ __forceinline__ int first_slot(int u) const { return (u & (SUB - 1)) * CS + g * UB; }
+
+  // UB consecutive ints of the ring (UB is 4 or 8; the offset is a multiple of UB): 16-byte LDS reads
+  __device__ __forceinline__ void read_ints(const int* p, int (&out)[UB]) const {
+    const int4* p4 = reinterpret_cast<const int4*>(__builtin_assume_aligned(p, 16));
 #pragma unroll
-    for (int j = 0; j < UB; ++j) c[j] = st[j];
+    for (int j = 0; j < UB; j += 4) {
+      int4 t = p4[j / 4];
+      out[j] = t.x; out[j + 1] = t.y; out[j + 2] = t.z; out[j + 3] = t.w;
+    }
+  }
+
+  __device__ __forceinline__ void read_cols(int u, int (&c)[UB]) const {
+    read_ints(stage(u >> LOG2SUB) + first_slot(u), c);
+  }
+
+  __device__ __forceinline__ void read_vals(int u, float (&v)[UB]) const {
+    int t[UB];
+    read_ints(stage(u >> LOG2SUB) + kChunkSlots + first_slot(u), t);
+#pragma unroll
+    for (int j = 0; j < UB; ++j) v[j] = __int_as_float(t[j]);
+  }
+
+  // gathers: the UB rows of X this lane group multiplies in one step
+  __device__ __forceinline__ void issue(const int (&c)[UB], float (&x)[UB][VEC]) const {
 #pragma unroll
     for (int j = 0; j < UB; ++j) {
       if constexpr (IDX32) {
@@ -330,27 +366,22 @@ struct HybWalker {
     }
   }
 
-  __device__ __forceinline__ void consume(int u, int meta, const float (&x)[UB][VEC]) {
-    const int lw = meta & 63, count = (meta >> 6) & 127;
-    const bool hand_over = (meta >> 13) & 1;
+  __device__ __forceinline__ void consume(int u, int meta, const float (&v)[UB], const float (&x)[UB][VEC]) {
+    const int lw = meta & 63;
+    const bool hand_over = (meta >> 6) & 1;
     const int sub = u & (SUB - 1);
-    const int first = sub * CS + g * UB;  // this group's first slot of the chunk
-    const int* st = stage(u >> LOG2SUB);
-    float v[UB];
-#pragma unroll
-    for (int j = 0; j < UB; ++j) v[j] = __int_as_float(st[kChunkSlots + first + j]);
+    const int* rows = stage(u >> LOG2SUB) + 2 * kChunkSlots;
     if (lw < S::kLog2Steps) {
       // several rows inside the group's share: hand each one over as it ends
-      int rid[UB];
-#pragma unroll
-      for (int j = 0; j < UB; ++j) rid[j] = st[2 * kChunkSlots + first + j];
+      int r[UB];
+      read_ints(rows + first_slot(u), r);
       const int width_mask = (1 << lw) - 1;
 #pragma unroll
       for (int j = 0; j < UB; ++j) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
         if (((j + 1) & width_mask) == 0) {
-          sink(rid[j], first + j < count, acc);
+          sink(r[j], r[j] >= 0, acc);
 #pragma unroll
           for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
         }
@@ -364,17 +395,16 @@ struct HybWalker {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
     if (one_row_chunk && !(hand_over && sub == SUB - 1)) return;  // the row goes on: keep the sums in registers
-    const int groups = (one_row_chunk || lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));
     if (!one_row_chunk && lw >= S::kLog2Chunk && (((sub + 1) * CS) & ((1 << lw) - 1)) != 0) return;  // row spans steps
-    for (int d = 1; d < groups; d <<= 1) {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], d * LG, 64);
-    }
+    int groups = (one_row_chunk || lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));
+    // With 8-lane groups the two halves of the wave hand over separately (one cross-lane level saved).
+    if (LG == 8 && groups == 8) groups = 4;
+    sum_groups<VEC, LG>(acc, groups);
     const int g_first = g & ~(groups - 1);
-    // (a row cut into several chunks keeps its partial sums in registers in between,
-    //  so for a one-row chunk even groups past `count` take part; its row id sits in slot 0)
-    const int rid = st[2 * kChunkSlots + (one_row_chunk ? 0 : sub * CS + g_first * UB)];
-    sink(rid, g == g_first && (one_row_chunk || sub * CS + g_first * UB < count), acc);
+    // (a row cut into several chunks keeps its partial sums in registers in between, so for a one-row
+    //  chunk even groups past the last real slot take part; its row sits in slot 0)
+    const int r = rows[one_row_chunk ? 0 : sub * CS + g_first * UB];
+    sink(r, g == g_first && r >= 0, acc);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
   }
@@ -384,24 +414,34 @@ struct HybWalker {
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
     if (n_chunks <= 0) return;
     const int n_steps = n_chunks * SUB;
-    // chunks 0..3 are fetched at once; 0..2 are parked, 3 stays in registers for the first loop step
-    Fetched f0, f1, f2, fp;
-    fetch(0, f0); fetch(1, f1); fetch(2, f2); fetch(3, fp);
-    park(0, f0); park(1, f1); park(2, f2);
-    int m0 = f0.meta, m1 = f1.meta, m2 = f2.meta, m3 = 0;  // facts of chunks k, k+1, k+2, k+3 (k = chunk of step u)
+    // Chunks 0..5 are requested at once; 0..2 are parked right away, 3..5 stay in registers.  From then on the
+    // triples of chunk k+6 are requested while chunk k is multiplied and parked three steps later, when they
+    // have long arrived: a load that is waited for too early stalls every load queued behind it.
+    Fetched f0, f1, f2, fa, fb, fc;
+    fetch(0, f0); fetch(1, f1); fetch(2, f2); fetch(3, fa); fetch(4, fb); fetch(5, fc);
+    int m0 = park(0, f0), m1 = park(1, f1), m2 = park(2, f2), m3 = 0;  // facts of chunks k .. k+3 (k = chunk of step u)
     float xa[UB][VEC], xb[UB][VEC];
-    issue(0, xa);
-    issue(n_steps > 1 ? 1 : 0, xb);
+    {
+      int c[UB];
+      read_cols(0, c);
+      issue(c, xa);
+      read_cols(n_steps > 1 ? 1 : 0, c);
+      issue(c, xb);
+    }
     // one step; `x` holds the gathers of step u and is refilled with those of step u+2
     auto step = [&](int u, float (&x)[UB][VEC]) {
-      if (SUB == 1 || (u & (SUB - 1)) == 0) {  // first step of chunk k: chunk k+3 arrives, chunk k+4 is requested
+      float v[UB];
+      int c[UB];
+      read_vals(u, v);      // LDS reads first: their latency hides behind the bookkeeping below
+      read_cols(u + 2, c);
+      if (SUB == 1 || (u & (SUB - 1)) == 0) {  // first step of chunk k: chunk k+3 is parked, chunk k+6 requested
         const int k = u >> LOG2SUB;
-        park(k + 3, fp);
-        m3 = fp.meta;
-        fetch(k + 4, fp);
+        m3 = park(k + 3, fa);
+        fa = fb; fb = fc;
+        fetch(k + 6, fc);
       }
-      consume(u, m0, x);
-      issue(u + 2, x);
+      consume(u, m0, v, x);
+      issue(c, x);
       if (SUB == 1 || (u & (SUB - 1)) == SUB - 1) { m0 = m1; m1 = m2; m2 = m3; }
     };
     int u = 0;
@@ -412,12 +452,18 @@ struct HybWalker {
     // 1..3 steps left; the gathers of steps u and u+1 are in flight
     const int left = n_steps - u;
     auto last = [&](int uu, float (&x)[UB][VEC]) {
-      consume(uu, m0, x);
+      float v[UB];
+      read_vals(uu, v);
+      consume(uu, m0, v, x);
       if (SUB == 1 || (uu & (SUB - 1)) == SUB - 1) { m0 = m1; m1 = m2; m2 = m3; }
     };
-    if (SUB > 1 && (u & (SUB - 1)) == 0) { park((u >> LOG2SUB) + 3, fp); m3 = fp.meta; }
+    if (SUB > 1 && (u & (SUB - 1)) == 0) m3 = park((u >> LOG2SUB) + 3, fa);
     last(u, xa);
-    if (left == 3) issue(u + 2, xa);
+    if (left == 3) {
+      int c[UB];
+      read_cols(u + 2, c);
+      issue(c, xa);
+    }
     if (left >= 2) last(u + 1, xb);
     if (left == 3) last(u + 2, xa);
   }
@@ -427,7 +473,7 @@ template <int VEC, int LG, bool IDX32>
 __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   using S = Shape<VEC, LG>;
   using W = HybWalker<VEC, LG, IDX32>;
-  extern __shared__ float smem[];  // [row_block][kTile] tile of Y, then the waves' chunk rings
+  extern __shared__ __align__(16) float smem[];  // [row_block][kTile] tile of Y, then the waves' chunk rings
   float* tile = smem;
   int64_t rb;
   int tile_id;
@@ -441,7 +487,7 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   const int fl = lane & (LG - 1);
   const int f0 = tile_id * S::kTile + fl * VEC;
   const bool f_active = f0 < a.feat;
-  int* ring = reinterpret_cast<int*>(smem + row_block * S::kTile) + wave * (W::kRing * W::kStageInts);
+  int* ring = reinterpret_cast<int*>(smem + row_block * S::kTile) + wave * (W::kRing * W::kRecord);
 
   for (int i = tid; i < rows_here * S::kTile; i += kHybBlock) tile[i] = 0.f;
   __syncthreads();
@@ -455,8 +501,8 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   if (my_turns > 0 && (n_turns - 1) % kHybWaves == wave) my_chunks -= n_turns * kChunksPerTurn - n_list;
 
   const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
-  W wk{a, a.chunks + c0, my_chunks, wave, lane, lane / LG, ring, (unsigned)a.feat * 4u, (unsigned)f_read * 4u,
-       LdsSink<VEC, LG>{tile, rb_first, fl, f_active}, {}};
+  W wk{a, a.stream + (size_t)c0 * W::kRecord, my_chunks, wave, lane, lane / LG, ring,
+       (unsigned)a.feat * 4u, (unsigned)f_read * 4u, LdsSink<VEC, LG>{tile, fl, f_active}, {}};
   wk.run();
   __syncthreads();
 
@@ -586,7 +632,7 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
   Geometry g;
   if (!plan(h->n_row_blocks, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
   SpmmArgs a;
-  a.chunks = h->chunks; a.row_ids = h->row_ids; a.cols = h->cols; a.vals = h->vals;
+  a.stream = h->stream;
   a.X = X; a.Y = Y; a.n_rows = h->n_rows; a.n_row_blocks = h->n_row_blocks; a.log2_row_block = h->log2_row_block;
   a.feat = feat; a.n_tiles = g.n_tiles; a.map_mode = g.map_mode; a.map_param = g.map_param;
   const size_t lds_bytes = sizeof(float) * ((size_t)g.vec * g.lg << h->log2_row_block) +

@@ -44,7 +44,7 @@ struct sptir_hyb {
   int32_t* cols;             // device [S+T]
   float* vals;               // device [S+T]
   int32_t* row_len;          // device [R+M], real length of every ELL row / remainder piece
-  sptir::Chunk* chunks;      // device [n_chunks], grouped by (phase, row block)
+  int32_t* stream;           // device [n_chunks * 192]: the chunks as fixed records, grouped by (phase, row block)
   int64_t* rb_chunk_ptr;     // device [n_phases * n_row_blocks + 1], first chunk of each group
   int64_t n_chunks;
   int32_t log2_row_block;    // rows of Y one workgroup accumulates in LDS (power of two)
