@@ -316,17 +316,21 @@ struct CellRef {
   int32_t q_lo, q_hi;  // run of rows in row_ids
 };
 
+// Every (phase, row block) group owns ppg*nb real cells and one trailing pad cell that rounds the group's
+// chunk count up to a multiple of kChunksPerQuad (the SpMM kernel fetches chunks four at a time).
+__device__ __forceinline__ int cells_per_group(const CellShape& cs) { return cs.ppg * cs.nb + 1; }
+
 __device__ __forceinline__ bool decode_cell(const CellShape& cs, int64_t cell, const int32_t* __restrict__ bin_rb_ptr,
                                             CellRef* r) {
-  r->bin = (int)(cell % cs.nb);
-  int64_t t = cell / cs.nb;
-  int pl = (int)(t % cs.ppg);
-  t /= cs.ppg;
+  const int cpg = cells_per_group(cs);
+  int within = (int)(cell % cpg);
+  int64_t t = cell / cpg;
   r->rb = (int)(t % cs.n_rb);
   r->phase = (int)(t / cs.n_rb);
-  r->p = r->phase * cs.ppg + pl;
+  r->bin = within % cs.nb;
+  r->p = r->phase * cs.ppg + within / cs.nb;
   r->q_lo = r->q_hi = 0;
-  if (r->p >= cs.c) return false;
+  if (within == cpg - 1 || r->p >= cs.c) return false;  // pad cell, or a partition past the last one
   const int32_t* ptr = bin_rb_ptr + ((int64_t)r->p * cs.nb + r->bin) * ((int64_t)cs.n_rb + 1) + r->rb;
   r->q_lo = ptr[0];
   r->q_hi = ptr[1];
@@ -352,6 +356,17 @@ __global__ void k_cell_chunk_counts(CellShape cs, int64_t n_cells, const int32_t
   cell_chunks[cell] = n;
 }
 
+// one thread per (phase, row block) group: the pad cell gets what is missing to a multiple of kChunksPerQuad
+__global__ void k_group_pad(CellShape cs, int64_t n_groups, long long* cell_chunks) {
+  int64_t grp = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (grp >= n_groups) return;
+  const int cpg = cells_per_group(cs);
+  long long* c = cell_chunks + grp * cpg;
+  long long total = 0;
+  for (int i = 0; i < cpg - 1; ++i) total += c[i];
+  c[cpg - 1] = (kChunksPerQuad - total % kChunksPerQuad) % kChunksPerQuad;
+}
+
 __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t* __restrict__ bin_rb_ptr,
                                    const long long* __restrict__ cell_first_chunk,
                                    const int32_t* __restrict__ row_len, const int64_t* __restrict__ bucket_row_ptr,
@@ -362,7 +377,7 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
   CellRef r;
   bool any = decode_cell(cs, cell, bin_rb_ptr, &r);
   int64_t it = cell_first_chunk[cell];
-  const int64_t group_first_cell = cell - cell % ((int64_t)cs.ppg * cs.nb);
+  const int64_t group_first_cell = cell - cell % cells_per_group(cs);
   const int64_t list_begin = cell_first_chunk[group_first_cell];  // first chunk of this (phase, row block)
   if (cell == group_first_cell) rb_chunk_ptr[(int64_t)r.phase * cs.n_rb + r.rb] = it;
   if (!any) return;
@@ -410,12 +425,14 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
 // ------------------------------------------------------------ chunk stream
 // What the SpMM kernel actually reads: the chunks re-tiled into fixed records,
 // in list order, so that the address of every record follows from its list
-// position alone (no dependent descriptor load inside the gather loop):
-//   stream[q*192 +   0.. 63]  column ids   (slots past `count` repeat the last real column)
-//   stream[q*192 +  64..127]  values       (slots past `count` hold +0.0f)
-//   stream[q*192 + 128..191]  per slot: row relative to the first row of the row block in bits 0..15,
-//                             the chunk's log2w in bits 16..21, its hand-over flag in bit 22;
-//                             slots past `count` hold -1
+// position alone (no dependent descriptor load inside the gather loop).  Four
+// consecutive chunks form a quad of 3 KB, fetched with one 16-byte load per
+// lane and array:
+//   quad[  0..255]  column ids, chunk i at 64*i  (slots past `count` repeat the last real column)
+//   quad[256..511]  values                        (slots past `count` hold +0.0f)
+//   quad[512..767]  per slot: row relative to the first row of the row block in bits 0..15,
+//                   the chunk's log2w in bits 16..21, its hand-over flag in bit 22;
+//                   slots past `count` hold -1
 // One wavefront per chunk; reads the canonical arrays through the descriptor.
 __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chunk* __restrict__ chunks,
                                                      const int32_t* __restrict__ row_ids,
@@ -427,14 +444,22 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chu
   const Chunk ck = chunks[q];
   const int lw = (int)(ck.meta & 63u), count = (int)((ck.meta >> 6) & 127u);
   const int hand_over = (int)((ck.meta >> 13) & 1u);
+  // chunk i of quad Q sits at slots 64*i .. 64*i+63 of the quad's three 256-slot arrays
+  int32_t* quad = stream + (q / kChunksPerQuad) * (3 * kChunkSlots * kChunksPerQuad);
+  const int at = (int)(q % kChunksPerQuad) * kChunkSlots + lane;
+  if (count == 0) {  // padding of a group: contributes nothing, hands nothing over
+    quad[at] = 0;
+    quad[kChunkSlots * kChunksPerQuad + at] = 0;
+    quad[2 * kChunkSlots * kChunksPerQuad + at] = -1;
+    return;
+  }
   const int o = lane < count ? lane : count - 1;
   int32_t col = cols[ck.slot0 + o];
   float val = vals[ck.slot0 + o];
   int32_t rid = row_ids[ck.row0 + (o >> lw)];
-  int32_t* rec = stream + q * (3 * kChunkSlots);
-  rec[lane] = col;
-  rec[kChunkSlots + lane] = lane < count ? __float_as_int(val) : 0;
-  rec[2 * kChunkSlots + lane] =
+  quad[at] = col;
+  quad[kChunkSlots * kChunksPerQuad + at] = lane < count ? __float_as_int(val) : 0;
+  quad[2 * kChunkSlots * kChunksPerQuad + at] =
       lane < count ? ((rid & ((1 << log2_rb) - 1)) | (lw << 16) | (hand_over << 22)) : -1;
 }
 
@@ -618,7 +643,8 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
     cs.n_phases = (s.c + cs.ppg - 1) / cs.ppg;
     h->log2_row_block = cs.log2_rb; h->n_row_blocks = cs.n_rb;
     h->parts_per_phase = cs.ppg; h->n_phases = cs.n_phases;
-    const int64_t n_cells = (int64_t)cs.n_phases * cs.n_rb * cs.ppg * cs.nb;
+    const int64_t n_groups = (int64_t)cs.n_phases * cs.n_rb;
+    const int64_t n_cells = n_groups * ((int64_t)cs.ppg * cs.nb + 1);
     const int64_t n_bounds = (int64_t)s.c * s.nb * ((int64_t)cs.n_rb + 1);
     if (n_cells > 0x7FFFFFFF || n_bounds > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
     const size_t o_bounds = tmp2.reserve(sizeof(int32_t) * (size_t)(n_bounds ? n_bounds : 1));
@@ -684,6 +710,8 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
                          h->bucket_row_ptr, h->rem_part_ptr, h->row_ids, d_bounds);
       hipLaunchKernelGGL(k_cell_chunk_counts, dim3((unsigned)((n_cells + 255) / 256)), dim3(256), 0, stream, cs,
                          n_cells, d_bounds, h->row_len, d_cell_chunks);
+      hipLaunchKernelGGL(k_group_pad, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, stream, cs, n_groups,
+                         d_cell_chunks);
       hipLaunchKernelGGL(k_scan_sequences<long long>, dim3(1), dim3(kBuildBlock), 0, stream, d_cell_chunks,
                          (int32_t)n_cells, d_cell_total);
       BUILD_HIP(hipGetLastError());
@@ -695,6 +723,7 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
       size_t bytes = sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1);
       tmp_chunks = alloc(bytes, actx, stream);  // descriptors are only needed until the stream is packed
       if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
+      BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, bytes, stream));  // count 0 marks the padding chunks
       bytes = sizeof(int32_t) * 3 * kChunkSlots * (size_t)(n_chunks ? n_chunks : 1);
       h->stream = (int32_t*)alloc(bytes, actx, stream);
       if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }

@@ -266,16 +266,17 @@ constexpr int kHybBlock = 64 * kHybWaves;
 // One wavefront's walk over its share of a row block's chunk list.
 //
 // The unit of the pipeline is a "step": kChunk = kGroups*kSteps slots of a
-// 64-slot chunk (the whole chunk when a lane group is 8 lanes wide).  A chunk
-// is a fixed 768-byte record of the stream whose address follows from its list
-// position, so nothing in the loop waits for a descriptor.  Its (column,
-// value, row) triples are requested one per lane, six chunks ahead, and parked
-// three steps later in a small per-wave LDS ring; from there every lane group
-// reads the kSteps columns / values it needs with wide LDS reads (all lanes of
-// a group read the same address, which LDS broadcasts).  While step u is
-// multiplied, the X gathers of steps u+1 and u+2 are in flight.  The
-// steady-state loop body holds no conditional memory operation, so that the
-// compiler's wait counters stay exact; the last steps are peeled.
+// 64-slot chunk (the whole chunk when a lane group is 8 lanes wide).  Chunks
+// come in quads: a quad is a fixed 3 KB record of the stream whose address
+// follows from its list position, so nothing in the loop waits for a
+// descriptor.  A lane requests 16 bytes of each of the quad's three arrays
+// (columns, values, row words) two quads ahead and parks them one quad later
+// in a per-wave LDS ring of two quads; from there every lane group reads the
+// kSteps columns / values it needs with 16-byte LDS reads (all lanes of a group
+// read the same address, which LDS broadcasts).  While step u is multiplied,
+// the X gathers of steps u+1 and u+2 are in flight.  The loop body covers one
+// quad and holds no conditional memory operation, so that the compiler's wait
+// counters stay exact; the last quad is peeled.
 //
 // The lane groups that share a row add their partial sums up with cross-lane
 // moves; the leading group adds the row sum into the workgroup's LDS tile of Y
@@ -284,51 +285,52 @@ template <int VEC, int LG, bool IDX32>
 struct HybWalker {
   using S = Shape<VEC, LG>;
   static constexpr int UB = S::kSteps, CS = S::kChunk;
-  static constexpr int SUB = kChunkSlots / CS;  // steps per chunk
-  static constexpr int LOG2SUB = ilog2(SUB);
-  static constexpr int kRing = 4;               // chunks parked in LDS per wave
-  static constexpr int kRecord = 3 * kChunkSlots;
+  static constexpr int SUB = kChunkSlots / CS;              // steps per chunk
+  static constexpr int kQuadSteps = kChunksPerQuad * SUB;   // steps per quad
+  static constexpr int kQuadSlots = kChunksPerQuad * kChunkSlots;
+  static constexpr int kQuadInts = 3 * kQuadSlots;          // [cols | vals | row words]
+  static constexpr int kRingInts = 2 * kQuadInts;           // two quads parked per wave
 
-  struct Fetched {  // one chunk on its way from memory: a (column, value, row word) triple per lane
-    int col, val, row;
+  struct Fetched {  // a quad on its way from memory: slots 4*lane .. 4*lane+3 of each array
+    int col[4], val[4], row[4];
   };
 
   const SpmmArgs& a;
-  const int32_t* records;  // stream of this (phase, row block)
-  int n_chunks;            // chunks of this wave
+  const int32_t* quads;  // stream of this (phase, row block)
+  int n_quads;           // quads of this wave
   int wave, lane, g;
-  int* ring;               // this wave's LDS ring: kRing x [cols | vals | rows]
+  int* ring;             // this wave's LDS ring
   unsigned row_bytes, lane_bytes;  // bytes per row of X, byte offset of this lane's features
   LdsSink<VEC, LG> sink;
   float acc[VEC];
 
-  // local chunk number -> position in the row block's list (turns of kChunksPerTurn chunks, dealt round-robin)
-  __device__ __forceinline__ int list_pos(int k) const {
-    return ((k / kChunksPerTurn) * kHybWaves + wave) * kChunksPerTurn + (k % kChunksPerTurn);
+  // local quad number -> position in the row block's list (turns of two quads, dealt round-robin to the waves)
+  __device__ __forceinline__ int list_quad(int q) const {
+    constexpr int kQuadsPerTurn = kChunksPerTurn / kChunksPerQuad;
+    return ((q / kQuadsPerTurn) * kHybWaves + wave) * kQuadsPerTurn + (q % kQuadsPerTurn);
   }
 
-  __device__ __forceinline__ void fetch(int k, Fetched& f) const {
-    k = k < n_chunks ? k : n_chunks - 1;
-    const int q = list_pos(k);
-    const int32_t* rec = records + (size_t)q * kRecord;
-    f.col = rec[lane];
-    f.val = rec[kChunkSlots + lane];
-    f.row = rec[2 * kChunkSlots + lane];
+  __device__ __forceinline__ void fetch(int q, Fetched& f) const {
+    q = q < n_quads ? q : n_quads - 1;
+    const int4* rec = reinterpret_cast<const int4*>(quads + (size_t)list_quad(q) * kQuadInts);
+    const int4 c = rec[lane], v = rec[kQuadSlots / 4 + lane], r = rec[2 * kQuadSlots / 4 + lane];
+    f.col[0] = c.x; f.col[1] = c.y; f.col[2] = c.z; f.col[3] = c.w;
+    f.val[0] = v.x; f.val[1] = v.y; f.val[2] = v.z; f.val[3] = v.w;
+    f.row[0] = r.x; f.row[1] = r.y; f.row[2] = r.z; f.row[3] = r.w;
   }
 
-  __device__ __forceinline__ int* stage(int k) const { return ring + (k & (kRing - 1)) * kRecord; }
+  __device__ __forceinline__ int* slot_of(int q) const { return ring + (q & 1) * kQuadInts; }
 
-  // returns the chunk's facts (wave-uniform; slot 0 is always a real slot): log2w | hand-over << 6
-  __device__ __forceinline__ int park(int k, const Fetched& f) const {
-    int* st = stage(k);
-    st[lane] = f.col;
-    st[kChunkSlots + lane] = f.val;
-    st[2 * kChunkSlots + lane] = f.row < 0 ? -1 : (f.row & 0xFFFF);
-    return __builtin_amdgcn_readfirstlane(f.row) >> 16;
+  // parks quad q; m[i] receives the facts of its chunk i (wave-uniform): log2w | hand-over << 6.
+  // (slot 0 of a chunk is a real slot, or the whole chunk is padding and reads as "nothing to hand over")
+  __device__ __forceinline__ void park(int q, const Fetched& f, int (&m)[kChunksPerQuad]) const {
+    int4* st = reinterpret_cast<int4*>(slot_of(q));
+    st[lane] = make_int4(f.col[0], f.col[1], f.col[2], f.col[3]);
+    st[kQuadSlots / 4 + lane] = make_int4(f.val[0], f.val[1], f.val[2], f.val[3]);
+    st[2 * kQuadSlots / 4 + lane] = make_int4(f.row[0], f.row[1], f.row[2], f.row[3]);
+#pragma unroll
+    for (int i = 0; i < kChunksPerQuad; ++i) m[i] = __builtin_amdgcn_readlane(f.row[0], i * (kChunkSlots / 4)) >> 16;
   }
-
-  // first slot of this lane group in step u, as an offset into the chunk's record
-  __device__ __forceinline__ int first_slot(int u) const { return (u & (SUB - 1)) * CS + g * UB; }
 
   // UB consecutive ints of the ring (UB is 4 or 8; the offset is a multiple of UB): 16-byte LDS reads
   __device__ __forceinline__ void read_ints(const int* p, int (&out)[UB]) const {
@@ -340,23 +342,15 @@ struct HybWalker {
     }
   }
 
-  __device__ __forceinline__ void read_cols(int u, int (&c)[UB]) const {
-    read_ints(stage(u >> LOG2SUB) + first_slot(u), c);
-  }
-
-  __device__ __forceinline__ void read_vals(int u, float (&v)[UB]) const {
-    int t[UB];
-    read_ints(stage(u >> LOG2SUB) + kChunkSlots + first_slot(u), t);
-#pragma unroll
-    for (int j = 0; j < UB; ++j) v[j] = __int_as_float(t[j]);
-  }
+  // first slot of this lane group in step s of a quad (s = 0 .. kQuadSteps-1), as an offset into a quad array
+  __device__ __forceinline__ int first_slot(int s) const { return s * CS + g * UB; }
 
   // gathers: the UB rows of X this lane group multiplies in one step
   __device__ __forceinline__ void issue(const int (&c)[UB], float (&x)[UB][VEC]) const {
 #pragma unroll
     for (int j = 0; j < UB; ++j) {
       if constexpr (IDX32) {
-        // column ids are below 2^24 here, so the 24-bit multiply is exact
+        // column ids are below 2^24 here, so the 24-bit multiply-add is exact
         unsigned off = __umul24((unsigned)c[j], row_bytes) + lane_bytes;
         load_vec<VEC>(x[j], reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.X) + off));
       } else {
@@ -366,22 +360,24 @@ struct HybWalker {
     }
   }
 
-  __device__ __forceinline__ void consume(int u, int meta, const float (&v)[UB], const float (&x)[UB][VEC]) {
+  // step s of the quad parked at `st` whose chunk facts are m[]
+  __device__ __forceinline__ void consume(const int* st, int s, int meta, const float (&v)[UB],
+                                          const float (&x)[UB][VEC]) {
     const int lw = meta & 63;
     const bool hand_over = (meta >> 6) & 1;
-    const int sub = u & (SUB - 1);
-    const int* rows = stage(u >> LOG2SUB) + 2 * kChunkSlots;
+    const int sub = s & (SUB - 1);
+    const int* rows = st + 2 * kQuadSlots;
     if (lw < S::kLog2Steps) {
       // several rows inside the group's share: hand each one over as it ends
       int r[UB];
-      read_ints(rows + first_slot(u), r);
+      read_ints(rows + first_slot(s), r);
       const int width_mask = (1 << lw) - 1;
 #pragma unroll
       for (int j = 0; j < UB; ++j) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
         if (((j + 1) & width_mask) == 0) {
-          sink(r[j], r[j] >= 0, acc);
+          sink(r[j] & 0xFFFF, r[j] >= 0, acc);
 #pragma unroll
           for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
         }
@@ -402,9 +398,10 @@ struct HybWalker {
     sum_groups<VEC, LG>(acc, groups);
     const int g_first = g & ~(groups - 1);
     // (a row cut into several chunks keeps its partial sums in registers in between, so for a one-row
-    //  chunk even groups past the last real slot take part; its row sits in slot 0)
-    const int r = rows[one_row_chunk ? 0 : sub * CS + g_first * UB];
-    sink(r, g == g_first && r >= 0, acc);
+    //  chunk even groups past the last real slot take part; its row sits in the chunk's slot 0)
+    const int chunk0 = (s - sub) * CS;
+    const int r = rows[one_row_chunk ? chunk0 : first_slot(s) - (g - g_first) * UB];
+    sink(r & 0xFFFF, g == g_first && r >= 0, acc);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
   }
@@ -412,60 +409,57 @@ struct HybWalker {
   __device__ __forceinline__ void run() {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-    if (n_chunks <= 0) return;
-    const int n_steps = n_chunks * SUB;
-    // Chunks 0..5 are requested at once; 0..2 are parked right away, 3..5 stay in registers.  From then on the
-    // triples of chunk k+6 are requested while chunk k is multiplied and parked three steps later, when they
-    // have long arrived: a load that is waited for too early stalls every load queued behind it.
-    Fetched f0, f1, f2, fa, fb, fc;
-    fetch(0, f0); fetch(1, f1); fetch(2, f2); fetch(3, fa); fetch(4, fb); fetch(5, fc);
-    int m0 = park(0, f0), m1 = park(1, f1), m2 = park(2, f2), m3 = 0;  // facts of chunks k .. k+3 (k = chunk of step u)
+    if (n_quads <= 0) return;
+    // Quads 0 and 1 are requested at once and quad 0 is parked.  From then on, at the start of quad Q, quad Q+1
+    // (requested a whole quad earlier, so long arrived: a load that is waited for too early stalls every load
+    // queued behind it) is parked and quad Q+2 is requested.
+    Fetched f, f_first;
+    fetch(0, f_first);
+    fetch(1, f);
+    int m_cur[kChunksPerQuad], m_next[kChunksPerQuad];
+    park(0, f_first, m_cur);
     float xa[UB][VEC], xb[UB][VEC];
     {
       int c[UB];
-      read_cols(0, c);
+      read_ints(slot_of(0) + first_slot(0), c);
       issue(c, xa);
-      read_cols(n_steps > 1 ? 1 : 0, c);
+      read_ints(slot_of(0) + first_slot(1), c);
       issue(c, xb);
     }
-    // one step; `x` holds the gathers of step u and is refilled with those of step u+2
-    auto step = [&](int u, float (&x)[UB][VEC]) {
+    // one step of quad Q: `x` holds the gathers of step s and is refilled with those of step s+2
+    auto step = [&](int Q, int s, float (&x)[UB][VEC], bool refill) {
+      const int* st = slot_of(Q);
+      int t[UB];
       float v[UB];
+      read_ints(st + kQuadSlots + first_slot(s), t);  // LDS reads first: their latency hides behind what follows
+#pragma unroll
+      for (int j = 0; j < UB; ++j) v[j] = __int_as_float(t[j]);
       int c[UB];
-      read_vals(u, v);      // LDS reads first: their latency hides behind the bookkeeping below
-      read_cols(u + 2, c);
-      if (SUB == 1 || (u & (SUB - 1)) == 0) {  // first step of chunk k: chunk k+3 is parked, chunk k+6 requested
-        const int k = u >> LOG2SUB;
-        m3 = park(k + 3, fa);
-        fa = fb; fb = fc;
-        fetch(k + 6, fc);
+      if (refill) {
+        const int s2 = s + 2;
+        read_ints((s2 < kQuadSteps ? st : slot_of(Q + 1)) + first_slot(s2 & (kQuadSteps - 1)), c);
       }
-      consume(u, m0, v, x);
-      issue(c, x);
-      if (SUB == 1 || (u & (SUB - 1)) == SUB - 1) { m0 = m1; m1 = m2; m2 = m3; }
+      consume(st, s, m_cur[s / SUB], v, x);
+      if (refill) issue(c, x);
     };
-    int u = 0;
-    for (; u + 3 < n_steps; u += 2) {
-      step(u, xa);
-      step(u + 1, xb);
+    int Q = 0;
+    for (; Q + 1 < n_quads; ++Q) {
+      park(Q + 1, f, m_next);
+      fetch(Q + 2, f);
+#pragma unroll
+      for (int s = 0; s < kQuadSteps; s += 2) {
+        step(Q, s, xa, true);
+        step(Q, s + 1, xb, true);
+      }
+#pragma unroll
+      for (int i = 0; i < kChunksPerQuad; ++i) m_cur[i] = m_next[i];
     }
-    // 1..3 steps left; the gathers of steps u and u+1 are in flight
-    const int left = n_steps - u;
-    auto last = [&](int uu, float (&x)[UB][VEC]) {
-      float v[UB];
-      read_vals(uu, v);
-      consume(uu, m0, v, x);
-      if (SUB == 1 || (uu & (SUB - 1)) == SUB - 1) { m0 = m1; m1 = m2; m2 = m3; }
-    };
-    if (SUB > 1 && (u & (SUB - 1)) == 0) m3 = park((u >> LOG2SUB) + 3, fa);
-    last(u, xa);
-    if (left == 3) {
-      int c[UB];
-      read_cols(u + 2, c);
-      issue(c, xa);
+    // last quad: its steps 0 and 1 are in flight, nothing follows it
+#pragma unroll
+    for (int s = 0; s < kQuadSteps; s += 2) {
+      step(Q, s, xa, s + 2 < kQuadSteps);
+      step(Q, s + 1, xb, s + 3 < kQuadSteps);
     }
-    if (left >= 2) last(u + 1, xb);
-    if (left == 3) last(u + 2, xa);
   }
 };
 
@@ -487,13 +481,13 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   const int fl = lane & (LG - 1);
   const int f0 = tile_id * S::kTile + fl * VEC;
   const bool f_active = f0 < a.feat;
-  int* ring = reinterpret_cast<int*>(smem + row_block * S::kTile) + wave * (W::kRing * W::kRecord);
+  int* ring = reinterpret_cast<int*>(smem + row_block * S::kTile) + wave * W::kRingInts;
 
   for (int i = tid; i < rows_here * S::kTile; i += kHybBlock) tile[i] = 0.f;
   __syncthreads();
 
   const int64_t c0 = a.rb_chunk_ptr[rb];
-  const int n_list = (int)(a.rb_chunk_ptr[rb + 1] - c0);
+  const int n_list = (int)(a.rb_chunk_ptr[rb + 1] - c0);  // a multiple of kChunksPerQuad
   // this wave's chunks: turns wave, wave + kHybWaves, ... of kChunksPerTurn chunks each
   const int n_turns = (n_list + kChunksPerTurn - 1) / kChunksPerTurn;
   int my_turns = n_turns > wave ? (n_turns - wave + kHybWaves - 1) / kHybWaves : 0;
@@ -501,7 +495,7 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   if (my_turns > 0 && (n_turns - 1) % kHybWaves == wave) my_chunks -= n_turns * kChunksPerTurn - n_list;
 
   const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
-  W wk{a, a.stream + (size_t)c0 * W::kRecord, my_chunks, wave, lane, lane / LG, ring,
+  W wk{a, a.stream + (size_t)c0 * (3 * kChunkSlots), my_chunks / kChunksPerQuad, wave, lane, lane / LG, ring,
        (unsigned)a.feat * 4u, (unsigned)f_read * 4u, LdsSink<VEC, LG>{tile, fl, f_active}, {}};
   wk.run();
   __syncthreads();
@@ -636,7 +630,7 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
   a.X = X; a.Y = Y; a.n_rows = h->n_rows; a.n_row_blocks = h->n_row_blocks; a.log2_row_block = h->log2_row_block;
   a.feat = feat; a.n_tiles = g.n_tiles; a.map_mode = g.map_mode; a.map_param = g.map_param;
   const size_t lds_bytes = sizeof(float) * ((size_t)g.vec * g.lg << h->log2_row_block) +
-                           sizeof(int) * kHybWaves * 4 * 3 * kChunkSlots;  // Y tile + the waves' chunk rings
+                           sizeof(int) * kHybWaves * 2 * 3 * kChunkSlots * kChunksPerQuad;  // Y tile + the waves' rings
   const bool idx32 = h->n_cols < (1 << 24) && x_bytes < ((size_t)1 << 32);
   for (int phase = 0; phase < h->n_phases; ++phase) {
     a.rb_chunk_ptr = h->rb_chunk_ptr + (size_t)phase * h->n_row_blocks;

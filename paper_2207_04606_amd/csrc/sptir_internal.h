@@ -24,6 +24,7 @@ static_assert(sizeof(Chunk) == 16, "Chunk must stay 16 bytes");
 
 constexpr int kChunkSlots = 64;
 constexpr int kRowLog2W = 31;
+constexpr int kChunksPerQuad = 4;  // chunks the SpMM kernel fetches with one load per lane and array
 constexpr int kChunksPerTurn = 8;  // consecutive chunks one wavefront takes before the next wavefront's turn
 constexpr int kBuildBlock = 256;  // rows per workgroup in the builder kernels
 
