@@ -481,8 +481,9 @@ int log2_row_block_setting(int32_t n_rows) {
   const char* e = getenv("SPTIR_ROW_BLOCK");
   long v = e ? atol(e) : 0;
   if (v < 32 || v > 1024 || (v & (v - 1))) {
-    // enough row blocks to fill 256 CUs several times over, else smaller blocks
-    v = 256;
+    // 128 rows keep a workgroup's LDS (Y tile + chunk rings) at 40 KB, four workgroups per CU;
+    // smaller blocks when there would not be enough of them to fill 256 CUs several times over
+    v = 128;
     while (v > 64 && n_rows / v < 512) v >>= 1;
   }
   int l = 0;
