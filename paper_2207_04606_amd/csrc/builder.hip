@@ -339,6 +339,18 @@ __device__ __forceinline__ bool decode_cell(const CellShape& cs, int64_t cell, c
 
 __device__ __forceinline__ int chunks_of_length(int len) { return (len + kChunkSlots - 1) / kChunkSlots; }
 
+// Rows of the buckets of width 8..64 are taken eight at a time ("row sets"): chunk t of a set holds
+// entries 8t .. 8t+7 of each of its eight rows, one row per octet, so that in the SpMM kernel every lane
+// group keeps the running sum of its own row and no cross-lane reduction is needed.  A set needs
+// ceil(longest row / 8) chunks.  The last (rows % 8) rows of a cell are cut the plain way.
+__device__ __forceinline__ bool bin_uses_row_sets(int bin, int k) { return bin <= k && bin >= 3 && bin <= 6; }
+
+__device__ __forceinline__ int set_chunks(const int32_t* __restrict__ row_len, int32_t q0) {
+  int longest = 0;
+  for (int i = 0; i < 8; ++i) longest = max(longest, row_len[q0 + i]);
+  return (longest + 7) >> 3;
+}
+
 __global__ void k_cell_chunk_counts(CellShape cs, int64_t n_cells, const int32_t* __restrict__ bin_rb_ptr,
                                     const int32_t* __restrict__ row_len, long long* cell_chunks) {
   int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -346,11 +358,14 @@ __global__ void k_cell_chunk_counts(CellShape cs, int64_t n_cells, const int32_t
   CellRef r;
   long long n = 0;
   if (decode_cell(cs, cell, bin_rb_ptr, &r)) {
+    int32_t q = r.q_lo;
+    if (bin_uses_row_sets(r.bin, cs.k))
+      for (; q + 8 <= r.q_hi; q += 8) n += set_chunks(row_len, q);
     if (r.bin <= cs.k && (1 << r.bin) < kChunkSlots) {
       int rows_per_chunk = kChunkSlots >> r.bin;
-      n = (r.q_hi - r.q_lo + rows_per_chunk - 1) / rows_per_chunk;
+      n += (r.q_hi - q + rows_per_chunk - 1) / rows_per_chunk;
     } else {
-      for (int32_t q = r.q_lo; q < r.q_hi; ++q) n += chunks_of_length(row_len[q]);
+      for (; q < r.q_hi; ++q) n += chunks_of_length(row_len[q]);
     }
   }
   cell_chunks[cell] = n;
@@ -384,26 +399,35 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
   // A wave carries the partial sum of a row that continues in its next chunk;
   // it must hand it over at the end of every group of kChunksPerTurn chunks,
   // because the next group belongs to another wave.
-  auto emit = [&](int64_t slot0, int32_t row0, int lw, int count, bool row_ends) {
+  auto emit = [&](int64_t slot0, int32_t row0, int lw, int count, bool row_ends, uint32_t extra = 0u) {
     bool turn_ends = ((it - list_begin) % kChunksPerTurn) == kChunksPerTurn - 1;
     Chunk ck;
     ck.slot0 = slot0;
     ck.row0 = row0;
-    ck.meta = (uint32_t)lw | ((uint32_t)count << 6) | ((row_ends || turn_ends) ? (1u << 13) : 0u);
+    ck.meta = (uint32_t)lw | ((uint32_t)count << 6) | ((row_ends || turn_ends) ? (1u << 13) : 0u) | extra;
     chunks[it++] = ck;
   };
   if (r.bin <= cs.k) {
     int64_t b = (int64_t)r.p * (cs.k + 1) + r.bin;
     int64_t width = (int64_t)1 << r.bin;
     int64_t first_slot = bucket_slot_ptr[b] + ((int64_t)r.q_lo - bucket_row_ptr[b]) * width;
+    int32_t q_plain = r.q_lo;  // rows from here on are cut the plain way
+    if (bin_uses_row_sets(r.bin, cs.k)) {
+      for (; q_plain + 8 <= r.q_hi; q_plain += 8) {
+        const int n_t = set_chunks(row_len, q_plain);
+        for (int t = 0; t < n_t; ++t)  // to the kernel a set chunk looks like eight rows of width 8
+          emit(first_slot + ((int64_t)(q_plain - r.q_lo) << r.bin), q_plain, 3, kChunkSlots, t == n_t - 1,
+               kChunkIsRowSet | ((uint32_t)t << 15) | ((uint32_t)r.bin << 21));
+      }
+    }
     if (width < kChunkSlots) {  // several whole rows per chunk
       int rows_per_chunk = kChunkSlots >> r.bin;
-      for (int32_t q = r.q_lo; q < r.q_hi; q += rows_per_chunk) {
+      for (int32_t q = q_plain; q < r.q_hi; q += rows_per_chunk) {
         int rows = r.q_hi - q < rows_per_chunk ? r.q_hi - q : rows_per_chunk;
         emit(first_slot + ((int64_t)(q - r.q_lo) << r.bin), q, r.bin, rows << r.bin, true);
       }
     } else {  // a row takes one chunk per 64 real entries
-      for (int32_t q = r.q_lo; q < r.q_hi; ++q) {
+      for (int32_t q = q_plain; q < r.q_hi; ++q) {
         int len = row_len[q];
         int64_t row_slot = first_slot + (int64_t)(q - r.q_lo) * width;
         for (int off = 0; off < len; off += kChunkSlots)
@@ -453,10 +477,19 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chu
     quad[2 * kChunkSlots * kChunksPerQuad + at] = -1;
     return;
   }
-  const int o = lane < count ? lane : count - 1;
-  int32_t col = cols[ck.slot0 + o];
-  float val = vals[ck.slot0 + o];
-  int32_t rid = row_ids[ck.row0 + (o >> lw)];
+  int64_t src;
+  int32_t rid;
+  if (ck.meta & kChunkIsRowSet) {  // octet g of the chunk = entries 8t .. 8t+7 of the set's row g
+    const int t = (int)((ck.meta >> 15) & 63u), log2_width = (int)((ck.meta >> 21) & 31u);
+    src = ck.slot0 + ((int64_t)(lane >> 3) << log2_width) + 8 * t + (lane & 7);
+    rid = row_ids[ck.row0 + (lane >> 3)];
+  } else {
+    const int o = lane < count ? lane : count - 1;
+    src = ck.slot0 + o;
+    rid = row_ids[ck.row0 + (o >> lw)];
+  }
+  int32_t col = cols[src];
+  float val = vals[src];
   quad[at] = col;
   quad[kChunkSlots * kChunksPerQuad + at] = lane < count ? __float_as_int(val) : 0;
   quad[2 * kChunkSlots * kChunksPerQuad + at] =

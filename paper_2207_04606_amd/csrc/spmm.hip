@@ -391,6 +391,8 @@ struct HybWalker {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
     if (one_row_chunk && !(hand_over && sub == SUB - 1)) return;  // the row goes on: keep the sums in registers
+    // a row-set chunk (eight rows, eight entries each): every octet keeps its row's sum until the set's last chunk
+    if (SUB == 1 && lw == 3 && !hand_over) return;
     if (!one_row_chunk && lw >= S::kLog2Chunk && (((sub + 1) * CS) & ((1 << lw) - 1)) != 0) return;  // row spans steps
     int groups = (one_row_chunk || lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));
     // With 8-lane groups the two halves of the wave hand over separately (one cross-lane level saved).
