@@ -393,18 +393,15 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
   bool any = decode_cell(cs, cell, bin_rb_ptr, &r);
   int64_t it = cell_first_chunk[cell];
   const int64_t group_first_cell = cell - cell % cells_per_group(cs);
-  const int64_t list_begin = cell_first_chunk[group_first_cell];  // first chunk of this (phase, row block)
   if (cell == group_first_cell) rb_chunk_ptr[(int64_t)r.phase * cs.n_rb + r.rb] = it;
   if (!any) return;
-  // A wave carries the partial sum of a row that continues in its next chunk;
-  // it must hand it over at the end of every group of kChunksPerTurn chunks,
-  // because the next group belongs to another wave.
+  // The whole list of a (phase, row block) is walked by one wavefront, which carries the partial sum of a
+  // row that continues in the next chunk in registers and hands it over when the row (or row set) ends.
   auto emit = [&](int64_t slot0, int32_t row0, int lw, int count, bool row_ends, uint32_t extra = 0u) {
-    bool turn_ends = ((it - list_begin) % kChunksPerTurn) == kChunksPerTurn - 1;
     Chunk ck;
     ck.slot0 = slot0;
     ck.row0 = row0;
-    ck.meta = (uint32_t)lw | ((uint32_t)count << 6) | ((row_ends || turn_ends) ? (1u << 13) : 0u) | extra;
+    ck.meta = (uint32_t)lw | ((uint32_t)count << 6) | (row_ends ? (1u << 13) : 0u) | extra;
     chunks[it++] = ck;
   };
   if (r.bin <= cs.k) {
@@ -508,16 +505,16 @@ struct Blob {  // bump allocator over one device allocation
 };
 
 // Tuning knobs (environment, read when a hyb object is built):
-//   SPTIR_ROW_BLOCK        rows of Y a workgroup keeps in LDS (power of two, 32..1024)
+//   SPTIR_ROW_BLOCK        rows of Y one wavefront keeps in LDS (power of two, 8..256)
 //   SPTIR_PARTS_PER_PHASE  column partitions swept per SpMM launch (default: chosen from the sizes)
 int log2_row_block_setting(int32_t n_rows) {
   const char* e = getenv("SPTIR_ROW_BLOCK");
   long v = e ? atol(e) : 0;
-  if (v < 32 || v > 1024 || (v & (v - 1))) {
-    // 128 rows keep a workgroup's LDS (Y tile + chunk rings) at 40 KB, four workgroups per CU;
+  if (v < 8 || v > 256 || (v & (v - 1))) {
+    // 32 rows x 128 bytes = 4 KB of LDS per wavefront next to its 6 KB chunk ring: 16 wavefronts per CU;
     // smaller blocks when there would not be enough of them to fill 256 CUs several times over
-    v = 128;
-    while (v > 64 && n_rows / v < 512) v >>= 1;
+    v = 32;
+    while (v > 8 && n_rows / v < 4096) v >>= 1;
   }
   int l = 0;
   while ((1L << l) < v) ++l;

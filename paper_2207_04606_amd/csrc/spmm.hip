@@ -2,30 +2,28 @@
 // 2207.04606), and the single-pass CSR variant the paper calls "no-hyb".
 //
 // Mapping (gfx950, wave64).  The feature dimension is cut into tiles of
-// LG*VEC floats (32 floats = one 128-byte line of X by default).  A workgroup
+// LG*VEC floats (32 floats = one 128-byte line of X by default).  A wavefront
 // owns one (row block, feature tile): it keeps that tile of the row block's Y
-// rows in LDS, walks every work item of the row block (all column partitions,
-// all ELL buckets, the remainder) and finally writes the Y tile once with
-// plain coalesced stores.  Y therefore needs no zero fill and no global
-// atomics, and rows without non-zeros come out as 0 (the init block of the
-// SpMM script in appendix A).
+// rows (32 rows by default, 4 KB) in its own piece of LDS, walks every chunk of
+// the row block's list (all column partitions of the launch, all ELL buckets,
+// the remainder) and finally writes the Y tile with plain coalesced stores.
+// Nothing is shared between wavefronts: no atomics, no barriers, no zero fill
+// of Y, and rows without non-zeros come out as 0 (the init block of the SpMM
+// script in appendix A).
 //
-// A wavefront takes work items from the workgroup's list one at a time.  Its
-// 64 lanes form 64/LG lane groups; a group covers the tile with VEC floats per
-// lane, so one wave load instruction gathers 64/LG different rows of X, each
-// as one contiguous 128-byte read.  Stored (column, value, row) triples are
-// read one per lane, a chunk of slots at a time, and handed to the groups by
-// cross-lane reads.  The loop is software pipelined: the gathers of chunk n+1
-// are in flight while chunk n is multiplied, the triples of chunk n+2 are
-// being fetched.  Partial sums stay in registers (section 4.2.1 names this as
-// what a CSR code generator misses) and go to LDS once per ELL row.
+// The 64 lanes form 64/LG lane groups; a group covers the tile with VEC floats
+// per lane, so one wave load instruction gathers 64/LG different rows of X,
+// each as one contiguous 128-byte read.  Partial sums stay in registers
+// (section 4.2.1 names this as what a CSR code generator misses) and go to the
+// LDS tile once per row.
 //
-// Workgroup -> (row block, tile): consecutive workgroup ids are dealt
+// Workgroup -> (row blocks, tile): consecutive workgroup ids are dealt
 // round-robin to the 8 XCDs, each with a private L2.  Tiles are bound to
 // blockIdx.x % 8 where the tile count allows it, so an XCD's L2 only ever holds
-// its own feature tile of X; the items of a row block sweep the column
-// partitions in ascending order, which keeps the X slice in flight L2-sized
-// (the purpose section 4.2.1 gives for column partitioning).
+// its own feature tile of X; the chunks of a row block sweep the column
+// partitions in ascending order, and long-row matrices get one launch per
+// partition, which keeps the X slice in flight L2-sized (the purpose section
+// 4.2.1 gives for column partitioning).
 #include "sptir_internal.h"
 
 namespace sptir {
@@ -64,25 +62,30 @@ struct Shape {
   static constexpr int kLog2Chunk = ilog2(kChunk);
 };
 
-// LDS position of feature (fl*VEC + e) of local row r.  Lane fl of a group
-// owns features fl*VEC .. fl*VEC+VEC-1; storing component e of all lanes side
-// by side, and rotating rows against each other, spreads a flush over banks.
+// LDS position of the VEC floats lane fl of a group owns in local row r of the wavefront's Y tile.  Rows are
+// rotated against each other by one lane's share, so that lane groups working on neighbouring rows
+// (a row-set chunk hands eight rows over at once) hit different banks.
 template <int VEC, int LG>
-__device__ __forceinline__ int lds_index(int r, int fl, int e) {
-  constexpr int T = VEC * LG;
-  return r * T + ((e * LG + fl + r * LG) & (T - 1));
+__device__ __forceinline__ int tile_index(int r, int fl) {
+  return (r * LG + ((fl + r) & (LG - 1))) * VEC;
 }
 
-// Adds a finished row sum into the workgroup's Y tile; r is the row relative to the row block.
+// Adds a finished row sum into the wavefront's Y tile; r is the row relative to the row block.  The tile is
+// private to the wavefront and a row is handed over by exactly one lane group per instruction, so a plain
+// read-add-write is enough (LDS float atomics cost several times more).
 template <int VEC, int LG>
-struct LdsSink {
+struct TileSink {
   float* tile;     // [row_block][kTile] in LDS
   int fl;
   bool f_active;
   __device__ __forceinline__ void operator()(int r, bool valid, const float (&acc)[VEC]) const {
     if (valid && f_active) {
+      float* p = tile + tile_index<VEC, LG>(r, fl);
+      float t[VEC];
+      load_vec<VEC>(t, p);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) atomicAdd(&tile[lds_index<VEC, LG>(r, fl, e)], acc[e]);
+      for (int e = 0; e < VEC; ++e) t[e] += acc[e];
+      store_vec<VEC>(p, t);
     }
   }
 };
@@ -279,8 +282,7 @@ constexpr int kHybBlock = 64 * kHybWaves;
 // counters stay exact; the last quad is peeled.
 //
 // The lane groups that share a row add their partial sums up with cross-lane
-// moves; the leading group adds the row sum into the workgroup's LDS tile of Y
-// (float LDS atomics: other wavefronts may be working on the same row).
+// moves; the leading group adds the row sum into the wavefront's LDS tile of Y.
 template <int VEC, int LG, bool IDX32>
 struct HybWalker {
   using S = Shape<VEC, LG>;
@@ -297,22 +299,16 @@ struct HybWalker {
 
   const SpmmArgs& a;
   const int32_t* quads;  // stream of this (phase, row block)
-  int n_quads;           // quads of this wave
-  int wave, lane, g;
+  int n_quads;
+  int lane, g;
   int* ring;             // this wave's LDS ring
   unsigned row_bytes, lane_bytes;  // bytes per row of X, byte offset of this lane's features
-  LdsSink<VEC, LG> sink;
+  TileSink<VEC, LG> sink;
   float acc[VEC];
-
-  // local quad number -> position in the row block's list (turns of two quads, dealt round-robin to the waves)
-  __device__ __forceinline__ int list_quad(int q) const {
-    constexpr int kQuadsPerTurn = kChunksPerTurn / kChunksPerQuad;
-    return ((q / kQuadsPerTurn) * kHybWaves + wave) * kQuadsPerTurn + (q % kQuadsPerTurn);
-  }
 
   __device__ __forceinline__ void fetch(int q, Fetched& f) const {
     q = q < n_quads ? q : n_quads - 1;
-    const int4* rec = reinterpret_cast<const int4*>(quads + (size_t)list_quad(q) * kQuadInts);
+    const int4* rec = reinterpret_cast<const int4*>(quads + (size_t)q * kQuadInts);
     const int4 c = rec[lane], v = rec[kQuadSlots / 4 + lane], r = rec[2 * kQuadSlots / 4 + lane];
     f.col[0] = c.x; f.col[1] = c.y; f.col[2] = c.z; f.col[3] = c.w;
     f.val[0] = v.x; f.val[1] = v.y; f.val[2] = v.z; f.val[3] = v.w;
@@ -394,9 +390,7 @@ struct HybWalker {
     // a row-set chunk (eight rows, eight entries each): every octet keeps its row's sum until the set's last chunk
     if (SUB == 1 && lw == 3 && !hand_over) return;
     if (!one_row_chunk && lw >= S::kLog2Chunk && (((sub + 1) * CS) & ((1 << lw) - 1)) != 0) return;  // row spans steps
-    int groups = (one_row_chunk || lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));
-    // With 8-lane groups the two halves of the wave hand over separately (one cross-lane level saved).
-    if (LG == 8 && groups == 8) groups = 4;
+    const int groups = (one_row_chunk || lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));
     sum_groups<VEC, LG>(acc, groups);
     const int g_first = g & ~(groups - 1);
     // (a row cut into several chunks keeps its partial sums in registers in between, so for a one-row
@@ -447,10 +441,13 @@ struct HybWalker {
     int Q = 0;
     for (; Q + 1 < n_quads; ++Q) {
       park(Q + 1, f, m_next);
-      fetch(Q + 2, f);
 #pragma unroll
       for (int s = 0; s < kQuadSteps; s += 2) {
         step(Q, s, xa, true);
+        // Loads come back in issue order, so the slow request for quad Q+2 (it comes from memory, the gathers
+        // from L2) delays whatever is issued after it.  Placed right behind a batch of gathers, the first
+        // loads it can delay are those of the next step, which are not needed before two more steps.
+        if (s == 0) fetch(Q + 2, f);
         step(Q, s + 1, xb, true);
       }
 #pragma unroll
@@ -469,54 +466,48 @@ template <int VEC, int LG, bool IDX32>
 __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   using S = Shape<VEC, LG>;
   using W = HybWalker<VEC, LG, IDX32>;
-  extern __shared__ __align__(16) float smem[];  // [row_block][kTile] tile of Y, then the waves' chunk rings
-  float* tile = smem;
-  int64_t rb;
+  extern __shared__ __align__(16) float smem[];  // per wavefront: [row_block][kTile] tile of Y, then its quad ring
+  int64_t unit;
   int tile_id;
-  decode_block(a.map_mode, a.map_param, a.n_tiles, &rb, &tile_id);
+  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t rb = unit * kHybWaves + wave;  // the wavefronts of a workgroup are independent of each other
   if (rb >= a.n_row_blocks) return;
   const int row_block = 1 << a.log2_row_block;
   const int rb_first = (int)(rb << a.log2_row_block);
   const int rows_here = min(row_block, a.n_rows - rb_first);
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int fl = lane & (LG - 1);
+  const int g = lane / LG, fl = lane & (LG - 1);
   const int f0 = tile_id * S::kTile + fl * VEC;
   const bool f_active = f0 < a.feat;
-  int* ring = reinterpret_cast<int*>(smem + row_block * S::kTile) + wave * W::kRingInts;
+  const int wave_floats = row_block * S::kTile + W::kRingInts;
+  float* tile = smem + wave * wave_floats;
+  int* ring = reinterpret_cast<int*>(tile + row_block * S::kTile);
 
-  for (int i = tid; i < rows_here * S::kTile; i += kHybBlock) tile[i] = 0.f;
-  __syncthreads();
+  // the tile starts from zero, or from what earlier launches (column partitions) left in Y
+  float* y0 = a.Y + (size_t)rb_first * (size_t)a.feat + f0;
+  for (int r = g; r < row_block; r += S::kGroups) {
+    float init[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) init[e] = 0.f;
+    if (a.accumulate && f_active && r < rows_here) load_vec<VEC>(init, y0 + (size_t)r * (size_t)a.feat);
+    store_vec<VEC>(tile + tile_index<VEC, LG>(r, fl), init);
+  }
 
   const int64_t c0 = a.rb_chunk_ptr[rb];
   const int n_list = (int)(a.rb_chunk_ptr[rb + 1] - c0);  // a multiple of kChunksPerQuad
-  // this wave's chunks: turns wave, wave + kHybWaves, ... of kChunksPerTurn chunks each
-  const int n_turns = (n_list + kChunksPerTurn - 1) / kChunksPerTurn;
-  int my_turns = n_turns > wave ? (n_turns - wave + kHybWaves - 1) / kHybWaves : 0;
-  int my_chunks = my_turns * kChunksPerTurn;
-  if (my_turns > 0 && (n_turns - 1) % kHybWaves == wave) my_chunks -= n_turns * kChunksPerTurn - n_list;
-
   const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
-  W wk{a, a.stream + (size_t)c0 * (3 * kChunkSlots), my_chunks / kChunksPerQuad, wave, lane, lane / LG, ring,
-       (unsigned)a.feat * 4u, (unsigned)f_read * 4u, LdsSink<VEC, LG>{tile, fl, f_active}, {}};
+  W wk{a, a.stream + (size_t)c0 * (3 * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
+       (unsigned)a.feat * 4u, (unsigned)f_read * 4u, TileSink<VEC, LG>{tile, fl, f_active}, {}};
   wk.run();
-  __syncthreads();
 
   // write the tile: a lane group per row, one 128-byte line per group
-  const int g = tid / LG;
-  for (int r = g; r < rows_here; r += kHybBlock / LG) {
-    if (!f_active) continue;
-    float out[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) out[e] = tile[lds_index<VEC, LG>(r, fl, e)];
-    float* y = a.Y + (size_t)(rb_first + r) * (size_t)a.feat + f0;
-    if (a.accumulate) {
-      float old[VEC];
-      load_vec<VEC>(old, y);
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) out[e] += old[e];
+  if (f_active) {
+    for (int r = g; r < rows_here; r += S::kGroups) {
+      float out[VEC];
+      load_vec<VEC>(out, tile + tile_index<VEC, LG>(r, fl));
+      store_vec<VEC>(y0 + (size_t)r * (size_t)a.feat, out);
     }
-    store_vec<VEC>(y, out);
   }
 }
 
@@ -626,13 +617,14 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
   if (h->n_rows == 0) return SPTIR_OK;
 
   Geometry g;
-  if (!plan(h->n_row_blocks, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
+  if (!plan(((int64_t)h->n_row_blocks + kHybWaves - 1) / kHybWaves, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
   SpmmArgs a;
   a.stream = h->stream;
   a.X = X; a.Y = Y; a.n_rows = h->n_rows; a.n_row_blocks = h->n_row_blocks; a.log2_row_block = h->log2_row_block;
   a.feat = feat; a.n_tiles = g.n_tiles; a.map_mode = g.map_mode; a.map_param = g.map_param;
-  const size_t lds_bytes = sizeof(float) * ((size_t)g.vec * g.lg << h->log2_row_block) +
-                           sizeof(int) * kHybWaves * 2 * 3 * kChunkSlots * kChunksPerQuad;  // Y tile + the waves' rings
+  // per wavefront: its Y tile and its ring of two quads
+  const size_t lds_bytes = (size_t)kHybWaves * (sizeof(float) * ((size_t)g.vec * g.lg << h->log2_row_block) +
+                                                sizeof(int) * 2 * 3 * kChunkSlots * kChunksPerQuad);
   const bool idx32 = h->n_cols < (1 << 24) && x_bytes < ((size_t)1 << 32);
   for (int phase = 0; phase < h->n_phases; ++phase) {
     a.rb_chunk_ptr = h->rb_chunk_ptr + (size_t)phase * h->n_row_blocks;

@@ -28,7 +28,6 @@ static_assert(sizeof(Chunk) == 16, "Chunk must stay 16 bytes");
 constexpr int kChunkSlots = 64;
 constexpr int kRowLog2W = 31;
 constexpr int kChunksPerQuad = 4;  // chunks the SpMM kernel fetches with one load per lane and array
-constexpr int kChunksPerTurn = 8;  // consecutive chunks one wavefront takes before the next wavefront's turn
 constexpr int kBuildBlock = 256;  // rows per workgroup in the builder kernels
 
 }  // namespace sptir
@@ -51,7 +50,7 @@ struct sptir_hyb {
   int32_t* stream;           // device [n_chunks * 192]: the chunks as fixed records, grouped by (phase, row block)
   int64_t* rb_chunk_ptr;     // device [n_phases * n_row_blocks + 1], first chunk of each group
   int64_t n_chunks;
-  int32_t log2_row_block;    // rows of Y one workgroup accumulates in LDS (power of two)
+  int32_t log2_row_block;    // rows of Y one wavefront accumulates in LDS (power of two)
   int32_t n_row_blocks;
   int32_t parts_per_phase;   // column partitions swept by one SpMM launch
   int32_t n_phases;
