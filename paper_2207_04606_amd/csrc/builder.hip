@@ -447,31 +447,38 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
 // What the SpMM kernel actually reads: the chunks re-tiled into fixed records,
 // in list order, so that the address of every record follows from its list
 // position alone (no dependent descriptor load inside the gather loop).  Four
-// consecutive chunks form a quad of 3 KB, fetched with one 16-byte load per
-// lane and array:
+// consecutive chunks form a quad, fetched with one 16-byte load per lane and
+// array.  The 12-byte form (3 KB per quad):
 //   quad[  0..255]  column ids, chunk i at 64*i  (slots past `count` repeat the last real column)
 //   quad[256..511]  values                        (slots past `count` hold +0.0f)
 //   quad[512..767]  per slot: row relative to the first row of the row block in bits 0..15,
 //                   the chunk's log2w in bits 16..21, its hand-over flag in bit 22;
 //                   slots past `count` hold -1
+// The compact form (2 KB per quad; the kernel's time goes with the bytes it has
+// to pull from beyond L2, and every feature tile re-reads the stream) folds the
+// row word into the column word, see kCompactColBits:
+//   quad[  0..255]  column - first column of the launch | row << 20 | real << 27 | log2w code << 28 | hand-over << 31
+//   quad[256..511]  values
 // One wavefront per chunk; reads the canonical arrays through the descriptor.
 __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chunk* __restrict__ chunks,
                                                      const int32_t* __restrict__ row_ids,
                                                      const int32_t* __restrict__ cols, const float* __restrict__ vals,
-                                                     int32_t log2_rb, int32_t* stream) {
+                                                     int32_t log2_rb, int32_t compact, int32_t phase_width,
+                                                     int32_t* stream) {
   int64_t q = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (q >= n_chunks) return;
   int lane = threadIdx.x & 63;
   const Chunk ck = chunks[q];
   const int lw = (int)(ck.meta & 63u), count = (int)((ck.meta >> 6) & 127u);
   const int hand_over = (int)((ck.meta >> 13) & 1u);
-  // chunk i of quad Q sits at slots 64*i .. 64*i+63 of the quad's three 256-slot arrays
-  int32_t* quad = stream + (q / kChunksPerQuad) * (3 * kChunkSlots * kChunksPerQuad);
+  // chunk i of quad Q sits at slots 64*i .. 64*i+63 of the quad's 256-slot arrays
+  constexpr int kQuadSlots = kChunkSlots * kChunksPerQuad;
+  int32_t* quad = stream + (q / kChunksPerQuad) * ((compact ? 2 : 3) * kQuadSlots);
   const int at = (int)(q % kChunksPerQuad) * kChunkSlots + lane;
   if (count == 0) {  // padding of a group: contributes nothing, hands nothing over
-    quad[at] = 0;
-    quad[kChunkSlots * kChunksPerQuad + at] = 0;
-    quad[2 * kChunkSlots * kChunksPerQuad + at] = -1;
+    quad[at] = compact ? (int32_t)0xF0000000u : 0;
+    quad[kQuadSlots + at] = 0;
+    if (!compact) quad[2 * kQuadSlots + at] = -1;
     return;
   }
   int64_t src;
@@ -487,10 +494,17 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chu
   }
   int32_t col = cols[src];
   float val = vals[src];
-  quad[at] = col;
-  quad[kChunkSlots * kChunksPerQuad + at] = lane < count ? __float_as_int(val) : 0;
-  quad[2 * kChunkSlots * kChunksPerQuad + at] =
-      lane < count ? ((rid & ((1 << log2_rb) - 1)) | (lw << 16) | (hand_over << 22)) : -1;
+  const int local_row = rid & ((1 << log2_rb) - 1);
+  const bool real = lane < count;
+  quad[kQuadSlots + at] = real ? __float_as_int(val) : 0;
+  if (compact) {
+    const uint32_t col_rel = (uint32_t)(col - (col / phase_width) * phase_width);  // a launch covers phase_width columns
+    quad[at] = (int32_t)(col_rel | ((uint32_t)local_row << kCompactColBits) | ((uint32_t)real << 27) |
+                         ((uint32_t)(lw > 6 ? 7 : lw) << 28) | ((uint32_t)hand_over << 31));
+  } else {
+    quad[at] = col;
+    quad[2 * kQuadSlots + at] = real ? (local_row | (lw << 16) | (hand_over << 22)) : -1;
+  }
 }
 
 // --------------------------------------------------------------- host helpers
@@ -507,6 +521,7 @@ struct Blob {  // bump allocator over one device allocation
 // Tuning knobs (environment, read when a hyb object is built):
 //   SPTIR_ROW_BLOCK        rows of Y one wavefront keeps in LDS (power of two, 8..256)
 //   SPTIR_PARTS_PER_PHASE  column partitions swept per SpMM launch (default: chosen from the sizes)
+//   SPTIR_WIDE_STREAM      non-zero: always write the 12-byte stream records
 int log2_row_block_setting(int32_t n_rows) {
   const char* e = getenv("SPTIR_ROW_BLOCK");
   long v = e ? atol(e) : 0;
@@ -671,6 +686,14 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
     cs.log2_rb = log2_row_block_setting(s.n_rows);
     cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
     cs.ppg = parts_per_phase_setting(s.c, s.w, s.n_rows, h->S + h->T);
+    {
+      // the compact stream needs the columns of one launch to fit kCompactColBits and the row block 7 bits
+      const char* e = getenv("SPTIR_WIDE_STREAM");
+      const int64_t max_span = (int64_t)1 << kCompactColBits;
+      bool compact = !(e && atoi(e) != 0) && s.w <= max_span && cs.log2_rb <= kCompactMaxLog2RowBlock;
+      if (compact && (int64_t)cs.ppg * s.w > max_span) cs.ppg = (int32_t)(max_span / s.w);
+      h->compact_stream = compact ? 1 : 0;
+    }
     cs.n_phases = (s.c + cs.ppg - 1) / cs.ppg;
     h->log2_row_block = cs.log2_rb; h->n_row_blocks = cs.n_rb;
     h->parts_per_phase = cs.ppg; h->n_phases = cs.n_phases;
@@ -755,7 +778,7 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
       tmp_chunks = alloc(bytes, actx, stream);  // descriptors are only needed until the stream is packed
       if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
       BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, bytes, stream));  // count 0 marks the padding chunks
-      bytes = sizeof(int32_t) * 3 * kChunkSlots * (size_t)(n_chunks ? n_chunks : 1);
+      bytes = sizeof(int32_t) * (h->compact_stream ? 2 : 3) * kChunkSlots * (size_t)(n_chunks ? n_chunks : 1);
       h->stream = (int32_t*)alloc(bytes, actx, stream);
       if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += bytes;
@@ -768,7 +791,8 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
       int64_t blocks = (n_chunks + 3) / 4;
       if (blocks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
       hipLaunchKernelGGL(k_pack_stream, dim3((unsigned)blocks), dim3(256), 0, stream, (int64_t)n_chunks,
-                         (const Chunk*)tmp_chunks, h->row_ids, h->cols, h->vals, cs.log2_rb, h->stream);
+                         (const Chunk*)tmp_chunks, h->row_ids, h->cols, h->vals, cs.log2_rb, h->compact_stream,
+                         (int32_t)((int64_t)cs.ppg * s.w > 0x7FFFFFFF ? 0x7FFFFFFF : (int64_t)cs.ppg * s.w), h->stream);
     }
     {
       int64_t total = n_chunks;

@@ -270,10 +270,10 @@ constexpr int kHybBlock = 64 * kHybWaves;
 //
 // The unit of the pipeline is a "step": kChunk = kGroups*kSteps slots of a
 // 64-slot chunk (the whole chunk when a lane group is 8 lanes wide).  Chunks
-// come in quads: a quad is a fixed 3 KB record of the stream whose address
-// follows from its list position, so nothing in the loop waits for a
-// descriptor.  A lane requests 16 bytes of each of the quad's three arrays
-// (columns, values, row words) two quads ahead and parks them one quad later
+// come in quads: a quad is a fixed record of the stream (2 KB compact, 3 KB
+// WIDE) whose address follows from its list position, so nothing in the loop
+// waits for a descriptor.  A lane requests 16 bytes of each of the quad's
+// arrays two quads ahead and parks them one quad later
 // in a per-wave LDS ring of two quads; from there every lane group reads the
 // kSteps columns / values it needs with 16-byte LDS reads (all lanes of a group
 // read the same address, which LDS broadcasts).  While step u is multiplied,
@@ -283,18 +283,19 @@ constexpr int kHybBlock = 64 * kHybWaves;
 //
 // The lane groups that share a row add their partial sums up with cross-lane
 // moves; the leading group adds the row sum into the wavefront's LDS tile of Y.
-template <int VEC, int LG, bool IDX32>
+template <int VEC, int LG, bool IDX32, bool WIDE>
 struct HybWalker {
   using S = Shape<VEC, LG>;
   static constexpr int UB = S::kSteps, CS = S::kChunk;
   static constexpr int SUB = kChunkSlots / CS;              // steps per chunk
   static constexpr int kQuadSteps = kChunksPerQuad * SUB;   // steps per quad
   static constexpr int kQuadSlots = kChunksPerQuad * kChunkSlots;
-  static constexpr int kQuadInts = 3 * kQuadSlots;          // [cols | vals | row words]
+  static constexpr int kArrays = WIDE ? 3 : 2;              // [cols | vals | row words] or [col+row words | vals]
+  static constexpr int kQuadInts = kArrays * kQuadSlots;
   static constexpr int kRingInts = 2 * kQuadInts;           // two quads parked per wave
 
   struct Fetched {  // a quad on its way from memory: slots 4*lane .. 4*lane+3 of each array
-    int col[4], val[4], row[4];
+    int col[4], val[4], row[WIDE ? 4 : 1];
   };
 
   const SpmmArgs& a;
@@ -309,23 +310,34 @@ struct HybWalker {
   __device__ __forceinline__ void fetch(int q, Fetched& f) const {
     q = q < n_quads ? q : n_quads - 1;
     const int4* rec = reinterpret_cast<const int4*>(quads + (size_t)q * kQuadInts);
-    const int4 c = rec[lane], v = rec[kQuadSlots / 4 + lane], r = rec[2 * kQuadSlots / 4 + lane];
+    const int4 c = rec[lane], v = rec[kQuadSlots / 4 + lane];
     f.col[0] = c.x; f.col[1] = c.y; f.col[2] = c.z; f.col[3] = c.w;
     f.val[0] = v.x; f.val[1] = v.y; f.val[2] = v.z; f.val[3] = v.w;
-    f.row[0] = r.x; f.row[1] = r.y; f.row[2] = r.z; f.row[3] = r.w;
+    if constexpr (WIDE) {
+      const int4 r = rec[2 * kQuadSlots / 4 + lane];
+      f.row[0] = r.x; f.row[1] = r.y; f.row[2] = r.z; f.row[3] = r.w;
+    }
   }
+
+  // what a slot's row word says (WIDE: its own array; compact: the upper bits of the column word)
+  static __device__ __forceinline__ int local_row(int r) { return WIDE ? (r & 0xFFFF) : ((r >> kCompactColBits) & 127); }
+  static __device__ __forceinline__ bool row_valid(int r) { return WIDE ? r >= 0 : ((r >> 27) & 1) != 0; }
 
   __device__ __forceinline__ int* slot_of(int q) const { return ring + (q & 1) * kQuadInts; }
 
-  // parks quad q; m[i] receives the facts of its chunk i (wave-uniform): log2w | hand-over << 6.
+  // parks quad q; m[i] receives the facts of its chunk i (wave-uniform), taken from the chunk's slot 0:
+  // log2w | hand-over << 6 (WIDE) or log2w code | hand-over << 3 (compact).
   // (slot 0 of a chunk is a real slot, or the whole chunk is padding and reads as "nothing to hand over")
   __device__ __forceinline__ void park(int q, const Fetched& f, int (&m)[kChunksPerQuad]) const {
     int4* st = reinterpret_cast<int4*>(slot_of(q));
     st[lane] = make_int4(f.col[0], f.col[1], f.col[2], f.col[3]);
     st[kQuadSlots / 4 + lane] = make_int4(f.val[0], f.val[1], f.val[2], f.val[3]);
-    st[2 * kQuadSlots / 4 + lane] = make_int4(f.row[0], f.row[1], f.row[2], f.row[3]);
+    if constexpr (WIDE) st[2 * kQuadSlots / 4 + lane] = make_int4(f.row[0], f.row[1], f.row[2], f.row[3]);
 #pragma unroll
-    for (int i = 0; i < kChunksPerQuad; ++i) m[i] = __builtin_amdgcn_readlane(f.row[0], i * (kChunkSlots / 4)) >> 16;
+    for (int i = 0; i < kChunksPerQuad; ++i) {
+      if constexpr (WIDE) m[i] = __builtin_amdgcn_readlane(f.row[0], i * (kChunkSlots / 4)) >> 16;
+      else m[i] = (int)((unsigned)__builtin_amdgcn_readlane(f.col[0], i * (kChunkSlots / 4)) >> 28);
+    }
   }
 
   // UB consecutive ints of the ring (UB is 4 or 8; the offset is a multiple of UB): 16-byte LDS reads
@@ -345,13 +357,14 @@ struct HybWalker {
   __device__ __forceinline__ void issue(const int (&c)[UB], float (&x)[UB][VEC]) const {
 #pragma unroll
     for (int j = 0; j < UB; ++j) {
+      const unsigned col = WIDE ? (unsigned)c[j] : ((unsigned)c[j] & ((1u << kCompactColBits) - 1u));
       if constexpr (IDX32) {
         // column ids are below 2^24 here, so the 24-bit multiply-add is exact
-        unsigned off = __umul24((unsigned)c[j], row_bytes) + lane_bytes;
+        unsigned off = __umul24(col, row_bytes) + lane_bytes;
         load_vec<VEC>(x[j], reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.X) + off));
       } else {
         load_vec<VEC>(x[j], reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.X) +
-                                                            (size_t)c[j] * row_bytes + lane_bytes));
+                                                            (size_t)col * row_bytes + lane_bytes));
       }
     }
   }
@@ -359,10 +372,11 @@ struct HybWalker {
   // step s of the quad parked at `st` whose chunk facts are m[]
   __device__ __forceinline__ void consume(const int* st, int s, int meta, const float (&v)[UB],
                                           const float (&x)[UB][VEC]) {
-    const int lw = meta & 63;
-    const bool hand_over = (meta >> 6) & 1;
+    // (compact: a chunk cut from a row wider than 64 slots carries code 7; every test below only asks lw >= 6)
+    const int lw = WIDE ? (meta & 63) : (meta & 7);
+    const bool hand_over = ((meta >> (WIDE ? 6 : 3)) & 1) != 0;
     const int sub = s & (SUB - 1);
-    const int* rows = st + 2 * kQuadSlots;
+    const int* rows = st + (WIDE ? 2 * kQuadSlots : 0);
     if (lw < S::kLog2Steps) {
       // several rows inside the group's share: hand each one over as it ends
       int r[UB];
@@ -373,7 +387,7 @@ struct HybWalker {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
         if (((j + 1) & width_mask) == 0) {
-          sink(r[j] & 0xFFFF, r[j] >= 0, acc);
+          sink(local_row(r[j]), row_valid(r[j]), acc);
 #pragma unroll
           for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
         }
@@ -397,7 +411,7 @@ struct HybWalker {
     //  chunk even groups past the last real slot take part; its row sits in the chunk's slot 0)
     const int chunk0 = (s - sub) * CS;
     const int r = rows[one_row_chunk ? chunk0 : first_slot(s) - (g - g_first) * UB];
-    sink(r & 0xFFFF, g == g_first && r >= 0, acc);
+    sink(local_row(r), g == g_first && row_valid(r), acc);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
   }
@@ -462,10 +476,10 @@ struct HybWalker {
   }
 };
 
-template <int VEC, int LG, bool IDX32>
+template <int VEC, int LG, bool IDX32, bool WIDE>
 __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   using S = Shape<VEC, LG>;
-  using W = HybWalker<VEC, LG, IDX32>;
+  using W = HybWalker<VEC, LG, IDX32, WIDE>;
   extern __shared__ __align__(16) float smem[];  // per wavefront: [row_block][kTile] tile of Y, then its quad ring
   int64_t unit;
   int tile_id;
@@ -497,7 +511,7 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   const int64_t c0 = a.rb_chunk_ptr[rb];
   const int n_list = (int)(a.rb_chunk_ptr[rb + 1] - c0);  // a multiple of kChunksPerQuad
   const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
-  W wk{a, a.stream + (size_t)c0 * (3 * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
+  W wk{a, a.stream + (size_t)c0 * (W::kArrays * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
        (unsigned)a.feat * 4u, (unsigned)f_read * 4u, TileSink<VEC, LG>{tile, fl, f_active}, {}};
   wk.run();
 
@@ -586,21 +600,27 @@ bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   return a0 < b0 + nb && b0 < a0 + na;
 }
 
-template <int VEC, int LG, bool IDX32>
+template <int VEC, int LG, bool IDX32, bool WIDE>
 void launch_hyb_one(const Geometry& g, size_t lds_bytes, hipStream_t stream, const SpmmArgs& a) {
   static bool raised = false;  // row blocks of 1024 rows need more than the default 64 KB of dynamic LDS
   if (!raised && lds_bytes > 48 * 1024) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_hyb<VEC, LG, IDX32>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_hyb<VEC, LG, IDX32, WIDE>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
     raised = true;
   }
-  hipLaunchKernelGGL((k_spmm_hyb<VEC, LG, IDX32>), dim3((unsigned)g.grid), dim3(kHybBlock), lds_bytes, stream, a);
+  hipLaunchKernelGGL((k_spmm_hyb<VEC, LG, IDX32, WIDE>), dim3((unsigned)g.grid), dim3(kHybBlock), lds_bytes, stream,
+                     a);
 }
 
 template <int VEC, int LG>
-void launch_hyb(const Geometry& g, size_t lds_bytes, hipStream_t stream, const SpmmArgs& a, bool idx32) {
-  if (idx32) launch_hyb_one<VEC, LG, true>(g, lds_bytes, stream, a);
-  else launch_hyb_one<VEC, LG, false>(g, lds_bytes, stream, a);
+void launch_hyb(const Geometry& g, size_t lds_bytes, hipStream_t stream, const SpmmArgs& a, bool idx32, bool wide) {
+  if (wide) {
+    if (idx32) launch_hyb_one<VEC, LG, true, true>(g, lds_bytes, stream, a);
+    else launch_hyb_one<VEC, LG, false, true>(g, lds_bytes, stream, a);
+  } else {
+    if (idx32) launch_hyb_one<VEC, LG, true, false>(g, lds_bytes, stream, a);
+    else launch_hyb_one<VEC, LG, false, false>(g, lds_bytes, stream, a);
+  }
 }
 
 }  // namespace
@@ -623,16 +643,21 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
   a.X = X; a.Y = Y; a.n_rows = h->n_rows; a.n_row_blocks = h->n_row_blocks; a.log2_row_block = h->log2_row_block;
   a.feat = feat; a.n_tiles = g.n_tiles; a.map_mode = g.map_mode; a.map_param = g.map_param;
   // per wavefront: its Y tile and its ring of two quads
+  const bool wide = !h->compact_stream;
   const size_t lds_bytes = (size_t)kHybWaves * (sizeof(float) * ((size_t)g.vec * g.lg << h->log2_row_block) +
-                                                sizeof(int) * 2 * 3 * kChunkSlots * kChunksPerQuad);
-  const bool idx32 = h->n_cols < (1 << 24) && x_bytes < ((size_t)1 << 32);
+                                                sizeof(int) * 2 * (wide ? 3 : 2) * kChunkSlots * kChunksPerQuad);
+  // A compact stream holds columns relative to the first column of its launch, which moves into the X pointer.
+  const size_t span = (size_t)h->parts_per_phase * (size_t)h->w;
+  const bool idx32 = wide ? (h->n_cols < (1 << 24) && x_bytes < ((size_t)1 << 32))
+                          : (span * feat * sizeof(float) < ((size_t)1 << 32));
   for (int phase = 0; phase < h->n_phases; ++phase) {
     a.rb_chunk_ptr = h->rb_chunk_ptr + (size_t)phase * h->n_row_blocks;
     a.accumulate = phase > 0;
-    if (g.vec == 4 && g.lg == 8) launch_hyb<4, 8>(g, lds_bytes, stream, a, idx32);
-    else if (g.vec == 4) launch_hyb<4, 4>(g, lds_bytes, stream, a, idx32);
-    else if (g.vec == 2) launch_hyb<2, 16>(g, lds_bytes, stream, a, idx32);
-    else launch_hyb<1, 32>(g, lds_bytes, stream, a, idx32);
+    a.X = wide ? X : X + (size_t)phase * span * (size_t)feat;
+    if (g.vec == 4 && g.lg == 8) launch_hyb<4, 8>(g, lds_bytes, stream, a, idx32, wide);
+    else if (g.vec == 4) launch_hyb<4, 4>(g, lds_bytes, stream, a, idx32, wide);
+    else if (g.vec == 2) launch_hyb<2, 16>(g, lds_bytes, stream, a, idx32, wide);
+    else launch_hyb<1, 32>(g, lds_bytes, stream, a, idx32, wide);
   }
   SPTIR_HIP(hipGetLastError());
   return SPTIR_OK;

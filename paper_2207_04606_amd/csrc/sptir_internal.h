@@ -29,6 +29,11 @@ constexpr int kChunkSlots = 64;
 constexpr int kRowLog2W = 31;
 constexpr int kChunksPerQuad = 4;  // chunks the SpMM kernel fetches with one load per lane and array
 constexpr int kBuildBlock = 256;  // rows per workgroup in the builder kernels
+// Compact stream records spend 8 bytes per slot instead of 12: one word holds the column relative to the first
+// column of the launch (bits 0..19), the row relative to the row block (20..26), "slot is real" (27), the chunk's
+// log2w code (28..30; 7 = cut from a row wider than a chunk) and its hand-over flag (31); the other word the value.
+constexpr int kCompactColBits = 20;
+constexpr int kCompactMaxLog2RowBlock = 7;
 
 }  // namespace sptir
 
@@ -47,7 +52,8 @@ struct sptir_hyb {
   int32_t* cols;             // device [S+T]
   float* vals;               // device [S+T]
   int32_t* row_len;          // device [R+M], real length of every ELL row / remainder piece
-  int32_t* stream;           // device [n_chunks * 192]: the chunks as fixed records, grouped by (phase, row block)
+  int32_t* stream;           // device [n_chunks * 128 or 192]: the chunks as fixed records, grouped by (phase, row block)
+  int32_t compact_stream;    // 1: 8-byte slots (columns relative to the launch), 0: 12-byte slots (global columns)
   int64_t* rb_chunk_ptr;     // device [n_phases * n_row_blocks + 1], first chunk of each group
   int64_t n_chunks;
   int32_t log2_row_block;    // rows of Y one wavefront accumulates in LDS (power of two)

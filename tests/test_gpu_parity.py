@@ -266,3 +266,46 @@ def test_spmm_on_side_stream_and_repeat(gpu_lib):
             gpu_lib.sptir_spmm(hyb, d.X, Y, stream=s)
     s.synchronize()
     assert_y_close(Y.cpu().numpy(), Yr, Sr, what="side stream")
+
+
+@pytest.mark.parametrize("knobs", [
+    {"SPTIR_WIDE_STREAM": "1"}, {"SPTIR_PARTS_PER_PHASE": "1"}, {"SPTIR_PARTS_PER_PHASE": "2", "SPTIR_WIDE_STREAM": "1"},
+    {"SPTIR_ROW_BLOCK": "8"}, {"SPTIR_ROW_BLOCK": "64", "SPTIR_PARTS_PER_PHASE": "3"}, {"SPTIR_ROW_BLOCK": "128"},
+    {"SPTIR_ROW_BLOCK": "256"}])
+def test_spmm_launch_plan_knobs(gpu_lib, monkeypatch, knobs):
+    """Every launch plan the builder can choose (record form, partitions per launch, rows per wavefront) computes
+    the same Y; two runs on one handle agree bit for bit (no atomics anywhere on the path)."""
+    say(f"[knobs] {knobs}")
+    for key, value in knobs.items():
+        monkeypatch.setenv(key, value)
+    for feat, c, k in ((32, 5, 4), (7, 3, 2), (128, 4, 7)):
+        w = ragged_workload(300 + feat, 2300, 2100, feat, max_deg=1500, long_rows=8)
+        d, hyb, got, want, info = build_both(gpu_lib, w, c, k)
+        assert_same_hyb(got, want)
+        if "SPTIR_PARTS_PER_PHASE" in knobs:
+            ppg = int(knobs["SPTIR_PARTS_PER_PHASE"])
+            assert info["n_phases"] == -(-c // ppg)
+        if "SPTIR_ROW_BLOCK" in knobs:
+            assert info["row_block"] == int(knobs["SPTIR_ROW_BLOCK"])
+        Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+        gpu_lib.sptir_spmm(hyb, d.X, Y)
+        Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+        assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"{knobs} feat={feat}")
+        Y2 = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+        gpu_lib.sptir_spmm(hyb, d.X, Y2)
+        assert torch.equal(Y, Y2)
+
+
+@pytest.mark.parametrize("c", [1, 2, 4, 9])
+def test_spmm_many_columns(gpu_lib, c):
+    """More than 2^20 columns per partition (c = 1, 2) cannot use launch-relative 20-bit columns; c = 4 can, but
+    only one partition per launch; c = 9 fits three."""
+    n_rows, n_cols, feat = 700, 2_500_000, 4
+    say(f"[many columns] c={c}")
+    w = ragged_workload(900 + c, n_rows, n_cols, feat, max_deg=400, long_rows=4)
+    d, hyb, got, want, info = build_both(gpu_lib, w, c, 5)
+    assert_same_hyb(got, want)
+    Y = torch.full((n_rows, feat), float("nan"), device="cuda")
+    gpu_lib.sptir_spmm(hyb, d.X, Y)
+    Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+    assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"many columns c={c}")
