@@ -199,7 +199,7 @@ def main():
         "bound": "hbm", "achieved": round(per_launch_bytes / per_launch_ms / 1e6, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(per_launch_bytes / per_launch_ms / 1e6 / HBM_PEAK_GBS, 4),
         "traffic": read_traffic("social_feat128"),
-        "kernel": "k_spmm_hyb<4, 8, true>", "launches_per_step": info["n_phases"],
+        "kernel": "k_spmm_hyb<4, 8, true, false>", "launches_per_step": info["n_phases"],
         "avg_launch_ms": round(per_launch_ms, 4), "algorithmic_bytes_per_launch": per_launch_bytes,
         # the path is a cache-served gather, not an HBM stream: each stored slot pulls feat*4 bytes of X
         # through the vector-memory return path, whose peak is 64 B/clk/CU
@@ -226,6 +226,17 @@ def main():
         X = torch.from_numpy(X_host_128).to(dev)
         Y = torch.empty(w.n_rows, 128, device=dev)
         out["cold_ms_per_step"] = round(time_cold(sptir, torch, hyb, X, Y, 10, scratch), 4)
+        # the single-pass CSR kernel ("no-hyb") on the same graph and X, for the comparison section 4.2.1 makes
+        for _ in range(3):
+            sptir.sptir_spmm_csr(w.n_rows, w.n_cols, indptr, indices, values, X, Y)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            sptir.sptir_spmm_csr(w.n_rows, w.n_cols, indptr, indices, values, X, Y)
+        torch.cuda.synchronize()
+        csr_ms = (time.perf_counter() - t0) * 1e3 / 10
+        out["no_hyb_csr"] = {"ms_per_step": round(csr_ms, 4), "gflops": round(2.0 * w.nnz * 128 / csr_ms / 1e6, 1),
+                             "hyb_speedup": round(csr_ms / head["wall_ms"], 3)}
         del X, Y
         hyb.destroy()
         del indptr, indices, values
