@@ -12,6 +12,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -73,18 +74,20 @@ __global__ void k_validate_rows(int32_t n_rows, int64_t nnz, const int32_t* __re
 
 __global__ void k_validate_elems(int64_t nnz, int32_t n_cols, const int32_t* __restrict__ indices,
                                  unsigned long long* flags) {
-  int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  bool descent = false, range = false;
-  if (q < nnz) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  unsigned int descents = 0;
+  bool range = false;
+  for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nnz; q += stride) {
     int32_t col = indices[q];
-    range = (col < 0) || (col >= n_cols);
-    descent = (q > 0) && (col <= indices[q - 1]);
+    range |= (col < 0) || (col >= n_cols);
+    descents += (q > 0) && (col <= indices[q - 1]);
   }
-  unsigned long long d = __ballot(descent);
-  unsigned long long g = __ballot(range);
+  // a grid-wide count through one address: one atomic per wavefront, a few thousand in all
+  for (int d = 32; d > 0; d >>= 1) descents += __shfl_down(descents, d, 64);
+  unsigned long long any_range = __ballot(range);
   if ((threadIdx.x & 63) == 0) {
-    if (d) atomicAdd(&flags[2], (unsigned long long)__popcll(d));
-    if (g) flags[1] = 1;
+    if (descents) atomicAdd(&flags[2], (unsigned long long)descents);
+    if (any_range) flags[1] = 1;
   }
 }
 
@@ -337,7 +340,10 @@ __device__ __forceinline__ bool decode_cell(const CellShape& cs, int64_t cell, c
   return r->q_hi > r->q_lo;
 }
 
-__device__ __forceinline__ int chunks_of_length(int len) { return (len + kChunkSlots - 1) / kChunkSlots; }
+// (a long piece contributes no chunks: a workgroup of its own sums it)
+__device__ __forceinline__ int chunks_of_length(int len) {
+  return len > kLongRowSlots ? 0 : (len + kChunkSlots - 1) / kChunkSlots;
+}
 
 // Rows of the buckets of width 8..64 are taken eight at a time ("row sets"): chunk t of a set holds
 // entries 8t .. 8t+7 of each of its eight rows, one row per octet, so that in the SpMM kernel every lane
@@ -352,7 +358,8 @@ __device__ __forceinline__ int set_chunks(const int32_t* __restrict__ row_len, i
 }
 
 __global__ void k_cell_chunk_counts(CellShape cs, int64_t n_cells, const int32_t* __restrict__ bin_rb_ptr,
-                                    const int32_t* __restrict__ row_len, long long* cell_chunks) {
+                                    const int32_t* __restrict__ row_len, long long* cell_chunks,
+                                    unsigned long long* n_long) {
   int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (cell >= n_cells) return;
   CellRef r;
@@ -365,33 +372,49 @@ __global__ void k_cell_chunk_counts(CellShape cs, int64_t n_cells, const int32_t
       int rows_per_chunk = kChunkSlots >> r.bin;
       n += (r.q_hi - q + rows_per_chunk - 1) / rows_per_chunk;
     } else {
-      for (; q < r.q_hi; ++q) n += chunks_of_length(row_len[q]);
+      for (; q < r.q_hi; ++q) {
+        n += chunks_of_length(row_len[q]);
+        if (row_len[q] > kLongRowSlots) atomicAdd(n_long, 1ull);
+      }
     }
   }
   cell_chunks[cell] = n;
 }
 
-// one thread per (phase, row block) group: the pad cell gets what is missing to a multiple of kChunksPerQuad
-__global__ void k_group_pad(CellShape cs, int64_t n_groups, long long* cell_chunks) {
+// One thread per (phase, row block) group: the pad cell gets what is missing to a multiple of kChunksPerQuad,
+// the group's counts become their exclusive prefix inside the group, group_total[grp] their sum.
+__global__ void k_group_scan(CellShape cs, int64_t n_groups, long long* cell_chunks, long long* group_total) {
   int64_t grp = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (grp >= n_groups) return;
   const int cpg = cells_per_group(cs);
   long long* c = cell_chunks + grp * cpg;
   long long total = 0;
-  for (int i = 0; i < cpg - 1; ++i) total += c[i];
-  c[cpg - 1] = (kChunksPerQuad - total % kChunksPerQuad) % kChunksPerQuad;
+  for (int i = 0; i < cpg - 1; ++i) {
+    long long n = c[i];
+    c[i] = total;
+    total += n;
+  }
+  c[cpg - 1] = total;
+  group_total[grp] = total + (kChunksPerQuad - total % kChunksPerQuad) % kChunksPerQuad;
 }
+
+constexpr int kGroupSeq = 1024;  // groups per sequence of the two-level scan over group totals
 
 __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t* __restrict__ bin_rb_ptr,
                                    const long long* __restrict__ cell_first_chunk,
-                                   const int32_t* __restrict__ row_len, const int64_t* __restrict__ bucket_row_ptr,
+                                   const long long* __restrict__ group_first_chunk,
+                                   const long long* __restrict__ seq_first_chunk,
+                                   const int32_t* __restrict__ row_len, const int32_t* __restrict__ row_ids,
+                                   const int64_t* __restrict__ bucket_row_ptr,
                                    const int64_t* __restrict__ bucket_slot_ptr, const int64_t* __restrict__ rem_ptr,
-                                   int64_t S, Chunk* chunks, int64_t* rb_chunk_ptr) {
+                                   int64_t S, Chunk* chunks, int64_t* rb_chunk_ptr, LongPiece* long_pieces,
+                                   unsigned long long* long_cursor) {
   int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (cell >= n_cells) return;
   CellRef r;
   bool any = decode_cell(cs, cell, bin_rb_ptr, &r);
-  int64_t it = cell_first_chunk[cell];
+  const int64_t grp = cell / cells_per_group(cs);
+  int64_t it = cell_first_chunk[cell] + group_first_chunk[grp] + seq_first_chunk[grp / kGroupSeq];
   const int64_t group_first_cell = cell - cell % cells_per_group(cs);
   if (cell == group_first_cell) rb_chunk_ptr[(int64_t)r.phase * cs.n_rb + r.rb] = it;
   if (!any) return;
@@ -403,6 +426,11 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
     ck.row0 = row0;
     ck.meta = (uint32_t)lw | ((uint32_t)count << 6) | (row_ends ? (1u << 13) : 0u) | extra;
     chunks[it++] = ck;
+  };
+  auto set_aside = [&](int64_t slot0, int32_t q, int len) {  // a long piece: listed in no particular order
+    LongPiece lp;
+    lp.slot0 = slot0; lp.row = row_ids[q]; lp.len = len; lp.q = q; lp.pad_ = 0;
+    long_pieces[atomicAdd(long_cursor, 1ull)] = lp;
   };
   if (r.bin <= cs.k) {
     int64_t b = (int64_t)r.p * (cs.k + 1) + r.bin;
@@ -427,6 +455,7 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
       for (int32_t q = q_plain; q < r.q_hi; ++q) {
         int len = row_len[q];
         int64_t row_slot = first_slot + (int64_t)(q - r.q_lo) * width;
+        if (len > kLongRowSlots) { set_aside(row_slot, q, len); continue; }
         for (int off = 0; off < len; off += kChunkSlots)
           emit(row_slot + off, q, kRowLog2W, len - off < kChunkSlots ? len - off : kChunkSlots,
                off + kChunkSlots >= len);
@@ -436,6 +465,7 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
     for (int32_t q = r.q_lo; q < r.q_hi; ++q) {
       int64_t begin = rem_ptr[q - cs.R];
       int len = row_len[q];
+      if (len > kLongRowSlots) { set_aside(S + begin, q, len); continue; }
       for (int off = 0; off < len; off += kChunkSlots)
         emit(S + begin + off, q, kRowLog2W, len - off < kChunkSlots ? len - off : kChunkSlots,
              off + kChunkSlots >= len);
@@ -628,8 +658,8 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
       hipLaunchKernelGGL(k_validate_rows, dim3((s.n_rows + 255) / 256), dim3(256), 0, stream, s.n_rows, csr->nnz,
                          csr->indptr, csr->indices, d_flags);
     if (csr->nnz > 0)
-      hipLaunchKernelGGL(k_validate_elems, dim3((unsigned)((csr->nnz + 255) / 256)), dim3(256), 0, stream, csr->nnz,
-                         s.n_cols, csr->indices, d_flags);
+      hipLaunchKernelGGL(k_validate_elems, dim3((unsigned)std::min<int64_t>((csr->nnz + 255) / 256, 4096)), dim3(256),
+                         0, stream, csr->nnz, s.n_cols, csr->indices, d_flags);
     BUILD_HIP(hipGetLastError());
     BUILD_HIP(hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, stream));
     BUILD_HIP(hipStreamSynchronize(stream));
@@ -703,12 +733,19 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
     if (n_cells > 0x7FFFFFFF || n_bounds > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
     const size_t o_bounds = tmp2.reserve(sizeof(int32_t) * (size_t)(n_bounds ? n_bounds : 1));
     const size_t o_cell_chunks = tmp2.reserve(sizeof(long long) * (size_t)(n_cells ? n_cells : 1));
-    const size_t o_cell_total = tmp2.reserve(sizeof(long long));
+    const int64_t n_seq = (n_groups + kGroupSeq - 1) / kGroupSeq;
+    const size_t o_group_tot = tmp2.reserve(sizeof(long long) * (size_t)(n_seq ? n_seq * kGroupSeq : 1));
+    const size_t o_seq_tot = tmp2.reserve(sizeof(long long) * (size_t)(n_seq ? n_seq : 1));
+    const size_t o_cell_total = tmp2.reserve(2 * sizeof(long long));  // chunks in all, long pieces in all
+    const size_t o_long_cursor = tmp2.reserve(sizeof(long long));
     tmp2.base = (char*)alloc(tmp2.size, actx, stream);
     if (!tmp2.base) { st = SPTIR_ERR_ALLOC; goto fail; }
     int32_t* d_bounds = (int32_t*)(tmp2.base + o_bounds);
     long long* d_cell_chunks = (long long*)(tmp2.base + o_cell_chunks);
+    long long* d_group_tot = (long long*)(tmp2.base + o_group_tot);
+    long long* d_seq_tot = (long long*)(tmp2.base + o_seq_tot);
     long long* d_cell_total = (long long*)(tmp2.base + o_cell_total);
+    unsigned long long* d_long_cursor = (unsigned long long*)(tmp2.base + o_long_cursor);
 
     // ---- the handle's device arrays (the chunk list follows further down)
     struct { void** p; size_t bytes; } wanted[] = {
@@ -758,21 +795,31 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
     BUILD_HIP(hipGetLastError());
 
     // ---- chunk descriptors, grouped by (phase, row block)
-    long long n_chunks = 0;
+    long long n_chunks = 0, n_long = 0;
     if (n_cells > 0) {
+      long long totals[2] = {0, 0};
+      BUILD_HIP(hipMemsetAsync(d_group_tot, 0, sizeof(long long) * (size_t)n_seq * kGroupSeq, stream));
+      BUILD_HIP(hipMemsetAsync(d_cell_total, 0, 2 * sizeof(long long), stream));
+      BUILD_HIP(hipMemsetAsync(d_long_cursor, 0, sizeof(long long), stream));
       hipLaunchKernelGGL(k_cell_bounds, dim3((unsigned)((n_bounds + 255) / 256)), dim3(256), 0, stream, cs,
                          h->bucket_row_ptr, h->rem_part_ptr, h->row_ids, d_bounds);
       hipLaunchKernelGGL(k_cell_chunk_counts, dim3((unsigned)((n_cells + 255) / 256)), dim3(256), 0, stream, cs,
-                         n_cells, d_bounds, h->row_len, d_cell_chunks);
-      hipLaunchKernelGGL(k_group_pad, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, stream, cs, n_groups,
-                         d_cell_chunks);
-      hipLaunchKernelGGL(k_scan_sequences<long long>, dim3(1), dim3(kBuildBlock), 0, stream, d_cell_chunks,
-                         (int32_t)n_cells, d_cell_total);
+                         n_cells, d_bounds, h->row_len, d_cell_chunks, (unsigned long long*)(d_cell_total + 1));
+      hipLaunchKernelGGL(k_group_scan, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, stream, cs, n_groups,
+                         d_cell_chunks, d_group_tot);
+      // chunks before a cell = its prefix inside the group + the group's inside its sequence + the sequence's
+      hipLaunchKernelGGL(k_scan_sequences<long long>, dim3((unsigned)n_seq), dim3(kBuildBlock), 0, stream,
+                         d_group_tot, (int32_t)kGroupSeq, d_seq_tot);
+      hipLaunchKernelGGL(k_scan_sequences<long long>, dim3(1), dim3(kBuildBlock), 0, stream, d_seq_tot,
+                         (int32_t)n_seq, d_cell_total);
       BUILD_HIP(hipGetLastError());
-      BUILD_HIP(hipMemcpyAsync(&n_chunks, d_cell_total, sizeof(long long), hipMemcpyDeviceToHost, stream));
+      BUILD_HIP(hipMemcpyAsync(totals, d_cell_total, 2 * sizeof(long long), hipMemcpyDeviceToHost, stream));
       BUILD_HIP(hipStreamSynchronize(stream));
+      n_chunks = totals[0];
+      n_long = totals[1];
     }
     h->n_chunks = n_chunks;
+    if (n_long > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
     {
       size_t bytes = sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1);
       tmp_chunks = alloc(bytes, actx, stream);  // descriptors are only needed until the stream is packed
@@ -782,11 +829,47 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
       h->stream = (int32_t*)alloc(bytes, actx, stream);
       if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += bytes;
+      if (n_long > 0) {
+        bytes = sizeof(LongPiece) * (size_t)n_long;
+        h->long_pieces = (LongPiece*)alloc(bytes, actx, stream);
+        if (!h->long_pieces) { st = SPTIR_ERR_ALLOC; goto fail; }
+        h->device_bytes += bytes;
+      }
     }
     if (n_cells > 0)
       hipLaunchKernelGGL(k_cell_fill_chunks, dim3((unsigned)((n_cells + 255) / 256)), dim3(256), 0, stream, cs,
-                         n_cells, d_bounds, d_cell_chunks, h->row_len, h->bucket_row_ptr, h->bucket_slot_ptr,
-                         h->rem_ptr, h->S, (Chunk*)tmp_chunks, h->rb_chunk_ptr);
+                         n_cells, d_bounds, d_cell_chunks, d_group_tot, d_seq_tot, h->row_len, h->row_ids,
+                         h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_ptr, h->S, (Chunk*)tmp_chunks,
+                         h->rb_chunk_ptr, h->long_pieces, d_long_cursor);
+    if (n_long > 0) {
+      // The long pieces arrive in no particular order: sort them by (row, partition) on the host, so that
+      // one workgroup sums all pieces of a row in a fixed order.  There are few of them by construction
+      // (each holds more than kLongRowSlots non-zeros).
+      std::vector<LongPiece> lp((size_t)n_long);
+      BUILD_HIP(hipMemcpyAsync(lp.data(), h->long_pieces, sizeof(LongPiece) * lp.size(), hipMemcpyDeviceToHost,
+                               stream));
+      BUILD_HIP(hipStreamSynchronize(stream));
+      std::sort(lp.begin(), lp.end(), [](const LongPiece& x, const LongPiece& y) {
+        return x.row != y.row ? x.row < y.row : x.q < y.q;
+      });
+      std::vector<int32_t> rows, ptr;
+      for (size_t i = 0; i < lp.size(); ++i) {
+        if (i == 0 || lp[i].row != lp[i - 1].row) { rows.push_back(lp[i].row); ptr.push_back((int32_t)i); }
+      }
+      ptr.push_back((int32_t)lp.size());
+      h->n_long_rows = (int32_t)rows.size();
+      h->long_rows = (int32_t*)alloc(sizeof(int32_t) * rows.size(), actx, stream);
+      h->long_piece_ptr = (int32_t*)alloc(sizeof(int32_t) * ptr.size(), actx, stream);
+      if (!h->long_rows || !h->long_piece_ptr) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += sizeof(int32_t) * (rows.size() + ptr.size());
+      BUILD_HIP(hipMemcpyAsync(h->long_pieces, lp.data(), sizeof(LongPiece) * lp.size(), hipMemcpyHostToDevice,
+                               stream));
+      BUILD_HIP(hipMemcpyAsync(h->long_rows, rows.data(), sizeof(int32_t) * rows.size(), hipMemcpyHostToDevice,
+                               stream));
+      BUILD_HIP(hipMemcpyAsync(h->long_piece_ptr, ptr.data(), sizeof(int32_t) * ptr.size(), hipMemcpyHostToDevice,
+                               stream));
+      BUILD_HIP(hipStreamSynchronize(stream));  // the host vectors go out of scope
+    }
     if (n_chunks > 0) {
       int64_t blocks = (n_chunks + 3) / 4;
       if (blocks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }

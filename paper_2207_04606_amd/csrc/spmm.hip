@@ -569,6 +569,86 @@ __global__ __launch_bounds__(64 * kCsrWaves) void k_spmm_csr(CsrArgs a) {
                              lane, f_active, sink);
 }
 
+// ---------------------------------------------------------------- long rows
+// A row piece with more than kLongRowSlots real entries would keep one wavefront busy long after the rest of
+// the launch has drained, so the builder sets such pieces aside.  Here one workgroup of kLongWaves wavefronts
+// takes all long pieces of one row: every wavefront sums a contiguous share of every piece, the shares meet
+// in LDS in wavefront order (fixed, so the result does not change from run to run), and wavefront 0 adds
+// the total to the row of Y, which the chunk-list launches have written before (same stream).
+struct LongArgs {
+  const int32_t* long_rows;
+  const int32_t* long_piece_ptr;
+  const LongPiece* long_pieces;
+  const int32_t* cols;
+  const float* vals;
+  const float* X;
+  float* Y;
+  int32_t n_long_rows;
+  int32_t feat;
+  int32_t n_tiles;
+  int32_t map_mode;
+  int32_t map_param;
+};
+
+constexpr int kLongWaves = 16;
+
+template <int VEC>
+struct RegisterSink {  // adds the row sum the walk hands over to a running total in registers
+  float* total;
+  __device__ __forceinline__ void operator()(int, bool valid, const float (&acc)[VEC]) const {
+    if (valid) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) total[e] += acc[e];
+    }
+  }
+};
+
+template <int VEC, int LG>
+__global__ __launch_bounds__(64 * kLongWaves) void k_spmm_long(LongArgs a) {
+  using S = Shape<VEC, LG>;
+  __shared__ float partial[kLongWaves][S::kTile];
+  int64_t unit;
+  int tile_id;
+  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
+  if (unit >= a.n_long_rows) return;  // (whole workgroup)
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int lane = threadIdx.x & 63;
+  const int fl = lane & (LG - 1);
+  const int f0 = tile_id * S::kTile + fl * VEC;
+  const bool f_active = f0 < a.feat;
+  float total[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) total[e] = 0.f;
+  RegisterSink<VEC> sink{total};
+  const int p_lo = a.long_piece_ptr[unit], p_hi = a.long_piece_ptr[unit + 1];
+  for (int p = p_lo; p < p_hi; ++p) {
+    const LongPiece lp = a.long_pieces[p];
+    // shares are whole chunks, so that every wavefront reads aligned runs of the piece
+    const int n_chunks = (lp.len + S::kChunk - 1) / S::kChunk;
+    const int per_wave = (n_chunks + kLongWaves - 1) / kLongWaves;
+    const int first = wave * per_wave * S::kChunk;
+    const int count = min(lp.len - first, per_wave * S::kChunk);
+    if (count > 0)
+      walk_slots<VEC, LG, false>(a.cols + lp.slot0 + first, a.vals + lp.slot0 + first, nullptr, a.X + f0, a.feat,
+                                 kRowLog2W, count, lane, f_active, sink);
+  }
+  if (lane < LG) {  // the walk leaves a row's sum in the lanes of the first lane group
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) partial[wave][fl * VEC + e] = total[e];
+  }
+  __syncthreads();
+  if (wave == 0 && lane < LG && f_active) {
+    float* y = a.Y + (size_t)a.long_rows[unit] * (size_t)a.feat + f0;
+    float out[VEC];
+    load_vec<VEC>(out, y);
+    for (int w = 0; w < kLongWaves; ++w) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) out[e] += partial[w][fl * VEC + e];
+    }
+    store_vec<VEC>(y, out);
+  }
+}
+
 // launch geometry shared by both SpMM entry points
 struct Geometry {
   int vec, lg, n_tiles, map_mode, map_param;
@@ -658,6 +738,20 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
     else if (g.vec == 4) launch_hyb<4, 4>(g, lds_bytes, stream, a, idx32, wide);
     else if (g.vec == 2) launch_hyb<2, 16>(g, lds_bytes, stream, a, idx32, wide);
     else launch_hyb<1, 32>(g, lds_bytes, stream, a, idx32, wide);
+  }
+  if (h->n_long_rows > 0) {
+    Geometry gl;
+    if (!plan(h->n_long_rows, feat, X, Y, &gl)) return SPTIR_ERR_OVERFLOW;
+    LongArgs la;
+    la.long_rows = h->long_rows; la.long_piece_ptr = h->long_piece_ptr; la.long_pieces = h->long_pieces;
+    la.cols = h->cols; la.vals = h->vals; la.X = X; la.Y = Y;
+    la.n_long_rows = h->n_long_rows; la.feat = feat;
+    la.n_tiles = gl.n_tiles; la.map_mode = gl.map_mode; la.map_param = gl.map_param;
+    dim3 grid((unsigned)gl.grid), block(64 * kLongWaves);
+    if (gl.vec == 4 && gl.lg == 8) hipLaunchKernelGGL((k_spmm_long<4, 8>), grid, block, 0, stream, la);
+    else if (gl.vec == 4) hipLaunchKernelGGL((k_spmm_long<4, 4>), grid, block, 0, stream, la);
+    else if (gl.vec == 2) hipLaunchKernelGGL((k_spmm_long<2, 16>), grid, block, 0, stream, la);
+    else hipLaunchKernelGGL((k_spmm_long<1, 32>), grid, block, 0, stream, la);
   }
   SPTIR_HIP(hipGetLastError());
   return SPTIR_OK;

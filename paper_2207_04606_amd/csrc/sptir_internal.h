@@ -29,6 +29,19 @@ constexpr int kChunkSlots = 64;
 constexpr int kRowLog2W = 31;
 constexpr int kChunksPerQuad = 4;  // chunks the SpMM kernel fetches with one load per lane and array
 constexpr int kBuildBlock = 256;  // rows per workgroup in the builder kernels
+// A row piece (ELL row or remainder piece) with more real entries than this is kept out of the chunk lists,
+// which one wavefront walks alone, and is summed by a whole workgroup in a launch of its own.
+constexpr int kLongRowSlots = 2048;
+
+// One long row piece: `len` consecutive slots of the fused (cols, vals) arrays starting at slot0.
+struct LongPiece {
+  int64_t slot0;
+  int32_t row;
+  int32_t len;
+  int32_t q;  // position in row_ids (orders the pieces of a row by column partition)
+  int32_t pad_;
+};
+static_assert(sizeof(LongPiece) == 24, "LongPiece must stay 24 bytes");
 // Compact stream records spend 8 bytes per slot instead of 12: one word holds the column relative to the first
 // column of the launch (bits 0..19), the row relative to the row block (20..26), "slot is real" (27), the chunk's
 // log2w code (28..30; 7 = cut from a row wider than a chunk) and its hand-over flag (31); the other word the value.
@@ -56,6 +69,11 @@ struct sptir_hyb {
   int32_t compact_stream;    // 1: 8-byte slots (columns relative to the launch), 0: 12-byte slots (global columns)
   int64_t* rb_chunk_ptr;     // device [n_phases * n_row_blocks + 1], first chunk of each group
   int64_t n_chunks;
+  // rows with long pieces: the pieces of long_rows[i] are long_pieces[long_piece_ptr[i] .. long_piece_ptr[i+1])
+  int32_t n_long_rows;
+  int32_t* long_rows;        // device [n_long_rows], ascending
+  int32_t* long_piece_ptr;   // device [n_long_rows + 1]
+  sptir::LongPiece* long_pieces;  // device
   int32_t log2_row_block;    // rows of Y one wavefront accumulates in LDS (power of two)
   int32_t n_row_blocks;
   int32_t parts_per_phase;   // column partitions swept by one SpMM launch
