@@ -98,11 +98,11 @@ typedef struct {
   int64_t n_pad_slots;      /* S + T - nnz */
   int64_t n_rem_pieces;     /* M */
   int64_t n_rem_nnz;        /* T */
-  int64_t n_work_items;     /* chunk descriptors one sptir_spmm call walks */
+  int64_t n_work_items;     /* 64-slot chunks one sptir_spmm call walks (padding chunks included) */
   int32_t item_slots;       /* stored slots per chunk */
-  int32_t row_block;        /* rows of Y one workgroup accumulates on chip */
-  int32_t n_phases;         /* kernel launches per sptir_spmm (groups of column partitions) */
-  int32_t reserved;
+  int32_t row_block;        /* rows of Y one wavefront accumulates on chip */
+  int32_t n_phases;         /* chunk-list launches per sptir_spmm (groups of column partitions) */
+  int32_t n_long_rows;      /* rows with a piece of more than 2048 non-zeros: one more launch sums those */
   int64_t device_bytes;     /* device memory the handle owns */
 } sptir_hyb_info_t;
 
@@ -143,11 +143,16 @@ int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows);
  *   X  device, [n_cols, feat] row-major float32, read only
  *   Y  device, [n_rows, feat] row-major float32, must not overlap X
  *   feat >= 1
- * Only enqueues work on `stream` (no synchronisation, no allocation).
- * Partial sums of a row meet in on-chip float atomic adds whose order is not
- * fixed, so the low-order bits of Y may differ between runs.  A pad slot
- * multiplies X by +0.0f: X must be finite.
- * Errors: INVALID_ARG, HIP.
+ * Only enqueues work on `stream` (no synchronisation, no allocation): one
+ * launch per group of column partitions (sptir_hyb_info_t.n_phases), each
+ * adding to what the earlier ones left in Y, plus one for rows with very long
+ * pieces.  No atomics are used and every sum has a fixed order, so two calls
+ * with the same handle and X give bit-identical Y.  The order differs from
+ * CSR order (sums are regrouped by partition and bucket), so Y matches a CSR
+ * product only up to float rounding.  A pad slot multiplies X by +0.0f: X must
+ * be finite.
+ * Errors: INVALID_ARG, OVERFLOW (feat so large that the launch grid exceeds
+ * 2^31 workgroups), HIP.
  */
 sptir_status_t sptir_spmm(const sptir_hyb_t* hyb, const float* X, float* Y, int32_t feat, void* stream);
 

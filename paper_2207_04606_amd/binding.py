@@ -46,7 +46,7 @@ class _Info(ctypes.Structure):
                 ("n_rem_pieces", ctypes.c_int64), ("n_rem_nnz", ctypes.c_int64),
                 ("n_work_items", ctypes.c_int64), ("item_slots", ctypes.c_int32),
                 ("row_block", ctypes.c_int32), ("n_phases", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
+                ("n_long_rows", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
 
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p)

@@ -79,6 +79,7 @@ sptir_status_t sptir_hyb_info(const sptir_hyb_t* h, sptir_hyb_info_t* out) {
   o.n_rem_pieces = h->M; o.n_rem_nnz = h->T;
   o.n_work_items = h->n_chunks; o.item_slots = sptir::kChunkSlots; o.row_block = 1 << h->log2_row_block;
   o.n_phases = h->n_phases;
+  o.n_long_rows = h->n_long_rows;
   o.device_bytes = (int64_t)h->device_bytes;
   *out = o;
   return SPTIR_OK;

@@ -552,14 +552,18 @@ struct Blob {  // bump allocator over one device allocation
 //   SPTIR_ROW_BLOCK        rows of Y one wavefront keeps in LDS (power of two, 8..256)
 //   SPTIR_PARTS_PER_PHASE  column partitions swept per SpMM launch (default: chosen from the sizes)
 //   SPTIR_WIDE_STREAM      non-zero: always write the 12-byte stream records
-int log2_row_block_setting(int32_t n_rows) {
+int log2_row_block_setting(int32_t n_rows, double slots_per_row_and_launch) {
   const char* e = getenv("SPTIR_ROW_BLOCK");
   long v = e ? atol(e) : 0;
   if (v < 8 || v > 256 || (v & (v - 1))) {
-    // 32 rows x 128 bytes = 4 KB of LDS per wavefront next to its 6 KB chunk ring: 16 wavefronts per CU;
-    // smaller blocks when there would not be enough of them to fill 256 CUs several times over
+    // A wavefront walks the list of one (launch, row block) alone.  Every (partition, bucket) cell of the
+    // list starts a new chunk, so short lists are mostly padding: aim at some 1400 stored slots (22 chunks)
+    // per list.  32 rows x 128 bytes = 4 KB of LDS per wavefront next to its 4 KB (6 KB) chunk ring leaves
+    // the register file to cap the CU at 16 wavefronts; 128 rows is the most a compact record can address.
     v = 32;
-    while (v > 8 && n_rows / v < 4096) v >>= 1;
+    while (v < 128 && v * slots_per_row_and_launch < 1400.0) v <<= 1;
+    // ... but keep at least ~1024 row blocks, or the 256 CUs do not fill
+    while (v > 8 && n_rows / v < 1024) v >>= 1;
   }
   int l = 0;
   while ((1L << l) < v) ++l;
@@ -582,7 +586,9 @@ int parts_per_phase_setting(int32_t c, int32_t w, int32_t n_rows, int64_t slots)
   if (fit >= c) return c;
   long phases = (c + fit - 1) / fit;
   const double slots_per_row = n_rows > 0 ? (double)slots / n_rows : 0.0;
-  if (slots_per_row < 2.5 * (double)(phases - 1)) return c;   // Y traffic would outweigh the L2 hits
+  // measured: 8 slots per row and 4 partitions run 1.7x faster in one launch, 420 slots per row and 8 partitions
+  // 1.5x faster in 8 launches
+  if (slots_per_row < 16.0 * (double)(phases - 1)) return c;   // Y traffic would outweigh the L2 hits
   return (int)fit;
 }
 
@@ -713,9 +719,10 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
     // ---- launch shape of the SpMM: row blocks and phases
     CellShape cs;
     cs.c = s.c; cs.k = s.k; cs.nb = s.nb; cs.R = h->R;
-    cs.log2_rb = log2_row_block_setting(s.n_rows);
-    cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
     cs.ppg = parts_per_phase_setting(s.c, s.w, s.n_rows, h->S + h->T);
+    cs.log2_rb = log2_row_block_setting(
+        s.n_rows, s.n_rows > 0 ? (double)(h->S + h->T) / s.n_rows / ((s.c + cs.ppg - 1) / cs.ppg) : 0.0);
+    cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
     {
       // the compact stream needs the columns of one launch to fit kCompactColBits and the row block 7 bits
       const char* e = getenv("SPTIR_WIDE_STREAM");
