@@ -327,3 +327,14 @@ def test_spmm_long_rows(gpu_lib, c, k, feat):
         assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"long rows c={c} k={k}")
         Ys.append(Y)
     assert torch.equal(Ys[0], Ys[1])
+
+
+def test_sweep_module_runs(gpu_lib, monkeypatch, capsys):
+    """The c / d sweep driver runs end to end on the smallest graph and prints one JSON record per point."""
+    import json
+    from paper_2207_04606_amd import sweep
+    monkeypatch.setattr("sys.argv", ["sweep", "--config", "tiny", "--reps", "1", "--c-values", "1,3", "--d-values", "8,33"])
+    sweep.main()
+    lines = [json.loads(l) for l in capsys.readouterr().out.splitlines() if l.startswith("{")]
+    assert [(p["sweep"], p["c"], p["feat"]) for p in lines] == [("c", 1, 128), ("c", 3, 128), ("d", 1, 8), ("d", 1, 33)]
+    assert all(p["hyb_ms"] > 0 and p["no_hyb_ms"] > 0 for p in lines)
