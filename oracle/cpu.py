@@ -1,4 +1,4 @@
-"""ctypes front end of oracle/hyb_oracle.c (plain C, fp64 arithmetic).
+"""ctypes front end of oracle/hyb_oracle.c and oracle/sddmm_oracle.c (plain C, fp64 arithmetic).
 
 All arithmetic lives in the C file; this module only compiles it with gcc,
 marshals numpy arrays in and copies the resulting arrays out.
@@ -13,7 +13,7 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "hyb_oracle.c")
+_SRCS = [os.path.join(_HERE, "hyb_oracle.c"), os.path.join(_HERE, "sddmm_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle_hyb.so")
 _lib = None
 
@@ -35,8 +35,8 @@ class _CHyb(ctypes.Structure):
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, *_SRCS, "-lm"])
     return _LIB
 
 
@@ -158,6 +158,23 @@ def spmm_hyb(h: HybArrays, X):
     lib.oracle_spmm_hyb(ctypes.byref(ch), ctypes.c_void_p(X.ctypes.data), ctypes.c_int32(feat),
                         ctypes.c_void_p(Y.ctypes.data))
     return Y
+
+
+def sddmm_csr(n_rows, indptr, indices, values, X, Yt, want_abs=True):
+    """B_values[q] = A_ij * sum_k X[i,k] * Yt[j,k] for every stored (i,j), fp64; also the magnitude sums."""
+    lib = _load()
+    indptr, indices, values = _csr_args(indptr, indices, values)
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    Yt = np.ascontiguousarray(Yt, dtype=np.float32)
+    assert X.shape[1] == Yt.shape[1] and X.shape[0] == n_rows
+    d = X.shape[1]
+    B = np.empty(indices.shape[0], dtype=np.float64)
+    M = np.empty(indices.shape[0], dtype=np.float64) if want_abs else None
+    lib.oracle_sddmm_csr(ctypes.c_int32(n_rows), ctypes.c_void_p(indptr.ctypes.data),
+                         ctypes.c_void_p(indices.ctypes.data), ctypes.c_void_p(values.ctypes.data),
+                         ctypes.c_void_p(X.ctypes.data), ctypes.c_void_p(Yt.ctypes.data), ctypes.c_int32(d),
+                         ctypes.c_void_p(B.ctypes.data), ctypes.c_void_p(M.ctypes.data if want_abs else None))
+    return (B, M) if want_abs else B
 
 
 def num_threads() -> int:
