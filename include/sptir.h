@@ -1,5 +1,6 @@
 /*
- * sptir.h - C ABI of the hyb(c,k) composable-format SpMM library for gfx950.
+ * sptir.h - C ABI of the hyb(c,k) composable-format SpMM library for gfx950
+ * (plus SDDMM on CSR, the other sparse operator of the paper's GNN section).
  *
  * The operations follow the SpMM problem statement of the paper (arXiv
  * 2207.04606): A is sparse in CSR with int32 indices and float32 values, X and
@@ -163,6 +164,23 @@ sptir_status_t sptir_spmm(const sptir_hyb_t* hyb, const float* X, float* Y, int3
  * are not re-validated).  Only enqueues work on `stream`.
  */
 sptir_status_t sptir_spmm_csr(const sptir_csr_t* csr, const float* X, float* Y, int32_t feat, void* stream);
+
+/*
+ * SDDMM on the structure of a CSR matrix (the SDDMM equation of Section 4.2):
+ *     B[i,j] = A[i,j] * sum_k X[i,k] * Y[k,j]      for every stored (i,j) of A.
+ * The paper does not fix how Y is laid out; this entry point takes its
+ * transpose, so that both dense operands are read by rows:
+ *   X         device, [n_rows, feat] row-major float32
+ *   Yt        device, [n_cols, feat] row-major float32, Yt[j,k] = Y[k,j]
+ *   B_values  device, [nnz] float32, parallel to csr->values (same row/column per position);
+ *             may be csr->values itself, must not overlap anything else
+ * The CSR arrays are device pointers and are assumed valid (not re-validated).
+ * Only enqueues work on `stream`; no allocation.  Every entry is a fixed-order
+ * sum, so results are reproducible bit for bit.
+ * Errors: INVALID_ARG, OVERFLOW (nnz >= 2^31), HIP.
+ */
+sptir_status_t sptir_sddmm_csr(const sptir_csr_t* csr, const float* X, const float* Yt, float* B_values,
+                               int32_t feat, void* stream);
 
 /* Releases the handle and its device arrays.  NULL is accepted. */
 sptir_status_t sptir_hyb_destroy(sptir_hyb_t* hyb);

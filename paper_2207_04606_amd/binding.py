@@ -56,7 +56,7 @@ _lib = None
 _hip = None
 
 EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_default_bucket_log2", "sptir_spmm",
-                    "sptir_spmm_csr", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
+                    "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
                     "sptir_status_string", "sptir_last_hip_error")
 
 
@@ -78,6 +78,9 @@ def load_library(path: str | None = None):
     lib.sptir_default_bucket_log2.argtypes = [ctypes.c_int64, ctypes.c_int32]
     lib.sptir_spmm.restype = ctypes.c_int
     lib.sptir_spmm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+    lib.sptir_sddmm_csr.restype = ctypes.c_int
+    lib.sptir_sddmm_csr.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                    ctypes.c_int32, ctypes.c_void_p]
     lib.sptir_spmm_csr.restype = ctypes.c_int
     lib.sptir_spmm_csr.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                    ctypes.c_void_p]
@@ -261,3 +264,19 @@ def sptir_set_allocator(use_torch: bool) -> None:
         st = lib.sptir_set_allocator(ctypes.cast(None, _ALLOC_FN), ctypes.cast(None, _FREE_FN), None)
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_set_allocator")
+
+
+def sptir_sddmm_csr(n_rows: int, n_cols: int, indptr, indices, values, X, Yt, B_values, stream=None) -> None:
+    """B_values[q] = values[q] * <X[row(q)], Yt[indices[q]]> for every stored position q."""
+    _dev(X, torch.float32, "X"); _dev(Yt, torch.float32, "Yt"); _dev(B_values, torch.float32, "B_values")
+    if X.dim() != 2 or Yt.dim() != 2 or X.shape[1] != Yt.shape[1]:
+        raise ValueError("X and Yt must be 2-D with the same number of columns")
+    if X.shape[0] != n_rows or Yt.shape[0] != n_cols:
+        raise ValueError("X / Yt row counts do not match the matrix")
+    if B_values.dim() != 1 or B_values.shape[0] != values.shape[0]:
+        raise ValueError("B_values must have one entry per stored position")
+    csr = _csr_struct(n_rows, n_cols, indptr, indices, values)
+    st = load_library().sptir_sddmm_csr(ctypes.byref(csr), X.data_ptr() or None, Yt.data_ptr() or None,
+                                        B_values.data_ptr() or None, X.shape[1], _stream_ptr(stream))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_sddmm_csr")
