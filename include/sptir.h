@@ -138,6 +138,23 @@ sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_parts, int3
 int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows);
 
 /*
+ * Format search (the tuning rule of Section 4.2.1: try several c, keep the
+ * fastest).  Builds hyb(c, k) for every c of c_candidates (host array;
+ * n_candidates == 0 selects the paper's {1, 2, 4, 8, 16}), runs sptir_spmm
+ * `reps` times after one warm-up on zero-filled scratch operands of width
+ * `feat`, and returns the decomposition with the smallest mean time.
+ *   max_bucket_log2  k for every candidate; negative selects sptir_default_bucket_log2
+ *   best_c           receives the chosen c (may be NULL)
+ *   ms_per_candidate host array [n_candidates] of mean milliseconds (may be NULL)
+ * Allocates X and Y scratch (n_cols*feat and n_rows*feat floats) through the
+ * allocator hook and synchronises `stream`.  Errors: those of sptir_hyb_build
+ * and sptir_spmm; on error nothing is returned and nothing stays allocated.
+ */
+sptir_status_t sptir_hyb_search(const sptir_csr_t* csr, const int32_t* c_candidates, int32_t n_candidates,
+                                int32_t max_bucket_log2, int32_t feat, int32_t reps, void* stream,
+                                sptir_hyb_t** out, int32_t* best_c, float* ms_per_candidate);
+
+/*
  * Y = A * X on the hyb decomposition (SpMM equation of Section 4.2.1; Y is
  * overwritten, rows without non-zeros become 0, as the init block of the
  * Appendix A script prescribes).

@@ -55,7 +55,7 @@ _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 _lib = None
 _hip = None
 
-EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_default_bucket_log2", "sptir_spmm",
+EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
                     "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
                     "sptir_status_string", "sptir_last_hip_error")
 
@@ -81,6 +81,10 @@ def load_library(path: str | None = None):
     lib.sptir_sddmm_csr.restype = ctypes.c_int
     lib.sptir_sddmm_csr.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.c_int32, ctypes.c_void_p]
+    lib.sptir_hyb_search.restype = ctypes.c_int
+    lib.sptir_hyb_search.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p),
+                                     ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
     lib.sptir_spmm_csr.restype = ctypes.c_int
     lib.sptir_spmm_csr.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                    ctypes.c_void_p]
@@ -174,6 +178,24 @@ def sptir_hyb_build(n_rows: int, n_cols: int, indptr, indices, values, n_col_par
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_hyb_build")
     return Hyb(out.value)
+
+
+def sptir_hyb_search(n_rows: int, n_cols: int, indptr, indices, values, feat: int, c_candidates=(),
+                     max_bucket_log2: int = -1, reps: int = 3, stream=None):
+    """Builds hyb(c, k) for every candidate c, times SpMM at `feat`, returns (fastest Hyb, its c, [ms per c])."""
+    lib = load_library()
+    csr = _csr_struct(n_rows, n_cols, indptr, indices, values)
+    cands = [int(c) for c in c_candidates]
+    n = len(cands)
+    arr = (ctypes.c_int32 * max(n, 1))(*cands)
+    ms = (ctypes.c_float * max(n, 5))()
+    best_c = ctypes.c_int32(0)
+    out = ctypes.c_void_p(None)
+    st = lib.sptir_hyb_search(ctypes.byref(csr), arr if n else None, n, max_bucket_log2, feat, reps,
+                              _stream_ptr(stream), ctypes.byref(out), ctypes.byref(best_c), ms if n else None)
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_hyb_search")
+    return Hyb(out.value), int(best_c.value), [float(ms[i]) for i in range(n)]
 
 
 def sptir_hyb_destroy(hyb: Hyb) -> None:

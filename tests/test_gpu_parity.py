@@ -338,3 +338,27 @@ def test_sweep_module_runs(gpu_lib, monkeypatch, capsys):
     lines = [json.loads(l) for l in capsys.readouterr().out.splitlines() if l.startswith("{")]
     assert [(p["sweep"], p["c"], p["feat"]) for p in lines] == [("c", 1, 128), ("c", 3, 128), ("d", 1, 8), ("d", 1, 33)]
     assert all(p["hyb_ms"] > 0 and p["no_hyb_ms"] > 0 for p in lines)
+
+
+def test_hyb_search_picks_a_candidate(gpu_lib):
+    """The format search returns one of its candidates, built exactly like a direct build with that c."""
+    w = ragged_workload(77, 3000, 3500, 64, max_deg=900, long_rows=6)
+    d = upload(w)
+    hyb, best_c, ms = gpu_lib.sptir_hyb_search(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 64,
+                                               c_candidates=(1, 3, 8), max_bucket_log2=5, reps=2)
+    assert best_c in (1, 3, 8) and len(ms) == 3 and all(t > 0 for t in ms)
+    assert best_c == (1, 3, 8)[int(np.argmin(ms))]
+    got, info = fetch_hyb(gpu_lib, hyb)
+    assert info["n_col_parts"] == best_c and info["max_bucket_log2"] == 5
+    assert_same_hyb(got, oracle.hyb_build(w.n_rows, w.n_cols, w.indptr, w.indices, w.values, best_c, 5))
+    Y = torch.full((w.n_rows, 64), float("nan"), device="cuda")
+    gpu_lib.sptir_spmm(hyb, d.X, Y)
+    Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+    assert_y_close(Y.cpu().numpy(), Yr, Sr, what="search")
+    # defaults: the paper's candidate set and its rule for k
+    hyb2, c2, _ = gpu_lib.sptir_hyb_search(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 32)
+    info2 = gpu_lib.sptir_hyb_info(hyb2)
+    assert c2 in (1, 2, 4, 8, 16) and info2["n_col_parts"] == c2
+    assert info2["max_bucket_log2"] == gpu_lib.sptir_default_bucket_log2(w.nnz, w.n_rows)
+    with pytest.raises(gpu_lib.SptirError):
+        gpu_lib.sptir_hyb_search(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 32, c_candidates=(2, 0))
