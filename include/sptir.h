@@ -199,6 +199,42 @@ sptir_status_t sptir_spmm_csr(const sptir_csr_t* csr, const float* X, float* Y, 
 sptir_status_t sptir_sddmm_csr(const sptir_csr_t* csr, const float* X, const float* Yt, float* B_values,
                                int32_t feat, void* stream);
 
+/*
+ * The same SDDMM with its entries visited in column-partition order, the way
+ * Section 4.2.1 partitions columns for cache locality: a plan lists the entries
+ * of every partition, each of the 8 XCDs sweeps its own partitions one after
+ * the other, and the rows of Yt of one partition stay in that XCD's L2.  The
+ * plan depends on the sparse structure only and is reused for any values, X,
+ * Yt and feat.
+ *   n_col_parts  number of column partitions; 0 chooses it from feat_hint (the
+ *                feature size the plan will mostly run at) and the row lengths,
+ *                and may settle for 1, which keeps CSR order
+ *   csr->values  is not read (may be NULL); indptr / indices are device arrays,
+ *                columns strictly ascending inside a row (UNSORTED if the pieces
+ *                do not tile the rows)
+ * The plan owns device memory of about 12 bytes per non-zero, obtained through
+ * the allocator hook; sptir_sddmm_plan_build synchronises `stream`.
+ */
+typedef struct sptir_sddmm_plan sptir_sddmm_plan_t;
+
+typedef struct {
+  int32_t n_rows, n_cols;
+  int32_t n_col_parts;  /* partitions in use (1: entries stay in CSR order) */
+  int32_t part_width;
+  int64_t nnz;
+  int64_t n_runs;       /* runs of at most 512 entries, one wavefront each (0 when n_col_parts == 1) */
+  int64_t device_bytes;
+} sptir_sddmm_plan_info_t;
+
+sptir_status_t sptir_sddmm_plan_build(const sptir_csr_t* csr, int32_t n_col_parts, int32_t feat_hint, void* stream,
+                                      sptir_sddmm_plan_t** out);
+/* values, B_values: device [nnz] in CSR order (B_values may be values itself); X, Yt, feat as for sptir_sddmm_csr.
+ * Only enqueues work on `stream`; no allocation; results are bit-reproducible. */
+sptir_status_t sptir_sddmm(const sptir_sddmm_plan_t* plan, const float* values, const float* X, const float* Yt,
+                           float* B_values, int32_t feat, void* stream);
+sptir_status_t sptir_sddmm_plan_info(const sptir_sddmm_plan_t* plan, sptir_sddmm_plan_info_t* out);
+sptir_status_t sptir_sddmm_plan_destroy(sptir_sddmm_plan_t* plan); /* NULL is accepted */
+
 /* Releases the handle and its device arrays.  NULL is accepted. */
 sptir_status_t sptir_hyb_destroy(sptir_hyb_t* hyb);
 

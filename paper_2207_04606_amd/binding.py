@@ -49,6 +49,12 @@ class _Info(ctypes.Structure):
                 ("n_long_rows", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
 
 
+class _PlanInfo(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32), ("n_col_parts", ctypes.c_int32),
+                ("part_width", ctypes.c_int32), ("nnz", ctypes.c_int64), ("n_runs", ctypes.c_int64),
+                ("device_bytes", ctypes.c_int64)]
+
+
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 
@@ -56,7 +62,8 @@ _lib = None
 _hip = None
 
 EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
-                    "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
+                    "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_sddmm_plan_build", "sptir_sddmm",
+                    "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
                     "sptir_status_string", "sptir_last_hip_error")
 
 
@@ -85,6 +92,16 @@ def load_library(path: str | None = None):
     lib.sptir_hyb_search.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
                                      ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p),
                                      ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p]
+    lib.sptir_sddmm_plan_build.restype = ctypes.c_int
+    lib.sptir_sddmm_plan_build.argtypes = [ctypes.POINTER(_Csr), ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                           ctypes.POINTER(ctypes.c_void_p)]
+    lib.sptir_sddmm.restype = ctypes.c_int
+    lib.sptir_sddmm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                ctypes.c_int32, ctypes.c_void_p]
+    lib.sptir_sddmm_plan_info.restype = ctypes.c_int
+    lib.sptir_sddmm_plan_info.argtypes = [ctypes.c_void_p, ctypes.POINTER(_PlanInfo)]
+    lib.sptir_sddmm_plan_destroy.restype = ctypes.c_int
+    lib.sptir_sddmm_plan_destroy.argtypes = [ctypes.c_void_p]
     lib.sptir_spmm_csr.restype = ctypes.c_int
     lib.sptir_spmm_csr.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                    ctypes.c_void_p]
@@ -130,11 +147,14 @@ def _dev(t: torch.Tensor, dtype, what: str) -> torch.Tensor:
 
 
 def _csr_struct(n_rows, n_cols, indptr, indices, values):
-    _dev(indptr, torch.int32, "indptr"); _dev(indices, torch.int32, "indices"); _dev(values, torch.float32, "values")
-    if indptr.numel() != n_rows + 1 or indices.numel() != values.numel():
+    """values may be None where only the structure is read."""
+    _dev(indptr, torch.int32, "indptr"); _dev(indices, torch.int32, "indices")
+    if values is not None:
+        _dev(values, torch.float32, "values")
+    if indptr.numel() != n_rows + 1 or (values is not None and indices.numel() != values.numel()):
         raise ValueError("CSR array sizes do not match")
     return _Csr(n_rows, n_cols, indices.numel(), indptr.data_ptr(), indices.data_ptr() or None,
-                values.data_ptr() or None)
+                (values.data_ptr() or None) if values is not None else None)
 
 
 def sptir_status_string(status: int) -> str:
@@ -302,3 +322,71 @@ def sptir_sddmm_csr(n_rows: int, n_cols: int, indptr, indices, values, X, Yt, B_
                                         B_values.data_ptr() or None, X.shape[1], _stream_ptr(stream))
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_sddmm_csr")
+
+
+class SddmmPlan:
+    """Owner of a sptir_sddmm_plan_t handle."""
+
+    def __init__(self, handle, nnz, n_rows, n_cols):
+        self._h = ctypes.c_void_p(handle)
+        self.nnz, self.n_rows, self.n_cols = nnz, n_rows, n_cols
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise RuntimeError("plan already destroyed")
+        return self._h
+
+    def destroy(self):
+        sptir_sddmm_plan_destroy(self)
+
+    def __del__(self):
+        try:
+            if self._h and _lib is not None:
+                _lib.sptir_sddmm_plan_destroy(self._h)
+                self._h = ctypes.c_void_p(None)
+        except Exception:
+            pass
+
+
+def sptir_sddmm_plan_build(n_rows: int, n_cols: int, indptr, indices, n_col_parts: int = 0, feat_hint: int = 0,
+                           stream=None) -> SddmmPlan:
+    lib = load_library()
+    csr = _csr_struct(n_rows, n_cols, indptr, indices, None)
+    out = ctypes.c_void_p(None)
+    st = lib.sptir_sddmm_plan_build(ctypes.byref(csr), n_col_parts, feat_hint, _stream_ptr(stream), ctypes.byref(out))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_sddmm_plan_build")
+    return SddmmPlan(out.value, int(indices.shape[0]), n_rows, n_cols)
+
+
+def sptir_sddmm(plan: SddmmPlan, values, X, Yt, B_values, stream=None) -> None:
+    _dev(values, torch.float32, "values"); _dev(X, torch.float32, "X"); _dev(Yt, torch.float32, "Yt")
+    _dev(B_values, torch.float32, "B_values")
+    if X.dim() != 2 or Yt.dim() != 2 or X.shape[1] != Yt.shape[1]:
+        raise ValueError("X and Yt must be 2-D with the same number of columns")
+    if X.shape[0] != plan.n_rows or Yt.shape[0] != plan.n_cols:
+        raise ValueError("X / Yt row counts do not match the plan")
+    if values.dim() != 1 or values.shape[0] != plan.nnz or B_values.shape != values.shape:
+        raise ValueError("values and B_values must have one entry per stored position")
+    st = load_library().sptir_sddmm(plan.handle, values.data_ptr() or None, X.data_ptr() or None,
+                                    Yt.data_ptr() or None, B_values.data_ptr() or None, X.shape[1],
+                                    _stream_ptr(stream))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_sddmm")
+
+
+def sptir_sddmm_plan_info(plan: SddmmPlan) -> dict:
+    info = _PlanInfo()
+    st = load_library().sptir_sddmm_plan_info(plan.handle, ctypes.byref(info))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_sddmm_plan_info")
+    return {name: getattr(info, name) for name, _ in _PlanInfo._fields_}
+
+
+def sptir_sddmm_plan_destroy(plan: SddmmPlan) -> None:
+    if plan._h:
+        st = load_library().sptir_sddmm_plan_destroy(plan._h)
+        plan._h = ctypes.c_void_p(None)
+        if st != SPTIR_OK:
+            raise SptirError(st, "sptir_sddmm_plan_destroy")

@@ -29,7 +29,8 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "sptir_internal.h"), os.path.join(ROOT, "include", "sptir.h")]
+    deps = sources() + [os.path.join(CSRC, "sptir_internal.h"), os.path.join(CSRC, "sptir_scan.h"),
+                        os.path.join(ROOT, "include", "sptir.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

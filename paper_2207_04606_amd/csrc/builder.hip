@@ -17,27 +17,18 @@
 #include <vector>
 
 #include "sptir_internal.h"
+#include "sptir_scan.h"
 
 namespace sptir {
 namespace {
 
 constexpr int kMaxBins = 32;  // k <= 30 -> bins 0..k plus the remainder bin k+1
-constexpr int kWaves = kBuildBlock / 64;
 
 struct BuildShape {
   int32_t n_rows, n_cols, c, k, w;
   int32_t nb;  // bins per partition = k + 2
   int32_t NB;  // row blocks = ceil(n_rows / 256)
 };
-
-// first position q in [lo, hi) whose column is >= bound
-__device__ __forceinline__ int lower_bound_col(const int32_t* __restrict__ indices, int lo, int hi, int64_t bound) {
-  while (lo < hi) {
-    int mid = lo + ((hi - lo) >> 1);
-    if ((int64_t)indices[mid] < bound) lo = mid + 1; else hi = mid;
-  }
-  return lo;
-}
 
 // start and length of row r's piece in partition p
 __device__ __forceinline__ void row_piece(const BuildShape& s, const int32_t* __restrict__ indptr,
@@ -117,54 +108,6 @@ __global__ __launch_bounds__(kBuildBlock) void k_count(BuildShape s, const int32
   __syncthreads();
   if (tid < s.nb) counts[((int64_t)p * s.nb + tid) * s.NB + rb] = hist[tid];
   if (tid == 0) rem_nnz[(int64_t)p * s.NB + rb] = (int64_t)sum_nnz;
-}
-
-// ---------------------------------------------------------------------- scan
-template <typename T>
-__device__ __forceinline__ T wave_inclusive_scan(T v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    T o = __shfl_up(v, d, 64);
-    if (lane >= d) v += o;
-  }
-  return v;
-}
-
-// exclusive scan over the 256 threads of a workgroup; *total = sum of all
-template <typename T>
-__device__ __forceinline__ T block_exclusive_scan(T v, T* wave_sums /* [kWaves] shared */, T* total) {
-  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  T incl = wave_inclusive_scan(v, lane);
-  __syncthreads();  // wave_sums may still be read from a previous call
-  if (lane == 63) wave_sums[wave] = incl;
-  __syncthreads();
-  T base = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < kWaves; ++w) {
-    T ws = wave_sums[w];
-    if (w < wave) base += ws;
-    tot += ws;
-  }
-  *total = tot;
-  return base + incl - v;
-}
-
-// One workgroup per sequence: data[seq*len .. +len) becomes its exclusive
-// prefix, totals[seq] its sum.
-template <typename T>
-__global__ __launch_bounds__(kBuildBlock) void k_scan_sequences(T* data, int32_t len, T* totals) {
-  __shared__ T wave_sums[kWaves];
-  T* seq = data + (int64_t)blockIdx.x * len;
-  T carry = 0;
-  for (int32_t base = 0; base < len; base += kBuildBlock) {
-    int32_t e = base + (int32_t)threadIdx.x;
-    T v = (e < len) ? seq[e] : (T)0;
-    T tot;
-    T ex = block_exclusive_scan(v, wave_sums, &tot);
-    if (e < len) seq[e] = carry + ex;
-    carry += tot;
-  }
-  if (threadIdx.x == 0) totals[blockIdx.x] = carry;
 }
 
 // ------------------------------------------------------------------- scatter

@@ -123,3 +123,60 @@ def test_sddmm_named_configs(gpu_lib, name):
     Br, Mr = oracle.sddmm_csr(w.n_rows, w.indptr, w.indices, w.values, Xr, w.X)
     worst = assert_b_close(B, Br, Mr, name)
     say(f"[sddmm config] {name}: max_err={worst:.2e}")
+
+
+def run_sddmm_plan(sptir, w, Xr, Yt, c, feat_hint=0, in_place=False):
+    dev = "cuda"
+    ip = torch.from_numpy(w.indptr).to(dev)
+    ix = torch.from_numpy(w.indices).to(dev)
+    va = torch.from_numpy(w.values).to(dev)
+    plan = sptir.sptir_sddmm_plan_build(w.n_rows, w.n_cols, ip, ix, c, feat_hint)
+    info = sptir.sptir_sddmm_plan_info(plan)
+    B = va if in_place else torch.full((w.nnz,), float("nan"), device=dev)
+    sptir.sptir_sddmm(plan, va, torch.from_numpy(Xr).to(dev), torch.from_numpy(Yt).to(dev), B)
+    out = B.cpu().numpy()
+    plan.destroy()
+    return out, info
+
+
+@pytest.mark.parametrize("c", [1, 2, 3, 8, 16, 40, 2000])
+@pytest.mark.parametrize("feat", [4, 32, 100, 128, 7])
+def test_sddmm_with_plan_equals_csr_order(gpu_lib, c, feat):
+    """Partition order changes where an entry is computed, not how: the plan path must give the very bits of the
+    CSR-order kernel (same per-entry arithmetic), for any number of partitions including more than columns."""
+    say(f"[sddmm plan] c={c} feat={feat}")
+    w = ragged_workload(800 + feat, 1300, 1100, feat, max_deg=700, long_rows=5)
+    Xr = left_operand(w, feat, feat)
+    want = run_sddmm(gpu_lib, w, Xr, w.X)
+    got, info = run_sddmm_plan(gpu_lib, w, Xr, w.X, c)
+    assert info["n_col_parts"] == min(c, w.n_cols) and info["nnz"] == w.nnz
+    assert np.array_equal(got, want)
+    Br, Mr = oracle.sddmm_csr(w.n_rows, w.indptr, w.indices, w.values, Xr, w.X)
+    assert_b_close(got, Br, Mr, f"plan c={c} feat={feat}")
+
+
+def test_sddmm_plan_edge_cases(gpu_lib):
+    dev = "cuda"
+    # no entries
+    w0 = workloads.random_csr(3, 4, np.array([0, 0, 0]), 1, 8)
+    got, info = run_sddmm_plan(gpu_lib, w0, left_operand(w0, 8, 4), w0.X, 2)
+    assert got.shape == (0,) and info["nnz"] == 0
+    # in place, automatic partition count, repeatable
+    w = ragged_workload(49, 2000, 2500, 64, max_deg=1200, long_rows=10)
+    Xr = left_operand(w, 64, 1)
+    a, info = run_sddmm_plan(gpu_lib, w, Xr, w.X, 0, feat_hint=64)
+    b, _ = run_sddmm_plan(gpu_lib, w, Xr, w.X, 0, feat_hint=64, in_place=True)
+    assert np.array_equal(a, b) and info["n_col_parts"] in (1,) + tuple(range(8, 1025, 8))
+    with pytest.raises(gpu_lib.SptirError):       # negative partition count
+        gpu_lib.sptir_sddmm_plan_build(w.n_rows, w.n_cols, torch.from_numpy(w.indptr).to(dev),
+                                       torch.from_numpy(w.indices).to(dev), -1)
+
+
+@pytest.mark.parametrize("name", ["medium", "protein", "social"])
+def test_sddmm_plan_named_configs(gpu_lib, name):
+    w = workloads.make_config(name, feat=128)
+    Xr = left_operand(w, 128, 9)
+    B, info = run_sddmm_plan(gpu_lib, w, Xr, w.X, 0, feat_hint=128)
+    say(f"[sddmm plan config] {name}: c={info['n_col_parts']} runs={info['n_runs']} bytes={info['device_bytes']}")
+    Br, Mr = oracle.sddmm_csr(w.n_rows, w.indptr, w.indices, w.values, Xr, w.X)
+    assert_b_close(B, Br, Mr, name)
