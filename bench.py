@@ -237,6 +237,33 @@ def main():
         csr_ms = (time.perf_counter() - t0) * 1e3 / 10
         out["no_hyb_csr"] = {"ms_per_step": round(csr_ms, 4), "gflops": round(2.0 * w.nnz * 128 / csr_ms / 1e6, 1),
                              "hyb_speedup": round(csr_ms / head["wall_ms"], 3)}
+        # SDDMM on the same graph (B_ij = A_ij <X_i, Yt_j>), entries in CSR order and in column-partition order
+        Xl = torch.randn(w.n_rows, 128, device=dev, generator=torch.Generator(device=dev).manual_seed(3))
+        Bv = torch.empty(w.nnz, device=dev)
+
+        def timed(fn, reps=10):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / reps
+
+        sddmm_csr_ms = timed(lambda: sptir.sptir_sddmm_csr(w.n_rows, w.n_cols, indptr, indices, values, Xl, X, Bv))
+        t0 = time.perf_counter()
+        plan = sptir.sptir_sddmm_plan_build(w.n_rows, w.n_cols, indptr, indices, 0, 128)
+        torch.cuda.synchronize()
+        plan_ms = (time.perf_counter() - t0) * 1e3
+        sddmm_ms = timed(lambda: sptir.sptir_sddmm(plan, values, Xl, X, Bv))
+        pinfo = sptir.sptir_sddmm_plan_info(plan)
+        plan.destroy()
+        out["sddmm_feat128"] = {"ms_per_step": round(sddmm_ms, 4), "gflops": round(2.0 * w.nnz * 128 / sddmm_ms / 1e6, 1),
+                                "n_col_parts": pinfo["n_col_parts"], "plan_build_ms": round(plan_ms, 3),
+                                "gather_gbs": round(w.nnz * 512.0 / sddmm_ms / 1e6, 1),
+                                "csr_order_ms_per_step": round(sddmm_csr_ms, 4)}
+        del Xl, Bv
         del X, Y
         hyb.destroy()
         del indptr, indices, values
