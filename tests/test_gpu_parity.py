@@ -362,3 +362,37 @@ def test_hyb_search_picks_a_candidate(gpu_lib):
     assert info2["max_bucket_log2"] == gpu_lib.sptir_default_bucket_log2(w.nnz, w.n_rows)
     with pytest.raises(gpu_lib.SptirError):
         gpu_lib.sptir_hyb_search(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 32, c_candidates=(2, 0))
+
+
+def test_spmm_and_sddmm_replay_in_a_hip_graph(gpu_lib):
+    """sptir_spmm / sptir_sddmm only enqueue kernels, so a stream capture records them; every replay (with
+    eager work and synchronisation in between, and new operand values) must match the eager result."""
+    w = workloads.make_config("small")
+    d, hyb, got, want, info = build_both(gpu_lib, w, w.n_col_parts, w.max_bucket_log2)
+    plan = gpu_lib.sptir_sddmm_plan_build(w.n_rows, w.n_cols, d.indptr, d.indices, 8)
+    X = d.X.clone()
+    Xl = torch.randn(w.n_rows, w.feat, device="cuda")
+    Y = torch.empty(w.n_rows, w.feat, device="cuda")
+    B = torch.empty(w.nnz, device="cuda")
+    gpu_lib.sptir_spmm(hyb, X, Y)                      # first calls outside the capture (one-time set-up)
+    gpu_lib.sptir_sddmm(plan, d.values, Xl, X, B)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            gpu_lib.sptir_spmm(hyb, X, Y, stream=side)
+            gpu_lib.sptir_sddmm(plan, d.values, Xl, X, B, stream=side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        X.copy_(torch.randn_like(X))                   # new values in the captured buffers
+        Y.fill_(float("nan")); B.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        Y_eager = torch.empty_like(Y); B_eager = torch.empty_like(B)
+        gpu_lib.sptir_spmm(hyb, X, Y_eager)
+        gpu_lib.sptir_sddmm(plan, d.values, Xl, X, B_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(Y, Y_eager) and torch.equal(B, B_eager), f"replay {rep}"
