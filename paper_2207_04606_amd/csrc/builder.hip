@@ -500,11 +500,13 @@ int log2_row_block_setting(int32_t n_rows, double slots_per_row_and_launch) {
   long v = e ? atol(e) : 0;
   if (v < 8 || v > 256 || (v & (v - 1))) {
     // A wavefront walks the list of one (launch, row block) alone.  Every (partition, bucket) cell of the
-    // list starts a new chunk, so short lists are mostly padding: aim at some 1400 stored slots (22 chunks)
-    // per list.  32 rows x 128 bytes = 4 KB of LDS per wavefront next to its 4 KB (6 KB) chunk ring leaves
-    // the register file to cap the CU at 16 wavefronts; 128 rows is the most a compact record can address.
+    // list starts a new chunk and lists are rounded up to whole quads, so short lists are mostly padding: aim
+    // at some 2800 stored slots (44 chunks) per list.  32 rows x 128 bytes = 4 KB of LDS per wavefront next to
+    // its 4 KB (6 KB) chunk ring leaves the register file to cap the CU at 16 wavefronts, 64 rows allow 12
+    // (measured on the largest graph: 9 % fewer chunks and 3 - 8 % less time with 64 rows, slower again
+    // with 128); 128 rows is the most a compact record can address.
     v = 32;
-    while (v < 128 && v * slots_per_row_and_launch < 1400.0) v <<= 1;
+    while (v < 128 && v * slots_per_row_and_launch < 2800.0) v <<= 1;
     // ... but keep at least ~1024 row blocks, or the 256 CUs do not fill
     while (v > 8 && n_rows / v < 1024) v >>= 1;
   }
