@@ -1,4 +1,4 @@
-"""ctypes front end of oracle/hyb_oracle.c and oracle/sddmm_oracle.c (plain C, fp64 arithmetic).
+"""ctypes front end of the C oracles (hyb_oracle.c, sddmm_oracle.c, rgms_oracle.c; fp64 arithmetic).
 
 All arithmetic lives in the C file; this module only compiles it with gcc,
 marshals numpy arrays in and copies the resulting arrays out.
@@ -13,7 +13,7 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "hyb_oracle.c"), os.path.join(_HERE, "sddmm_oracle.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("hyb_oracle.c", "sddmm_oracle.c", "rgms_oracle.c")]
 _LIB = os.path.join(_HERE, "liboracle_hyb.so")
 _lib = None
 
@@ -175,6 +175,25 @@ def sddmm_csr(n_rows, indptr, indices, values, X, Yt, want_abs=True):
                          ctypes.c_void_p(X.ctypes.data), ctypes.c_void_p(Yt.ctypes.data), ctypes.c_int32(d),
                          ctypes.c_void_p(B.ctypes.data), ctypes.c_void_p(M.ctypes.data if want_abs else None))
     return (B, M) if want_abs else B
+
+
+def rgms(n_rel, n_rows, indptr, indices, values, X, W, want_abs=True):
+    """Y[i,l] = sum_r sum_j sum_k A[r,i,j] X[j,k] W[r,k,l] in fp64; A stacked slice after slice in CSR."""
+    lib = _load()
+    indptr, indices, values = _csr_args(indptr, indices, values)
+    assert indptr.shape[0] == n_rel * n_rows + 1
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    assert W.ndim == 3 and W.shape[0] == n_rel and W.shape[1] == X.shape[1]
+    d_in, d_out = W.shape[1], W.shape[2]
+    Y = np.empty((n_rows, d_out), dtype=np.float64)
+    S = np.empty((n_rows, d_out), dtype=np.float64) if want_abs else None
+    lib.oracle_rgms(ctypes.c_int32(n_rel), ctypes.c_int32(n_rows), ctypes.c_void_p(indptr.ctypes.data),
+                    ctypes.c_void_p(indices.ctypes.data), ctypes.c_void_p(values.ctypes.data),
+                    ctypes.c_void_p(X.ctypes.data), ctypes.c_void_p(W.ctypes.data), ctypes.c_int32(d_in),
+                    ctypes.c_int32(d_out), ctypes.c_void_p(Y.ctypes.data),
+                    ctypes.c_void_p(S.ctypes.data if want_abs else None))
+    return (Y, S) if want_abs else Y
 
 
 def num_threads() -> int:
