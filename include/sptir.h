@@ -235,6 +235,49 @@ sptir_status_t sptir_sddmm(const sptir_sddmm_plan_t* plan, const float* values, 
 sptir_status_t sptir_sddmm_plan_info(const sptir_sddmm_plan_t* plan, sptir_sddmm_plan_info_t* out);
 sptir_status_t sptir_sddmm_plan_destroy(sptir_sddmm_plan_t* plan); /* NULL is accepted */
 
+/*
+ * Relational gather-matmul-scatter (RGMS equation of Section 4.4):
+ *     Y[i,l] = sum_r sum_j sum_k A[r,i,j] * X[j,k] * W[r,k,l]
+ * with A a 3-D sparse tensor of n_relations slices, each n_rows x n_cols.  As
+ * in the paper, every slice is decomposed into hyb(1, k) buckets (k = 5 unless
+ * given) and one fused kernel gathers rows of X, multiplies by W[r] on the
+ * matrix cores and scatters into Y; X W[r] is never materialised.
+ *   stacked   A as one CSR matrix of n_relations * n_rows rows and n_cols
+ *             columns: stacked row r * n_rows + i holds A[r,i,:] (device arrays,
+ *             int32 indices strictly ascending inside a stacked row, float32
+ *             values; validated like sptir_hyb_build's input)
+ *   max_bucket_log2   0..5, or negative for the paper's 5
+ * sptir_rgms_build owns device memory through the allocator hook and
+ * synchronises `stream`.  Errors: those of sptir_hyb_build; INVALID_ARG if
+ * stacked->n_rows is not a multiple of n_relations.
+ */
+typedef struct sptir_rgms_handle sptir_rgms_t;
+
+typedef struct {
+  int32_t n_relations, n_rows, n_cols, max_bucket_log2;
+  int64_t nnz;
+  int64_t n_stacked_rows_stored;  /* (relation, row) pairs with at least one entry, remainder pieces included */
+  int64_t n_pad_slots;
+  int64_t n_tiles;                /* 32-row tiles, one wavefront each */
+  int64_t device_bytes;
+} sptir_rgms_info_t;
+
+sptir_status_t sptir_rgms_build(const sptir_csr_t* stacked, int32_t n_relations, int32_t max_bucket_log2,
+                                void* stream, sptir_rgms_t** out);
+/*
+ *   X  device, [n_cols, d_in] row-major float32, 16-byte aligned
+ *   W  device, [n_relations, d_in, d_out] row-major float32
+ *   Y  device, [n_rows, d_out] row-major float32, overwritten (rows without entries become 0)
+ *   d_in in {32, 64, 128}, d_out a multiple of 32 (UNSUPPORTED otherwise; the paper runs 32 x 32)
+ * Only enqueues work on `stream`; no allocation.  Products and sums are float32 (float32 matrix-core
+ * instructions); the contributions of different relations and buckets meet in Y through float atomic adds
+ * in no fixed order, so results agree between runs to rounding, not bit for bit.  X must be finite (pad slots).
+ */
+sptir_status_t sptir_rgms(const sptir_rgms_t* rgms, const float* X, const float* W, float* Y, int32_t d_in,
+                          int32_t d_out, void* stream);
+sptir_status_t sptir_rgms_info(const sptir_rgms_t* rgms, sptir_rgms_info_t* out);
+sptir_status_t sptir_rgms_destroy(sptir_rgms_t* rgms); /* NULL is accepted */
+
 /* Releases the handle and its device arrays.  NULL is accepted. */
 sptir_status_t sptir_hyb_destroy(sptir_hyb_t* hyb);
 

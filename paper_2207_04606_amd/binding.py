@@ -55,6 +55,13 @@ class _PlanInfo(ctypes.Structure):
                 ("device_bytes", ctypes.c_int64)]
 
 
+class _RgmsInfo(ctypes.Structure):
+    _fields_ = [("n_relations", ctypes.c_int32), ("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32),
+                ("max_bucket_log2", ctypes.c_int32), ("nnz", ctypes.c_int64),
+                ("n_stacked_rows_stored", ctypes.c_int64), ("n_pad_slots", ctypes.c_int64),
+                ("n_tiles", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
+
+
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p)
 _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 
@@ -63,7 +70,8 @@ _hip = None
 
 EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
                     "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_sddmm_plan_build", "sptir_sddmm",
-                    "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
+                    "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_rgms_build", "sptir_rgms", "sptir_rgms_info",
+                    "sptir_rgms_destroy", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
                     "sptir_status_string", "sptir_last_hip_error")
 
 
@@ -102,6 +110,16 @@ def load_library(path: str | None = None):
     lib.sptir_sddmm_plan_info.argtypes = [ctypes.c_void_p, ctypes.POINTER(_PlanInfo)]
     lib.sptir_sddmm_plan_destroy.restype = ctypes.c_int
     lib.sptir_sddmm_plan_destroy.argtypes = [ctypes.c_void_p]
+    lib.sptir_rgms_build.restype = ctypes.c_int
+    lib.sptir_rgms_build.argtypes = [ctypes.POINTER(_Csr), ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                     ctypes.POINTER(ctypes.c_void_p)]
+    lib.sptir_rgms.restype = ctypes.c_int
+    lib.sptir_rgms.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                               ctypes.c_int32, ctypes.c_void_p]
+    lib.sptir_rgms_info.restype = ctypes.c_int
+    lib.sptir_rgms_info.argtypes = [ctypes.c_void_p, ctypes.POINTER(_RgmsInfo)]
+    lib.sptir_rgms_destroy.restype = ctypes.c_int
+    lib.sptir_rgms_destroy.argtypes = [ctypes.c_void_p]
     lib.sptir_spmm_csr.restype = ctypes.c_int
     lib.sptir_spmm_csr.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                    ctypes.c_void_p]
@@ -390,3 +408,70 @@ def sptir_sddmm_plan_destroy(plan: SddmmPlan) -> None:
         plan._h = ctypes.c_void_p(None)
         if st != SPTIR_OK:
             raise SptirError(st, "sptir_sddmm_plan_destroy")
+
+
+class Rgms:
+    """Owner of a sptir_rgms_t handle."""
+
+    def __init__(self, handle, n_rel, n_rows, n_cols):
+        self._h = ctypes.c_void_p(handle)
+        self.n_rel, self.n_rows, self.n_cols = n_rel, n_rows, n_cols
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise RuntimeError("rgms object already destroyed")
+        return self._h
+
+    def destroy(self):
+        sptir_rgms_destroy(self)
+
+    def __del__(self):
+        try:
+            if self._h and _lib is not None:
+                _lib.sptir_rgms_destroy(self._h)
+                self._h = ctypes.c_void_p(None)
+        except Exception:
+            pass
+
+
+def sptir_rgms_build(n_relations: int, n_rows: int, n_cols: int, indptr, indices, values, max_bucket_log2: int = -1,
+                     stream=None) -> Rgms:
+    """indptr covers the n_relations * n_rows stacked rows (relation after relation)."""
+    lib = load_library()
+    csr = _csr_struct(n_relations * n_rows, n_cols, indptr, indices, values)
+    out = ctypes.c_void_p(None)
+    st = lib.sptir_rgms_build(ctypes.byref(csr), n_relations, max_bucket_log2, _stream_ptr(stream), ctypes.byref(out))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_rgms_build")
+    return Rgms(out.value, n_relations, n_rows, n_cols)
+
+
+def sptir_rgms(rgms: Rgms, X, W, Y, stream=None) -> None:
+    _dev(X, torch.float32, "X"); _dev(W, torch.float32, "W"); _dev(Y, torch.float32, "Y")
+    if X.dim() != 2 or W.dim() != 3 or Y.dim() != 2:
+        raise ValueError("X and Y must be 2-D, W 3-D")
+    if X.shape[0] != rgms.n_cols or Y.shape[0] != rgms.n_rows or W.shape[0] != rgms.n_rel:
+        raise ValueError("operand sizes do not match the tensor")
+    if W.shape[1] != X.shape[1] or W.shape[2] != Y.shape[1]:
+        raise ValueError("W must be [n_relations, d_in, d_out]")
+    st = load_library().sptir_rgms(rgms.handle, X.data_ptr() or None, W.data_ptr() or None, Y.data_ptr() or None,
+                                   X.shape[1], Y.shape[1], _stream_ptr(stream))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_rgms")
+
+
+def sptir_rgms_info(rgms: Rgms) -> dict:
+    info = _RgmsInfo()
+    st = load_library().sptir_rgms_info(rgms.handle, ctypes.byref(info))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_rgms_info")
+    return {name: getattr(info, name) for name, _ in _RgmsInfo._fields_}
+
+
+def sptir_rgms_destroy(rgms: Rgms) -> None:
+    if rgms._h:
+        st = load_library().sptir_rgms_destroy(rgms._h)
+        rgms._h = ctypes.c_void_p(None)
+        if st != SPTIR_OK:
+            raise SptirError(st, "sptir_rgms_destroy")

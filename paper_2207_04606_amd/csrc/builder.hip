@@ -544,6 +544,11 @@ using namespace sptir;
 
 extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
                                           void* stream_, sptir_hyb_t** out) {
+  return sptir::hyb_build_impl(csr, n_col_parts, max_bucket_log2, stream_, out, true);
+}
+
+sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
+                                     void* stream_, sptir_hyb_t** out, bool with_spmm_plan) {
   if (!csr || !out) return SPTIR_ERR_INVALID_ARG;
   if (csr->n_rows < 0 || csr->n_cols < 0 || csr->nnz < 0) return SPTIR_ERR_INVALID_ARG;
   if (n_col_parts < 1 || max_bucket_log2 < 0 || max_bucket_log2 > 30) return SPTIR_ERR_INVALID_ARG;
@@ -668,6 +673,8 @@ extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_
     cs.log2_rb = log2_row_block_setting(
         s.n_rows, s.n_rows > 0 ? (double)(h->S + h->T) / s.n_rows / ((s.c + cs.ppg - 1) / cs.ppg) : 0.0);
     cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
+    if (!with_spmm_plan) cs.n_rb = 0;  // no row blocks, no cells, no chunks: only the canonical arrays are built
+    h->spmm_plan = with_spmm_plan ? 1 : 0;
     {
       // the compact stream needs the columns of one launch to fit kCompactColBits and the row block 7 bits
       const char* e = getenv("SPTIR_WIDE_STREAM");

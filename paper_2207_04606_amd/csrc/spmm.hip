@@ -715,6 +715,7 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
   if (x_bytes && y_bytes && overlaps(X, x_bytes, Y, y_bytes)) return SPTIR_ERR_INVALID_ARG;
   hipStream_t stream = (hipStream_t)stream_;
   if (h->n_rows == 0) return SPTIR_OK;
+  if (!h->spmm_plan) return SPTIR_ERR_UNSUPPORTED;
 
   Geometry g;
   if (!plan(((int64_t)h->n_row_blocks + kHybWaves - 1) / kHybWaves, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;

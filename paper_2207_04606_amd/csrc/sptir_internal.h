@@ -66,6 +66,7 @@ struct sptir_hyb {
   float* vals;               // device [S+T]
   int32_t* row_len;          // device [R+M], real length of every ELL row / remainder piece
   int32_t* stream;           // device [n_chunks * 128 or 192]: the chunks as fixed records, grouped by (phase, row block)
+  int32_t spmm_plan;         // 0: built without the chunk stream (canonical arrays only); sptir_spmm refuses it
   int32_t compact_stream;    // 1: 8-byte slots (columns relative to the launch), 0: 12-byte slots (global columns)
   int64_t* rb_chunk_ptr;     // device [n_phases * n_row_blocks + 1], first chunk of each group
   int64_t n_chunks;
@@ -90,6 +91,10 @@ namespace sptir {
 void current_allocator(sptir_alloc_fn* a, sptir_free_fn* f, void** ctx);
 void* default_alloc(size_t bytes, void* ctx, void* stream);
 void default_free(void* p, void* ctx);
+
+// sptir_hyb_build, optionally without the SpMM launch plan (for users of the canonical arrays alone)
+sptir_status_t hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2, void* stream,
+                              sptir_hyb_t** out, bool with_spmm_plan);
 
 // records a failed HIP call for sptir_last_hip_error(); returns SPTIR_ERR_HIP
 sptir_status_t note_hip_error(hipError_t e, const char* what);
