@@ -257,71 +257,111 @@ __global__ void k_cell_bounds(CellShape cs, const int64_t* __restrict__ bucket_r
   bin_rb_ptr[t] = (int32_t)lo;
 }
 
-struct CellRef {
-  int phase, rb, p, bin;
-  int32_t q_lo, q_hi;  // run of rows in row_ids
+// Cells of one (phase, row block) group, in chunk order: for every partition of the phase its nb bin cells and
+// one queue cell, then one pad cell that rounds the group's chunk count up to a multiple of kChunksPerQuad (the
+// SpMM kernel fetches chunks four at a time).
+//
+// How the rows of a (group, partition) become chunks:
+//  * buckets of width 1, 2, 4: 64/width whole rows per chunk, in the bucket's cell;
+//  * every other row piece (buckets of width >= 8, remainder pieces; at most kLongRowSlots entries) is cut into
+//    octets of 8 entries and dealt to eight queues, one per lane group of the SpMM kernel: chunk t of the queue
+//    cell holds the t-th octet of every queue.  A lane group then walks whole rows alone, keeps the running sum
+//    in registers and needs no cross-lane reduction; octets that would hold nothing but pads do not exist.  A
+//    row goes to the queue that is shortest so far (buckets are visited widest first, so this is the
+//    longest-first rule up to a factor of two);
+//  * unless the row alone is longer than an even share of what is still to be dealt: such a row is cut "wide"
+//    instead, into chunks of 64 entries that all eight lane groups share, in its bucket's cell.
+// The rows of one partition are distinct, so two queues never hand over the same row of Y in one instruction.
+__device__ __forceinline__ int cells_per_part(const CellShape& cs) { return cs.nb + 1; }
+__device__ __forceinline__ int cells_per_group(const CellShape& cs) { return cs.ppg * (cs.nb + 1) + 1; }
+__device__ __forceinline__ bool bin_is_narrow(const CellShape& cs, int bin) { return bin <= cs.k && bin < 3; }
+
+struct QueueOctet {  // what lane group g does in one chunk of a queue cell (all zero: nothing)
+  int64_t slot;      // first of up to 8 consecutive slots of the fused (cols, vals) arrays
+  int32_t q;         // the row piece (index into row_ids)
+  int32_t info;      // real entries (1..8) | (the piece ends here) << 8
 };
+static_assert(sizeof(QueueOctet) == 16, "QueueOctet must stay 16 bytes");
+constexpr uint32_t kChunkIsQueue = 1u << 14;
 
-// Every (phase, row block) group owns ppg*nb real cells and one trailing pad cell that rounds the group's
-// chunk count up to a multiple of kChunksPerQuad (the SpMM kernel fetches chunks four at a time).
-__device__ __forceinline__ int cells_per_group(const CellShape& cs) { return cs.ppg * cs.nb + 1; }
+__device__ __forceinline__ int chunks_of_length(int len) { return (len + kChunkSlots - 1) / kChunkSlots; }
 
-__device__ __forceinline__ bool decode_cell(const CellShape& cs, int64_t cell, const int32_t* __restrict__ bin_rb_ptr,
-                                            CellRef* r) {
-  const int cpg = cells_per_group(cs);
-  int within = (int)(cell % cpg);
-  int64_t t = cell / cpg;
-  r->rb = (int)(t % cs.n_rb);
-  r->phase = (int)(t / cs.n_rb);
-  r->bin = within % cs.nb;
-  r->p = r->phase * cs.ppg + within / cs.nb;
-  r->q_lo = r->q_hi = 0;
-  if (within == cpg - 1 || r->p >= cs.c) return false;  // pad cell, or a partition past the last one
-  const int32_t* ptr = bin_rb_ptr + ((int64_t)r->p * cs.nb + r->bin) * ((int64_t)cs.n_rb + 1) + r->rb;
-  r->q_lo = ptr[0];
-  r->q_hi = ptr[1];
-  return r->q_hi > r->q_lo;
-}
-
-// (a long piece contributes no chunks: a workgroup of its own sums it)
-__device__ __forceinline__ int chunks_of_length(int len) {
-  return len > kLongRowSlots ? 0 : (len + kChunkSlots - 1) / kChunkSlots;
-}
-
-// Rows of the buckets of width 8..64 are taken eight at a time ("row sets"): chunk t of a set holds
-// entries 8t .. 8t+7 of each of its eight rows, one row per octet, so that in the SpMM kernel every lane
-// group keeps the running sum of its own row and no cross-lane reduction is needed.  A set needs
-// ceil(longest row / 8) chunks.  The last (rows % 8) rows of a cell are cut the plain way.
-__device__ __forceinline__ bool bin_uses_row_sets(int bin, int k) { return bin <= k && bin >= 3 && bin <= 6; }
-
-__device__ __forceinline__ int set_chunks(const int32_t* __restrict__ row_len, int32_t q0) {
-  int longest = 0;
-  for (int i = 0; i < 8; ++i) longest = max(longest, row_len[q0 + i]);
-  return (longest + 7) >> 3;
-}
-
-__global__ void k_cell_chunk_counts(CellShape cs, int64_t n_cells, const int32_t* __restrict__ bin_rb_ptr,
-                                    const int32_t* __restrict__ row_len, long long* cell_chunks,
-                                    unsigned long long* n_long) {
-  int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (cell >= n_cells) return;
-  CellRef r;
-  long long n = 0;
-  if (decode_cell(cs, cell, bin_rb_ptr, &r)) {
-    int32_t q = r.q_lo;
-    if (bin_uses_row_sets(r.bin, cs.k))
-      for (; q + 8 <= r.q_hi; q += 8) n += set_chunks(row_len, q);
-    if (r.bin <= cs.k && (1 << r.bin) < kChunkSlots) {
-      int rows_per_chunk = kChunkSlots >> r.bin;
-      n += (r.q_hi - q + rows_per_chunk - 1) / rows_per_chunk;
-    } else {
-      for (; q < r.q_hi; ++q) {
-        n += chunks_of_length(row_len[q]);
-        if (row_len[q] > kLongRowSlots) atomicAdd(n_long, 1ull);
-      }
+// Walks the big row pieces of partition p in row block rb and tells the visitor what becomes of each:
+//   v.on_long(bin, q, len)                 set aside for the long-row launch
+//   v.on_wide(bin, q, len)                 cut into 64-entry chunks
+//   v.on_queued(bin, q, len, g, start)     octets start .. start + ceil(len/8) - 1 of queue g
+// and returns the length of the longest queue.
+template <typename Visitor>
+__device__ __forceinline__ int deal_partition(const CellShape& cs, const int32_t* __restrict__ bin_rb_ptr,
+                                              const int32_t* __restrict__ row_len, int p, int rb, Visitor& v) {
+  const int64_t per_bin = (int64_t)cs.n_rb + 1;
+  long long to_deal = 0;  // octets not dealt yet
+  for (int bin = 0; bin < cs.nb; ++bin) {
+    if (bin_is_narrow(cs, bin)) continue;
+    const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
+    for (int32_t q = ptr[0]; q < ptr[1]; ++q) {
+      const int len = row_len[q];
+      if (len <= kLongRowSlots) to_deal += (len + 7) >> 3;
     }
   }
-  cell_chunks[cell] = n;
+  int load[8];
+#pragma unroll
+  for (int g = 0; g < 8; ++g) load[g] = 0;
+  for (int bin = cs.nb - 1; bin >= 0; --bin) {
+    if (bin_is_narrow(cs, bin)) continue;
+    const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
+    for (int32_t q = ptr[0]; q < ptr[1]; ++q) {
+      const int len = row_len[q];
+      if (len > kLongRowSlots) { v.on_long(bin, q, len); continue; }
+      const int octets = (len + 7) >> 3;
+      const long long share = (to_deal + 7) >> 3;
+      to_deal -= octets;
+      if (len > kChunkSlots && octets > share) { v.on_wide(bin, q, len); continue; }
+      int best = 0, best_load = load[0];
+#pragma unroll
+      for (int g = 1; g < 8; ++g)
+        if (load[g] < best_load) { best_load = load[g]; best = g; }
+      v.on_queued(bin, q, len, best, best_load);
+#pragma unroll
+      for (int g = 0; g < 8; ++g) load[g] += (g == best) ? octets : 0;
+    }
+  }
+  int longest = 0;
+#pragma unroll
+  for (int g = 0; g < 8; ++g) longest = max(longest, load[g]);
+  return longest;
+}
+
+// One thread per (group, partition of its phase): chunk counts of that partition's cells.
+struct CountVisitor {
+  long long* cell;  // the partition's nb + 1 counts
+  unsigned long long* n_long;
+  __device__ void on_long(int, int32_t, int) { atomicAdd(n_long, 1ull); }
+  __device__ void on_wide(int bin, int32_t, int len) { cell[bin] += chunks_of_length(len); }
+  __device__ void on_queued(int, int32_t, int, int, int) {}
+};
+
+__global__ void k_part_chunk_counts(CellShape cs, int64_t n_parts, const int32_t* __restrict__ bin_rb_ptr,
+                                    const int32_t* __restrict__ row_len, long long* cell_chunks,
+                                    unsigned long long* n_long) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_parts) return;
+  const int64_t grp = t / cs.ppg;
+  const int p_local = (int)(t % cs.ppg);
+  const int rb = (int)(grp % cs.n_rb), phase = (int)(grp / cs.n_rb);
+  const int p = phase * cs.ppg + p_local;
+  long long* cell = cell_chunks + grp * cells_per_group(cs) + (int64_t)p_local * cells_per_part(cs);
+  for (int i = 0; i <= cs.nb; ++i) cell[i] = 0;
+  if (p >= cs.c) return;  // a partition past the last one
+  const int64_t per_bin = (int64_t)cs.n_rb + 1;
+  for (int bin = 0; bin < cs.nb; ++bin) {
+    if (!bin_is_narrow(cs, bin)) continue;
+    const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
+    const int rows_per_chunk = kChunkSlots >> bin;
+    cell[bin] = (ptr[1] - ptr[0] + rows_per_chunk - 1) / rows_per_chunk;
+  }
+  CountVisitor v{cell, n_long};
+  cell[cs.nb] = deal_partition(cs, bin_rb_ptr, row_len, p, rb, v);
 }
 
 // One thread per (phase, row block) group: the pad cell gets what is missing to a multiple of kChunksPerQuad,
@@ -343,76 +383,106 @@ __global__ void k_group_scan(CellShape cs, int64_t n_groups, long long* cell_chu
 
 constexpr int kGroupSeq = 1024;  // groups per sequence of the two-level scan over group totals
 
-__global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t* __restrict__ bin_rb_ptr,
+// One thread per (group, partition): writes the chunk descriptors the counts above announced.
+struct FillVisitor {
+  const CellShape& cs;
+  int p;
+  int64_t first_chunk;          // of the partition's first cell
+  const long long* cell;        // scanned counts: chunks of this group before each of the partition's cells ...
+  long long cell0;              // ... minus those before its first cell
+  const int32_t* row_ids;
+  const int64_t* bucket_row_ptr;
+  const int64_t* bucket_slot_ptr;
+  const int64_t* rem_ptr;
+  int64_t S;
+  Chunk* chunks;
+  QueueOctet* octets;
+  LongPiece* long_pieces;
+  unsigned long long* long_cursor;
+  int wide_bin;                 // bin whose wide rows are being written, and the next free chunk of its cell
+  int64_t wide_it;
+
+  __device__ int64_t cell_first(int i) const { return first_chunk + (cell[i] - cell0); }
+  __device__ int64_t slot_of(int bin, int32_t q) const {
+    if (bin <= cs.k) {
+      const int64_t b = (int64_t)p * (cs.k + 1) + bin;
+      return bucket_slot_ptr[b] + (((int64_t)q - bucket_row_ptr[b]) << bin);
+    }
+    return S + rem_ptr[q - cs.R];
+  }
+  __device__ void on_long(int bin, int32_t q, int len) {  // listed in no particular order
+    LongPiece lp;
+    lp.slot0 = slot_of(bin, q); lp.row = row_ids[q]; lp.len = len; lp.q = q; lp.pad_ = 0;
+    long_pieces[atomicAdd(long_cursor, 1ull)] = lp;
+  }
+  __device__ void on_wide(int bin, int32_t q, int len) {
+    if (bin != wide_bin) { wide_bin = bin; wide_it = cell_first(bin); }
+    const int64_t slot0 = slot_of(bin, q);
+    for (int off = 0; off < len; off += kChunkSlots) {
+      Chunk ck;
+      ck.slot0 = slot0 + off; ck.row0 = q;
+      const int count = len - off < kChunkSlots ? len - off : kChunkSlots;
+      ck.meta = (uint32_t)kRowLog2W | ((uint32_t)count << 6) | (off + kChunkSlots >= len ? (1u << 13) : 0u);
+      chunks[wide_it++] = ck;
+    }
+  }
+  __device__ void on_queued(int bin, int32_t q, int len, int g, int start) {
+    const int64_t slot0 = slot_of(bin, q);
+    const int64_t first = cell_first(cs.nb) + start;
+    const int n_oct = (len + 7) >> 3;
+    for (int i = 0; i < n_oct; ++i) {
+      QueueOctet o;
+      o.slot = slot0 + 8 * i; o.q = q;
+      o.info = (len - 8 * i < 8 ? len - 8 * i : 8) | (i == n_oct - 1 ? 0x100 : 0);
+      octets[(first + i) * 8 + g] = o;
+    }
+  }
+};
+
+__global__ void k_part_fill_chunks(CellShape cs, int64_t n_parts, const int32_t* __restrict__ bin_rb_ptr,
                                    const long long* __restrict__ cell_first_chunk,
                                    const long long* __restrict__ group_first_chunk,
                                    const long long* __restrict__ seq_first_chunk,
                                    const int32_t* __restrict__ row_len, const int32_t* __restrict__ row_ids,
                                    const int64_t* __restrict__ bucket_row_ptr,
                                    const int64_t* __restrict__ bucket_slot_ptr, const int64_t* __restrict__ rem_ptr,
-                                   int64_t S, Chunk* chunks, int64_t* rb_chunk_ptr, LongPiece* long_pieces,
-                                   unsigned long long* long_cursor) {
-  int64_t cell = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (cell >= n_cells) return;
-  CellRef r;
-  bool any = decode_cell(cs, cell, bin_rb_ptr, &r);
-  const int64_t grp = cell / cells_per_group(cs);
-  int64_t it = cell_first_chunk[cell] + group_first_chunk[grp] + seq_first_chunk[grp / kGroupSeq];
-  const int64_t group_first_cell = cell - cell % cells_per_group(cs);
-  if (cell == group_first_cell) rb_chunk_ptr[(int64_t)r.phase * cs.n_rb + r.rb] = it;
-  if (!any) return;
-  // The whole list of a (phase, row block) is walked by one wavefront, which carries the partial sum of a
-  // row that continues in the next chunk in registers and hands it over when the row (or row set) ends.
-  auto emit = [&](int64_t slot0, int32_t row0, int lw, int count, bool row_ends, uint32_t extra = 0u) {
+                                   int64_t S, Chunk* chunks, QueueOctet* octets, int64_t* rb_chunk_ptr,
+                                   LongPiece* long_pieces, unsigned long long* long_cursor) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_parts) return;
+  const int64_t grp = t / cs.ppg;
+  const int p_local = (int)(t % cs.ppg);
+  const int rb = (int)(grp % cs.n_rb), phase = (int)(grp / cs.n_rb);
+  const int p = phase * cs.ppg + p_local;
+  const long long* cell = cell_first_chunk + grp * cells_per_group(cs) + (int64_t)p_local * cells_per_part(cs);
+  const int64_t group_first = group_first_chunk[grp] + seq_first_chunk[grp / kGroupSeq];
+  if (p_local == 0) rb_chunk_ptr[(int64_t)phase * cs.n_rb + rb] = group_first;
+  if (p >= cs.c) return;
+  FillVisitor v{cs, p, group_first + cell[0], cell, cell[0], row_ids, bucket_row_ptr, bucket_slot_ptr, rem_ptr, S,
+                chunks, octets, long_pieces, long_cursor, -1, 0};
+  // buckets narrower than 8: several whole rows per chunk
+  const int64_t per_bin = (int64_t)cs.n_rb + 1;
+  for (int bin = 0; bin < cs.nb; ++bin) {
+    if (!bin_is_narrow(cs, bin)) continue;
+    const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
+    const int rows_per_chunk = kChunkSlots >> bin;
+    int64_t it = v.cell_first(bin);
+    for (int32_t q = ptr[0]; q < ptr[1]; q += rows_per_chunk) {
+      const int rows = ptr[1] - q < rows_per_chunk ? ptr[1] - q : rows_per_chunk;
+      Chunk ck;
+      ck.slot0 = v.slot_of(bin, q); ck.row0 = q;
+      ck.meta = (uint32_t)bin | ((uint32_t)(rows << bin) << 6) | (1u << 13);
+      chunks[it++] = ck;
+    }
+  }
+  const int n_queue_chunks = deal_partition(cs, bin_rb_ptr, row_len, p, rb, v);
+  const int64_t first = v.cell_first(cs.nb);
+  for (int i = 0; i < n_queue_chunks; ++i) {  // to the kernel a queue chunk looks like eight rows of width 8
     Chunk ck;
-    ck.slot0 = slot0;
-    ck.row0 = row0;
-    ck.meta = (uint32_t)lw | ((uint32_t)count << 6) | (row_ends ? (1u << 13) : 0u) | extra;
-    chunks[it++] = ck;
-  };
-  auto set_aside = [&](int64_t slot0, int32_t q, int len) {  // a long piece: listed in no particular order
-    LongPiece lp;
-    lp.slot0 = slot0; lp.row = row_ids[q]; lp.len = len; lp.q = q; lp.pad_ = 0;
-    long_pieces[atomicAdd(long_cursor, 1ull)] = lp;
-  };
-  if (r.bin <= cs.k) {
-    int64_t b = (int64_t)r.p * (cs.k + 1) + r.bin;
-    int64_t width = (int64_t)1 << r.bin;
-    int64_t first_slot = bucket_slot_ptr[b] + ((int64_t)r.q_lo - bucket_row_ptr[b]) * width;
-    int32_t q_plain = r.q_lo;  // rows from here on are cut the plain way
-    if (bin_uses_row_sets(r.bin, cs.k)) {
-      for (; q_plain + 8 <= r.q_hi; q_plain += 8) {
-        const int n_t = set_chunks(row_len, q_plain);
-        for (int t = 0; t < n_t; ++t)  // to the kernel a set chunk looks like eight rows of width 8
-          emit(first_slot + ((int64_t)(q_plain - r.q_lo) << r.bin), q_plain, 3, kChunkSlots, t == n_t - 1,
-               kChunkIsRowSet | ((uint32_t)t << 15) | ((uint32_t)r.bin << 21));
-      }
-    }
-    if (width < kChunkSlots) {  // several whole rows per chunk
-      int rows_per_chunk = kChunkSlots >> r.bin;
-      for (int32_t q = q_plain; q < r.q_hi; q += rows_per_chunk) {
-        int rows = r.q_hi - q < rows_per_chunk ? r.q_hi - q : rows_per_chunk;
-        emit(first_slot + ((int64_t)(q - r.q_lo) << r.bin), q, r.bin, rows << r.bin, true);
-      }
-    } else {  // a row takes one chunk per 64 real entries
-      for (int32_t q = q_plain; q < r.q_hi; ++q) {
-        int len = row_len[q];
-        int64_t row_slot = first_slot + (int64_t)(q - r.q_lo) * width;
-        if (len > kLongRowSlots) { set_aside(row_slot, q, len); continue; }
-        for (int off = 0; off < len; off += kChunkSlots)
-          emit(row_slot + off, q, kRowLog2W, len - off < kChunkSlots ? len - off : kChunkSlots,
-               off + kChunkSlots >= len);
-      }
-    }
-  } else {
-    for (int32_t q = r.q_lo; q < r.q_hi; ++q) {
-      int64_t begin = rem_ptr[q - cs.R];
-      int len = row_len[q];
-      if (len > kLongRowSlots) { set_aside(S + begin, q, len); continue; }
-      for (int off = 0; off < len; off += kChunkSlots)
-        emit(S + begin + off, q, kRowLog2W, len - off < kChunkSlots ? len - off : kChunkSlots,
-             off + kChunkSlots >= len);
-    }
+    ck.slot0 = first + i;  // its octets are octets[8 * slot0 ..]
+    ck.row0 = 0;
+    ck.meta = 3u | ((uint32_t)kChunkSlots << 6) | kChunkIsQueue;
+    chunks[first + i] = ck;
   }
 }
 
@@ -425,7 +495,8 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
 //   quad[  0..255]  column ids, chunk i at 64*i  (slots past `count` repeat the last real column)
 //   quad[256..511]  values                        (slots past `count` hold +0.0f)
 //   quad[512..767]  per slot: row relative to the first row of the row block in bits 0..15,
-//                   the chunk's log2w in bits 16..21, its hand-over flag in bit 22;
+//                   the chunk's log2w in bits 16..21, the hand-over flag in bit 22 (the chunk's, or in a
+//                   queue chunk the octet's), bit 23: the slot belongs to no row (an idle octet);
 //                   slots past `count` hold -1
 // The compact form (2 KB per quad; the kernel's time goes with the bytes it has
 // to pull from beyond L2, and every feature tile re-reads the stream) folds the
@@ -435,6 +506,7 @@ __global__ void k_cell_fill_chunks(CellShape cs, int64_t n_cells, const int32_t*
 // One wavefront per chunk; reads the canonical arrays through the descriptor.
 __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chunk* __restrict__ chunks,
                                                      const int32_t* __restrict__ row_ids,
+                                                     const QueueOctet* __restrict__ octets,
                                                      const int32_t* __restrict__ cols, const float* __restrict__ vals,
                                                      int32_t log2_rb, int32_t compact, int32_t phase_width,
                                                      int32_t* stream) {
@@ -443,7 +515,6 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chu
   int lane = threadIdx.x & 63;
   const Chunk ck = chunks[q];
   const int lw = (int)(ck.meta & 63u), count = (int)((ck.meta >> 6) & 127u);
-  const int hand_over = (int)((ck.meta >> 13) & 1u);
   // chunk i of quad Q sits at slots 64*i .. 64*i+63 of the quad's 256-slot arrays
   constexpr int kQuadSlots = kChunkSlots * kChunksPerQuad;
   int32_t* quad = stream + (q / kChunksPerQuad) * ((compact ? 2 : 3) * kQuadSlots);
@@ -456,27 +527,39 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chu
   }
   int64_t src;
   int32_t rid;
-  if (ck.meta & kChunkIsRowSet) {  // octet g of the chunk = entries 8t .. 8t+7 of the set's row g
-    const int t = (int)((ck.meta >> 15) & 63u), log2_width = (int)((ck.meta >> 21) & 31u);
-    src = ck.slot0 + ((int64_t)(lane >> 3) << log2_width) + 8 * t + (lane & 7);
-    rid = row_ids[ck.row0 + (lane >> 3)];
+  bool real, valid;
+  int hand_over = (int)((ck.meta >> 13) & 1u);
+  if (ck.meta & kChunkIsQueue) {  // octet g of the chunk: up to 8 entries of one row piece, or nothing
+    const QueueOctet o = octets[ck.slot0 * 8 + (lane >> 3)];
+    const int n = o.info & 0xFF, j = lane & 7;
+    if (n == 0) {  // an idle lane group: zeros that belong to no row
+      quad[at] = compact ? (int32_t)(3u << 28) : 0;
+      quad[kQuadSlots + at] = 0;
+      if (!compact) quad[2 * kQuadSlots + at] = (3 << 16) | (1 << 23);  // the chunk's log2w, "no row"
+      return;
+    }
+    src = o.slot + (j < n ? j : n - 1);
+    rid = row_ids[o.q];
+    real = j < n;
+    valid = true;  // a pad of an octet still names the octet's row: the lane group hands the row over by its first slot
+    hand_over = (o.info >> 8) & 1;
   } else {
     const int o = lane < count ? lane : count - 1;
     src = ck.slot0 + o;
     rid = row_ids[ck.row0 + (o >> lw)];
+    real = valid = lane < count;
   }
   int32_t col = cols[src];
   float val = vals[src];
   const int local_row = rid & ((1 << log2_rb) - 1);
-  const bool real = lane < count;
   quad[kQuadSlots + at] = real ? __float_as_int(val) : 0;
   if (compact) {
     const uint32_t col_rel = (uint32_t)(col - (col / phase_width) * phase_width);  // a launch covers phase_width columns
-    quad[at] = (int32_t)(col_rel | ((uint32_t)local_row << kCompactColBits) | ((uint32_t)real << 27) |
+    quad[at] = (int32_t)(col_rel | ((uint32_t)local_row << kCompactColBits) | ((uint32_t)valid << 27) |
                          ((uint32_t)(lw > 6 ? 7 : lw) << 28) | ((uint32_t)hand_over << 31));
   } else {
     quad[at] = col;
-    quad[2 * kQuadSlots + at] = real ? (local_row | (lw << 16) | (hand_over << 22)) : -1;
+    quad[2 * kQuadSlots + at] = valid ? (local_row | (lw << 16) | (hand_over << 22)) : -1;
   }
 }
 
@@ -583,6 +666,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   if (!tmp.base) return SPTIR_ERR_ALLOC;
   Blob tmp2;
   void* tmp_chunks = nullptr;
+  void* tmp_octets = nullptr;
 
   sptir_hyb* h = new (std::nothrow) sptir_hyb();
   if (!h) { free_(tmp.base, actx); return SPTIR_ERR_ALLOC; }
@@ -687,7 +771,8 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     h->log2_row_block = cs.log2_rb; h->n_row_blocks = cs.n_rb;
     h->parts_per_phase = cs.ppg; h->n_phases = cs.n_phases;
     const int64_t n_groups = (int64_t)cs.n_phases * cs.n_rb;
-    const int64_t n_cells = n_groups * ((int64_t)cs.ppg * cs.nb + 1);
+    const int64_t n_cells = n_groups * ((int64_t)cs.ppg * (cs.nb + 1) + 1);
+    const int64_t n_parts = n_groups * cs.ppg;
     const int64_t n_bounds = (int64_t)s.c * s.nb * ((int64_t)cs.n_rb + 1);
     if (n_cells > 0x7FFFFFFF || n_bounds > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
     const size_t o_bounds = tmp2.reserve(sizeof(int32_t) * (size_t)(n_bounds ? n_bounds : 1));
@@ -762,8 +847,8 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       BUILD_HIP(hipMemsetAsync(d_long_cursor, 0, sizeof(long long), stream));
       hipLaunchKernelGGL(k_cell_bounds, dim3((unsigned)((n_bounds + 255) / 256)), dim3(256), 0, stream, cs,
                          h->bucket_row_ptr, h->rem_part_ptr, h->row_ids, d_bounds);
-      hipLaunchKernelGGL(k_cell_chunk_counts, dim3((unsigned)((n_cells + 255) / 256)), dim3(256), 0, stream, cs,
-                         n_cells, d_bounds, h->row_len, d_cell_chunks, (unsigned long long*)(d_cell_total + 1));
+      hipLaunchKernelGGL(k_part_chunk_counts, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs,
+                         n_parts, d_bounds, h->row_len, d_cell_chunks, (unsigned long long*)(d_cell_total + 1));
       hipLaunchKernelGGL(k_group_scan, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, stream, cs, n_groups,
                          d_cell_chunks, d_group_tot);
       // chunks before a cell = its prefix inside the group + the group's inside its sequence + the sequence's
@@ -784,6 +869,10 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       tmp_chunks = alloc(bytes, actx, stream);  // descriptors are only needed until the stream is packed
       if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
       BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, bytes, stream));  // count 0 marks the padding chunks
+      bytes = sizeof(QueueOctet) * 8 * (size_t)(n_chunks ? n_chunks : 1);
+      tmp_octets = alloc(bytes, actx, stream);  // indexed by chunk, so that queue cells need no numbering of their own
+      if (!tmp_octets) { st = SPTIR_ERR_ALLOC; goto fail; }
+      BUILD_HIP(hipMemsetAsync(tmp_octets, 0, bytes, stream));  // all zero: an idle lane group
       bytes = sizeof(int32_t) * (h->compact_stream ? 2 : 3) * kChunkSlots * (size_t)(n_chunks ? n_chunks : 1);
       h->stream = (int32_t*)alloc(bytes, actx, stream);
       if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
@@ -795,11 +884,11 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
         h->device_bytes += bytes;
       }
     }
-    if (n_cells > 0)
-      hipLaunchKernelGGL(k_cell_fill_chunks, dim3((unsigned)((n_cells + 255) / 256)), dim3(256), 0, stream, cs,
-                         n_cells, d_bounds, d_cell_chunks, d_group_tot, d_seq_tot, h->row_len, h->row_ids,
+    if (n_parts > 0)
+      hipLaunchKernelGGL(k_part_fill_chunks, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs,
+                         n_parts, d_bounds, d_cell_chunks, d_group_tot, d_seq_tot, h->row_len, h->row_ids,
                          h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_ptr, h->S, (Chunk*)tmp_chunks,
-                         h->rb_chunk_ptr, h->long_pieces, d_long_cursor);
+                         (QueueOctet*)tmp_octets, h->rb_chunk_ptr, h->long_pieces, d_long_cursor);
     if (n_long > 0) {
       // The long pieces arrive in no particular order: sort them by (row, partition) on the host, so that
       // one workgroup sums all pieces of a row in a fixed order.  There are few of them by construction
@@ -833,7 +922,8 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       int64_t blocks = (n_chunks + 3) / 4;
       if (blocks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
       hipLaunchKernelGGL(k_pack_stream, dim3((unsigned)blocks), dim3(256), 0, stream, (int64_t)n_chunks,
-                         (const Chunk*)tmp_chunks, h->row_ids, h->cols, h->vals, cs.log2_rb, h->compact_stream,
+                         (const Chunk*)tmp_chunks, h->row_ids, (const QueueOctet*)tmp_octets, h->cols, h->vals,
+                         cs.log2_rb, h->compact_stream,
                          (int32_t)((int64_t)cs.ppg * s.w > 0x7FFFFFFF ? 0x7FFFFFFF : (int64_t)cs.ppg * s.w), h->stream);
     }
     {
@@ -847,6 +937,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   free_(tmp.base, actx);
   if (tmp2.base) free_(tmp2.base, actx);
   if (tmp_chunks) free_(tmp_chunks, actx);
+  if (tmp_octets) free_(tmp_octets, actx);
   *out = h;
   return SPTIR_OK;
 
@@ -855,6 +946,7 @@ fail:
   free_(tmp.base, actx);
   if (tmp2.base) free_(tmp2.base, actx);
   if (tmp_chunks) free_(tmp_chunks, actx);
+  if (tmp_octets) free_(tmp_octets, actx);
   sptir_hyb_destroy(h);
   return st;
 #undef BUILD_HIP

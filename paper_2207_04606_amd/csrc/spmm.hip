@@ -321,7 +321,10 @@ struct HybWalker {
 
   // what a slot's row word says (WIDE: its own array; compact: the upper bits of the column word)
   static __device__ __forceinline__ int local_row(int r) { return WIDE ? (r & 0xFFFF) : ((r >> kCompactColBits) & 127); }
-  static __device__ __forceinline__ bool row_valid(int r) { return WIDE ? r >= 0 : ((r >> 27) & 1) != 0; }
+  static __device__ __forceinline__ bool row_valid(int r) {
+    return WIDE ? (r >= 0 && ((r >> 23) & 1) == 0) : ((r >> 27) & 1) != 0;
+  }
+  static __device__ __forceinline__ bool slot_hands_over(int r) { return WIDE ? ((r >> 22) & 1) != 0 : r < 0; }
 
   __device__ __forceinline__ int* slot_of(int q) const { return ring + (q & 1) * kQuadInts; }
 
@@ -401,8 +404,17 @@ struct HybWalker {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
     if (one_row_chunk && !(hand_over && sub == SUB - 1)) return;  // the row goes on: keep the sums in registers
-    // a row-set chunk (eight rows, eight entries each): every octet keeps its row's sum until the set's last chunk
-    if (SUB == 1 && lw == 3 && !hand_over) return;
+    if (SUB == 1 && UB == 8 && lw == 3) {
+      // a queue chunk: every lane group walks a row of its own, octet by octet, and the word of the octet's
+      // first slot says whether the row ends here
+      const int r = rows[first_slot(s)];
+      if (slot_hands_over(r)) {
+        sink(local_row(r), row_valid(r), acc);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+      }
+      return;
+    }
     if (!one_row_chunk && lw >= S::kLog2Chunk && (((sub + 1) * CS) & ((1 << lw) - 1)) != 0) return;  // row spans steps
     const int groups = (one_row_chunk || lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));
     sum_groups<VEC, LG>(acc, groups);

@@ -19,10 +19,9 @@ struct Chunk {
   int64_t slot0;
   int32_t row0;
   // bits 0..5 log2w, bits 6..12 count (1..64), bit 13: hand the row's partial sum over after this chunk,
-  // bit 14: row-set chunk (then bits 15..20: which group of 8 entries, bits 21..25: log2 of the bucket width)
+  // bit 14: queue chunk (eight octets of eight different rows; slot0 then indexes the builder's octet table)
   uint32_t meta;
 };
-constexpr uint32_t kChunkIsRowSet = 1u << 14;
 static_assert(sizeof(Chunk) == 16, "Chunk must stay 16 bytes");
 
 constexpr int kChunkSlots = 64;
