@@ -20,6 +20,9 @@
 //   scatter    float atomic adds of the 32 x 32 results into the rows of Y
 //              (a row of Y collects from every relation and bucket, in no
 //              fixed order: results agree to rounding, not bit for bit).
+//              These atomics execute beyond L2 and bound the kernel at about
+//              1 TB/s of added bytes; ordering the tiles by destination row
+//              was measured to change nothing.
 // Y is zero-filled first by a kernel of its own (the operator overwrites Y).
 #include <string.h>
 
