@@ -4,7 +4,7 @@
 // Mapping (gfx950, wave64).  The feature dimension is cut into tiles of
 // LG*VEC floats (32 floats = one 128-byte line of X by default).  A wavefront
 // owns one (row block, feature tile): it keeps that tile of the row block's Y
-// rows (32 rows by default, 4 KB) in its own piece of LDS, walks every chunk of
+// rows (32 to 128 rows, 4 to 16 KB) in its own piece of LDS, walks every chunk of
 // the row block's list (all column partitions of the launch, all ELL buckets,
 // the remainder) and finally writes the Y tile with plain coalesced stores.
 // Nothing is shared between wavefronts: no atomics, no barriers, no zero fill
@@ -64,7 +64,7 @@ struct Shape {
 
 // LDS position of the VEC floats lane fl of a group owns in local row r of the wavefront's Y tile.  Rows are
 // rotated against each other by one lane's share, so that lane groups working on neighbouring rows
-// (a row-set chunk hands eight rows over at once) hit different banks.
+// (the lane groups of a queue chunk may hand eight rows over at once) hit different banks.
 template <int VEC, int LG>
 __device__ __forceinline__ int tile_index(int r, int fl) {
   return (r * LG + ((fl + r) & (LG - 1))) * VEC;
