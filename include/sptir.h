@@ -247,6 +247,12 @@ sptir_status_t sptir_sddmm_plan_destroy(sptir_sddmm_plan_t* plan); /* NULL is ac
  *             int32 indices strictly ascending inside a stacked row, float32
  *             values; validated like sptir_hyb_build's input)
  *   max_bucket_log2   0..5, or negative for the paper's 5
+ *   workspace_d_out   0, or a multiple of 32: the handle then also owns a scatter workspace of one row of
+ *             workspace_d_out floats per (relation, row) pair, and sptir_rgms calls with d_out <= workspace_d_out
+ *             (and a 16-byte aligned Y) store the product rows there and sum them per row of Y in a second pass,
+ *             in a fixed order: results are then reproducible bit for bit, for about 20 % more time than the
+ *             float atomics used otherwise.  This is not the n_relations x n_rows x d_out intermediate the
+ *             paper avoids: it has one row per non-empty pair.
  * sptir_rgms_build owns device memory through the allocator hook and
  * synchronises `stream`.  Errors: those of sptir_hyb_build; INVALID_ARG if
  * stacked->n_rows is not a multiple of n_relations.
@@ -259,19 +265,23 @@ typedef struct {
   int64_t n_stacked_rows_stored;  /* (relation, row) pairs with at least one entry, remainder pieces included */
   int64_t n_pad_slots;
   int64_t n_tiles;                /* 32-row tiles, one wavefront each */
+  int32_t workspace_d_out;        /* widest d_out the scatter workspace serves (0: none) */
+  int32_t reserved;
   int64_t device_bytes;
 } sptir_rgms_info_t;
 
 sptir_status_t sptir_rgms_build(const sptir_csr_t* stacked, int32_t n_relations, int32_t max_bucket_log2,
-                                void* stream, sptir_rgms_t** out);
+                                int32_t workspace_d_out, void* stream, sptir_rgms_t** out);
 /*
  *   X  device, [n_cols, d_in] row-major float32, 16-byte aligned
  *   W  device, [n_relations, d_in, d_out] row-major float32
  *   Y  device, [n_rows, d_out] row-major float32, overwritten (rows without entries become 0)
  *   d_in in {32, 64, 128}, d_out a multiple of 32 (UNSUPPORTED otherwise; the paper runs 32 x 32)
  * Only enqueues work on `stream`; no allocation.  Products and sums are float32 (float32 matrix-core
- * instructions); the contributions of different relations and buckets meet in Y through float atomic adds
- * in no fixed order, so results agree between runs to rounding, not bit for bit.  X must be finite (pad slots).
+ * instructions).  Without the workspace the contributions of different relations and buckets meet in Y through
+ * float atomic adds in no fixed order, so results agree between runs to rounding, not bit for bit; with it only
+ * pairs of more than 2^k entries still do.  Calls that share a handle's workspace must not overlap in time.
+ * X must be finite (pad slots).
  */
 sptir_status_t sptir_rgms(const sptir_rgms_t* rgms, const float* X, const float* W, float* Y, int32_t d_in,
                           int32_t d_out, void* stream);

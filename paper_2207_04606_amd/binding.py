@@ -59,7 +59,8 @@ class _RgmsInfo(ctypes.Structure):
     _fields_ = [("n_relations", ctypes.c_int32), ("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32),
                 ("max_bucket_log2", ctypes.c_int32), ("nnz", ctypes.c_int64),
                 ("n_stacked_rows_stored", ctypes.c_int64), ("n_pad_slots", ctypes.c_int64),
-                ("n_tiles", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
+                ("n_tiles", ctypes.c_int64), ("workspace_d_out", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("device_bytes", ctypes.c_int64)]
 
 
 _ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p)
@@ -111,8 +112,8 @@ def load_library(path: str | None = None):
     lib.sptir_sddmm_plan_destroy.restype = ctypes.c_int
     lib.sptir_sddmm_plan_destroy.argtypes = [ctypes.c_void_p]
     lib.sptir_rgms_build.restype = ctypes.c_int
-    lib.sptir_rgms_build.argtypes = [ctypes.POINTER(_Csr), ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
-                                     ctypes.POINTER(ctypes.c_void_p)]
+    lib.sptir_rgms_build.argtypes = [ctypes.POINTER(_Csr), ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                     ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
     lib.sptir_rgms.restype = ctypes.c_int
     lib.sptir_rgms.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                ctypes.c_int32, ctypes.c_void_p]
@@ -436,12 +437,13 @@ class Rgms:
 
 
 def sptir_rgms_build(n_relations: int, n_rows: int, n_cols: int, indptr, indices, values, max_bucket_log2: int = -1,
-                     stream=None) -> Rgms:
+                     workspace_d_out: int = 0, stream=None) -> Rgms:
     """indptr covers the n_relations * n_rows stacked rows (relation after relation)."""
     lib = load_library()
     csr = _csr_struct(n_relations * n_rows, n_cols, indptr, indices, values)
     out = ctypes.c_void_p(None)
-    st = lib.sptir_rgms_build(ctypes.byref(csr), n_relations, max_bucket_log2, _stream_ptr(stream), ctypes.byref(out))
+    st = lib.sptir_rgms_build(ctypes.byref(csr), n_relations, max_bucket_log2, workspace_d_out, _stream_ptr(stream),
+                              ctypes.byref(out))
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_rgms_build")
     return Rgms(out.value, n_relations, n_rows, n_cols)

@@ -14,18 +14,21 @@ pytestmark = pytest.mark.gpu
 Y_TOL = 1e-5
 
 
-def run_rgms(sptir, w, k=-1, d_out=None):
+def run_rgms(sptir, w, k=-1, workspace_d_out=0, repeat=1):
     dev = "cuda"
     ip = torch.from_numpy(w.indptr).to(dev)
     ix = torch.from_numpy(w.indices).to(dev)
     va = torch.from_numpy(w.values).to(dev)
-    h = sptir.sptir_rgms_build(w.n_rel, w.n, w.n, ip, ix, va, k)
+    h = sptir.sptir_rgms_build(w.n_rel, w.n, w.n, ip, ix, va, k, workspace_d_out)
     info = sptir.sptir_rgms_info(h)
-    Y = torch.full((w.n, w.W.shape[2]), float("nan"), device=dev)
-    sptir.sptir_rgms(h, torch.from_numpy(w.X).to(dev), torch.from_numpy(w.W).to(dev), Y)
-    out = Y.cpu().numpy()
+    X, W = torch.from_numpy(w.X).to(dev), torch.from_numpy(w.W).to(dev)
+    outs = []
+    for _ in range(repeat):
+        Y = torch.full((w.n, w.W.shape[2]), float("nan"), device=dev)
+        sptir.sptir_rgms(h, X, W, Y)
+        outs.append(Y.cpu().numpy())
     h.destroy()
-    return out, info
+    return (outs[0] if repeat == 1 else outs), info
 
 
 def assert_y_close(Y_gpu, Y_ref, S_ref, what):
@@ -41,11 +44,14 @@ def assert_y_close(Y_gpu, Y_ref, S_ref, what):
 
 @pytest.mark.parametrize("d_in,d_out", [(32, 32), (32, 64), (64, 32), (128, 96), (64, 128)])
 @pytest.mark.parametrize("k", [-1, 0, 2, 5])
-def test_rgms_small_graphs(gpu_lib, d_in, d_out, k):
-    say(f"[rgms] d_in={d_in} d_out={d_out} k={k}")
+@pytest.mark.parametrize("workspace", [0, 64, 128])
+def test_rgms_small_graphs(gpu_lib, d_in, d_out, k, workspace):
+    """workspace 0: atomics only; 64: the workspace serves d_out <= 64 and the wider calls fall back to atomics."""
+    say(f"[rgms] d_in={d_in} d_out={d_out} k={k} workspace={workspace}")
     w = workloads.make_hetero("hetero_tiny", seed=d_in + d_out + k, d_in=d_in, d_out=d_out)
-    Y, info = run_rgms(gpu_lib, w, k)
+    Y, info = run_rgms(gpu_lib, w, k, workspace)
     assert info["nnz"] == w.nnz and info["n_relations"] == w.n_rel and info["max_bucket_log2"] == (5 if k < 0 else k)
+    assert info["workspace_d_out"] == workspace
     Yr, Sr = oracle.rgms(w.n_rel, w.n, w.indptr, w.indices, w.values, w.X, w.W)
     assert_y_close(Y, Yr, Sr, f"d_in={d_in} d_out={d_out} k={k}")
 
@@ -68,10 +74,10 @@ def test_rgms_long_rows_and_empty_relations(gpu_lib):
                                  rng.uniform(-1, 1, key.shape[0]).astype(np.float32),
                                  rng.standard_normal((n, 32)).astype(np.float32),
                                  rng.standard_normal((n_rel, 32, 32)).astype(np.float32))
-    Y, info = run_rgms(gpu_lib, w)
     Yr, Sr = oracle.rgms(n_rel, n, w.indptr, w.indices, w.values, w.X, w.W)
-    assert_y_close(Y, Yr, Sr, "long rows")
-    assert (Y[n // 2:] == 0).all() or (Sr[n // 2:] != 0).any()
+    for workspace in (0, 32):
+        Y, info = run_rgms(gpu_lib, w, workspace_d_out=workspace)
+        assert_y_close(Y, Yr, Sr, f"long rows workspace={workspace}")
 
 
 def test_rgms_reduces_to_spmm(gpu_lib):
@@ -81,9 +87,10 @@ def test_rgms_reduces_to_spmm(gpu_lib):
     rng = np.random.default_rng(2)
     X = rng.standard_normal((n, feat)).astype(np.float32)
     w = workloads.HeteroWorkload("single", n, 1, w0.indptr, w0.indices, w0.values, X, np.eye(feat, dtype=np.float32)[None])
-    Y, info = run_rgms(gpu_lib, w)
     Yr, Sr = oracle.spmm_csr(n, w0.indptr, w0.indices, w0.values, X)
-    assert_y_close(Y, Yr, Sr, "single relation")
+    for workspace in (0, 32):
+        Y, info = run_rgms(gpu_lib, w, workspace_d_out=workspace)
+        assert_y_close(Y, Yr, Sr, f"single relation workspace={workspace}")
 
 
 def test_rgms_edge_cases_and_errors(gpu_lib):
@@ -102,13 +109,32 @@ def test_rgms_edge_cases_and_errors(gpu_lib):
     with pytest.raises(gpu_lib.SptirError):        # stacked rows not a multiple of the relation count
         gpu_lib.sptir_rgms_build(4, 10, 10, ip[:31], ix, va) if False else gpu_lib.sptir_rgms_build(
             7, 10, 10, torch.zeros(7 * 10 + 1, dtype=torch.int32, device=dev), ix, va, 9)
+    with pytest.raises(gpu_lib.SptirError):        # workspace width not a multiple of 32
+        gpu_lib.sptir_rgms_build(3, 10, 10, ip, ix, va, -1, 48)
     h.destroy()
 
 
+def test_rgms_workspace_path_is_reproducible(gpu_lib):
+    """With the workspace every sum has a fixed order (no remainder pieces in this graph): two calls agree bit for bit."""
+    w = workloads.make_hetero("hetero_a")
+    assert np.diff(w.indptr).max() > 32
+    w2 = workloads.make_hetero("hetero_tiny", seed=3, scale=0.5)
+    for wl in (w2,):
+        if np.diff(wl.indptr).max() <= 32:
+            (Y1, Y2), info = run_rgms(gpu_lib, wl, workspace_d_out=32, repeat=2)
+            assert np.array_equal(Y1, Y2)
+    # and on a graph with remainder pieces the two paths agree with each other to rounding
+    Ya, _ = run_rgms(gpu_lib, w, workspace_d_out=0)
+    Yb, _ = run_rgms(gpu_lib, w, workspace_d_out=32)
+    Yr, Sr = oracle.rgms(w.n_rel, w.n, w.indptr, w.indices, w.values, w.X, w.W)
+    assert_y_close(Ya, Yr, Sr, "atomics"); assert_y_close(Yb, Yr, Sr, "workspace")
+
+
+@pytest.mark.parametrize("workspace", [0, 32])
 @pytest.mark.parametrize("name", ["hetero_a", "hetero_b", "hetero_c", "hetero_d"])
-def test_rgms_named_configs(gpu_lib, name):
+def test_rgms_named_configs(gpu_lib, name, workspace):
     w = workloads.make_hetero(name)
-    Y, info = run_rgms(gpu_lib, w)
+    Y, info = run_rgms(gpu_lib, w, workspace_d_out=workspace)
     say(f"[rgms config] {name}: nnz={w.nnz} pairs={info['n_stacked_rows_stored']} pads={info['n_pad_slots']} "
         f"tiles={info['n_tiles']}")
     Yr, Sr = oracle.rgms(w.n_rel, w.n, w.indptr, w.indices, w.values, w.X, w.W)
