@@ -933,6 +933,25 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     }
     BUILD_HIP(hipGetLastError());
     BUILD_HIP(hipStreamSynchronize(stream));
+    if (n_groups > 0) {
+      // ---- launch order of the row blocks: longest list first, so that the last wavefronts of a launch to
+      //      finish are short ones (row blocks of a power-law graph differ several-fold in work)
+      std::vector<int64_t> ptr((size_t)n_groups + 1);
+      std::vector<int32_t> order((size_t)n_groups);
+      BUILD_HIP(hipMemcpyAsync(ptr.data(), h->rb_chunk_ptr, sizeof(int64_t) * ptr.size(), hipMemcpyDeviceToHost, stream));
+      BUILD_HIP(hipStreamSynchronize(stream));
+      for (int32_t ph = 0; ph < cs.n_phases; ++ph) {
+        int32_t* o = order.data() + (size_t)ph * cs.n_rb;
+        const int64_t* pp = ptr.data() + (size_t)ph * cs.n_rb;
+        for (int32_t j = 0; j < cs.n_rb; ++j) o[j] = j;
+        std::stable_sort(o, o + cs.n_rb, [&](int32_t x, int32_t y) { return pp[x + 1] - pp[x] > pp[y + 1] - pp[y]; });
+      }
+      h->rb_order = (int32_t*)alloc(sizeof(int32_t) * order.size(), actx, stream);
+      if (!h->rb_order) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += sizeof(int32_t) * order.size();
+      BUILD_HIP(hipMemcpyAsync(h->rb_order, order.data(), sizeof(int32_t) * order.size(), hipMemcpyHostToDevice, stream));
+      BUILD_HIP(hipStreamSynchronize(stream));  // the host vector goes out of scope
+    }
   }
   free_(tmp.base, actx);
   if (tmp2.base) free_(tmp2.base, actx);

@@ -251,6 +251,7 @@ __device__ __forceinline__ void decode_block(int map_mode, int map_param, int n_
 struct SpmmArgs {
   const int32_t* stream;        // chunk records: [cols | vals | local rows] x 64
   const int64_t* rb_chunk_ptr;  // this phase's [n_row_blocks + 1]
+  const int32_t* rb_order;      // this phase's [n_row_blocks]: which row block the i-th wavefront of the launch takes
   const float* X;
   float* Y;
   int32_t n_rows;
@@ -498,8 +499,9 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t rb = unit * kHybWaves + wave;  // the wavefronts of a workgroup are independent of each other
-  if (rb >= a.n_row_blocks) return;
+  const int64_t slot = unit * kHybWaves + wave;  // the wavefronts of a workgroup are independent of each other
+  if (slot >= a.n_row_blocks) return;
+  const int64_t rb = a.rb_order[slot];
   const int row_block = 1 << a.log2_row_block;
   const int rb_first = (int)(rb << a.log2_row_block);
   const int rows_here = min(row_block, a.n_rows - rb_first);
@@ -745,6 +747,7 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
                           : (span * feat * sizeof(float) < ((size_t)1 << 32));
   for (int phase = 0; phase < h->n_phases; ++phase) {
     a.rb_chunk_ptr = h->rb_chunk_ptr + (size_t)phase * h->n_row_blocks;
+    a.rb_order = h->rb_order + (size_t)phase * h->n_row_blocks;
     a.accumulate = phase > 0;
     a.X = wide ? X : X + (size_t)phase * span * (size_t)feat;
     if (g.vec == 4 && g.lg == 8) launch_hyb<4, 8>(g, lds_bytes, stream, a, idx32, wide);

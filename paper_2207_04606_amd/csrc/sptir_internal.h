@@ -68,6 +68,7 @@ struct sptir_hyb {
   int32_t spmm_plan;         // 0: built without the chunk stream (canonical arrays only); sptir_spmm refuses it
   int32_t compact_stream;    // 1: 8-byte slots (columns relative to the launch), 0: 12-byte slots (global columns)
   int64_t* rb_chunk_ptr;     // device [n_phases * n_row_blocks + 1], first chunk of each group
+  int32_t* rb_order;         // device [n_phases * n_row_blocks]: the row blocks of a launch, longest list first
   int64_t n_chunks;
   // rows with long pieces: the pieces of long_rows[i] are long_pieces[long_piece_ptr[i] .. long_piece_ptr[i+1])
   int32_t n_long_rows;
