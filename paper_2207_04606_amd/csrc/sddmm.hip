@@ -8,13 +8,14 @@
 // consecutive entries, one wavefront each, so the work per wavefront is the
 // same whatever the row lengths.  A wavefront takes 64 entries at a time with
 // one coalesced load of their columns and values.  Eight lane groups of eight
-// lanes then work on eight entries at once: lane fl of a group holds floats
+// lanes then work on eight entries at once (group g on entries 8g .. 8g+7 of
+// the 64, one after the other, so that its row changes rarely): lane fl of a group holds floats
 // 4*(8t + fl) .. +3 (t = 0..T-1) of the entry's row of X in registers (loaded
 // only when the row changes) and gathers the same floats of row j of Yt, one
 // 128-byte line per group and load.  Stage one of the reduction is the lane's
 // own dot product; stage two is a reduce-scatter over the eight lanes of the
-// group, after which a lane transpose puts the 64 results back in entry order
-// for one coalesced store.
+// group, which leaves lane 8g + fl with the result of entry 8g + fl: the 64
+// results are in entry order for one coalesced store.
 //
 // With a plan (sptir_sddmm_plan_build) the entries are visited in column-
 // partition order instead of CSR order, the locality argument section 4.2.1
@@ -122,6 +123,14 @@ __global__ __launch_bounds__(64 * kSddmmWaves, T <= 4 ? 4 : 2) void k_sddmm(Sddm
   const int f_lane = 4 * fl;  // float offset of this lane inside every 32-float stripe
 
   int row_lo = PLAN ? 0 : row_of_entry(a.indptr, a.n_rows, e_begin);  // row of the chunk's first entry (wave-uniform)
+  // The rows of X a chunk needs are staged in LDS once per chunk: every load instruction then brings up to eight
+  // different rows (one per lane group), where a reload inside the entry loop costs the address path a whole
+  // instruction even if a single lane group asks for it - and in partition order a row lasts only a few entries.
+  // (Measured: pays for feature sizes of 128 and 256 in partition order, costs a little everywhere else.)
+  constexpr int kStage = !PLAN ? 0 : (T == 4 ? 16 : (T == 8 ? 8 : 0));  // rows of X staged per wavefront (8 KB)
+  __shared__ __align__(16) float x_stage[kSddmmWaves][kStage > 0 ? kStage : 1][32 * T];
+  __shared__ int row_table[kSddmmWaves][kStage > 0 ? kStage : 1];
+  const int wave = threadIdx.x >> 6;
   float4 x[T];
   int x_row = -1;
 #pragma unroll
@@ -149,12 +158,38 @@ __global__ __launch_bounds__(64 * kSddmmWaves, T <= 4 ? 4 : 2) void k_sddmm(Sddm
         while (row_reg + 1 < a.n_rows && e_lane >= (int64_t)a.indptr[row_reg + 1]) ++row_reg;
       }
     }
+    bool staged = false;
+    int rank_reg = 0, x_rank = -1;
+    if constexpr (kStage > 0) {
+      // entries arrive row by row: a lane whose row differs from its left neighbour's starts a new row
+      const int left = __shfl_up(row_reg, 1, 64);
+      const bool head = lane == 0 || row_reg != left;
+      const unsigned long long heads = __ballot(head);
+      const int n_distinct = __popcll(heads);
+      rank_reg = __popcll(heads & ((2ull << lane) - 1ull)) - 1;  // which of the chunk's rows this lane's entry uses
+      staged = n_distinct <= kStage;                             // (wave-uniform)
+      if (staged) {
+        if (head) row_table[wave][rank_reg] = row_reg;
+        for (int k0 = 0; k0 < n_distinct; k0 += 8) {
+          const int k = k0 + g;
+          if (k < n_distinct) {
+            const float* xr = a.X + (size_t)row_table[wave][k] * feat + f_lane;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+              const float4 v = f_ok[t] ? *reinterpret_cast<const float4*>(xr + 32 * t) : make_float4(0.f, 0.f, 0.f, 0.f);
+              *reinterpret_cast<float4*>(&x_stage[wave][k][32 * t + f_lane]) = v;
+            }
+          }
+        }
+        x_row = -1;  // the registers are about to hold staged rows
+      }
+    }
     // Gathers run kAhead entries ahead of the multiplies; the scheduling barriers keep the compiler from
     // hoisting all eight entries' loads to the top (T*8 float4 of registers).
     constexpr int kAhead = T <= 8 ? 2 : 1;
     float4 y[kAhead + 1][T];
     auto issue = [&](int i, float4 (&yb)[T]) {
-      const int c = __shfl(col_reg, i * 8 + g, 64);  // lane i*8+g fetched this group's i-th entry
+      const int c = __shfl(col_reg, g * 8 + i, 64);  // lane g*8+i fetched this group's i-th entry
       const float* yr = a.Yt + (size_t)c * feat + f_lane;
 #pragma unroll
       for (int t = 0; t < T; ++t) {
@@ -167,14 +202,23 @@ __global__ __launch_bounds__(64 * kSddmmWaves, T <= 4 ? 4 : 2) void k_sddmm(Sddm
     for (int i = 0; i < kAhead; ++i) issue(i, y[i]);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int r = __shfl(row_reg, i * 8 + g, 64);
-      if (r != x_row) {  // (entries past the end carry row_lo: a harmless reload)
-        const float* xr = a.X + (size_t)r * feat + f_lane;
+      if (staged) {
+        const int rk = __shfl(rank_reg, g * 8 + i, 64);
+        if (rk != x_rank) {
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-          x[t] = f_ok[t] ? *reinterpret_cast<const float4*>(xr + 32 * t) : make_float4(0.f, 0.f, 0.f, 0.f);
+          for (int t = 0; t < T; ++t) x[t] = *reinterpret_cast<const float4*>(&x_stage[wave][rk][32 * t + f_lane]);
+          x_rank = rk;
         }
-        x_row = r;
+      } else {
+        const int r = __shfl(row_reg, g * 8 + i, 64);
+        if (r != x_row) {  // (entries past the end carry a valid row: a harmless reload)
+          const float* xr = a.X + (size_t)r * feat + f_lane;
+#pragma unroll
+          for (int t = 0; t < T; ++t) {
+            x[t] = f_ok[t] ? *reinterpret_cast<const float4*>(xr + 32 * t) : make_float4(0.f, 0.f, 0.f, 0.f);
+          }
+          x_row = r;
+        }
       }
       if (i + kAhead < 8) issue(i + kAhead, y[(i + kAhead) % (kAhead + 1)]);
       float acc = 0.f;
@@ -186,8 +230,8 @@ __global__ __launch_bounds__(64 * kSddmmWaves, T <= 4 ? 4 : 2) void k_sddmm(Sddm
       p[i] = acc;
       __builtin_amdgcn_sched_barrier(0);
     }
-    const float total = reduce_scatter8(p, fl);               // lane (g, fl): entry base + fl*8 + g
-    const float mine = __shfl(total, (lane & 7) * 8 + (lane >> 3), 64);  // lane L: entry base + L
+    // lane (g, fl) ends with the total of p[fl], i.e. of entry base + g*8 + fl = base + lane: its own entry
+    const float mine = reduce_scatter8(p, fl);
     if (in) a.B[out_pos] = val_reg * mine;
     if constexpr (!PLAN) row_lo = __builtin_amdgcn_readlane(row_reg, 63);  // (a lane past the end kept row_lo itself)
     // the last lane's entry may lie past the end only in the run's last chunk, after which nothing follows
