@@ -24,6 +24,7 @@
 // partitions in ascending order, and long-row matrices get one launch per
 // partition, which keeps the X slice in flight L2-sized (the purpose section
 // 4.2.1 gives for column partitioning).
+#include <cstdlib>
 #include "sptir_internal.h"
 
 namespace sptir {
@@ -258,7 +259,8 @@ struct SpmmArgs {
   int32_t n_row_blocks;
   int32_t log2_row_block;
   int32_t feat;
-  int32_t n_tiles;
+  int32_t n_tiles;     // feature tiles of this launch, the first of which is tile0
+  int32_t tile0;
   int32_t map_mode;
   int32_t map_param;
   int32_t accumulate;  // 0: Y tile is overwritten, 1: added to (a later phase)
@@ -330,8 +332,9 @@ struct HybWalker {
   __device__ __forceinline__ int* slot_of(int q) const { return ring + (q & 1) * kQuadInts; }
 
   // parks quad q; m[i] receives the facts of its chunk i (wave-uniform), taken from the chunk's slot 0:
-  // log2w | hand-over << 6 (WIDE) or log2w code | hand-over << 3 (compact).
-  // (slot 0 of a chunk is a real slot, or the whole chunk is padding and reads as "nothing to hand over")
+  // log2w | hand-over << 6 | no row << 7 (WIDE) or real | log2w code << 1 | hand-over << 4 (compact).
+  // (slot 0 of a chunk is a real slot, or the first of an idle octet, or the whole chunk is padding at the
+  //  end of a list, which chunk_is_padding() tells apart)
   __device__ __forceinline__ void park(int q, const Fetched& f, int (&m)[kChunksPerQuad]) const {
     int4* st = reinterpret_cast<int4*>(slot_of(q));
     st[lane] = make_int4(f.col[0], f.col[1], f.col[2], f.col[3]);
@@ -340,9 +343,11 @@ struct HybWalker {
 #pragma unroll
     for (int i = 0; i < kChunksPerQuad; ++i) {
       if constexpr (WIDE) m[i] = __builtin_amdgcn_readlane(f.row[0], i * (kChunkSlots / 4)) >> 16;
-      else m[i] = (int)((unsigned)__builtin_amdgcn_readlane(f.col[0], i * (kChunkSlots / 4)) >> 28);
+      else m[i] = (int)((unsigned)__builtin_amdgcn_readlane(f.col[0], i * (kChunkSlots / 4)) >> 27);
     }
   }
+
+  static __device__ __forceinline__ bool chunk_is_padding(int m) { return WIDE ? m == -1 : m == 0x1E; }
 
   // UB consecutive ints of the ring (UB is 4 or 8; the offset is a multiple of UB): 16-byte LDS reads
   __device__ __forceinline__ void read_ints(const int* p, int (&out)[UB]) const {
@@ -377,8 +382,8 @@ struct HybWalker {
   __device__ __forceinline__ void consume(const int* st, int s, int meta, const float (&v)[UB],
                                           const float (&x)[UB][VEC]) {
     // (compact: a chunk cut from a row wider than 64 slots carries code 7; every test below only asks lw >= 6)
-    const int lw = WIDE ? (meta & 63) : (meta & 7);
-    const bool hand_over = ((meta >> (WIDE ? 6 : 3)) & 1) != 0;
+    const int lw = WIDE ? (meta & 63) : ((meta >> 1) & 7);
+    const bool hand_over = ((meta >> (WIDE ? 6 : 4)) & 1) != 0;
     const int sub = s & (SUB - 1);
     const int* rows = st + (WIDE ? 2 * kQuadSlots : 0);
     if (lw < S::kLog2Steps) {
@@ -480,11 +485,15 @@ struct HybWalker {
 #pragma unroll
       for (int i = 0; i < kChunksPerQuad; ++i) m_cur[i] = m_next[i];
     }
-    // last quad: its steps 0 and 1 are in flight, nothing follows it
+    // last quad: its steps 0 and 1 are in flight, nothing follows it, and the padding chunks that round the
+    // list up to whole quads are neither gathered for nor multiplied
+    int n_real = 0;
+#pragma unroll
+    for (int i = 0; i < kChunksPerQuad; ++i) n_real += chunk_is_padding(m_cur[i]) ? 0 : SUB;
 #pragma unroll
     for (int s = 0; s < kQuadSteps; s += 2) {
-      step(Q, s, xa, s + 2 < kQuadSteps);
-      step(Q, s + 1, xb, s + 3 < kQuadSteps);
+      if (s < n_real) step(Q, s, xa, s + 2 < n_real);
+      if (s + 1 < n_real) step(Q, s + 1, xb, s + 3 < n_real);
     }
   }
 };
@@ -506,7 +515,7 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   const int rb_first = (int)(rb << a.log2_row_block);
   const int rows_here = min(row_block, a.n_rows - rb_first);
   const int g = lane / LG, fl = lane & (LG - 1);
-  const int f0 = tile_id * S::kTile + fl * VEC;
+  const int f0 = (a.tile0 + tile_id) * S::kTile + fl * VEC;
   const bool f_active = f0 < a.feat;
   const int wave_floats = row_block * S::kTile + W::kRingInts;
   float* tile = smem + wave * wave_floats;
@@ -669,13 +678,8 @@ struct Geometry {
   int64_t grid;
 };
 
-bool plan(int64_t n_units, int feat, const void* X, const void* Y, Geometry* g) {
-  uintptr_t align = (uintptr_t)X | (uintptr_t)Y;
-  if (feat % 4 == 0 && (align & 15) == 0) { g->vec = 4; g->lg = feat <= 16 ? 4 : 8; }
-  else if (feat % 2 == 0 && (align & 7) == 0) { g->vec = 2; g->lg = 16; }
-  else { g->vec = 1; g->lg = 32; }
-  int tf = g->vec * g->lg;
-  g->n_tiles = (feat + tf - 1) / tf;
+// how n_tiles feature tiles (g->n_tiles) and n_units units are dealt to workgroups
+bool plan_tiles(int64_t n_units, Geometry* g) {
   if (g->n_tiles % 8 == 0) {
     g->map_mode = kMapTilesPerXcd; g->map_param = g->n_tiles / 8;
     g->grid = n_units * g->n_tiles;
@@ -687,6 +691,32 @@ bool plan(int64_t n_units, int feat, const void* X, const void* Y, Geometry* g) 
     g->grid = n_units * g->n_tiles;
   }
   return g->grid <= 0x7FFFFFFF;
+}
+
+bool plan(int64_t n_units, int feat, const void* X, const void* Y, Geometry* g) {
+  uintptr_t align = (uintptr_t)X | (uintptr_t)Y;
+  if (feat % 4 == 0 && (align & 15) == 0) { g->vec = 4; g->lg = feat <= 16 ? 4 : 8; }
+  else if (feat % 2 == 0 && (align & 7) == 0) { g->vec = 2; g->lg = 16; }
+  else { g->vec = 1; g->lg = 32; }
+  int tf = g->vec * g->lg;
+  g->n_tiles = (feat + tf - 1) / tf;
+  return plan_tiles(n_units, g);
+}
+
+// Feature tiles per sweep over the launches of a call.  Every launch but the first reads back what the one
+// before it wrote to Y; that round trip stays inside the 256 MB memory-side cache only if the part of Y a sweep
+// touches is well below its size.  So a wide Y is produced in several sweeps, each over a group of feature tiles
+// (4 or 8, which still map whole XCDs to a tile).
+int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches) {
+  static const double limit_mb = [] {
+    const char* e = std::getenv("SPTIR_SWEEP_MB");
+    return e ? std::atof(e) : 160.0;
+  }();
+  if (n_launches < 2 || n_tiles % 4 != 0) return n_tiles;
+  const double tile_mb = (double)n_rows * tile_floats * sizeof(float) / (1024.0 * 1024.0);
+  if (tile_mb * n_tiles <= limit_mb) return n_tiles;
+  if (n_tiles % 8 == 0 && tile_mb * 8 <= limit_mb) return 8;
+  return 4;
 }
 
 bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
@@ -745,15 +775,22 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
   const size_t span = (size_t)h->parts_per_phase * (size_t)h->w;
   const bool idx32 = wide ? (h->n_cols < (1 << 24) && x_bytes < ((size_t)1 << 32))
                           : (span * feat * sizeof(float) < ((size_t)1 << 32));
-  for (int phase = 0; phase < h->n_phases; ++phase) {
-    a.rb_chunk_ptr = h->rb_chunk_ptr + (size_t)phase * h->n_row_blocks;
-    a.rb_order = h->rb_order + (size_t)phase * h->n_row_blocks;
-    a.accumulate = phase > 0;
-    a.X = wide ? X : X + (size_t)phase * span * (size_t)feat;
-    if (g.vec == 4 && g.lg == 8) launch_hyb<4, 8>(g, lds_bytes, stream, a, idx32, wide);
-    else if (g.vec == 4) launch_hyb<4, 4>(g, lds_bytes, stream, a, idx32, wide);
-    else if (g.vec == 2) launch_hyb<2, 16>(g, lds_bytes, stream, a, idx32, wide);
-    else launch_hyb<1, 32>(g, lds_bytes, stream, a, idx32, wide);
+  const int all_tiles = g.n_tiles;
+  const int per_sweep = tiles_per_sweep(all_tiles, g.vec * g.lg, h->n_rows, h->n_phases);
+  for (int tile0 = 0; tile0 < all_tiles; tile0 += per_sweep) {
+    g.n_tiles = all_tiles - tile0 < per_sweep ? all_tiles - tile0 : per_sweep;
+    if (!plan_tiles(((int64_t)h->n_row_blocks + kHybWaves - 1) / kHybWaves, &g)) return SPTIR_ERR_OVERFLOW;
+    a.n_tiles = g.n_tiles; a.tile0 = tile0; a.map_mode = g.map_mode; a.map_param = g.map_param;
+    for (int phase = 0; phase < h->n_phases; ++phase) {
+      a.rb_chunk_ptr = h->rb_chunk_ptr + (size_t)phase * h->n_row_blocks;
+      a.rb_order = h->rb_order + (size_t)phase * h->n_row_blocks;
+      a.accumulate = phase > 0;
+      a.X = wide ? X : X + (size_t)phase * span * (size_t)feat;
+      if (g.vec == 4 && g.lg == 8) launch_hyb<4, 8>(g, lds_bytes, stream, a, idx32, wide);
+      else if (g.vec == 4) launch_hyb<4, 4>(g, lds_bytes, stream, a, idx32, wide);
+      else if (g.vec == 2) launch_hyb<2, 16>(g, lds_bytes, stream, a, idx32, wide);
+      else launch_hyb<1, 32>(g, lds_bytes, stream, a, idx32, wide);
+    }
   }
   if (h->n_long_rows > 0) {
     Geometry gl;
