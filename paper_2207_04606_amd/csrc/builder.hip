@@ -257,79 +257,79 @@ __global__ void k_cell_bounds(CellShape cs, const int64_t* __restrict__ bucket_r
   bin_rb_ptr[t] = (int32_t)lo;
 }
 
-// Cells of one (phase, row block) group, in chunk order: for every partition of the phase its nb bin cells and
-// one queue cell, then one pad cell that rounds the group's chunk count up to a multiple of kChunksPerQuad (the
-// SpMM kernel fetches chunks four at a time).
+// Cells of one (phase, row block) group, in chunk order: for every partition of the phase its nb bin cells
+// (the chunks of that bin's rows that are cut wide) and one queue cell, then one pad cell that rounds the
+// group's chunk count up to a multiple of kChunksPerQuad (the SpMM kernel fetches chunks four at a time).
 //
-// How the rows of a (group, partition) become chunks:
-//  * buckets of width 1, 2, 4: 64/width whole rows per chunk, in the bucket's cell;
-//  * every other row piece (buckets of width >= 8, remainder pieces; at most kLongRowSlots entries) is cut into
-//    octets of 8 entries and dealt to eight queues, one per lane group of the SpMM kernel: chunk t of the queue
-//    cell holds the t-th octet of every queue.  A lane group then walks whole rows alone, keeps the running sum
-//    in registers and needs no cross-lane reduction; octets that would hold nothing but pads do not exist.  A
-//    row goes to the queue that is shortest so far (buckets are visited widest first, so this is the
-//    longest-first rule up to a factor of two);
-//  * unless the row alone is longer than an even share of what is still to be dealt: such a row is cut "wide"
-//    instead, into chunks of 64 entries that all eight lane groups share, in its bucket's cell.
+// How the row pieces of a (group, partition) become chunks (pieces of at most kLongRowSlots entries; bucket
+// rows and remainder pieces alike, each with its real entries only):
+//  * a piece is dealt whole to one of eight queues, one per lane group of the SpMM kernel, where its entries
+//    follow those of the piece before it without a gap; chunk t of the queue cell holds entries 8t .. 8t+7 of
+//    every queue, and the last entry of a piece carries a flag.  A lane group then walks whole rows alone,
+//    keeps the running sum in registers, hands it over at a flag and needs no cross-lane reduction; no pad of
+//    a bucket row is ever walked.  A piece goes to the queue that is shortest so far (buckets are visited
+//    widest first, so this is the longest-first rule up to a factor of two);
+//  * unless the piece is longer than a chunk and than an even share of what is still to be dealt: such a
+//    piece is cut "wide" instead, into chunks of 64 entries that all eight lane groups share, in its bin's cell.
 // The rows of one partition are distinct, so two queues never hand over the same row of Y in one instruction.
 __device__ __forceinline__ int cells_per_part(const CellShape& cs) { return cs.nb + 1; }
 __device__ __forceinline__ int cells_per_group(const CellShape& cs) { return cs.ppg * (cs.nb + 1) + 1; }
-__device__ __forceinline__ bool bin_is_narrow(const CellShape& cs, int bin) { return bin <= cs.k && bin < 3; }
 
-struct QueueOctet {  // what lane group g does in one chunk of a queue cell (all zero: nothing)
-  int64_t slot;      // first of up to 8 consecutive slots of the fused (cols, vals) arrays
-  int32_t q;         // the row piece (index into row_ids)
-  int32_t info;      // real entries (1..8) | (the piece ends here) << 8
+struct PiecePlace {     // where the entries of a queued row piece go (len 0: the piece is not queued)
+  int64_t slot0;        // its first slot in the fused (cols, vals) arrays
+  int64_t first_chunk;  // first chunk of the queue cell
+  int32_t where;        // position of its first entry in the queue | queue << 28
+  int32_t len;          // real entries
 };
-static_assert(sizeof(QueueOctet) == 16, "QueueOctet must stay 16 bytes");
+static_assert(sizeof(PiecePlace) == 24, "PiecePlace must stay 24 bytes");
 constexpr uint32_t kChunkIsQueue = 1u << 14;
 
 __device__ __forceinline__ int chunks_of_length(int len) { return (len + kChunkSlots - 1) / kChunkSlots; }
 
-// Walks the big row pieces of partition p in row block rb and tells the visitor what becomes of each:
+// Walks the row pieces of partition p in row block rb and tells the visitor what becomes of each:
 //   v.on_long(bin, q, len)                 set aside for the long-row launch
 //   v.on_wide(bin, q, len)                 cut into 64-entry chunks
-//   v.on_queued(bin, q, len, g, start)     octets start .. start + ceil(len/8) - 1 of queue g
-// and returns the length of the longest queue.
+//   v.on_queued(bin, q, len, g, start)     entries start .. start + len - 1 of queue g
+//   v.on_dealt(load, chunks)               at the end: entries per queue, chunks of the queue cell
+// and returns the chunks of the queue cell.
 template <typename Visitor>
 __device__ __forceinline__ int deal_partition(const CellShape& cs, const int32_t* __restrict__ bin_rb_ptr,
                                               const int32_t* __restrict__ row_len, int p, int rb, Visitor& v) {
   const int64_t per_bin = (int64_t)cs.n_rb + 1;
-  long long to_deal = 0;  // octets not dealt yet
+  long long to_deal = 0;  // entries not dealt yet
   for (int bin = 0; bin < cs.nb; ++bin) {
-    if (bin_is_narrow(cs, bin)) continue;
     const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
     for (int32_t q = ptr[0]; q < ptr[1]; ++q) {
       const int len = row_len[q];
-      if (len <= kLongRowSlots) to_deal += (len + 7) >> 3;
+      if (len <= kLongRowSlots) to_deal += len;
     }
   }
   int load[8];
 #pragma unroll
   for (int g = 0; g < 8; ++g) load[g] = 0;
   for (int bin = cs.nb - 1; bin >= 0; --bin) {
-    if (bin_is_narrow(cs, bin)) continue;
     const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
     for (int32_t q = ptr[0]; q < ptr[1]; ++q) {
       const int len = row_len[q];
       if (len > kLongRowSlots) { v.on_long(bin, q, len); continue; }
-      const int octets = (len + 7) >> 3;
       const long long share = (to_deal + 7) >> 3;
-      to_deal -= octets;
-      if (len > kChunkSlots && octets > share) { v.on_wide(bin, q, len); continue; }
+      to_deal -= len;
+      if (len > kChunkSlots && len > share) { v.on_wide(bin, q, len); continue; }
       int best = 0, best_load = load[0];
 #pragma unroll
       for (int g = 1; g < 8; ++g)
         if (load[g] < best_load) { best_load = load[g]; best = g; }
       v.on_queued(bin, q, len, best, best_load);
 #pragma unroll
-      for (int g = 0; g < 8; ++g) load[g] += (g == best) ? octets : 0;
+      for (int g = 0; g < 8; ++g) load[g] += (g == best) ? len : 0;
     }
   }
   int longest = 0;
 #pragma unroll
   for (int g = 0; g < 8; ++g) longest = max(longest, load[g]);
-  return longest;
+  const int chunks = (longest + 7) >> 3;
+  v.on_dealt(load, chunks);
+  return chunks;
 }
 
 // One thread per (group, partition of its phase): chunk counts of that partition's cells.
@@ -339,6 +339,7 @@ struct CountVisitor {
   __device__ void on_long(int, int32_t, int) { atomicAdd(n_long, 1ull); }
   __device__ void on_wide(int bin, int32_t, int len) { cell[bin] += chunks_of_length(len); }
   __device__ void on_queued(int, int32_t, int, int, int) {}
+  __device__ void on_dealt(const int (&)[8], int) {}
 };
 
 __global__ void k_part_chunk_counts(CellShape cs, int64_t n_parts, const int32_t* __restrict__ bin_rb_ptr,
@@ -353,13 +354,6 @@ __global__ void k_part_chunk_counts(CellShape cs, int64_t n_parts, const int32_t
   long long* cell = cell_chunks + grp * cells_per_group(cs) + (int64_t)p_local * cells_per_part(cs);
   for (int i = 0; i <= cs.nb; ++i) cell[i] = 0;
   if (p >= cs.c) return;  // a partition past the last one
-  const int64_t per_bin = (int64_t)cs.n_rb + 1;
-  for (int bin = 0; bin < cs.nb; ++bin) {
-    if (!bin_is_narrow(cs, bin)) continue;
-    const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
-    const int rows_per_chunk = kChunkSlots >> bin;
-    cell[bin] = (ptr[1] - ptr[0] + rows_per_chunk - 1) / rows_per_chunk;
-  }
   CountVisitor v{cell, n_long};
   cell[cs.nb] = deal_partition(cs, bin_rb_ptr, row_len, p, rb, v);
 }
@@ -383,9 +377,62 @@ __global__ void k_group_scan(CellShape cs, int64_t n_groups, long long* cell_chu
 
 constexpr int kGroupSeq = 1024;  // groups per sequence of the two-level scan over group totals
 
-// One thread per (group, partition): writes the chunk descriptors the counts above announced.
+// ------------------------------------------------------------ chunk stream
+// What the SpMM kernel actually reads: the chunks as fixed records, in list
+// order, so that the address of every record follows from its list position
+// alone (no dependent descriptor load inside the gather loop).  Four
+// consecutive chunks form a quad, fetched with one 16-byte load per lane and
+// array.  The 12-byte form (3 KB per quad):
+//   quad[  0..255]  column ids, chunk i at 64*i  (slots past the last real one repeat a real column)
+//   quad[256..511]  values                        (slots past the last real one hold +0.0f)
+//   quad[512..767]  per slot: row relative to the first row of the row block in bits 0..15,
+//                   the chunk's log2w in bits 16..21, the hand-over flag in bit 22 (the chunk's, or in a
+//                   queue chunk the slot's: the last entry of a row piece), bit 23: the slot belongs to no
+//                   row (past the end of a queue); slots of a wide chunk past its last entry hold -1
+// The compact form (2 KB per quad; the kernel's time goes with the bytes it has
+// to pull from beyond L2, and every feature tile re-reads the stream) folds the
+// row word into the column word, see kCompactColBits:
+//   quad[  0..255]  column - first column of the launch | row << 20 | real << 27 | log2w code << 28 | hand-over << 31
+//   quad[256..511]  values
+struct StreamShape {
+  int32_t* stream;
+  int32_t compact;
+  int32_t log2_rb;
+  int32_t phase_width;  // columns a launch covers
+};
+
+__device__ __forceinline__ void put_slot(const StreamShape& ss, int64_t chunk, int slot, int32_t col_word,
+                                         int32_t val_bits, int32_t row_word) {
+  constexpr int kQuadSlots = kChunkSlots * kChunksPerQuad;
+  int32_t* quad = ss.stream + (chunk / kChunksPerQuad) * ((ss.compact ? 2 : 3) * kQuadSlots);
+  const int at = (int)(chunk % kChunksPerQuad) * kChunkSlots + slot;
+  quad[at] = col_word;
+  quad[kQuadSlots + at] = val_bits;
+  if (!ss.compact) quad[2 * kQuadSlots + at] = row_word;
+}
+
+// entry e of a queued piece
+__device__ __forceinline__ void put_queue_entry(const StreamShape& ss, int64_t first_chunk, int where, int e,
+                                                int32_t col, float val, int32_t row, bool last) {
+  const int pos = (where & 0x0FFFFFFF) + e, g = (where >> 28) & 7;
+  const int local_row = row & ((1 << ss.log2_rb) - 1);
+  int32_t col_word, row_word = 0;
+  if (ss.compact) {
+    const uint32_t col_rel = (uint32_t)(col - (col / ss.phase_width) * ss.phase_width);
+    col_word = (int32_t)(col_rel | ((uint32_t)local_row << kCompactColBits) | (1u << 27) | (3u << 28) |
+                         ((uint32_t)last << 31));
+  } else {
+    col_word = col;
+    row_word = local_row | (3 << 16) | ((int)last << 22);
+  }
+  put_slot(ss, first_chunk + (pos >> 3), g * 8 + (pos & 7), col_word, __float_as_int(val), row_word);
+}
+
+// One thread per (group, partition): writes the chunk descriptors the counts above announced, the place of
+// every queued piece, and the slots past the end of each queue.
 struct FillVisitor {
   const CellShape& cs;
+  const StreamShape& ss;
   int p;
   int64_t first_chunk;          // of the partition's first cell
   const long long* cell;        // scanned counts: chunks of this group before each of the partition's cells ...
@@ -396,7 +443,7 @@ struct FillVisitor {
   const int64_t* rem_ptr;
   int64_t S;
   Chunk* chunks;
-  QueueOctet* octets;
+  PiecePlace* place;
   LongPiece* long_pieces;
   unsigned long long* long_cursor;
   int wide_bin;                 // bin whose wide rows are being written, and the next free chunk of its cell
@@ -427,26 +474,35 @@ struct FillVisitor {
     }
   }
   __device__ void on_queued(int bin, int32_t q, int len, int g, int start) {
-    const int64_t slot0 = slot_of(bin, q);
-    const int64_t first = cell_first(cs.nb) + start;
-    const int n_oct = (len + 7) >> 3;
-    for (int i = 0; i < n_oct; ++i) {
-      QueueOctet o;
-      o.slot = slot0 + 8 * i; o.q = q;
-      o.info = (len - 8 * i < 8 ? len - 8 * i : 8) | (i == n_oct - 1 ? 0x100 : 0);
-      octets[(first + i) * 8 + g] = o;
+    PiecePlace pl;
+    pl.slot0 = slot_of(bin, q); pl.first_chunk = cell_first(cs.nb); pl.where = start | (g << 28); pl.len = len;
+    place[q] = pl;
+  }
+  __device__ void on_dealt(const int (&load)[8], int n_chunks) {
+    const int64_t first = cell_first(cs.nb);
+    for (int i = 0; i < n_chunks; ++i) {  // the slots of a queue chunk are written piece by piece, not from here
+      Chunk ck;
+      ck.slot0 = 0; ck.row0 = 0;
+      ck.meta = 3u | ((uint32_t)kChunkSlots << 6) | kChunkIsQueue;
+      chunks[first + i] = ck;
     }
+#pragma unroll
+    for (int g = 0; g < 8; ++g)  // past the end of a queue: zeros that belong to no row
+      for (int pos = load[g]; pos < 8 * n_chunks; ++pos)
+        put_slot(ss, first + (pos >> 3), g * 8 + (pos & 7), ss.compact ? (int32_t)(3u << 28) : 0, 0,
+                 (3 << 16) | (1 << 23));
   }
 };
 
-__global__ void k_part_fill_chunks(CellShape cs, int64_t n_parts, const int32_t* __restrict__ bin_rb_ptr,
+__global__ void k_part_fill_chunks(CellShape cs, StreamShape ss, int64_t n_parts,
+                                   const int32_t* __restrict__ bin_rb_ptr,
                                    const long long* __restrict__ cell_first_chunk,
                                    const long long* __restrict__ group_first_chunk,
                                    const long long* __restrict__ seq_first_chunk,
                                    const int32_t* __restrict__ row_len, const int32_t* __restrict__ row_ids,
                                    const int64_t* __restrict__ bucket_row_ptr,
                                    const int64_t* __restrict__ bucket_slot_ptr, const int64_t* __restrict__ rem_ptr,
-                                   int64_t S, Chunk* chunks, QueueOctet* octets, int64_t* rb_chunk_ptr,
+                                   int64_t S, Chunk* chunks, PiecePlace* place, int64_t* rb_chunk_ptr,
                                    LongPiece* long_pieces, unsigned long long* long_cursor) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= n_parts) return;
@@ -458,108 +514,74 @@ __global__ void k_part_fill_chunks(CellShape cs, int64_t n_parts, const int32_t*
   const int64_t group_first = group_first_chunk[grp] + seq_first_chunk[grp / kGroupSeq];
   if (p_local == 0) rb_chunk_ptr[(int64_t)phase * cs.n_rb + rb] = group_first;
   if (p >= cs.c) return;
-  FillVisitor v{cs, p, group_first + cell[0], cell, cell[0], row_ids, bucket_row_ptr, bucket_slot_ptr, rem_ptr, S,
-                chunks, octets, long_pieces, long_cursor, -1, 0};
-  // buckets narrower than 8: several whole rows per chunk
-  const int64_t per_bin = (int64_t)cs.n_rb + 1;
-  for (int bin = 0; bin < cs.nb; ++bin) {
-    if (!bin_is_narrow(cs, bin)) continue;
-    const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
-    const int rows_per_chunk = kChunkSlots >> bin;
-    int64_t it = v.cell_first(bin);
-    for (int32_t q = ptr[0]; q < ptr[1]; q += rows_per_chunk) {
-      const int rows = ptr[1] - q < rows_per_chunk ? ptr[1] - q : rows_per_chunk;
-      Chunk ck;
-      ck.slot0 = v.slot_of(bin, q); ck.row0 = q;
-      ck.meta = (uint32_t)bin | ((uint32_t)(rows << bin) << 6) | (1u << 13);
-      chunks[it++] = ck;
-    }
-  }
-  const int n_queue_chunks = deal_partition(cs, bin_rb_ptr, row_len, p, rb, v);
-  const int64_t first = v.cell_first(cs.nb);
-  for (int i = 0; i < n_queue_chunks; ++i) {  // to the kernel a queue chunk looks like eight rows of width 8
-    Chunk ck;
-    ck.slot0 = first + i;  // its octets are octets[8 * slot0 ..]
-    ck.row0 = 0;
-    ck.meta = 3u | ((uint32_t)kChunkSlots << 6) | kChunkIsQueue;
-    chunks[first + i] = ck;
+  FillVisitor v{cs, ss, p, group_first + cell[0], cell, cell[0], row_ids, bucket_row_ptr, bucket_slot_ptr, rem_ptr, S,
+                chunks, place, long_pieces, long_cursor, -1, 0};
+  deal_partition(cs, bin_rb_ptr, row_len, p, rb, v);
+}
+
+// One thread per row piece: copies the entries of a queued piece to its place in the stream; short pieces
+// by their own lane, longer ones by the whole wavefront.
+__global__ __launch_bounds__(256) void k_pack_pieces(int64_t n_pieces, StreamShape ss,
+                                                     const PiecePlace* __restrict__ place,
+                                                     const int32_t* __restrict__ row_ids,
+                                                     const int32_t* __restrict__ cols,
+                                                     const float* __restrict__ vals) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  PiecePlace pl;
+  pl.slot0 = 0; pl.first_chunk = 0; pl.where = 0; pl.len = 0;
+  int32_t row = 0;
+  if (q < n_pieces) { pl = place[q]; row = row_ids[q]; }
+  constexpr int kOwnLaneMax = 4;
+  if (pl.len <= kOwnLaneMax)
+    for (int e = 0; e < pl.len; ++e)
+      put_queue_entry(ss, pl.first_chunk, pl.where, e, cols[pl.slot0 + e], vals[pl.slot0 + e], row, e == pl.len - 1);
+  unsigned long long wide = __ballot(pl.len > kOwnLaneMax);
+  while (wide) {
+    const int src = __ffsll((long long)wide) - 1;
+    wide &= wide - 1;
+    const long long slot0 = __shfl((long long)pl.slot0, src, 64);
+    const long long first_chunk = __shfl((long long)pl.first_chunk, src, 64);
+    const int where = __shfl(pl.where, src, 64), len = __shfl(pl.len, src, 64), row_s = __shfl(row, src, 64);
+    for (int e = lane; e < len; e += 64)
+      put_queue_entry(ss, first_chunk, where, e, cols[slot0 + e], vals[slot0 + e], row_s, e == len - 1);
   }
 }
 
-// ------------------------------------------------------------ chunk stream
-// What the SpMM kernel actually reads: the chunks re-tiled into fixed records,
-// in list order, so that the address of every record follows from its list
-// position alone (no dependent descriptor load inside the gather loop).  Four
-// consecutive chunks form a quad, fetched with one 16-byte load per lane and
-// array.  The 12-byte form (3 KB per quad):
-//   quad[  0..255]  column ids, chunk i at 64*i  (slots past `count` repeat the last real column)
-//   quad[256..511]  values                        (slots past `count` hold +0.0f)
-//   quad[512..767]  per slot: row relative to the first row of the row block in bits 0..15,
-//                   the chunk's log2w in bits 16..21, the hand-over flag in bit 22 (the chunk's, or in a
-//                   queue chunk the octet's), bit 23: the slot belongs to no row (an idle octet);
-//                   slots past `count` hold -1
-// The compact form (2 KB per quad; the kernel's time goes with the bytes it has
-// to pull from beyond L2, and every feature tile re-reads the stream) folds the
-// row word into the column word, see kCompactColBits:
-//   quad[  0..255]  column - first column of the launch | row << 20 | real << 27 | log2w code << 28 | hand-over << 31
-//   quad[256..511]  values
-// One wavefront per chunk; reads the canonical arrays through the descriptor.
-__global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, const Chunk* __restrict__ chunks,
+// One wavefront per chunk of a wide row (and per padding chunk of a group); reads the canonical arrays
+// through the descriptor.  Queue chunks are written by k_pack_pieces and k_part_fill_chunks.
+__global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, StreamShape ss,
+                                                     const Chunk* __restrict__ chunks,
                                                      const int32_t* __restrict__ row_ids,
-                                                     const QueueOctet* __restrict__ octets,
-                                                     const int32_t* __restrict__ cols, const float* __restrict__ vals,
-                                                     int32_t log2_rb, int32_t compact, int32_t phase_width,
-                                                     int32_t* stream) {
+                                                     const int32_t* __restrict__ cols,
+                                                     const float* __restrict__ vals) {
   int64_t q = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (q >= n_chunks) return;
   int lane = threadIdx.x & 63;
   const Chunk ck = chunks[q];
+  if (ck.meta & kChunkIsQueue) return;
   const int lw = (int)(ck.meta & 63u), count = (int)((ck.meta >> 6) & 127u);
-  // chunk i of quad Q sits at slots 64*i .. 64*i+63 of the quad's 256-slot arrays
-  constexpr int kQuadSlots = kChunkSlots * kChunksPerQuad;
-  int32_t* quad = stream + (q / kChunksPerQuad) * ((compact ? 2 : 3) * kQuadSlots);
-  const int at = (int)(q % kChunksPerQuad) * kChunkSlots + lane;
   if (count == 0) {  // padding of a group: contributes nothing, hands nothing over
-    quad[at] = compact ? (int32_t)0xF0000000u : 0;
-    quad[kQuadSlots + at] = 0;
-    if (!compact) quad[2 * kQuadSlots + at] = -1;
+    put_slot(ss, q, lane, ss.compact ? (int32_t)0xF0000000u : 0, 0, -1);
     return;
   }
-  int64_t src;
-  int32_t rid;
-  bool real, valid;
-  int hand_over = (int)((ck.meta >> 13) & 1u);
-  if (ck.meta & kChunkIsQueue) {  // octet g of the chunk: up to 8 entries of one row piece, or nothing
-    const QueueOctet o = octets[ck.slot0 * 8 + (lane >> 3)];
-    const int n = o.info & 0xFF, j = lane & 7;
-    if (n == 0) {  // an idle lane group: zeros that belong to no row
-      quad[at] = compact ? (int32_t)(3u << 28) : 0;
-      quad[kQuadSlots + at] = 0;
-      if (!compact) quad[2 * kQuadSlots + at] = (3 << 16) | (1 << 23);  // the chunk's log2w, "no row"
-      return;
-    }
-    src = o.slot + (j < n ? j : n - 1);
-    rid = row_ids[o.q];
-    real = j < n;
-    valid = true;  // a pad of an octet still names the octet's row: the lane group hands the row over by its first slot
-    hand_over = (o.info >> 8) & 1;
+  const int hand_over = (int)((ck.meta >> 13) & 1u);
+  const int o = lane < count ? lane : count - 1;
+  const int64_t src = ck.slot0 + o;
+  const int32_t rid = row_ids[ck.row0 + (o >> lw)];
+  const bool real = lane < count;
+  const int32_t col = cols[src];
+  const float val = vals[src];
+  const int local_row = rid & ((1 << ss.log2_rb) - 1);
+  if (ss.compact) {
+    const uint32_t col_rel = (uint32_t)(col - (col / ss.phase_width) * ss.phase_width);
+    put_slot(ss, q, lane,
+             (int32_t)(col_rel | ((uint32_t)local_row << kCompactColBits) | ((uint32_t)real << 27) |
+                       ((uint32_t)(lw > 6 ? 7 : lw) << 28) | ((uint32_t)hand_over << 31)),
+             real ? __float_as_int(val) : 0, 0);
   } else {
-    const int o = lane < count ? lane : count - 1;
-    src = ck.slot0 + o;
-    rid = row_ids[ck.row0 + (o >> lw)];
-    real = valid = lane < count;
-  }
-  int32_t col = cols[src];
-  float val = vals[src];
-  const int local_row = rid & ((1 << log2_rb) - 1);
-  quad[kQuadSlots + at] = real ? __float_as_int(val) : 0;
-  if (compact) {
-    const uint32_t col_rel = (uint32_t)(col - (col / phase_width) * phase_width);  // a launch covers phase_width columns
-    quad[at] = (int32_t)(col_rel | ((uint32_t)local_row << kCompactColBits) | ((uint32_t)valid << 27) |
-                         ((uint32_t)(lw > 6 ? 7 : lw) << 28) | ((uint32_t)hand_over << 31));
-  } else {
-    quad[at] = col;
-    quad[2 * kQuadSlots + at] = valid ? (local_row | (lw << 16) | (hand_over << 22)) : -1;
+    put_slot(ss, q, lane, col, real ? __float_as_int(val) : 0,
+             real ? (local_row | (lw << 16) | (hand_over << 22)) : -1);
   }
 }
 
@@ -666,7 +688,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   if (!tmp.base) return SPTIR_ERR_ALLOC;
   Blob tmp2;
   void* tmp_chunks = nullptr;
-  void* tmp_octets = nullptr;
+  void* tmp_place = nullptr;
 
   sptir_hyb* h = new (std::nothrow) sptir_hyb();
   if (!h) { free_(tmp.base, actx); return SPTIR_ERR_ALLOC; }
@@ -869,10 +891,10 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       tmp_chunks = alloc(bytes, actx, stream);  // descriptors are only needed until the stream is packed
       if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
       BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, bytes, stream));  // count 0 marks the padding chunks
-      bytes = sizeof(QueueOctet) * 8 * (size_t)(n_chunks ? n_chunks : 1);
-      tmp_octets = alloc(bytes, actx, stream);  // indexed by chunk, so that queue cells need no numbering of their own
-      if (!tmp_octets) { st = SPTIR_ERR_ALLOC; goto fail; }
-      BUILD_HIP(hipMemsetAsync(tmp_octets, 0, bytes, stream));  // all zero: an idle lane group
+      bytes = sizeof(PiecePlace) * (size_t)(h->R + M ? h->R + M : 1);
+      tmp_place = alloc(bytes, actx, stream);
+      if (!tmp_place) { st = SPTIR_ERR_ALLOC; goto fail; }
+      BUILD_HIP(hipMemsetAsync(tmp_place, 0, bytes, stream));  // len 0: not queued
       bytes = sizeof(int32_t) * (h->compact_stream ? 2 : 3) * kChunkSlots * (size_t)(n_chunks ? n_chunks : 1);
       h->stream = (int32_t*)alloc(bytes, actx, stream);
       if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
@@ -884,11 +906,14 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
         h->device_bytes += bytes;
       }
     }
+    StreamShape ss;
+    ss.stream = h->stream; ss.compact = h->compact_stream; ss.log2_rb = cs.log2_rb;
+    ss.phase_width = (int32_t)((int64_t)cs.ppg * s.w > 0x7FFFFFFF ? 0x7FFFFFFF : (int64_t)cs.ppg * s.w);
     if (n_parts > 0)
-      hipLaunchKernelGGL(k_part_fill_chunks, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs,
+      hipLaunchKernelGGL(k_part_fill_chunks, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs, ss,
                          n_parts, d_bounds, d_cell_chunks, d_group_tot, d_seq_tot, h->row_len, h->row_ids,
                          h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_ptr, h->S, (Chunk*)tmp_chunks,
-                         (QueueOctet*)tmp_octets, h->rb_chunk_ptr, h->long_pieces, d_long_cursor);
+                         (PiecePlace*)tmp_place, h->rb_chunk_ptr, h->long_pieces, d_long_cursor);
     if (n_long > 0) {
       // The long pieces arrive in no particular order: sort them by (row, partition) on the host, so that
       // one workgroup sums all pieces of a row in a fixed order.  There are few of them by construction
@@ -921,10 +946,12 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     if (n_chunks > 0) {
       int64_t blocks = (n_chunks + 3) / 4;
       if (blocks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
-      hipLaunchKernelGGL(k_pack_stream, dim3((unsigned)blocks), dim3(256), 0, stream, (int64_t)n_chunks,
-                         (const Chunk*)tmp_chunks, h->row_ids, (const QueueOctet*)tmp_octets, h->cols, h->vals,
-                         cs.log2_rb, h->compact_stream,
-                         (int32_t)((int64_t)cs.ppg * s.w > 0x7FFFFFFF ? 0x7FFFFFFF : (int64_t)cs.ppg * s.w), h->stream);
+      hipLaunchKernelGGL(k_pack_stream, dim3((unsigned)blocks), dim3(256), 0, stream, (int64_t)n_chunks, ss,
+                         (const Chunk*)tmp_chunks, h->row_ids, h->cols, h->vals);
+      const int64_t n_pieces = h->R + M;
+      if (n_pieces > 0)
+        hipLaunchKernelGGL(k_pack_pieces, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream, n_pieces, ss,
+                           (const PiecePlace*)tmp_place, h->row_ids, h->cols, h->vals);
     }
     {
       int64_t total = n_chunks;
@@ -956,7 +983,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   free_(tmp.base, actx);
   if (tmp2.base) free_(tmp2.base, actx);
   if (tmp_chunks) free_(tmp_chunks, actx);
-  if (tmp_octets) free_(tmp_octets, actx);
+  if (tmp_place) free_(tmp_place, actx);
   *out = h;
   return SPTIR_OK;
 
@@ -965,7 +992,7 @@ fail:
   free_(tmp.base, actx);
   if (tmp2.base) free_(tmp2.base, actx);
   if (tmp_chunks) free_(tmp_chunks, actx);
-  if (tmp_octets) free_(tmp_octets, actx);
+  if (tmp_place) free_(tmp_place, actx);
   sptir_hyb_destroy(h);
   return st;
 #undef BUILD_HIP

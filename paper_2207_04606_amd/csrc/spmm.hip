@@ -284,8 +284,10 @@ constexpr int kHybBlock = 64 * kHybWaves;
 // quad and holds no conditional memory operation, so that the compiler's wait
 // counters stay exact; the last quad is peeled.
 //
-// The lane groups that share a row add their partial sums up with cross-lane
-// moves; the leading group adds the row sum into the wavefront's LDS tile of Y.
+// In a queue chunk every lane group sums the rows of its own queue and adds a
+// finished row sum into the wavefront's LDS tile of Y; the lane groups that
+// share a chunk of one long row add their partial sums up with cross-lane moves
+// at the row's end, and the leading group hands the sum over.
 template <int VEC, int LG, bool IDX32, bool WIDE>
 struct HybWalker {
   using S = Shape<VEC, LG>;
@@ -378,58 +380,53 @@ struct HybWalker {
     }
   }
 
-  // step s of the quad parked at `st` whose chunk facts are m[]
+  // step s of the quad parked at `st` whose chunk facts are m[].  The stream holds two kinds of chunks:
+  //  * queue chunks (log2w 3): slots 8q .. 8q+7 continue queue q of the (row block, partition); every slot
+  //    names its row and the last entry of a row piece carries the hand-over flag;
+  //  * chunks cut from one wide row (log2w >= 6), which all lane groups share; the chunk's hand-over flag
+  //    says whether the row ends with it.
   __device__ __forceinline__ void consume(const int* st, int s, int meta, const float (&v)[UB],
                                           const float (&x)[UB][VEC]) {
-    // (compact: a chunk cut from a row wider than 64 slots carries code 7; every test below only asks lw >= 6)
+    // (compact: a chunk cut from a row wider than 64 slots carries code 7; the test below only asks lw >= 6)
     const int lw = WIDE ? (meta & 63) : ((meta >> 1) & 7);
     const bool hand_over = ((meta >> (WIDE ? 6 : 4)) & 1) != 0;
     const int sub = s & (SUB - 1);
     const int* rows = st + (WIDE ? 2 * kQuadSlots : 0);
-    if (lw < S::kLog2Steps) {
-      // several rows inside the group's share: hand each one over as it ends
+    if (lw < 6) {
       int r[UB];
       read_ints(rows + first_slot(s), r);
-      const int width_mask = (1 << lw) - 1;
 #pragma unroll
       for (int j = 0; j < UB; ++j) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
-        if (((j + 1) & width_mask) == 0) {
+        if (slot_hands_over(r[j])) {
           sink(local_row(r[j]), row_valid(r[j]), acc);
 #pragma unroll
           for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
         }
       }
+      if constexpr (SUB == 1 && UB == 8) return;  // this lane group walks the queue alone: the sum stays in registers
+      // Any other shape meets the queue again in another lane group or step, so what has been summed of an
+      // unfinished row is handed over now.  Lane groups that share an octet may hold parts of the same
+      // row: they take turns.
+      constexpr int kTurns = UB < 8 ? 8 / UB : 1;
+#pragma unroll
+      for (int turn = 0; turn < kTurns; ++turn)
+        sink(local_row(r[UB - 1]), row_valid(r[UB - 1]) && (g & (kTurns - 1)) == turn, acc);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
       return;
     }
-    // the group's share lies inside one row, which `groups` neighbouring lane groups share
-    const bool one_row_chunk = lw >= 6;
 #pragma unroll
     for (int j = 0; j < UB; ++j)
 #pragma unroll
       for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
-    if (one_row_chunk && !(hand_over && sub == SUB - 1)) return;  // the row goes on: keep the sums in registers
-    if (SUB == 1 && UB == 8 && lw == 3) {
-      // a queue chunk: every lane group walks a row of its own, octet by octet, and the word of the octet's
-      // first slot says whether the row ends here
-      const int r = rows[first_slot(s)];
-      if (slot_hands_over(r)) {
-        sink(local_row(r), row_valid(r), acc);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-      }
-      return;
-    }
-    if (!one_row_chunk && lw >= S::kLog2Chunk && (((sub + 1) * CS) & ((1 << lw) - 1)) != 0) return;  // row spans steps
-    const int groups = (one_row_chunk || lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));
-    sum_groups<VEC, LG>(acc, groups);
-    const int g_first = g & ~(groups - 1);
-    // (a row cut into several chunks keeps its partial sums in registers in between, so for a one-row
-    //  chunk even groups past the last real slot take part; its row sits in the chunk's slot 0)
-    const int chunk0 = (s - sub) * CS;
-    const int r = rows[one_row_chunk ? chunk0 : first_slot(s) - (g - g_first) * UB];
-    sink(local_row(r), g == g_first && row_valid(r), acc);
+    if (!(hand_over && sub == SUB - 1)) return;  // the row goes on: keep the sums in registers
+    sum_groups<VEC, LG>(acc, S::kGroups);
+    // (a row cut into several chunks keeps its partial sums in registers in between, so even groups past the
+    //  last real slot take part; its row sits in the chunk's slot 0)
+    const int r = rows[(s - sub) * CS];
+    sink(local_row(r), g == 0 && row_valid(r), acc);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
   }

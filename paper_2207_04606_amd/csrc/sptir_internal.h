@@ -9,17 +9,17 @@
 
 namespace sptir {
 
-// The SpMM kernel walks the stored slots in chunks of kChunkSlots consecutive
-// slots of the fused (cols, vals) arrays, starting at `slot0`.  Slot o of the
-// chunk belongs to row_ids[row0 + (o >> log2w)]: for an ELL bucket narrower
-// than a chunk log2w is the bucket's i (section 4.2.1: width 2^i, so a chunk
-// packs 64 / 2^i whole rows); a chunk cut from a wider row or from a piece of
-// the CSR remainder holds one row only and carries log2w = kRowLog2W.
+// The SpMM kernel walks the real entries of the stored rows in chunks of kChunkSlots slots.  A builder-side
+// descriptor stands for a chunk cut from one row (an ELL row of section 4.2.1 or a piece of the CSR remainder)
+// that is too long to be walked by one lane group: `count` consecutive slots of the fused (cols, vals) arrays
+// starting at `slot0`, all of row row_ids[row0]; it carries log2w = kRowLog2W.  Queue chunks, which hold eight
+// entries of each of eight lane-group queues, are written piece by piece and have a descriptor only to mark
+// their place; a descriptor with count 0 is the padding at the end of a (launch, row block) list.
 struct Chunk {
   int64_t slot0;
   int32_t row0;
   // bits 0..5 log2w, bits 6..12 count (1..64), bit 13: hand the row's partial sum over after this chunk,
-  // bit 14: queue chunk (eight octets of eight different rows; slot0 then indexes the builder's octet table)
+  // bit 14: queue chunk
   uint32_t meta;
 };
 static_assert(sizeof(Chunk) == 16, "Chunk must stay 16 bytes");
@@ -43,7 +43,8 @@ struct LongPiece {
 static_assert(sizeof(LongPiece) == 24, "LongPiece must stay 24 bytes");
 // Compact stream records spend 8 bytes per slot instead of 12: one word holds the column relative to the first
 // column of the launch (bits 0..19), the row relative to the row block (20..26), "slot is real" (27), the chunk's
-// log2w code (28..30; 7 = cut from a row wider than a chunk) and its hand-over flag (31); the other word the value.
+// log2w code (28..30; 3 = queue chunk, 7 = cut from one long row) and the hand-over flag (31; of the chunk, or in a
+// queue chunk of the slot: the last entry of a row piece); the other word the value.
 constexpr int kCompactColBits = 20;
 constexpr int kCompactMaxLog2RowBlock = 7;
 
