@@ -237,6 +237,20 @@ def main():
         csr_ms = (time.perf_counter() - t0) * 1e3 / 10
         out["no_hyb_csr"] = {"ms_per_step": round(csr_ms, 4), "gflops": round(2.0 * w.nnz * 128 / csr_ms / 1e6, 1),
                              "hyb_speedup": round(csr_ms / head["wall_ms"], 3)}
+        # the format search of section 4.2.1 (build every candidate c, time it, keep the fastest) over a few
+        # partition counts around the configured one; the headline above stays at the configured c
+        cands = [8, 12, 16, 24]
+        t0 = time.perf_counter()
+        best, best_c, cand_ms = sptir.sptir_hyb_search(w.n_rows, w.n_cols, indptr, indices, values, 128, cands,
+                                                       w.max_bucket_log2, reps=5)
+        torch.cuda.synchronize()
+        search_ms = (time.perf_counter() - t0) * 1e3
+        best_wall_ms, _ = time_spmm(sptir, torch, best, X, Y, 20, 3)
+        best.destroy()
+        out["format_search"] = {"candidates": cands, "ms_per_candidate": [round(m, 4) for m in cand_ms],
+                                "best_c": best_c, "best_ms_per_step": round(best_wall_ms, 4),
+                                "best_gflops": round(2.0 * w.nnz * 128 / best_wall_ms / 1e6, 1),
+                                "search_ms": round(search_ms, 1)}
         # SDDMM on the same graph (B_ij = A_ij <X_i, Yt_j>), entries in CSR order and in column-partition order
         Xl = torch.randn(w.n_rows, 128, device=dev, generator=torch.Generator(device=dev).manual_seed(3))
         Bv = torch.empty(w.nnz, device=dev)

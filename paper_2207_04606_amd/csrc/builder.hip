@@ -600,18 +600,16 @@ struct Blob {  // bump allocator over one device allocation
 //   SPTIR_ROW_BLOCK        rows of Y one wavefront keeps in LDS (power of two, 8..256)
 //   SPTIR_PARTS_PER_PHASE  column partitions swept per SpMM launch (default: chosen from the sizes)
 //   SPTIR_WIDE_STREAM      non-zero: always write the 12-byte stream records
-int log2_row_block_setting(int32_t n_rows, double slots_per_row_and_launch) {
+int log2_row_block_setting(int32_t n_rows) {
   const char* e = getenv("SPTIR_ROW_BLOCK");
   long v = e ? atol(e) : 0;
   if (v < 8 || v > 256 || (v & (v - 1))) {
-    // A wavefront walks the list of one (launch, row block) alone.  Every (partition, bucket) cell of the
-    // list starts a new chunk and lists are rounded up to whole quads, so short lists are mostly padding: aim
-    // at some 2800 stored slots (44 chunks) per list.  32 rows x 128 bytes = 4 KB of LDS per wavefront next to
-    // its 4 KB (6 KB) chunk ring leaves the register file to cap the CU at 16 wavefronts, 64 rows allow 12
-    // (measured on the largest graph: 9 % fewer chunks and 3 - 8 % less time with 64 rows, slower again
-    // with 128); 128 rows is the most a compact record can address.
-    v = 32;
-    while (v < 128 && v * slots_per_row_and_launch < 2800.0) v <<= 1;
+    // A wavefront walks the list of one (launch, row block) alone and keeps the block's tile of Y in LDS:
+    // 64 rows x 128 bytes = 8 KB next to its 4 KB (6 KB) chunk ring allow 12 wavefronts per CU.  Measured on
+    // the two large graphs: 32 rows cost 3 % (more lists, each rounded up to whole chunks), 128 rows 12 - 25 %
+    // (fewer wavefronts per CU); the low-degree graphs do not care.  128 rows is the most a compact record
+    // can address.
+    v = 64;
     // ... but keep at least ~1024 row blocks, or the 256 CUs do not fill
     while (v > 8 && n_rows / v < 1024) v >>= 1;
   }
@@ -776,8 +774,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     CellShape cs;
     cs.c = s.c; cs.k = s.k; cs.nb = s.nb; cs.R = h->R;
     cs.ppg = parts_per_phase_setting(s.c, s.w, s.n_rows, h->S + h->T);
-    cs.log2_rb = log2_row_block_setting(
-        s.n_rows, s.n_rows > 0 ? (double)(h->S + h->T) / s.n_rows / ((s.c + cs.ppg - 1) / cs.ppg) : 0.0);
+    cs.log2_rb = log2_row_block_setting(s.n_rows);
     cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
     if (!with_spmm_plan) cs.n_rb = 0;  // no row blocks, no cells, no chunks: only the canonical arrays are built
     h->spmm_plan = with_spmm_plan ? 1 : 0;

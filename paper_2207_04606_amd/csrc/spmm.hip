@@ -705,10 +705,8 @@ bool plan(int64_t n_units, int feat, const void* X, const void* Y, Geometry* g) 
 // touches is well below its size.  So a wide Y is produced in several sweeps, each over a group of feature tiles
 // (4 or 8, which still map whole XCDs to a tile).
 int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches) {
-  static const double limit_mb = [] {
-    const char* e = std::getenv("SPTIR_SWEEP_MB");
-    return e ? std::atof(e) : 160.0;
-  }();
+  const char* e = std::getenv("SPTIR_SWEEP_MB");  // tuning knob, read at every call
+  const double limit_mb = e ? std::atof(e) : 160.0;
   if (n_launches < 2 || n_tiles % 4 != 0) return n_tiles;
   const double tile_mb = (double)n_rows * tile_floats * sizeof(float) / (1024.0 * 1024.0);
   if (tile_mb * n_tiles <= limit_mb) return n_tiles;

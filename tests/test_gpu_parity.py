@@ -296,6 +296,27 @@ def test_spmm_launch_plan_knobs(gpu_lib, monkeypatch, knobs):
         assert torch.equal(Y, Y2)
 
 
+@pytest.mark.parametrize("feat", [128, 256, 320, 384, 520])
+def test_spmm_feature_sweeps(gpu_lib, monkeypatch, feat):
+    """A Y too wide for the memory-side cache is produced in several sweeps over the launches, each over a group
+    of 4 or 8 feature tiles; the limit is lowered here so that a small Y takes that path (feat = 320 and 520
+    have tile counts that do not split and run as one sweep)."""
+    say(f"[feature sweeps] feat={feat}")
+    monkeypatch.setenv("SPTIR_PARTS_PER_PHASE", "1")
+    w = ragged_workload(1300 + feat, 1500, 1800, feat, max_deg=900, long_rows=3)
+    d, hyb, got, want, info = build_both(gpu_lib, w, 3, 6)
+    assert info["n_phases"] == 3
+    Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+    Y_one = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+    gpu_lib.sptir_spmm(hyb, d.X, Y_one)
+    assert_y_close(Y_one.cpu().numpy(), Yr, Sr, what=f"one sweep feat={feat}")
+    for limit_mb in ("0.5", "0.0001"):   # 8 tiles of 1500 rows are 0.73 MB: sweeps of 4 tiles, then the same
+        monkeypatch.setenv("SPTIR_SWEEP_MB", limit_mb)
+        Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+        gpu_lib.sptir_spmm(hyb, d.X, Y)
+        assert torch.equal(Y, Y_one), f"feat={feat} limit={limit_mb}"
+
+
 @pytest.mark.parametrize("c", [1, 2, 4, 9])
 def test_spmm_many_columns(gpu_lib, c):
     """More than 2^20 columns per partition (c = 1, 2) cannot use launch-relative 20-bit columns; c = 4 can, but
