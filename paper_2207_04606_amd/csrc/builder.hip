@@ -687,6 +687,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   Blob tmp2;
   void* tmp_chunks = nullptr;
   void* tmp_place = nullptr;
+  void* tmp_order = nullptr;
 
   sptir_hyb* h = new (std::nothrow) sptir_hyb();
   if (!h) { free_(tmp.base, actx); return SPTIR_ERR_ALLOC; }
@@ -956,31 +957,21 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
                                hipMemcpyHostToDevice, stream));
     }
     BUILD_HIP(hipGetLastError());
-    BUILD_HIP(hipStreamSynchronize(stream));
     if (n_groups > 0) {
-      // ---- launch order of the row blocks: longest list first, so that the last wavefronts of a launch to
-      //      finish are short ones (row blocks of a power-law graph differ several-fold in work)
-      std::vector<int64_t> ptr((size_t)n_groups + 1);
-      std::vector<int32_t> order((size_t)n_groups);
-      BUILD_HIP(hipMemcpyAsync(ptr.data(), h->rb_chunk_ptr, sizeof(int64_t) * ptr.size(), hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipStreamSynchronize(stream));
-      for (int32_t ph = 0; ph < cs.n_phases; ++ph) {
-        int32_t* o = order.data() + (size_t)ph * cs.n_rb;
-        const int64_t* pp = ptr.data() + (size_t)ph * cs.n_rb;
-        for (int32_t j = 0; j < cs.n_rb; ++j) o[j] = j;
-        std::stable_sort(o, o + cs.n_rb, [&](int32_t x, int32_t y) { return pp[x + 1] - pp[x] > pp[y + 1] - pp[y]; });
-      }
-      h->rb_order = (int32_t*)alloc(sizeof(int32_t) * order.size(), actx, stream);
+      // ---- launch order of the row blocks: longest list first
+      h->rb_order = (int32_t*)alloc(sizeof(int32_t) * (size_t)n_groups, actx, stream);
       if (!h->rb_order) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += sizeof(int32_t) * order.size();
-      BUILD_HIP(hipMemcpyAsync(h->rb_order, order.data(), sizeof(int32_t) * order.size(), hipMemcpyHostToDevice, stream));
-      BUILD_HIP(hipStreamSynchronize(stream));  // the host vector goes out of scope
+      h->device_bytes += sizeof(int32_t) * (size_t)n_groups;
+      st = order_row_blocks(h->rb_chunk_ptr, cs.n_phases, cs.n_rb, h->rb_order, alloc, free_, actx, stream, &tmp_order);
+      if (st != SPTIR_OK) goto fail;
     }
+    BUILD_HIP(hipStreamSynchronize(stream));
   }
   free_(tmp.base, actx);
   if (tmp2.base) free_(tmp2.base, actx);
   if (tmp_chunks) free_(tmp_chunks, actx);
   if (tmp_place) free_(tmp_place, actx);
+  if (tmp_order) free_(tmp_order, actx);
   *out = h;
   return SPTIR_OK;
 
@@ -990,6 +981,7 @@ fail:
   if (tmp2.base) free_(tmp2.base, actx);
   if (tmp_chunks) free_(tmp_chunks, actx);
   if (tmp_place) free_(tmp_place, actx);
+  if (tmp_order) free_(tmp_order, actx);
   sptir_hyb_destroy(h);
   return st;
 #undef BUILD_HIP

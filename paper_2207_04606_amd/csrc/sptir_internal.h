@@ -97,6 +97,12 @@ void default_free(void* p, void* ctx);
 sptir_status_t hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2, void* stream,
                               sptir_hyb_t** out, bool with_spmm_plan);
 
+// rb_order[launch][i] = the row block with the i-th longest chunk list of that launch (order.hip).  Works on
+// `stream`; *scratch_out is device memory the caller frees once the stream has drained.
+sptir_status_t order_row_blocks(const int64_t* rb_chunk_ptr, int32_t n_launches, int32_t n_rb, int32_t* rb_order,
+                                sptir_alloc_fn alloc, sptir_free_fn free_, void* actx, hipStream_t stream,
+                                void** scratch_out);
+
 // records a failed HIP call for sptir_last_hip_error(); returns SPTIR_ERR_HIP
 sptir_status_t note_hip_error(hipError_t e, const char* what);
 
