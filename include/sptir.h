@@ -163,8 +163,12 @@ sptir_status_t sptir_hyb_search(const sptir_csr_t* csr, const int32_t* c_candida
  *   feat >= 1
  * Only enqueues work on `stream` (no synchronisation, no allocation): one
  * launch per group of column partitions (sptir_hyb_info_t.n_phases), each
- * adding to what the earlier ones left in Y, plus one for rows with very long
- * pieces.  No atomics are used and every sum has a fixed order, so two calls
+ * adding to what the earlier ones left in Y (a Y wider than the memory-side
+ * cache is produced in several such sweeps, each over a group of feature
+ * columns), plus two small ones for rows with very long pieces
+ * (sptir_hyb_info_t.n_long_rows > 0).  The partial sums of those rows pass
+ * through scratch memory that the handle owns: calls on one handle that has
+ * long rows must not overlap in time.  No atomics are used and every sum has a fixed order, so two calls
  * with the same handle and X give bit-identical Y.  The order differs from
  * CSR order (sums are regrouped by partition and bucket), so Y matches a CSR
  * product only up to float rounding.  A pad slot multiplies X by +0.0f: X must

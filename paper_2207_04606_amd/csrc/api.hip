@@ -59,7 +59,7 @@ sptir_status_t sptir_hyb_destroy(sptir_hyb_t* h) {
   if (!h) return SPTIR_OK;
   void* ptrs[] = {h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_part_ptr, h->rem_ptr,
                   h->row_ids, h->row_len, h->cols, h->vals, h->stream, h->rb_chunk_ptr, h->rb_order,
-                  h->long_rows, h->long_piece_ptr, h->long_pieces};
+                  h->long_rows, h->long_piece_ptr, h->long_pieces, h->long_seg_ptr, h->long_segs, h->long_partial};
   for (void* p : ptrs)
     if (p) h->free_(p, h->alloc_ctx);
   delete h;

@@ -933,6 +933,27 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       h->long_piece_ptr = (int32_t*)alloc(sizeof(int32_t) * ptr.size(), actx, stream);
       if (!h->long_rows || !h->long_piece_ptr) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += sizeof(int32_t) * (rows.size() + ptr.size());
+      // segments: one workgroup's worth of a long piece each
+      std::vector<LongSegment> segs;
+      std::vector<int32_t> seg_ptr;
+      for (size_t i = 0; i < rows.size(); ++i) {
+        seg_ptr.push_back((int32_t)segs.size());
+        for (int32_t j = ptr[i]; j < ptr[i + 1]; ++j)
+          for (int32_t off = 0; off < lp[j].len; off += kLongSegSlots)
+            segs.push_back(LongSegment{lp[j].slot0 + off, std::min<int32_t>(kLongSegSlots, lp[j].len - off), 0});
+        if (segs.size() > 0x3FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
+      }
+      seg_ptr.push_back((int32_t)segs.size());
+      h->n_long_segs = (int32_t)segs.size();
+      h->long_seg_ptr = (int32_t*)alloc(sizeof(int32_t) * seg_ptr.size(), actx, stream);
+      h->long_segs = (LongSegment*)alloc(sizeof(LongSegment) * segs.size(), actx, stream);
+      h->long_partial = (float*)alloc(sizeof(float) * kLongPartialFeat * segs.size(), actx, stream);
+      if (!h->long_seg_ptr || !h->long_segs || !h->long_partial) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += sizeof(int32_t) * seg_ptr.size() + (sizeof(LongSegment) + sizeof(float) * kLongPartialFeat) * segs.size();
+      BUILD_HIP(hipMemcpyAsync(h->long_seg_ptr, seg_ptr.data(), sizeof(int32_t) * seg_ptr.size(), hipMemcpyHostToDevice,
+                               stream));
+      BUILD_HIP(hipMemcpyAsync(h->long_segs, segs.data(), sizeof(LongSegment) * segs.size(), hipMemcpyHostToDevice,
+                               stream));
       BUILD_HIP(hipMemcpyAsync(h->long_pieces, lp.data(), sizeof(LongPiece) * lp.size(), hipMemcpyHostToDevice,
                                stream));
       BUILD_HIP(hipMemcpyAsync(h->long_rows, rows.data(), sizeof(int32_t) * rows.size(), hipMemcpyHostToDevice,

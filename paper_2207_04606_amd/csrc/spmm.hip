@@ -669,6 +669,78 @@ __global__ __launch_bounds__(64 * kLongWaves) void k_spmm_long(LongArgs a) {
   }
 }
 
+// The same sum with more workgroups, for Y no wider than kLongPartialFeat: one workgroup of kSegWaves wavefronts
+// per segment of a long piece leaves the segment's sum in `partial`, then k_long_reduce adds the segments of a
+// row to its row of Y in segment order (fixed, so the result is again the same from run to run).  A hub row of
+// 20,000 non-zeros is 20 workgroups' work instead of one's.
+struct SegmentArgs {
+  const LongSegment* segs;
+  const int32_t* cols;
+  const float* vals;
+  const float* X;
+  float* partial;  // [n_segs][feat]
+  int32_t n_segs;
+  int32_t feat;
+  int32_t n_tiles;
+  int32_t map_mode;
+  int32_t map_param;
+};
+
+constexpr int kSegWaves = 4;
+
+template <int VEC, int LG>
+__global__ __launch_bounds__(64 * kSegWaves) void k_long_segments(SegmentArgs a) {
+  using S = Shape<VEC, LG>;
+  __shared__ float share[kSegWaves][S::kTile];
+  int64_t unit;
+  int tile_id;
+  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
+  if (unit >= a.n_segs) return;  // (whole workgroup)
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int lane = threadIdx.x & 63;
+  const int fl = lane & (LG - 1);
+  const int f0 = tile_id * S::kTile + fl * VEC;
+  const bool f_active = f0 < a.feat;
+  float total[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) total[e] = 0.f;
+  RegisterSink<VEC> sink{total};
+  const LongSegment sg = a.segs[unit];
+  const int n_chunks = (sg.len + S::kChunk - 1) / S::kChunk;
+  const int per_wave = (n_chunks + kSegWaves - 1) / kSegWaves;
+  const int first = wave * per_wave * S::kChunk;
+  const int count = min(sg.len - first, per_wave * S::kChunk);
+  if (count > 0)
+    walk_slots<VEC, LG, false>(a.cols + sg.slot0 + first, a.vals + sg.slot0 + first, nullptr, a.X + f0, a.feat,
+                               kRowLog2W, count, lane, f_active, sink);
+  if (lane < LG) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) share[wave][fl * VEC + e] = total[e];
+  }
+  __syncthreads();
+  if (wave == 0 && lane < LG && f_active) {
+    float out[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) out[e] = share[0][fl * VEC + e];
+    for (int w = 1; w < kSegWaves; ++w) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) out[e] += share[w][fl * VEC + e];
+    }
+    store_vec<VEC>(a.partial + (size_t)unit * (size_t)a.feat + f0, out);
+  }
+}
+
+// one thread per (long row, feature)
+__global__ void k_long_reduce(const int32_t* __restrict__ long_rows, const int32_t* __restrict__ long_seg_ptr,
+                              const float* __restrict__ partial, float* Y, int32_t n_long_rows, int32_t feat) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= (int64_t)n_long_rows * feat) return;
+  const int i = (int)(t / feat), f = (int)(t % feat);
+  float sum = 0.f;
+  for (int sgm = long_seg_ptr[i]; sgm < long_seg_ptr[i + 1]; ++sgm) sum += partial[(size_t)sgm * feat + f];
+  Y[(size_t)long_rows[i] * (size_t)feat + f] += sum;
+}
+
 // launch geometry shared by both SpMM entry points
 struct Geometry {
   int vec, lg, n_tiles, map_mode, map_param;
@@ -787,7 +859,22 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
       else launch_hyb<1, 32>(g, lds_bytes, stream, a, idx32, wide);
     }
   }
-  if (h->n_long_rows > 0) {
+  if (h->n_long_rows > 0 && feat <= kLongPartialFeat) {
+    Geometry gl;
+    if (!plan(h->n_long_segs, feat, X, Y, &gl)) return SPTIR_ERR_OVERFLOW;
+    SegmentArgs sa;
+    sa.segs = h->long_segs; sa.cols = h->cols; sa.vals = h->vals; sa.X = X; sa.partial = h->long_partial;
+    sa.n_segs = h->n_long_segs; sa.feat = feat;
+    sa.n_tiles = gl.n_tiles; sa.map_mode = gl.map_mode; sa.map_param = gl.map_param;
+    dim3 grid((unsigned)gl.grid), block(64 * kSegWaves);
+    if (gl.vec == 4 && gl.lg == 8) hipLaunchKernelGGL((k_long_segments<4, 8>), grid, block, 0, stream, sa);
+    else if (gl.vec == 4) hipLaunchKernelGGL((k_long_segments<4, 4>), grid, block, 0, stream, sa);
+    else if (gl.vec == 2) hipLaunchKernelGGL((k_long_segments<2, 16>), grid, block, 0, stream, sa);
+    else hipLaunchKernelGGL((k_long_segments<1, 32>), grid, block, 0, stream, sa);
+    const int64_t n_out = (int64_t)h->n_long_rows * feat;
+    hipLaunchKernelGGL(k_long_reduce, dim3((unsigned)((n_out + 255) / 256)), dim3(256), 0, stream, h->long_rows,
+                       h->long_seg_ptr, h->long_partial, Y, h->n_long_rows, feat);
+  } else if (h->n_long_rows > 0) {
     Geometry gl;
     if (!plan(h->n_long_rows, feat, X, Y, &gl)) return SPTIR_ERR_OVERFLOW;
     LongArgs la;

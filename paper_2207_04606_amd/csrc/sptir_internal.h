@@ -41,6 +41,14 @@ struct LongPiece {
   int32_t pad_;
 };
 static_assert(sizeof(LongPiece) == 24, "LongPiece must stay 24 bytes");
+// A run of at most kLongSegSlots consecutive entries of a long piece.
+struct LongSegment {
+  int64_t slot0;
+  int32_t len;
+  int32_t pad_;
+};
+constexpr int kLongSegSlots = 1024;
+constexpr int kLongPartialFeat = 512;  // widest Y the per-segment partial sums are kept for
 // Compact stream records spend 8 bytes per slot instead of 12: one word holds the column relative to the first
 // column of the launch (bits 0..19), the row relative to the row block (20..26), "slot is real" (27), the chunk's
 // log2w code (28..30; 3 = queue chunk, 7 = cut from one long row) and the hand-over flag (31; of the chunk, or in a
@@ -76,6 +84,12 @@ struct sptir_hyb {
   int32_t* long_rows;        // device [n_long_rows], ascending
   int32_t* long_piece_ptr;   // device [n_long_rows + 1]
   sptir::LongPiece* long_pieces;  // device
+  // the long pieces cut into segments of at most kLongSegSlots entries, one workgroup each; the segments of
+  // long_rows[i] are long_segs[long_seg_ptr[i] .. long_seg_ptr[i+1]) and their partial sums meet in long_partial
+  int32_t n_long_segs;
+  int32_t* long_seg_ptr;     // device [n_long_rows + 1]
+  sptir::LongSegment* long_segs;  // device [n_long_segs]
+  float* long_partial;       // device [n_long_segs][kLongPartialFeat]
   int32_t log2_row_block;    // rows of Y one wavefront accumulates in LDS (power of two)
   int32_t n_row_blocks;
   int32_t parts_per_phase;   // column partitions swept by one SpMM launch

@@ -332,10 +332,11 @@ def test_spmm_many_columns(gpu_lib, c):
     assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"many columns c={c}")
 
 
-@pytest.mark.parametrize("c,k,feat", [(1, 3, 32), (3, 5, 64), (2, 30, 8), (4, 11, 100), (1, 0, 3)])
+@pytest.mark.parametrize("c,k,feat", [(1, 3, 32), (3, 5, 64), (2, 30, 8), (4, 11, 100), (1, 0, 3), (2, 4, 516)])
 def test_spmm_long_rows(gpu_lib, c, k, feat):
     """Rows with far more non-zeros than a wavefront's list should hold (remainder pieces, and ELL rows when k is
-    large) are summed by a workgroup each; several long pieces of one row (c > 1) land in the same row of Y."""
+    large) are cut into segments that a workgroup each sums (one workgroup per row when Y is wider than 512
+    floats); several long pieces of one row (c > 1) land in the same row of Y."""
     say(f"[long rows] c={c} k={k} feat={feat}")
     w = ragged_workload(500 + c + k, 900, 40_000, feat, max_deg=30_000, long_rows=7)
     d, hyb, got, want, info = build_both(gpu_lib, w, c, k)
