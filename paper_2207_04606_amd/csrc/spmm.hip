@@ -59,7 +59,6 @@ struct Shape {
   static constexpr int kSteps = LG < 8 ? LG : 8;     // slots a group takes from one chunk
   static constexpr int kChunk = kGroups * kSteps;    // slots per chunk (<= 64: one per lane)
   static constexpr int kTile = VEC * LG;             // floats per feature tile
-  static constexpr int kLog2Steps = ilog2(kSteps);
   static constexpr int kLog2Chunk = ilog2(kChunk);
 };
 
@@ -126,34 +125,32 @@ struct DirectSink {
   }
 };
 
-// Walks `count` stored slots cp/vp[0..count) for this lane's feature offset.
-// Slot o belongs to the row whose id is rp[o >> lw] (WITH_ROWS) and is handled
-// by lane group (o % kChunk) / kSteps.  Finished row sums go to `sink`.
-template <int VEC, int LG, bool WITH_ROWS, typename Sink>
-__device__ __forceinline__ void walk_slots(const int32_t* __restrict__ cp, const float* __restrict__ vp,
-                                           const int32_t* __restrict__ rp, const float* __restrict__ Xf,
-                                           int feat, int lw, int count, int lane, bool f_active, const Sink& sink) {
+// Sums one row's `count` entries cp/vp[0..count) times their rows of X for this lane's feature offset: entry o
+// is gathered by lane group (o % kChunk) / kSteps, the lane groups' partial sums meet once at the end, and the
+// row sum goes to `sink` from the first lane group.
+template <int VEC, int LG, typename Sink>
+__device__ __forceinline__ void walk_row(const int32_t* __restrict__ cp, const float* __restrict__ vp,
+                                         const float* __restrict__ Xf, int feat, int count, int lane, bool f_active,
+                                         const Sink& sink) {
   using S = Shape<VEC, LG>;
   constexpr int UB = S::kSteps, CS = S::kChunk;
   if (count <= 0) return;
   const int g = lane / LG;
   const int src0 = g * UB;  // lane that fetched slot (g*UB) of the chunk
   const int nch = (count + CS - 1) >> S::kLog2Chunk;
-  const int width_mask = (lw < 31) ? ((1 << lw) - 1) : 0x7FFFFFFF;
 
   float acc[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
 
-  // one (column, value, row id) triple per lane and chunk
-  auto fetch = [&](int ch, int& c, float& v, int& rid) {
+  // one (column, value) pair per lane and chunk; past the end a lane re-reads the last entry with value 0
+  auto fetch = [&](int ch, int& c, float& v) {
     int o = (ch << S::kLog2Chunk) + lane;
     bool ok = (CS == 64 || lane < CS) && o < count;
     int oc = o < count ? o : count - 1;
     c = cp[oc];
     float vv = vp[oc];
     v = ok ? vv : 0.f;
-    if constexpr (WITH_ROWS) rid = rp[oc >> lw]; else rid = 0;
   };
   auto issue = [&](int c_reg, float (&x)[UB][VEC]) {
 #pragma unroll
@@ -166,64 +163,45 @@ __device__ __forceinline__ void walk_slots(const int32_t* __restrict__ cp, const
       }
     }
   };
-  auto consume = [&](int ch, float v_reg, int rid_reg, const float (&x)[UB][VEC]) {
-    const int chunk0 = ch << S::kLog2Chunk;
+  auto consume = [&](float v_reg, const float (&x)[UB][VEC]) {
 #pragma unroll
     for (int u = 0; u < UB; ++u) {
       float v = __shfl(v_reg, src0 + u, 64);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v, x[u][e], acc[e]);
-      // rows no wider than a group's share end inside the group: no cross-lane sum
-      if (lw <= S::kLog2Steps && ((u + 1) & width_mask) == 0) {
-        int rid = __shfl(rid_reg, src0 + u, 64);
-        sink(rid, chunk0 + src0 + u < count, acc);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-      }
-    }
-    if (lw > S::kLog2Steps) {
-      // a wider row spans several lane groups and, beyond a chunk, several chunks
-      bool row_done = (ch == nch - 1) || lw < S::kLog2Chunk || (((ch + 1) << S::kLog2Chunk) & width_mask) == 0;
-      if (row_done) {
-        const int groups = (lw >= S::kLog2Chunk) ? S::kGroups : (1 << (lw - S::kLog2Steps));  // groups per row
-        for (int d = 1; d < groups; d <<= 1) {
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], d * LG, 64);
-        }
-        const int g_first = g & ~(groups - 1);
-        int rid = __shfl(rid_reg, g_first * UB, 64);
-        sink(rid, g == g_first && chunk0 + g_first * UB < count, acc);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
-      }
     }
   };
 
   // software pipeline: x0 / x1 hold the gathers of two consecutive chunks
   float x0[UB][VEC], x1[UB][VEC];
-  int c_a = 0, c_b = 0, c_p = 0, r_a = 0, r_b = 0, r_p = 0;
+  int c_a = 0, c_b = 0, c_p = 0;
   float v_a = 0.f, v_b = 0.f, v_p = 0.f;
-  fetch(0, c_a, v_a, r_a);
-  if (nch > 1) fetch(1, c_b, v_b, r_b);
+  fetch(0, c_a, v_a);
+  if (nch > 1) fetch(1, c_b, v_b);
   issue(c_a, x0);
-  if (nch > 2) fetch(2, c_p, v_p, r_p);
+  if (nch > 2) fetch(2, c_p, v_p);
   if (nch > 1) issue(c_b, x1);
   for (int ch = 0; ch < nch; ch += 2) {
-    consume(ch, v_a, r_a, x0);
+    consume(v_a, x0);
     if (ch + 2 < nch) {
-      c_a = c_p; v_a = v_p; r_a = r_p;
-      if (ch + 3 < nch) fetch(ch + 3, c_p, v_p, r_p);
+      c_a = c_p; v_a = v_p;
+      if (ch + 3 < nch) fetch(ch + 3, c_p, v_p);
       issue(c_a, x0);
     }
     if (ch + 1 < nch) {
-      consume(ch + 1, v_b, r_b, x1);
+      consume(v_b, x1);
       if (ch + 3 < nch) {
-        c_b = c_p; v_b = v_p; r_b = r_p;
-        if (ch + 4 < nch) fetch(ch + 4, c_p, v_p, r_p);
+        c_b = c_p; v_b = v_p;
+        if (ch + 4 < nch) fetch(ch + 4, c_p, v_p);
         issue(c_b, x1);
       }
     }
   }
+  for (int d = 1; d < S::kGroups; d <<= 1) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], d * LG, 64);
+  }
+  sink(0, g == 0, acc);
 }
 
 enum TileMap : int {
@@ -585,8 +563,7 @@ __global__ __launch_bounds__(64 * kCsrWaves) void k_spmm_csr(CsrArgs a) {
     return;
   }
   DirectSink<VEC, LG> sink{y, f_active};
-  walk_slots<VEC, LG, false>(a.indices + begin, a.values + begin, nullptr, a.X + f0, a.feat, kRowLog2W, end - begin,
-                             lane, f_active, sink);
+  walk_row<VEC, LG>(a.indices + begin, a.values + begin, a.X + f0, a.feat, end - begin, lane, f_active, sink);
 }
 
 // ---------------------------------------------------------------- long rows
@@ -649,8 +626,8 @@ __global__ __launch_bounds__(64 * kLongWaves) void k_spmm_long(LongArgs a) {
     const int first = wave * per_wave * S::kChunk;
     const int count = min(lp.len - first, per_wave * S::kChunk);
     if (count > 0)
-      walk_slots<VEC, LG, false>(a.cols + lp.slot0 + first, a.vals + lp.slot0 + first, nullptr, a.X + f0, a.feat,
-                                 kRowLog2W, count, lane, f_active, sink);
+      walk_row<VEC, LG>(a.cols + lp.slot0 + first, a.vals + lp.slot0 + first, a.X + f0, a.feat, count, lane,
+                        f_active, sink);
   }
   if (lane < LG) {  // the walk leaves a row's sum in the lanes of the first lane group
 #pragma unroll
@@ -711,8 +688,8 @@ __global__ __launch_bounds__(64 * kSegWaves) void k_long_segments(SegmentArgs a)
   const int first = wave * per_wave * S::kChunk;
   const int count = min(sg.len - first, per_wave * S::kChunk);
   if (count > 0)
-    walk_slots<VEC, LG, false>(a.cols + sg.slot0 + first, a.vals + sg.slot0 + first, nullptr, a.X + f0, a.feat,
-                               kRowLog2W, count, lane, f_active, sink);
+    walk_row<VEC, LG>(a.cols + sg.slot0 + first, a.vals + sg.slot0 + first, a.X + f0, a.feat, count, lane, f_active,
+                      sink);
   if (lane < LG) {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) share[wave][fl * VEC + e] = total[e];
