@@ -394,8 +394,9 @@ extern "C" sptir_status_t sptir_sddmm_plan_build(const sptir_csr_t* csr, int32_t
     const int64_t w_fit = std::max<int64_t>(1, (int64_t)(2.5 * 1024 * 1024) / (feat * 4));
     int64_t want = (n_cols + w_fit - 1) / w_fit;
     const int64_t by_piece = n_rows > 0 ? nnz / ((int64_t)n_rows * 4) : 0;
-    want = std::min(want, by_piece) / 8 * 8;
-    c = want >= 8 ? (int32_t)std::min<int64_t>(want, 1024) : 1;
+    // (to the nearest multiple of 8, as far as the pieces allow: measured, 7 wanted runs best with 8, 12 with 8)
+    want = std::min((want + 3) / 8 * 8, by_piece / 8 * 8);
+    c = (want >= 8 && n_cols > w_fit) ? (int32_t)std::min<int64_t>(want, 1024) : 1;
   }
   if (c > std::max(n_cols, 1)) c = std::max(n_cols, 1);
   if ((int64_t)n_rows * c > ((int64_t)1 << 36)) return SPTIR_ERR_OVERFLOW;
