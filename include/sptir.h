@@ -142,7 +142,10 @@ int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows);
  * fastest).  Builds hyb(c, k) for every c of c_candidates (host array;
  * n_candidates == 0 selects the paper's {1, 2, 4, 8, 16}), runs sptir_spmm
  * `reps` times after one warm-up on zero-filled scratch operands of width
- * `feat`, and returns the decomposition with the smallest mean time.
+ * `feat`, and returns the decomposition with the smallest mean time.  The
+ * launch plan of every candidate is sized for `feat` (feature sizes up to 64
+ * get smaller row blocks than sptir_hyb_build chooses, so that a launch still
+ * has enough wavefronts); the result serves any feat.
  *   max_bucket_log2  k for every candidate; negative selects sptir_default_bucket_log2
  *   best_c           receives the chosen c (may be NULL)
  *   ms_per_candidate host array [n_candidates] of mean milliseconds (may be NULL)

@@ -107,9 +107,10 @@ void current_allocator(sptir_alloc_fn* a, sptir_free_fn* f, void** ctx);
 void* default_alloc(size_t bytes, void* ctx, void* stream);
 void default_free(void* p, void* ctx);
 
-// sptir_hyb_build, optionally without the SpMM launch plan (for users of the canonical arrays alone)
+// sptir_hyb_build, optionally without the SpMM launch plan (for users of the canonical arrays alone), and with
+// the feature size the launch plan should suit (0: not known)
 sptir_status_t hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2, void* stream,
-                              sptir_hyb_t** out, bool with_spmm_plan);
+                              sptir_hyb_t** out, bool with_spmm_plan, int32_t feat_hint);
 
 // rb_order[launch][i] = the row block with the i-th longest chunk list of that launch (order.hip).  Works on
 // `stream`; *scratch_out is device memory the caller frees once the stream has drained.

@@ -59,7 +59,9 @@ def main():
         return e0.elapsed_time(e1) / args.reps
 
     def point(kind, c, feat, X, Y):
-        hyb = sptir.sptir_hyb_build(w.n_rows, w.n_cols, indptr, indices, values, c, w.max_bucket_log2)
+        # (through the search entry point with one candidate: its launch plan is sized for `feat`)
+        hyb, _, _ = sptir.sptir_hyb_search(w.n_rows, w.n_cols, indptr, indices, values, feat, c_candidates=(c,),
+                                           max_bucket_log2=w.max_bucket_log2, reps=1)
         info = sptir.sptir_hyb_info(hyb)
         ms = timed(lambda: sptir.sptir_spmm(hyb, X, Y))
         hyb.destroy()
