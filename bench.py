@@ -170,7 +170,8 @@ def main():
         bmin = bytes_min(w.nnz, w.n_rows, w.n_cols, feat)
         results[feat] = dict(wall_ms=wall_ms, event_ms=event_ms, gflops=flops / wall_ms / 1e6,
                              bmin_gbs=bmin / event_ms / 1e6, bmin=bmin,
-                             gather_gbs=(info["n_ell_slots"] + info["n_rem_nnz"]) * feat * 4.0 / event_ms / 1e6,
+                             # one row of X (feat * 4 bytes) is gathered per non-zero; bucket pads are not walked
+                             gather_gbs=w.nnz * feat * 4.0 / event_ms / 1e6,
                              Y=Y if feat == 128 else None)
         if feat == 256:
             del X, Y
@@ -186,7 +187,8 @@ def main():
                                "Y = A X per step" % w.nnz,
                    "n_rows": w.n_rows, "nnz": w.nnz, "feat": 128, "n_col_parts": w.n_col_parts,
                    "max_bucket_log2": w.max_bucket_log2, "stored_slots": info["n_ell_slots"] + info["n_rem_nnz"],
-                   "pad_slots": info["n_pad_slots"], "kernel_launches_per_step": info["n_phases"],
+                   "pad_slots": info["n_pad_slots"], "walked_slots": info["n_work_items"] * info["item_slots"],
+                   "kernel_launches_per_step": info["n_phases"],
                    "row_block": info["row_block"]},
         "hbm_gbs_min_model": round(head["bmin_gbs"], 1),
         "hbm_pct_of_peak": round(100.0 * head["bmin_gbs"] / HBM_PEAK_GBS, 2),
@@ -201,7 +203,7 @@ def main():
         "traffic": read_traffic("social_feat128"),
         "kernel": "k_spmm_hyb<4, 8, true, false>", "launches_per_step": info["n_phases"],
         "avg_launch_ms": round(per_launch_ms, 4), "algorithmic_bytes_per_launch": per_launch_bytes,
-        # the path is a cache-served gather, not an HBM stream: each stored slot pulls feat*4 bytes of X
+        # the path is a cache-served gather, not an HBM stream: each non-zero pulls feat*4 bytes of X
         # through the vector-memory return path, whose peak is 64 B/clk/CU
         "binding_roof": {"name": "vector-memory gather (L2 -> VGPR)", "achieved_gbs": round(head["gather_gbs"], 1),
                          "peak_gbs": GATHER_PEAK_GBS, "frac": round(head["gather_gbs"] / GATHER_PEAK_GBS, 4)},
