@@ -158,6 +158,27 @@ sptir_status_t sptir_hyb_search(const sptir_csr_t* csr, const int32_t* c_candida
                                 sptir_hyb_t** out, int32_t* best_c, float* ms_per_candidate);
 
 /*
+ * The launch plan that sptir_hyb_search (feat known) and sptir_spmm would choose for a matrix of these sizes:
+ * host arithmetic only, no device is touched.  stored_slots is what the decomposition stores (ELL slots with
+ * their pads plus remainder non-zeros; nnz is a fair stand-in).  Section 4.2.1 motivates column partitions by
+ * the cache hit rate of X; on this GPU that decides how many partitions one launch may sweep, see
+ * parts_per_launch.  X and Y are taken to be 16-byte aligned.
+ */
+typedef struct sptir_launch_plan {
+  int32_t row_block;         /* rows of Y one wavefront keeps in LDS */
+  int32_t parts_per_launch;  /* column partitions swept by one launch */
+  int32_t n_launches;        /* launches per sweep */
+  int32_t compact_stream;    /* 1: 8-byte records, 0: 12-byte records */
+  int32_t n_feature_tiles;   /* tiles of 32 (16 for feat <= 16) floats that Y is cut into */
+  int32_t tiles_per_sweep;   /* feature tiles one sweep over the launches covers */
+  int32_t n_sweeps;
+  int32_t reserved;
+} sptir_launch_plan_t;
+
+sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_slots, int32_t n_col_parts,
+                                 int32_t feat, sptir_launch_plan_t* out);
+
+/*
  * Y = A * X on the hyb decomposition (SpMM equation of Section 4.2.1; Y is
  * overwritten, rows without non-zeros become 0, as the init block of the
  * Appendix A script prescribes).

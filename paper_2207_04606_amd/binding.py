@@ -49,6 +49,12 @@ class _Info(ctypes.Structure):
                 ("n_long_rows", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
 
 
+class _LaunchPlan(ctypes.Structure):
+    _fields_ = [("row_block", ctypes.c_int32), ("parts_per_launch", ctypes.c_int32), ("n_launches", ctypes.c_int32),
+                ("compact_stream", ctypes.c_int32), ("n_feature_tiles", ctypes.c_int32),
+                ("tiles_per_sweep", ctypes.c_int32), ("n_sweeps", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
 class _PlanInfo(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32), ("n_col_parts", ctypes.c_int32),
                 ("part_width", ctypes.c_int32), ("nnz", ctypes.c_int64), ("n_runs", ctypes.c_int64),
@@ -73,7 +79,7 @@ EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_search"
                     "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_sddmm_plan_build", "sptir_sddmm",
                     "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_rgms_build", "sptir_rgms", "sptir_rgms_info",
                     "sptir_rgms_destroy", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
-                    "sptir_status_string", "sptir_last_hip_error")
+                    "sptir_launch_plan", "sptir_status_string", "sptir_last_hip_error")
 
 
 def load_library(path: str | None = None):
@@ -131,6 +137,9 @@ def load_library(path: str | None = None):
     lib.sptir_hyb_array.restype = ctypes.c_int
     lib.sptir_hyb_array.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p),
                                     ctypes.POINTER(ctypes.c_int64)]
+    lib.sptir_launch_plan.restype = ctypes.c_int
+    lib.sptir_launch_plan.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                      ctypes.POINTER(_LaunchPlan)]
     lib.sptir_status_string.restype = ctypes.c_char_p
     lib.sptir_status_string.argtypes = [ctypes.c_int]
     lib.sptir_last_hip_error.restype = ctypes.c_char_p
@@ -182,6 +191,15 @@ def sptir_status_string(status: int) -> str:
 
 def sptir_default_bucket_log2(nnz: int, n_rows: int) -> int:
     return int(load_library().sptir_default_bucket_log2(nnz, n_rows))
+
+
+def sptir_launch_plan(n_rows: int, n_cols: int, stored_slots: int, n_col_parts: int, feat: int) -> dict:
+    """The launch plan the library would choose for these sizes (host arithmetic only)."""
+    out = _LaunchPlan()
+    st = load_library().sptir_launch_plan(n_rows, n_cols, stored_slots, n_col_parts, feat, ctypes.byref(out))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_launch_plan")
+    return {name: int(getattr(out, name)) for name, _ in _LaunchPlan._fields_ if name != "reserved"}
 
 
 class Hyb:

@@ -131,3 +131,24 @@ int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows) {
 }
 
 }  // extern "C"
+
+extern "C" sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_slots, int32_t n_col_parts,
+                                            int32_t feat, sptir_launch_plan_t* out) {
+  if (!out || n_rows < 0 || n_cols < 0 || stored_slots < 0 || n_col_parts < 1 || feat < 1) return SPTIR_ERR_INVALID_ARG;
+  const int32_t w = (int32_t)(((int64_t)n_cols + n_col_parts - 1) / n_col_parts);
+  const sptir::LaunchShape ls = sptir::decide_launch_shape(n_rows, n_col_parts, w, stored_slots, feat);
+  int vec, lg;
+  sptir::lane_shape(feat, true, true, &vec, &lg);
+  const int tile = vec * lg;
+  sptir_launch_plan_t o;
+  o.row_block = 1 << ls.log2_row_block;
+  o.parts_per_launch = ls.parts_per_phase;
+  o.n_launches = ls.n_phases;
+  o.compact_stream = ls.compact;
+  o.n_feature_tiles = (feat + tile - 1) / tile;
+  o.tiles_per_sweep = sptir::tiles_per_sweep(o.n_feature_tiles, tile, n_rows, ls.n_phases);
+  o.n_sweeps = (o.n_feature_tiles + o.tiles_per_sweep - 1) / o.tiles_per_sweep;
+  o.reserved = 0;
+  *out = o;
+  return SPTIR_OK;
+}

@@ -645,6 +645,21 @@ int parts_per_phase_setting(int32_t c, int32_t w, int32_t n_rows, int64_t slots)
 }
 
 }  // namespace
+
+LaunchShape decide_launch_shape(int32_t n_rows, int32_t c, int32_t w, int64_t stored_slots, int32_t feat_hint) {
+  LaunchShape ls;
+  ls.parts_per_phase = parts_per_phase_setting(c, w, n_rows, stored_slots);
+  ls.log2_row_block = log2_row_block_setting(n_rows, feat_hint);
+  // the compact stream needs the columns of one launch to fit kCompactColBits and the row block 7 bits
+  const char* e = getenv("SPTIR_WIDE_STREAM");
+  const int64_t max_span = (int64_t)1 << kCompactColBits;
+  const bool compact = !(e && atoi(e) != 0) && w <= max_span && ls.log2_row_block <= kCompactMaxLog2RowBlock;
+  if (compact && (int64_t)ls.parts_per_phase * w > max_span) ls.parts_per_phase = (int32_t)(max_span / w);
+  ls.compact = compact ? 1 : 0;
+  ls.n_phases = (c + ls.parts_per_phase - 1) / ls.parts_per_phase;
+  return ls;
+}
+
 }  // namespace sptir
 
 using namespace sptir;
@@ -778,20 +793,12 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     // ---- launch shape of the SpMM: row blocks and phases
     CellShape cs;
     cs.c = s.c; cs.k = s.k; cs.nb = s.nb; cs.R = h->R;
-    cs.ppg = parts_per_phase_setting(s.c, s.w, s.n_rows, h->S + h->T);
-    cs.log2_rb = log2_row_block_setting(s.n_rows, feat_hint);
+    const LaunchShape ls = decide_launch_shape(s.n_rows, s.c, s.w, h->S + h->T, feat_hint);
+    cs.ppg = ls.parts_per_phase; cs.log2_rb = ls.log2_row_block; cs.n_phases = ls.n_phases;
+    h->compact_stream = ls.compact;
     cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
     if (!with_spmm_plan) cs.n_rb = 0;  // no row blocks, no cells, no chunks: only the canonical arrays are built
     h->spmm_plan = with_spmm_plan ? 1 : 0;
-    {
-      // the compact stream needs the columns of one launch to fit kCompactColBits and the row block 7 bits
-      const char* e = getenv("SPTIR_WIDE_STREAM");
-      const int64_t max_span = (int64_t)1 << kCompactColBits;
-      bool compact = !(e && atoi(e) != 0) && s.w <= max_span && cs.log2_rb <= kCompactMaxLog2RowBlock;
-      if (compact && (int64_t)cs.ppg * s.w > max_span) cs.ppg = (int32_t)(max_span / s.w);
-      h->compact_stream = compact ? 1 : 0;
-    }
-    cs.n_phases = (s.c + cs.ppg - 1) / cs.ppg;
     h->log2_row_block = cs.log2_rb; h->n_row_blocks = cs.n_rb;
     h->parts_per_phase = cs.ppg; h->n_phases = cs.n_phases;
     const int64_t n_groups = (int64_t)cs.n_phases * cs.n_rb;

@@ -741,26 +741,10 @@ bool plan_tiles(int64_t n_units, Geometry* g) {
 
 bool plan(int64_t n_units, int feat, const void* X, const void* Y, Geometry* g) {
   uintptr_t align = (uintptr_t)X | (uintptr_t)Y;
-  if (feat % 4 == 0 && (align & 15) == 0) { g->vec = 4; g->lg = feat <= 16 ? 4 : 8; }
-  else if (feat % 2 == 0 && (align & 7) == 0) { g->vec = 2; g->lg = 16; }
-  else { g->vec = 1; g->lg = 32; }
+  lane_shape(feat, (align & 15) == 0, (align & 7) == 0, &g->vec, &g->lg);
   int tf = g->vec * g->lg;
   g->n_tiles = (feat + tf - 1) / tf;
   return plan_tiles(n_units, g);
-}
-
-// Feature tiles per sweep over the launches of a call.  Every launch but the first reads back what the one
-// before it wrote to Y; that round trip stays inside the 256 MB memory-side cache only if the part of Y a sweep
-// touches is well below its size.  So a wide Y is produced in several sweeps, each over a group of feature tiles
-// (4 or 8, which still map whole XCDs to a tile).
-int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches) {
-  const char* e = std::getenv("SPTIR_SWEEP_MB");  // tuning knob, read at every call
-  const double limit_mb = e ? std::atof(e) : 160.0;
-  if (n_launches < 2 || n_tiles % 4 != 0) return n_tiles;
-  const double tile_mb = (double)n_rows * tile_floats * sizeof(float) / (1024.0 * 1024.0);
-  if (tile_mb * n_tiles <= limit_mb) return n_tiles;
-  if (n_tiles % 8 == 0 && tile_mb * 8 <= limit_mb) return 8;
-  return 4;
 }
 
 bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
@@ -792,6 +776,28 @@ void launch_hyb(const Geometry& g, size_t lds_bytes, hipStream_t stream, const S
 }
 
 }  // namespace
+
+// 8 lanes x 16 bytes (one 128-byte line of X per lane group) where size and alignment allow
+void lane_shape(int32_t feat, bool aligned16, bool aligned8, int* vec, int* lg) {
+  if (feat % 4 == 0 && aligned16) { *vec = 4; *lg = feat <= 16 ? 4 : 8; }
+  else if (feat % 2 == 0 && aligned8) { *vec = 2; *lg = 16; }
+  else { *vec = 1; *lg = 32; }
+}
+
+// Feature tiles per sweep over the launches of a call.  Every launch but the first reads back what the one
+// before it wrote to Y; that round trip stays inside the 256 MB memory-side cache only if the part of Y a sweep
+// touches is well below its size.  So a wide Y is produced in several sweeps, each over a group of feature tiles
+// (4 or 8, which still map whole XCDs to a tile).
+int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches) {
+  const char* e = std::getenv("SPTIR_SWEEP_MB");  // tuning knob, read at every call
+  const double limit_mb = e ? std::atof(e) : 160.0;
+  if (n_launches < 2 || n_tiles % 4 != 0) return n_tiles;
+  const double tile_mb = (double)n_rows * tile_floats * sizeof(float) / (1024.0 * 1024.0);
+  if (tile_mb * n_tiles <= limit_mb) return n_tiles;
+  if (n_tiles % 8 == 0 && tile_mb * 8 <= limit_mb) return 8;
+  return 4;
+}
+
 }  // namespace sptir
 
 using namespace sptir;

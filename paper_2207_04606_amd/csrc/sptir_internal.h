@@ -112,6 +112,20 @@ void default_free(void* p, void* ctx);
 sptir_status_t hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2, void* stream,
                               sptir_hyb_t** out, bool with_spmm_plan, int32_t feat_hint);
 
+// What the builder decides about the SpMM launches from the sizes alone (builder.hip; host code, no device access).
+struct LaunchShape {
+  int32_t log2_row_block;   // rows of Y per wavefront
+  int32_t parts_per_phase;  // column partitions per launch
+  int32_t n_phases;         // launches per sweep
+  int32_t compact;          // 1: 8-byte stream records
+};
+LaunchShape decide_launch_shape(int32_t n_rows, int32_t c, int32_t w, int64_t stored_slots, int32_t feat_hint);
+
+// Lane geometry sptir_spmm uses for `feat` when X and Y are 16-byte aligned, and the feature tiles one sweep over
+// the launches covers (spmm.hip; host code).
+void lane_shape(int32_t feat, bool aligned16, bool aligned8, int* vec, int* lg);
+int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches);
+
 // rb_order[launch][i] = the row block with the i-th longest chunk list of that launch (order.hip).  Works on
 // `stream`; *scratch_out is device memory the caller frees once the stream has drained.
 sptir_status_t order_row_blocks(const int64_t* rb_chunk_ptr, int32_t n_launches, int32_t n_rb, int32_t* rb_order,
