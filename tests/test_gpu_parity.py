@@ -386,6 +386,18 @@ def test_hyb_search_picks_a_candidate(gpu_lib):
         gpu_lib.sptir_hyb_search(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 32, c_candidates=(2, 0))
 
 
+@pytest.mark.parametrize("name,feat", [("small", 32), ("small", 128), ("medium", 64), ("medium", 256)])
+def test_launch_plan_query_matches_what_is_built(gpu_lib, name, feat):
+    """The host-only query announces the row blocks and launches that a search at the same feature size builds."""
+    w = workloads.make_config(name)
+    d = upload(w)
+    hyb, _, _ = gpu_lib.sptir_hyb_search(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, feat,
+                                         c_candidates=(w.n_col_parts,), max_bucket_log2=w.max_bucket_log2, reps=1)
+    info = gpu_lib.sptir_hyb_info(hyb)
+    plan = gpu_lib.sptir_launch_plan(w.n_rows, w.n_cols, info["n_ell_slots"] + info["n_rem_nnz"], w.n_col_parts, feat)
+    assert (plan["row_block"], plan["n_launches"]) == (info["row_block"], info["n_phases"])
+
+
 def test_spmm_and_sddmm_replay_in_a_hip_graph(gpu_lib):
     """sptir_spmm / sptir_sddmm only enqueue kernels, so a stream capture records them; every replay (with
     eager work and synchronisation in between, and new operand values) must match the eager result."""
