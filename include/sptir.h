@@ -100,10 +100,10 @@ typedef struct {
   int64_t n_rem_pieces;     /* M */
   int64_t n_rem_nnz;        /* T */
   int64_t n_work_items;     /* 64-slot chunks one sptir_spmm call walks (padding chunks included) */
-  int32_t item_slots;       /* stored slots per chunk */
+  int32_t item_slots;       /* slots per chunk */
   int32_t row_block;        /* rows of Y one wavefront accumulates on chip */
   int32_t n_phases;         /* chunk-list launches per sptir_spmm (groups of column partitions) */
-  int32_t n_long_rows;      /* rows with a piece of more than 2048 non-zeros: one more launch sums those */
+  int32_t n_long_rows;      /* rows with a piece of more than 2048 non-zeros: two more launches sum those */
   int64_t device_bytes;     /* device memory the handle owns */
 } sptir_hyb_info_t;
 

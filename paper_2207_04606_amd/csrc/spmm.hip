@@ -313,7 +313,7 @@ struct HybWalker {
 
   // parks quad q; m[i] receives the facts of its chunk i (wave-uniform), taken from the chunk's slot 0:
   // log2w | hand-over << 6 | no row << 7 (WIDE) or real | log2w code << 1 | hand-over << 4 (compact).
-  // (slot 0 of a chunk is a real slot, or the first of an idle octet, or the whole chunk is padding at the
+  // (slot 0 of a chunk is an entry, or a slot past the end of queue 0, or the whole chunk is padding at the
   //  end of a list, which chunk_is_padding() tells apart)
   __device__ __forceinline__ void park(int q, const Fetched& f, int (&m)[kChunksPerQuad]) const {
     int4* st = reinterpret_cast<int4*>(slot_of(q));
@@ -385,8 +385,8 @@ struct HybWalker {
       }
       if constexpr (SUB == 1 && UB == 8) return;  // this lane group walks the queue alone: the sum stays in registers
       // Any other shape meets the queue again in another lane group or step, so what has been summed of an
-      // unfinished row is handed over now.  Lane groups that share an octet may hold parts of the same
-      // row: they take turns.
+      // unfinished row is handed over now.  Lane groups that share the eight slots of a queue may hold
+      // parts of the same row: they take turns.
       constexpr int kTurns = UB < 8 ? 8 / UB : 1;
 #pragma unroll
       for (int turn = 0; turn < kTurns; ++turn)
