@@ -228,6 +228,7 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
 struct CellShape {
   int32_t c, k, nb;
   int32_t log2_rb, n_rb, ppg, n_phases;
+  int32_t long_len;  // pieces with more entries are set aside for the long-row launches
   int64_t R;
 };
 
@@ -261,7 +262,7 @@ __global__ void k_cell_bounds(CellShape cs, const int64_t* __restrict__ bucket_r
 // (the chunks of that bin's rows that are cut wide) and one queue cell, then one pad cell that rounds the
 // group's chunk count up to a multiple of kChunksPerQuad (the SpMM kernel fetches chunks four at a time).
 //
-// How the row pieces of a (group, partition) become chunks (pieces of at most kLongRowSlots entries; bucket
+// How the row pieces of a (group, partition) become chunks (pieces of at most long_len entries; bucket
 // rows and remainder pieces alike, each with its real entries only):
 //  * a piece is dealt whole to one of eight queues, one per lane group of the SpMM kernel, where its entries
 //    follow those of the piece before it without a gap; chunk t of the queue cell holds entries 8t .. 8t+7 of
@@ -301,7 +302,7 @@ __device__ __forceinline__ int deal_partition(const CellShape& cs, const int32_t
     const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
     for (int32_t q = ptr[0]; q < ptr[1]; ++q) {
       const int len = row_len[q];
-      if (len <= kLongRowSlots) to_deal += len;
+      if (len <= cs.long_len) to_deal += len;
     }
   }
   int load[8];
@@ -311,7 +312,7 @@ __device__ __forceinline__ int deal_partition(const CellShape& cs, const int32_t
     const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
     for (int32_t q = ptr[0]; q < ptr[1]; ++q) {
       const int len = row_len[q];
-      if (len > kLongRowSlots) { v.on_long(bin, q, len); continue; }
+      if (len > cs.long_len) { v.on_long(bin, q, len); continue; }
       const long long share = (to_deal + 7) >> 3;
       to_deal -= len;
       if (len > kChunkSlots && len > share) { v.on_wide(bin, q, len); continue; }
@@ -644,6 +645,21 @@ int parts_per_phase_setting(int32_t c, int32_t w, int32_t n_rows, int64_t slots)
   return (int)fit;
 }
 
+// A wavefront walks a chunk list alone, so the longest list bounds the launch from below.  A piece with more
+// entries than two average lists (at least 256, at most kLongRowSlots) leaves the lists for the long-row
+// launches, where a workgroup per 1024 entries sums it (measured on the 169,343-row graph with rows of up to
+// 13,000 entries: SpMM 0.134 -> 0.11 ms).
+//   SPTIR_LONG_LEN  overrides the threshold
+int32_t long_piece_setting(int64_t nnz, int64_t n_lists) {
+  const char* e = getenv("SPTIR_LONG_LEN");
+  long v = e ? atol(e) : 0;
+  if (v >= 1 && v <= kLongRowSlots) return (int32_t)v;
+  // (the long-row launches cost some 8 microseconds of their own: not worth it on a graph that is done in 10)
+  if (nnz < (1 << 19)) return kLongRowSlots;
+  const int64_t per_list = n_lists > 0 ? nnz / n_lists : 0;
+  return (int32_t)std::min<int64_t>(kLongRowSlots, std::max<int64_t>(256, 2 * per_list));
+}
+
 }  // namespace
 
 LaunchShape decide_launch_shape(int32_t n_rows, int32_t c, int32_t w, int64_t stored_slots, int32_t feat_hint) {
@@ -797,6 +813,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     cs.ppg = ls.parts_per_phase; cs.log2_rb = ls.log2_row_block; cs.n_phases = ls.n_phases;
     h->compact_stream = ls.compact;
     cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
+    cs.long_len = long_piece_setting(csr->nnz, (int64_t)cs.n_phases * cs.n_rb);
     if (!with_spmm_plan) cs.n_rb = 0;  // no row blocks, no cells, no chunks: only the canonical arrays are built
     h->spmm_plan = with_spmm_plan ? 1 : 0;
     h->log2_row_block = cs.log2_rb; h->n_row_blocks = cs.n_rb;
@@ -926,7 +943,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     if (n_long > 0) {
       // The long pieces arrive in no particular order: sort them by (row, partition) on the host, so that
       // one workgroup sums all pieces of a row in a fixed order.  There are few of them by construction
-      // (each holds more than kLongRowSlots non-zeros).
+      // (each holds more non-zeros than two average chunk lists).
       std::vector<LongPiece> lp((size_t)n_long);
       BUILD_HIP(hipMemcpyAsync(lp.data(), h->long_pieces, sizeof(LongPiece) * lp.size(), hipMemcpyDeviceToHost,
                                stream));
