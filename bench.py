@@ -30,6 +30,13 @@ def bytes_min(nnz, n_rows, n_cols, feat):
     return 8.0 * nnz + 4.0 * n_cols * feat + 4.0 * n_rows * feat
 
 
+def bytes_hyb(info, n_rows, n_cols, feat):
+    """What the decomposition as stored has to move at the least: every ELL slot (pads included) and row id,
+    every remainder non-zero and piece descriptor, X once, Y once."""
+    return (8.0 * info["n_ell_slots"] + 4.0 * info["n_ell_rows"] + 8.0 * info["n_rem_nnz"] + 12.0 * info["n_rem_pieces"]
+            + 4.0 * n_cols * feat + 4.0 * n_rows * feat)
+
+
 def time_spmm(sptir, torch, hyb, X, Y, steps, warmup):
     for _ in range(warmup):
         sptir.sptir_spmm(hyb, X, Y)
@@ -191,6 +198,8 @@ def main():
                    "kernel_launches_per_step": info["n_phases"],
                    "row_block": info["row_block"]},
         "hbm_gbs_min_model": round(head["bmin_gbs"], 1),
+        "hbm_gbs_hyb_model": round(bytes_hyb(info, w.n_rows, w.n_cols, 128) / head["event_ms"] / 1e6, 1),
+        "hbm_gbs_measured": None,
         "hbm_pct_of_peak": round(100.0 * head["bmin_gbs"] / HBM_PEAK_GBS, 2),
         "hyb_build_ms": round(build_ms, 3), "hyb_build_first_call_ms": round(build_first_ms, 3),
     }
@@ -208,6 +217,10 @@ def main():
         "binding_roof": {"name": "vector-memory gather (L2 -> VGPR)", "achieved_gbs": round(head["gather_gbs"], 1),
                          "peak_gbs": GATHER_PEAK_GBS, "frac": round(head["gather_gbs"] / GATHER_PEAK_GBS, 4)},
     }
+
+    if out["roofline"]["traffic"]:
+        # bytes that crossed the L2 boundary per second (rocprofv3 counters of the committed profile run)
+        out["hbm_gbs_measured"] = round(out["roofline"]["traffic"] / per_launch_ms / 1e6, 1)
 
     # ------------------------------------------------- CPU oracle beside it
     if not args.no_cpu:
