@@ -254,6 +254,13 @@ typedef struct {
   int64_t device_bytes;
 } sptir_sddmm_plan_info_t;
 
+/*
+ * The number of column partitions sptir_sddmm_plan_build chooses when it is passed n_col_parts == 0 (host
+ * arithmetic only): a multiple of 8 such that one partition's rows of Yt (width * feat * 4 bytes) fit an XCD's
+ * L2 and a (row, partition) piece still holds a few entries, or 1 (CSR order).  feat_hint 0 stands for 128.
+ */
+int32_t sptir_sddmm_default_col_parts(int32_t n_rows, int32_t n_cols, int64_t nnz, int32_t feat_hint);
+
 sptir_status_t sptir_sddmm_plan_build(const sptir_csr_t* csr, int32_t n_col_parts, int32_t feat_hint, void* stream,
                                       sptir_sddmm_plan_t** out);
 /* values, B_values: device [nnz] in CSR order (B_values may be values itself); X, Yt, feat as for sptir_sddmm_csr.

@@ -79,7 +79,7 @@ EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_search"
                     "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_sddmm_plan_build", "sptir_sddmm",
                     "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_rgms_build", "sptir_rgms", "sptir_rgms_info",
                     "sptir_rgms_destroy", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
-                    "sptir_launch_plan", "sptir_status_string", "sptir_last_hip_error")
+                    "sptir_launch_plan", "sptir_sddmm_default_col_parts", "sptir_status_string", "sptir_last_hip_error")
 
 
 def load_library(path: str | None = None):
@@ -137,6 +137,8 @@ def load_library(path: str | None = None):
     lib.sptir_hyb_array.restype = ctypes.c_int
     lib.sptir_hyb_array.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p),
                                     ctypes.POINTER(ctypes.c_int64)]
+    lib.sptir_sddmm_default_col_parts.restype = ctypes.c_int32
+    lib.sptir_sddmm_default_col_parts.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32]
     lib.sptir_launch_plan.restype = ctypes.c_int
     lib.sptir_launch_plan.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                       ctypes.POINTER(_LaunchPlan)]
@@ -191,6 +193,10 @@ def sptir_status_string(status: int) -> str:
 
 def sptir_default_bucket_log2(nnz: int, n_rows: int) -> int:
     return int(load_library().sptir_default_bucket_log2(nnz, n_rows))
+
+
+def sptir_sddmm_default_col_parts(n_rows: int, n_cols: int, nnz: int, feat_hint: int = 0) -> int:
+    return int(load_library().sptir_sddmm_default_col_parts(n_rows, n_cols, nnz, feat_hint))
 
 
 def sptir_launch_plan(n_rows: int, n_cols: int, stored_slots: int, n_col_parts: int, feat: int) -> dict:

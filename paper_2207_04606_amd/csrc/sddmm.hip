@@ -373,6 +373,20 @@ extern "C" sptir_status_t sptir_sddmm_plan_info(const sptir_sddmm_plan_t* p, spt
   return SPTIR_OK;
 }
 
+extern "C" int32_t sptir_sddmm_default_col_parts(int32_t n_rows, int32_t n_cols, int64_t nnz, int32_t feat_hint) {
+  // The rows of Yt of one partition should fit an XCD's L2 next to the rest of the traffic (2.5 of 4 MB); every
+  // (row, partition) piece re-reads its row of X, so a piece should hold a few entries; every XCD wants its
+  // own partitions, so c is a multiple of 8 - or 1, which leaves the entries in CSR order.
+  if (n_rows <= 0 || n_cols <= 0 || nnz <= 0) return 1;
+  const int64_t feat = feat_hint > 0 ? feat_hint : 128;
+  const int64_t w_fit = std::max<int64_t>(1, (int64_t)(2.5 * 1024 * 1024) / (feat * 4));
+  int64_t want = (n_cols + w_fit - 1) / w_fit;
+  const int64_t by_piece = nnz / ((int64_t)n_rows * 4);
+  // (to the nearest multiple of 8, as far as the pieces allow: measured, 7 wanted runs best with 8, 12 with 8)
+  want = std::min((want + 3) / 8 * 8, by_piece / 8 * 8);
+  return (want >= 8 && n_cols > w_fit) ? (int32_t)std::min<int64_t>(want, 1024) : 1;
+}
+
 extern "C" sptir_status_t sptir_sddmm_plan_build(const sptir_csr_t* csr, int32_t n_col_parts, int32_t feat_hint,
                                                  void* stream_, sptir_sddmm_plan_t** out) {
   if (!csr || !out || n_col_parts < 0 || feat_hint < 0) return SPTIR_ERR_INVALID_ARG;
@@ -385,19 +399,7 @@ extern "C" sptir_status_t sptir_sddmm_plan_build(const sptir_csr_t* csr, int32_t
   const int64_t nnz = csr->nnz;
 
   // ---- number of column partitions
-  int32_t c = n_col_parts;
-  if (c == 0) {
-    // The rows of Yt of one partition should fit an XCD's L2 next to the rest of the traffic (2.5 of 4 MB); every
-    // (row, partition) piece re-reads its row of X, so a piece should hold a few entries; every XCD wants its
-    // own partitions, so c is a multiple of 8 - or 1, which leaves the entries in CSR order.
-    const int64_t feat = feat_hint > 0 ? feat_hint : 128;
-    const int64_t w_fit = std::max<int64_t>(1, (int64_t)(2.5 * 1024 * 1024) / (feat * 4));
-    int64_t want = (n_cols + w_fit - 1) / w_fit;
-    const int64_t by_piece = n_rows > 0 ? nnz / ((int64_t)n_rows * 4) : 0;
-    // (to the nearest multiple of 8, as far as the pieces allow: measured, 7 wanted runs best with 8, 12 with 8)
-    want = std::min((want + 3) / 8 * 8, by_piece / 8 * 8);
-    c = (want >= 8 && n_cols > w_fit) ? (int32_t)std::min<int64_t>(want, 1024) : 1;
-  }
+  int32_t c = n_col_parts > 0 ? n_col_parts : sptir_sddmm_default_col_parts(n_rows, n_cols, nnz, feat_hint);
   if (c > std::max(n_cols, 1)) c = std::max(n_cols, 1);
   if ((int64_t)n_rows * c > ((int64_t)1 << 36)) return SPTIR_ERR_OVERFLOW;
 

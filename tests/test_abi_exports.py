@@ -44,3 +44,12 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.sptir_hyb_info(None, None) == 1
     assert lib.sptir_hyb_destroy(None) == 0
     assert lib.sptir_spmm(None, None, None, 4, None) == 1
+
+
+def test_header_is_plain_c():
+    """include/sptir.h is the boundary of a C ABI: a C99 compiler must accept it on its own."""
+    import subprocess
+    header = os.path.join(ROOT, "include", "sptir.h")
+    done = subprocess.run(["gcc", "-fsyntax-only", "-x", "c", "-std=c99", "-Wall", "-Werror", header],
+                          capture_output=True, text=True)
+    assert done.returncode == 0, done.stderr

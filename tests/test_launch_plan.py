@@ -85,3 +85,18 @@ def test_invalid_arguments():
         with pytest.raises(sptir.SptirError):
             sptir.sptir_launch_plan(*args)
     assert sptir.load_library().sptir_launch_plan(5, 5, 5, 1, 4, None) == 1
+
+
+def test_sddmm_partition_rule():
+    # one partition's rows of Yt should fit 2.5 MB: 232,965 x 512 B needs 46 partitions -> 48 (multiple of 8)
+    assert sptir.sptir_sddmm_default_col_parts(232965, 232965, 114615892, 128) == 48
+    assert sptir.sptir_sddmm_default_col_parts(232965, 232965, 114615892, 32) == 8     # 12 wanted: nearest is 8
+    assert sptir.sptir_sddmm_default_col_parts(232965, 232965, 114615892, 256) == 88
+    assert sptir.sptir_sddmm_default_col_parts(232965, 232965, 114615892, 0) == 48     # hint 0 stands for 128
+    assert sptir.sptir_sddmm_default_col_parts(132534, 132534, 39756333, 32) == 8      # 7 wanted
+    # 7 entries per row cannot be cut into pieces of 4: CSR order
+    assert sptir.sptir_sddmm_default_col_parts(169343, 169343, 1166243, 128) == 1
+    # Yt fits L2 whole
+    assert sptir.sptir_sddmm_default_col_parts(2708, 2708, 10556, 64) == 1
+    assert sptir.sptir_sddmm_default_col_parts(3000, 3000, 3000 * 400, 128) == 1
+    assert sptir.sptir_sddmm_default_col_parts(0, 5, 0, 128) == 1
