@@ -55,12 +55,22 @@ __device__ __forceinline__ int bin_of_length(int l, int k) {
 // Columns ascend strictly inside every row iff flags[2] == flags[3].
 __global__ void k_validate_rows(int32_t n_rows, int64_t nnz, const int32_t* __restrict__ indptr,
                                 const int32_t* __restrict__ indices, unsigned long long* flags) {
-  int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (r >= n_rows) return;
-  int64_t a = indptr[r], b = indptr[r + 1];
-  bool bad = (a < 0) || (b > nnz) || (a > b) || (r == 0 && a != 0) || (r == n_rows - 1 && b != nnz);
-  if (bad) { flags[0] = 1; return; }
-  if (a < b && a > 0 && indices[a] <= indices[a - 1]) atomicAdd(&flags[3], 1ull);
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  unsigned int legal_descents = 0;
+  bool bad = false;
+  for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_rows; r += stride) {
+    int64_t a = indptr[r], b = indptr[r + 1];
+    const bool bad_here = (a < 0) || (b > nnz) || (a > b) || (r == 0 && a != 0) || (r == n_rows - 1 && b != nnz);
+    bad |= bad_here;
+    legal_descents += !bad_here && a < b && a > 0 && indices[a] <= indices[a - 1];
+  }
+  // a grid-wide count through one address: one atomic per wavefront, a few thousand in all
+  for (int d = 32; d > 0; d >>= 1) legal_descents += __shfl_down(legal_descents, d, 64);
+  const unsigned long long any_bad = __ballot(bad);
+  if ((threadIdx.x & 63) == 0) {
+    if (legal_descents) atomicAdd(&flags[3], (unsigned long long)legal_descents);
+    if (any_bad) flags[0] = 1;
+  }
 }
 
 __global__ void k_validate_elems(int64_t nnz, int32_t n_cols, const int32_t* __restrict__ indices,
@@ -751,7 +761,8 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     unsigned long long flags[4] = {0, 0, 0, 0};
     BUILD_HIP(hipMemsetAsync(d_flags, 0, sizeof(flags), stream));
     if (s.n_rows > 0)
-      hipLaunchKernelGGL(k_validate_rows, dim3((s.n_rows + 255) / 256), dim3(256), 0, stream, s.n_rows, csr->nnz,
+      hipLaunchKernelGGL(k_validate_rows, dim3((unsigned)std::min<int64_t>(((int64_t)s.n_rows + 255) / 256, 4096)),
+                         dim3(256), 0, stream, s.n_rows, csr->nnz,
                          csr->indptr, csr->indices, d_flags);
     if (csr->nnz > 0)
       hipLaunchKernelGGL(k_validate_elems, dim3((unsigned)std::min<int64_t>((csr->nnz + 255) / 256, 4096)), dim3(256),

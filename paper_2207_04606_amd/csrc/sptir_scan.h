@@ -49,18 +49,31 @@ __device__ __forceinline__ T block_exclusive_scan(T v, T* wave_sums /* [kWaves] 
 }
 
 // One workgroup per sequence: data[seq*len .. +len) becomes its exclusive
-// prefix, totals[seq] its sum.
+// prefix, totals[seq] its sum.  A thread scans kScanPerThread consecutive
+// elements itself, so a long sequence costs few workgroup-wide steps.
+constexpr int kScanPerThread = 8;
+
 template <typename T>
 __global__ __launch_bounds__(kBuildBlock) void k_scan_sequences(T* data, int32_t len, T* totals) {
   __shared__ T wave_sums[kWaves];
   T* seq = data + (int64_t)blockIdx.x * len;
   T carry = 0;
-  for (int32_t base = 0; base < len; base += kBuildBlock) {
-    int32_t e = base + (int32_t)threadIdx.x;
-    T v = (e < len) ? seq[e] : (T)0;
+  for (int64_t base = 0; base < len; base += (int64_t)kBuildBlock * kScanPerThread) {
+    const int64_t e0 = base + (int64_t)threadIdx.x * kScanPerThread;
+    T v[kScanPerThread];
+    T mine = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; ++i) {
+      v[i] = (e0 + i < len) ? seq[e0 + i] : (T)0;
+      mine += v[i];
+    }
     T tot;
-    T ex = block_exclusive_scan(v, wave_sums, &tot);
-    if (e < len) seq[e] = carry + ex;
+    T before = carry + block_exclusive_scan(mine, wave_sums, &tot);
+#pragma unroll
+    for (int i = 0; i < kScanPerThread; ++i) {
+      if (e0 + i < len) seq[e0 + i] = before;
+      before += v[i];
+    }
     carry += tot;
   }
   if (threadIdx.x == 0) totals[blockIdx.x] = carry;
