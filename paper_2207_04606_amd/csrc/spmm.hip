@@ -4,9 +4,10 @@
 // Mapping (gfx950, wave64).  The feature dimension is cut into tiles of
 // LG*VEC floats (32 floats = one 128-byte line of X by default).  A wavefront
 // owns one (row block, feature tile): it keeps that tile of the row block's Y
-// rows (32 to 128 rows, 4 to 16 KB) in its own piece of LDS, walks every chunk of
-// the row block's list (all column partitions of the launch, all ELL buckets,
-// the remainder) and finally writes the Y tile with plain coalesced stores.
+// rows (64 rows, 8 KB, unless the graph is small) in its own piece of LDS, walks
+// every chunk of the row block's list (all column partitions of the launch, the
+// rows of all ELL buckets and the remainder, real entries only) and finally
+// writes the Y tile with plain coalesced stores.
 // Nothing is shared between wavefronts: no atomics, no barriers, no zero fill
 // of Y, and rows without non-zeros come out as 0 (the init block of the SpMM
 // script in appendix A).
