@@ -224,17 +224,15 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
 
 // ------------------------------------------------------- SpMM work-item list
 // The SpMM kernel keeps the Y rows of one row block (row_block consecutive
-// rows) in LDS, and walks the stored slots in chunks of kChunkSlots.  A chunk
-// descriptor never crosses a row-block boundary.  Rows ascend inside every
-// bucket and inside every partition's remainder, hence the rows of a bin that
-// fall into row block j are one contiguous run; a "cell" is that run for one
-// (phase, row block, partition, bin).  Cells are numbered
-//   ((phase * n_rb + rb) * ppg + p_local) * nb + bin,   p = phase * ppg + p_local,
-// and their chunks are laid out in that order, so the chunks of one (phase, row
-// block) are contiguous and sweep the column partitions in ascending order.
-// Rows of width < 64 are packed 64/width to a chunk.  A wider row (and a
-// remainder piece) takes ceil(len / 64) chunks for its len real entries:
-// chunks that would hold nothing but pads are never emitted.
+// rows) in LDS and walks the real entries of the block's row pieces in chunks
+// of kChunkSlots; a chunk never crosses a row-block boundary.  Rows ascend
+// inside every bucket and inside every partition's remainder, hence the rows
+// of a bin that fall into row block j are one contiguous run of row_ids; a
+// "cell" holds the chunks that one (phase, row block, partition) contributes
+// from one bin, or from its queues.  The cells of a (phase, row block) group
+// are numbered partition by partition (see cells_per_group below) and their
+// chunks are laid out in that order, so the chunks of a group are contiguous
+// and sweep the column partitions in ascending order.
 struct CellShape {
   int32_t c, k, nb;
   int32_t log2_rb, n_rb, ppg, n_phases;
