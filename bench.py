@@ -54,6 +54,26 @@ def time_spmm(sptir, torch, hyb, X, Y, steps, warmup):
     return wall_ms, event_ms
 
 
+def time_graph_replay(sptir, torch, hyb, X, Y, calls_per_graph, replays):
+    """sptir_spmm only enqueues kernels, so a stream capture records it: per-call time of replaying a graph of
+    `calls_per_graph` calls (what a launch-bound small graph costs without the per-launch host work)."""
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(calls_per_graph):
+                sptir.sptir_spmm(hyb, X, Y, stream=side)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(replays):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / (replays * calls_per_graph)
+
+
 def time_cold(sptir, torch, hyb, X, Y, reps, scratch):
     """Per-step time with the caches flushed before every step (outside the timed region)."""
     times = []
@@ -332,7 +352,9 @@ def main():
             bm = bytes_min(wc.nnz, wc.n_rows, wc.n_cols, wc.feat)
             others.append({"config": name, "nnz": wc.nnz, "feat": wc.feat,
                            "gflops": round(2.0 * wc.nnz * wc.feat / wall_ms / 1e6, 1),
-                           "ms_per_step": round(wall_ms, 4), "cold_ms_per_step": round(cold, 4),
+                           "ms_per_step": round(wall_ms, 4),
+                           "graph_replay_ms_per_step": round(time_graph_replay(sptir, torch, hc, X, Y, 10, 20), 4),
+                           "cold_ms_per_step": round(cold, 4),
                            "hbm_gbs_min_model_cold": round(bm / cold / 1e6, 1), "hyb_build_ms": round(b_ms, 3)})
             hc.destroy()
         out["other_configs"] = others
