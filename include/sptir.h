@@ -203,6 +203,22 @@ sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_
 sptir_status_t sptir_spmm(const sptir_hyb_t* hyb, const float* X, float* Y, int32_t feat, void* stream);
 
 /*
+ * sptir_spmm for callers that cannot allocate device memory or let a library do so: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * Y.  The one buffer sptir_spmm needs beyond its inputs and outputs, the partial sums of rows with very long
+ * pieces (sptir_hyb_info_t.n_long_rows > 0; one float per long-row segment and feature), does not come from the
+ * handle here but from a static device array of SPTIR_NOALLOC_SCRATCH_BYTES inside the library, which every
+ * GPU the library runs on holds until the process ends.  The call allocates and frees nothing, on any path.
+ * Needing more than that array holds (the product of the segment count and feat exceeds it) is refused with
+ * SPTIR_ERR_UNSUPPORTED before anything is enqueued, and sptir_last_hip_error() then says by how much.
+ * Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU race (also calls on
+ * different handles and different streams); calls ordered by a stream or by the caller are fine.  Nothing in
+ * the array has to start at zero: each call overwrites every element it later reads.
+ */
+#define SPTIR_NOALLOC_SCRATCH_BYTES (8u * 1024u * 1024u)
+sptir_status_t sptir_spmm_noalloc(const sptir_hyb_t* hyb, const float* X, float* Y, int32_t feat, void* stream);
+
+/*
  * Y = A * X straight from CSR, one pass, no decomposition: the "no-hyb"
  * variant that Section 4.2.1 compares hyb against.  Same argument meaning as
  * sptir_spmm; the CSR arrays are device pointers and are assumed valid (they
@@ -339,7 +355,8 @@ sptir_status_t sptir_hyb_array(const sptir_hyb_t* hyb, int32_t which, const void
 /* Static description of a status code. */
 const char* sptir_status_string(sptir_status_t status);
 
-/* Text of the last HIP error this thread saw inside the library ("" if none). */
+/* Text of the last HIP error this thread saw inside the library ("" if none); also the reason of the last
+ * SPTIR_ERR_UNSUPPORTED that sptir_spmm_noalloc returned on this thread. */
 const char* sptir_last_hip_error(void);
 
 #ifdef __cplusplus

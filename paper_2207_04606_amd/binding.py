@@ -28,7 +28,7 @@ class SptirError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         detail = sptir_status_string(status)
-        if status == 5:
+        if status == 5 or (status == 6 and where == "sptir_spmm_noalloc"):
             detail += ": " + _lib.sptir_last_hip_error().decode()
         super().__init__(f"{where}: {detail} (status {status})")
 
@@ -76,6 +76,7 @@ _lib = None
 _hip = None
 
 EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
+                    "sptir_spmm_noalloc",
                     "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_sddmm_plan_build", "sptir_sddmm",
                     "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_rgms_build", "sptir_rgms", "sptir_rgms_info",
                     "sptir_rgms_destroy", "sptir_hyb_destroy", "sptir_hyb_info", "sptir_hyb_array",
@@ -100,6 +101,8 @@ def load_library(path: str | None = None):
     lib.sptir_default_bucket_log2.argtypes = [ctypes.c_int64, ctypes.c_int32]
     lib.sptir_spmm.restype = ctypes.c_int
     lib.sptir_spmm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+    lib.sptir_spmm_noalloc.restype = ctypes.c_int
+    lib.sptir_spmm_noalloc.argtypes = lib.sptir_spmm.argtypes
     lib.sptir_sddmm_csr.restype = ctypes.c_int
     lib.sptir_sddmm_csr.argtypes = [ctypes.POINTER(_Csr), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.c_int32, ctypes.c_void_p]
@@ -305,6 +308,17 @@ def sptir_spmm(hyb: Hyb, X, Y, stream=None) -> None:
                                    _stream_ptr(stream))
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_spmm")
+
+
+def sptir_spmm_noalloc(hyb: Hyb, X, Y, stream=None) -> None:
+    """sptir_spmm through the entry point that allocates nothing (static scratch inside the library)."""
+    _dev(X, torch.float32, "X"); _dev(Y, torch.float32, "Y")
+    if X.dim() != 2 or Y.dim() != 2 or X.shape[1] != Y.shape[1]:
+        raise ValueError("X and Y must be 2-D with the same number of columns")
+    st = load_library().sptir_spmm_noalloc(hyb.handle, X.data_ptr() or None, Y.data_ptr() or None, X.shape[1],
+                                           _stream_ptr(stream))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_spmm_noalloc")
 
 
 def sptir_spmm_csr(n_rows: int, n_cols: int, indptr, indices, values, X, Y, stream=None) -> None:

@@ -42,6 +42,8 @@ sptir_status_t note_hip_error(hipError_t e, const char* what) {
   return SPTIR_ERR_HIP;
 }
 
+void note_error_text(const char* text) { snprintf(g_hip_error, sizeof(g_hip_error), "%s", text); }
+
 }  // namespace sptir
 
 extern "C" {

@@ -25,7 +25,9 @@
 // partitions in ascending order, and long-row matrices get one launch per
 // partition, which keeps the X slice in flight L2-sized (the purpose section
 // 4.2.1 gives for column partitioning).
+#include <cstdio>
 #include <cstdlib>
+#include <mutex>
 #include "sptir_internal.h"
 
 namespace sptir {
@@ -803,7 +805,10 @@ int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches
 
 using namespace sptir;
 
-extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat, void* stream_) {
+// The work of sptir_spmm; long_partial is where the segment sums of rows with very long pieces meet
+// ([n_long_segs][feat] floats; only read when such rows exist and feat <= kLongPartialFeat).
+static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat, void* stream_,
+                                  float* long_partial) {
   if (!h || feat < 1) return SPTIR_ERR_INVALID_ARG;
   if ((h->n_cols > 0 && !X) || (h->n_rows > 0 && !Y)) return SPTIR_ERR_INVALID_ARG;
   const size_t x_bytes = sizeof(float) * (size_t)h->n_cols * feat, y_bytes = sizeof(float) * (size_t)h->n_rows * feat;
@@ -847,7 +852,7 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
     Geometry gl;
     if (!plan(h->n_long_segs, feat, X, Y, &gl)) return SPTIR_ERR_OVERFLOW;
     SegmentArgs sa;
-    sa.segs = h->long_segs; sa.cols = h->cols; sa.vals = h->vals; sa.X = X; sa.partial = h->long_partial;
+    sa.segs = h->long_segs; sa.cols = h->cols; sa.vals = h->vals; sa.X = X; sa.partial = long_partial;
     sa.n_segs = h->n_long_segs; sa.feat = feat;
     sa.n_tiles = gl.n_tiles; sa.map_mode = gl.map_mode; sa.map_param = gl.map_param;
     dim3 grid((unsigned)gl.grid), block(64 * kSegWaves);
@@ -857,7 +862,7 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
     else hipLaunchKernelGGL((k_long_segments<1, 32>), grid, block, 0, stream, sa);
     const int64_t n_out = (int64_t)h->n_long_rows * feat;
     hipLaunchKernelGGL(k_long_reduce, dim3((unsigned)((n_out + 255) / 256)), dim3(256), 0, stream, h->long_rows,
-                       h->long_seg_ptr, h->long_partial, Y, h->n_long_rows, feat);
+                       h->long_seg_ptr, long_partial, Y, h->n_long_rows, feat);
   } else if (h->n_long_rows > 0) {
     Geometry gl;
     if (!plan(h->n_long_rows, feat, X, Y, &gl)) return SPTIR_ERR_OVERFLOW;
@@ -874,6 +879,58 @@ extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float
   }
   SPTIR_HIP(hipGetLastError());
   return SPTIR_OK;
+}
+
+extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat, void* stream_) {
+  return spmm_on_hyb(h, X, Y, feat, stream_, h ? h->long_partial : nullptr);
+}
+
+// ---------------------------------------------------------------- sptir_spmm_noalloc
+// The segment sums of long rows in memory that belongs to the loaded code object instead of the handle: every
+// GPU the library runs on holds its own copy of this array until the process ends.
+static constexpr size_t kStaticScratchFloats = SPTIR_NOALLOC_SCRATCH_BYTES / sizeof(float);
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+float* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, once asked for
+
+// `scratch` itself is only a host-side stand-in for the symbol: what kernels are given is this address.
+sptir_status_t scratch_of_current_device(float** out) {
+  int dev = -1;
+  SPTIR_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SPTIR_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    SPTIR_HIP(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    if (!p) return SPTIR_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return SPTIR_OK;
+}
+}  // namespace
+
+extern "C" sptir_status_t sptir_spmm_noalloc(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat,
+                                             void* stream_) {
+  if (!h || feat < 1) return SPTIR_ERR_INVALID_ARG;
+  float* partial = nullptr;
+  if (h->n_long_rows > 0 && feat <= kLongPartialFeat) {
+    if ((size_t)h->n_long_segs * (size_t)feat > kStaticScratchFloats) {
+      char msg[256];
+      snprintf(msg, sizeof(msg),
+               "sptir_spmm_noalloc: %lld long-row segments x %d features = %zu bytes of partial sums exceed the "
+               "static scratch of %zu bytes; use sptir_spmm",
+               (long long)h->n_long_segs, (int)feat, (size_t)h->n_long_segs * feat * sizeof(float),
+               (size_t)SPTIR_NOALLOC_SCRATCH_BYTES);
+      note_error_text(msg);
+      return SPTIR_ERR_UNSUPPORTED;
+    }
+    const sptir_status_t st = scratch_of_current_device(&partial);
+    if (st != SPTIR_OK) return st;
+  }
+  return spmm_on_hyb(h, X, Y, feat, stream_, partial);
 }
 
 extern "C" sptir_status_t sptir_spmm_csr(const sptir_csr_t* csr, const float* X, float* Y, int32_t feat,

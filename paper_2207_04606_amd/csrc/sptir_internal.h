@@ -135,6 +135,9 @@ sptir_status_t order_row_blocks(const int64_t* rb_chunk_ptr, int32_t n_launches,
 // records a failed HIP call for sptir_last_hip_error(); returns SPTIR_ERR_HIP
 sptir_status_t note_hip_error(hipError_t e, const char* what);
 
+// text for sptir_last_hip_error() where a refusal needs more than its status code
+void note_error_text(const char* text);
+
 #define SPTIR_HIP(call)                                                   \
   do {                                                                    \
     hipError_t e_ = (call);                                               \
