@@ -99,11 +99,17 @@ typedef struct {
   int64_t n_pad_slots;      /* S + T - nnz */
   int64_t n_rem_pieces;     /* M */
   int64_t n_rem_nnz;        /* T */
-  int64_t n_work_items;     /* 64-slot chunks one sptir_spmm call walks (padding chunks included) */
+  int64_t n_work_items;     /* 64-slot chunks of the chunk lists one sptir_spmm call walks (padding chunks included) */
   int32_t item_slots;       /* slots per chunk */
   int32_t row_block;        /* rows of Y one wavefront accumulates on chip */
-  int32_t n_phases;         /* chunk-list launches per sptir_spmm (groups of column partitions) */
-  int32_t n_long_rows;      /* rows with a piece of more than 2048 non-zeros: two more launches sum those */
+  int32_t n_phases;         /* chunk-list launches per sweep when rounds == 0 (groups of column partitions) */
+  int32_t rounds;           /* 1: every chunk list sweeps all column partitions and the lists run in rounds of as many
+                               row blocks as the GPU holds at once (Y is written once); 0: one launch per group of
+                               partitions, each adding to the Y of the one before */
+  int64_t n_heavy_pieces;   /* row pieces with more than heavy_len real entries: summed by a launch of their own */
+  int64_t n_heavy_items;    /* their 64-slot chunks */
+  int32_t heavy_len;
+  int32_t n_heavy_lists;    /* wavefronts of that launch per feature tile */
   int64_t device_bytes;     /* device memory the handle owns */
 } sptir_hyb_info_t;
 
@@ -133,6 +139,33 @@ sptir_status_t sptir_set_allocator(sptir_alloc_fn alloc, sptir_free_fn free_, vo
  */
 sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
                                void* stream, sptir_hyb_t** out);
+
+/*
+ * sptir_hyb_build with the choices spelled out that it otherwise makes from the sizes.  A zeroed struct (only
+ * struct_size set) asks for the defaults; none of these fields changes the canonical arrays or, beyond float
+ * rounding, the result of sptir_spmm.
+ */
+typedef struct {
+  int32_t struct_size;        /* sizeof(sptir_build_options_t) */
+  int32_t feat_hint;          /* feature size sptir_spmm will mostly run at (sizes the row blocks); 0: unknown */
+  int32_t row_block;          /* rows of Y per wavefront: a power of two in 8..256; 0: chosen */
+  int32_t parts_per_launch;   /* column partitions one chunk list sweeps; 0: chosen (n_col_parts when rounds) */
+  int32_t rounds;             /* 0: chosen; 1: rounds (see sptir_hyb_info_t.rounds); 2: one launch per group of partitions */
+  int32_t wide_stream;        /* 1: always 12-byte stream records */
+  int32_t heavy_len;          /* row pieces with more real entries are summed by the heavy-piece launch; 0: chosen */
+  int32_t sweep_kb;           /* rounds == 2 only: kilobytes of Y one sweep over the launches may touch; 0: 163840 */
+  int32_t release_canonical;  /* 1: free ELL_COL, ELL_VAL, REM_COL and REM_VAL once the SpMM stream is packed
+                                 (sptir_hyb_array then reports SPTIR_ERR_UNSUPPORTED for them) */
+  int32_t no_spmm_plan;       /* 1: canonical arrays only; sptir_spmm refuses the handle */
+  int32_t light_piece_len;    /* mean real length of the row pieces of at most 64 entries, if the caller knows it
+                                 (sptir_hyb_build takes it from its histogram); 0: unknown, taken to be short.
+                                 Rounds are chosen when it is below 16: Y round trips then cost more than the
+                                 wavefronts of a round lose by drifting apart */
+} sptir_build_options_t;
+
+sptir_status_t sptir_hyb_build_ex(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
+                                  const sptir_build_options_t* options /* NULL: defaults */, void* stream,
+                                  sptir_hyb_t** out);
 
 /* The paper's rule of thumb for k (Section 4.2.1): ceil(log2(nnz / n_rows)), clamped to [0, 30]. */
 int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows);
@@ -166,17 +199,18 @@ sptir_status_t sptir_hyb_search(const sptir_csr_t* csr, const int32_t* c_candida
  */
 typedef struct sptir_launch_plan {
   int32_t row_block;         /* rows of Y one wavefront keeps in LDS */
-  int32_t parts_per_launch;  /* column partitions swept by one launch */
-  int32_t n_launches;        /* launches per sweep */
+  int32_t parts_per_launch;  /* column partitions one chunk list sweeps */
+  int32_t n_launches;        /* chunk-list launches per sweep when rounds == 0 */
   int32_t compact_stream;    /* 1: 8-byte records, 0: 12-byte records */
   int32_t n_feature_tiles;   /* tiles of 32 (16 for feat <= 16) floats that Y is cut into */
   int32_t tiles_per_sweep;   /* feature tiles one sweep over the launches covers */
   int32_t n_sweeps;
-  int32_t reserved;
+  int32_t rounds;            /* 1: the chunk lists run in rounds and Y is written once */
 } sptir_launch_plan_t;
 
 sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_slots, int32_t n_col_parts,
-                                 int32_t feat, sptir_launch_plan_t* out);
+                                 int32_t feat, const sptir_build_options_t* options /* NULL: defaults */,
+                                 sptir_launch_plan_t* out);
 
 /*
  * Y = A * X on the hyb decomposition (SpMM equation of Section 4.2.1; Y is
@@ -185,18 +219,19 @@ sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_
  *   X  device, [n_cols, feat] row-major float32, read only
  *   Y  device, [n_rows, feat] row-major float32, must not overlap X
  *   feat >= 1
- * Only enqueues work on `stream` (no synchronisation, no allocation): one
- * launch per group of column partitions (sptir_hyb_info_t.n_phases), each
- * adding to what the earlier ones left in Y (a Y wider than the memory-side
- * cache is produced in several such sweeps, each over a group of feature
- * columns), plus two small ones for rows with very long pieces
- * (sptir_hyb_info_t.n_long_rows > 0).  The partial sums of those rows pass
- * through scratch memory that the handle owns: calls on one handle that has
- * long rows must not overlap in time.  No atomics are used and every sum has a fixed order, so two calls
- * with the same handle and X give bit-identical Y.  The order differs from
- * CSR order (sums are regrouped by partition and bucket), so Y matches a CSR
- * product only up to float rounding.  A pad slot multiplies X by +0.0f: X must
- * be finite.
+ * Only enqueues work on `stream` (no synchronisation, no allocation).  The
+ * chunk lists run in rounds (sptir_hyb_info_t.rounds: a launch per as many row
+ * blocks as the GPU holds wavefronts, Y written once) or as one launch per group
+ * of column partitions (n_phases launches, each adding to what the earlier ones
+ * left in Y; a Y wider than the memory-side cache is then produced in several
+ * such sweeps, each over a group of feature columns).  Heavy row pieces
+ * (n_heavy_pieces > 0) take two more launches per 128 features: their partial
+ * sums pass through scratch memory that the handle owns, so calls on one handle
+ * that has heavy pieces must not overlap in time.  No atomics are used and every
+ * sum has a fixed order, so two calls with the same handle and X on the same GPU
+ * give bit-identical Y.  The order differs from CSR order (sums are regrouped by
+ * partition and bucket), so Y matches a CSR product only up to float rounding.  A
+ * pad slot multiplies X by +0.0f: X must be finite.
  * Errors: INVALID_ARG, OVERFLOW (feat so large that the launch grid exceeds
  * 2^31 workgroups), HIP.
  */
@@ -205,14 +240,14 @@ sptir_status_t sptir_spmm(const sptir_hyb_t* hyb, const float* X, float* Y, int3
 /*
  * sptir_spmm for callers that cannot allocate device memory or let a library do so: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
- * Y.  The one buffer sptir_spmm needs beyond its inputs and outputs, the partial sums of rows with very long
- * pieces (sptir_hyb_info_t.n_long_rows > 0; one float per long-row segment and feature), does not come from the
- * handle here but from a static device array of SPTIR_NOALLOC_SCRATCH_BYTES inside the library, which every
- * GPU the library runs on holds until the process ends.  The call allocates and frees nothing, on any path.
- * Needing more than that array holds (the product of the segment count and feat exceeds it) is refused with
- * SPTIR_ERR_UNSUPPORTED before anything is enqueued, and sptir_last_hip_error() then says by how much.
- * Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU race (also calls on
- * different handles and different streams); calls ordered by a stream or by the caller are fine.  Nothing in
+ * Y.  The one buffer sptir_spmm needs beyond its inputs and outputs, the partial sums of heavy row pieces
+ * (sptir_hyb_info_t.n_heavy_pieces > 0; 128 floats for every heavy piece and every heavy list), does not come
+ * from the handle here but from a static device array of SPTIR_NOALLOC_SCRATCH_BYTES inside the library, which
+ * every GPU the library runs on holds until the process ends.  The call allocates and frees nothing, on any path.
+ * A matrix whose partial sums do not fit ((n_heavy_pieces + n_heavy_lists) * 512 bytes exceed the array) is
+ * refused with SPTIR_ERR_UNSUPPORTED before anything is enqueued, and sptir_last_hip_error() then says by how
+ * much.  Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU race (also calls
+ * on different handles and different streams); calls ordered by a stream or by the caller are fine.  Nothing in
  * the array has to start at zero: each call overwrites every element it later reads.
  */
 #define SPTIR_NOALLOC_SCRATCH_BYTES (8u * 1024u * 1024u)

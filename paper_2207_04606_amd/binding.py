@@ -45,14 +45,36 @@ class _Info(ctypes.Structure):
                 ("n_ell_slots", ctypes.c_int64), ("n_pad_slots", ctypes.c_int64),
                 ("n_rem_pieces", ctypes.c_int64), ("n_rem_nnz", ctypes.c_int64),
                 ("n_work_items", ctypes.c_int64), ("item_slots", ctypes.c_int32),
-                ("row_block", ctypes.c_int32), ("n_phases", ctypes.c_int32),
-                ("n_long_rows", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
+                ("row_block", ctypes.c_int32), ("n_phases", ctypes.c_int32), ("rounds", ctypes.c_int32),
+                ("n_heavy_pieces", ctypes.c_int64), ("n_heavy_items", ctypes.c_int64),
+                ("heavy_len", ctypes.c_int32), ("n_heavy_lists", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
+
+
+class _BuildOptions(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_int32), ("feat_hint", ctypes.c_int32), ("row_block", ctypes.c_int32),
+                ("parts_per_launch", ctypes.c_int32), ("rounds", ctypes.c_int32), ("wide_stream", ctypes.c_int32),
+                ("heavy_len", ctypes.c_int32), ("sweep_kb", ctypes.c_int32), ("release_canonical", ctypes.c_int32),
+                ("no_spmm_plan", ctypes.c_int32), ("light_piece_len", ctypes.c_int32)]
+
+
+def _options(options):
+    """dict of sptir_build_options_t fields -> the struct (None stays None: the library's defaults)."""
+    if not options:
+        return None
+    o = _BuildOptions()
+    o.struct_size = ctypes.sizeof(_BuildOptions)
+    names = {name for name, _ in _BuildOptions._fields_} - {"struct_size"}
+    for key, value in options.items():
+        if key not in names:
+            raise KeyError(f"unknown build option {key!r}")
+        setattr(o, key, int(value))
+    return o
 
 
 class _LaunchPlan(ctypes.Structure):
     _fields_ = [("row_block", ctypes.c_int32), ("parts_per_launch", ctypes.c_int32), ("n_launches", ctypes.c_int32),
                 ("compact_stream", ctypes.c_int32), ("n_feature_tiles", ctypes.c_int32),
-                ("tiles_per_sweep", ctypes.c_int32), ("n_sweeps", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("tiles_per_sweep", ctypes.c_int32), ("n_sweeps", ctypes.c_int32), ("rounds", ctypes.c_int32)]
 
 
 class _PlanInfo(ctypes.Structure):
@@ -75,7 +97,7 @@ _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 _lib = None
 _hip = None
 
-EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
+EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_build_ex", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
                     "sptir_spmm_noalloc",
                     "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_sddmm_plan_build", "sptir_sddmm",
                     "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_rgms_build", "sptir_rgms", "sptir_rgms_info",
@@ -97,6 +119,9 @@ def load_library(path: str | None = None):
     lib.sptir_hyb_build.restype = ctypes.c_int
     lib.sptir_hyb_build.argtypes = [ctypes.POINTER(_Csr), ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
                                     ctypes.POINTER(ctypes.c_void_p)]
+    lib.sptir_hyb_build_ex.restype = ctypes.c_int
+    lib.sptir_hyb_build_ex.argtypes = [ctypes.POINTER(_Csr), ctypes.c_int32, ctypes.c_int32,
+                                       ctypes.POINTER(_BuildOptions), ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
     lib.sptir_default_bucket_log2.restype = ctypes.c_int32
     lib.sptir_default_bucket_log2.argtypes = [ctypes.c_int64, ctypes.c_int32]
     lib.sptir_spmm.restype = ctypes.c_int
@@ -144,7 +169,7 @@ def load_library(path: str | None = None):
     lib.sptir_sddmm_default_col_parts.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32]
     lib.sptir_launch_plan.restype = ctypes.c_int
     lib.sptir_launch_plan.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
-                                      ctypes.POINTER(_LaunchPlan)]
+                                      ctypes.POINTER(_BuildOptions), ctypes.POINTER(_LaunchPlan)]
     lib.sptir_status_string.restype = ctypes.c_char_p
     lib.sptir_status_string.argtypes = [ctypes.c_int]
     lib.sptir_last_hip_error.restype = ctypes.c_char_p
@@ -202,20 +227,24 @@ def sptir_sddmm_default_col_parts(n_rows: int, n_cols: int, nnz: int, feat_hint:
     return int(load_library().sptir_sddmm_default_col_parts(n_rows, n_cols, nnz, feat_hint))
 
 
-def sptir_launch_plan(n_rows: int, n_cols: int, stored_slots: int, n_col_parts: int, feat: int) -> dict:
+def sptir_launch_plan(n_rows: int, n_cols: int, stored_slots: int, n_col_parts: int, feat: int,
+                      options: dict | None = None) -> dict:
     """The launch plan the library would choose for these sizes (host arithmetic only)."""
     out = _LaunchPlan()
-    st = load_library().sptir_launch_plan(n_rows, n_cols, stored_slots, n_col_parts, feat, ctypes.byref(out))
+    opt = _options(options)
+    st = load_library().sptir_launch_plan(n_rows, n_cols, stored_slots, n_col_parts, feat,
+                                          ctypes.byref(opt) if opt is not None else None, ctypes.byref(out))
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_launch_plan")
-    return {name: int(getattr(out, name)) for name, _ in _LaunchPlan._fields_ if name != "reserved"}
+    return {name: int(getattr(out, name)) for name, _ in _LaunchPlan._fields_}
 
 
 class Hyb:
     """Owner of a sptir_hyb_t handle."""
 
-    def __init__(self, handle):
+    def __init__(self, handle, n_rows=None, n_cols=None):
         self._h = ctypes.c_void_p(handle)
+        self.n_rows, self.n_cols = n_rows, n_cols   # kept here so that sptir_spmm need not ask per call
 
     @property
     def handle(self):
@@ -243,7 +272,21 @@ def sptir_hyb_build(n_rows: int, n_cols: int, indptr, indices, values, n_col_par
     st = lib.sptir_hyb_build(ctypes.byref(csr), n_col_parts, max_bucket_log2, _stream_ptr(stream), ctypes.byref(out))
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_hyb_build")
-    return Hyb(out.value)
+    return Hyb(out.value, n_rows, n_cols)
+
+
+def sptir_hyb_build_ex(n_rows: int, n_cols: int, indptr, indices, values, n_col_parts: int,
+                       max_bucket_log2: int, options: dict | None = None, stream=None) -> Hyb:
+    """sptir_hyb_build with a dict of sptir_build_options_t fields."""
+    lib = load_library()
+    csr = _csr_struct(n_rows, n_cols, indptr, indices, values)
+    out = ctypes.c_void_p(None)
+    opt = _options(options)
+    st = lib.sptir_hyb_build_ex(ctypes.byref(csr), n_col_parts, max_bucket_log2,
+                                ctypes.byref(opt) if opt is not None else None, _stream_ptr(stream), ctypes.byref(out))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_hyb_build_ex")
+    return Hyb(out.value, n_rows, n_cols)
 
 
 def sptir_hyb_search(n_rows: int, n_cols: int, indptr, indices, values, feat: int, c_candidates=(),
@@ -261,7 +304,7 @@ def sptir_hyb_search(n_rows: int, n_cols: int, indptr, indices, values, feat: in
                               _stream_ptr(stream), ctypes.byref(out), ctypes.byref(best_c), ms if n else None)
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_hyb_search")
-    return Hyb(out.value), int(best_c.value), [float(ms[i]) for i in range(n)]
+    return Hyb(out.value, n_rows, n_cols), int(best_c.value), [float(ms[i]) for i in range(n)]
 
 
 def sptir_hyb_destroy(hyb: Hyb) -> None:
@@ -301,8 +344,7 @@ def sptir_spmm(hyb: Hyb, X, Y, stream=None) -> None:
     _dev(X, torch.float32, "X"); _dev(Y, torch.float32, "Y")
     if X.dim() != 2 or Y.dim() != 2 or X.shape[1] != Y.shape[1]:
         raise ValueError("X and Y must be 2-D with the same number of columns")
-    info = sptir_hyb_info(hyb)
-    if X.shape[0] != info["n_cols"] or Y.shape[0] != info["n_rows"]:
+    if X.shape[0] != hyb.n_cols or Y.shape[0] != hyb.n_rows:
         raise ValueError("X / Y row counts do not match the matrix")
     st = load_library().sptir_spmm(hyb.handle, X.data_ptr() or None, Y.data_ptr() or None, X.shape[1],
                                    _stream_ptr(stream))
@@ -315,6 +357,8 @@ def sptir_spmm_noalloc(hyb: Hyb, X, Y, stream=None) -> None:
     _dev(X, torch.float32, "X"); _dev(Y, torch.float32, "Y")
     if X.dim() != 2 or Y.dim() != 2 or X.shape[1] != Y.shape[1]:
         raise ValueError("X and Y must be 2-D with the same number of columns")
+    if X.shape[0] != hyb.n_cols or Y.shape[0] != hyb.n_rows:
+        raise ValueError("X / Y row counts do not match the matrix")
     st = load_library().sptir_spmm_noalloc(hyb.handle, X.data_ptr() or None, Y.data_ptr() or None, X.shape[1],
                                            _stream_ptr(stream))
     if st != SPTIR_OK:

@@ -1,5 +1,6 @@
 // Handle management, allocator hook and status strings of the C ABI.
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <mutex>
@@ -61,9 +62,10 @@ sptir_status_t sptir_hyb_destroy(sptir_hyb_t* h) {
   if (!h) return SPTIR_OK;
   void* ptrs[] = {h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_part_ptr, h->rem_ptr,
                   h->row_ids, h->row_len, h->cols, h->vals, h->stream, h->rb_chunk_ptr, h->rb_order,
-                  h->long_rows, h->long_piece_ptr, h->long_pieces, h->long_seg_ptr, h->long_segs, h->long_partial};
+                  h->hlist_first_slot, h->row_slot_ptr, h->row_slots, h->partial};
   for (void* p : ptrs)
     if (p) h->free_(p, h->alloc_ctx);
+  free(h->hseg_list);
   delete h;
   return SPTIR_OK;
 }
@@ -81,7 +83,9 @@ sptir_status_t sptir_hyb_info(const sptir_hyb_t* h, sptir_hyb_info_t* out) {
   o.n_rem_pieces = h->M; o.n_rem_nnz = h->T;
   o.n_work_items = h->n_chunks; o.item_slots = sptir::kChunkSlots; o.row_block = 1 << h->log2_row_block;
   o.n_phases = h->n_phases;
-  o.n_long_rows = h->n_long_rows;
+  o.rounds = h->rounds;
+  o.n_heavy_pieces = h->n_heavy; o.n_heavy_items = h->n_heavy_chunks;
+  o.heavy_len = h->heavy_len; o.n_heavy_lists = h->n_heavy_lists;
   o.device_bytes = (int64_t)h->device_bytes;
   *out = o;
   return SPTIR_OK;
@@ -104,6 +108,9 @@ sptir_status_t sptir_hyb_array(const sptir_hyb_t* h, int32_t which, const void**
     case SPTIR_HYB_REM_VAL: p = h->vals + h->S; n = h->T; break;
     default: return SPTIR_ERR_INVALID_ARG;
   }
+  if (h->canonical_released && (which == SPTIR_HYB_ELL_COL || which == SPTIR_HYB_ELL_VAL ||
+                                which == SPTIR_HYB_REM_COL || which == SPTIR_HYB_REM_VAL))
+    return SPTIR_ERR_UNSUPPORTED;
   *dev_ptr = n ? p : nullptr;
   *n_elems = n;
   return SPTIR_OK;
@@ -135,10 +142,13 @@ int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows) {
 }  // extern "C"
 
 extern "C" sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_slots, int32_t n_col_parts,
-                                            int32_t feat, sptir_launch_plan_t* out) {
+                                            int32_t feat, const sptir_build_options_t* options,
+                                            sptir_launch_plan_t* out) {
   if (!out || n_rows < 0 || n_cols < 0 || stored_slots < 0 || n_col_parts < 1 || feat < 1) return SPTIR_ERR_INVALID_ARG;
   const int32_t w = (int32_t)(((int64_t)n_cols + n_col_parts - 1) / n_col_parts);
-  const sptir::LaunchShape ls = sptir::decide_launch_shape(n_rows, n_col_parts, w, stored_slots, feat);
+  sptir_build_options_t opt = sptir::complete_options(options);
+  if (opt.feat_hint == 0) opt.feat_hint = feat;
+  const sptir::LaunchShape ls = sptir::decide_launch_shape(n_rows, n_cols, n_col_parts, w, stored_slots, opt);
   int vec, lg;
   sptir::lane_shape(feat, true, true, &vec, &lg);
   const int tile = vec * lg;
@@ -148,9 +158,11 @@ extern "C" sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int6
   o.n_launches = ls.n_phases;
   o.compact_stream = ls.compact;
   o.n_feature_tiles = (feat + tile - 1) / tile;
-  o.tiles_per_sweep = sptir::tiles_per_sweep(o.n_feature_tiles, tile, n_rows, ls.n_phases);
+  o.tiles_per_sweep = ls.rounds ? o.n_feature_tiles
+                                : sptir::tiles_per_sweep(o.n_feature_tiles, tile, n_rows, ls.n_phases,
+                                                         opt.sweep_kb > 0 ? opt.sweep_kb : 160 * 1024);
   o.n_sweeps = (o.n_feature_tiles + o.tiles_per_sweep - 1) / o.tiles_per_sweep;
-  o.reserved = 0;
+  o.rounds = ls.rounds;
   *out = o;
   return SPTIR_OK;
 }

@@ -136,6 +136,7 @@ struct ScatterArgs {
   float* vals;
   int64_t* rem_ptr;
   int32_t* row_len;  // [R+M] real (unpadded) length of every ELL row and remainder piece
+  int32_t* piece_of; // [c][n_rows] position in row_ids of the piece of (row, partition), -1 where the piece is empty
   int64_t R, S, M, T;
 };
 
@@ -189,6 +190,7 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
   // Lanes without a piece stay alive with width 0: the wide copies below need all 64 lanes.
   int width = 0;
   int64_t dst = 0;
+  int32_t where = -1;  // position of this piece in row_ids
   if (bin >= 0) {
     int before = 0;
     for (int wv = 0; wv < wave; ++wv) before += wave_cnt[wv][bin];
@@ -196,19 +198,22 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
     if (!is_rem) {
       int64_t b = (int64_t)p * (s.k + 1) + bin;
       width = 1 << bin;
-      a.row_ids[a.bucket_row_ptr[b] + q] = r;
-      a.row_len[a.bucket_row_ptr[b] + q] = l;
+      where = (int32_t)(a.bucket_row_ptr[b] + q);
+      a.row_ids[where] = r;
+      a.row_len[where] = l;
       dst = a.bucket_slot_ptr[b] + q * width;
     } else {
       int64_t m = (int64_t)a.rem_part_ptr[p] + q;
       int64_t t0 = a.rem_nnz_base[p] + a.rem_nnz[(int64_t)p * s.NB + rb] + nnz_before;
-      a.row_ids[a.R + m] = r;
-      a.row_len[a.R + m] = l;
+      where = (int32_t)(a.R + m);
+      a.row_ids[where] = r;
+      a.row_len[where] = l;
       a.rem_ptr[m] = t0;
       width = l;
       dst = a.S + t0;
     }
   }
+  if (a.piece_of && r < s.n_rows) a.piece_of[(int64_t)p * s.n_rows + r] = where;
   // short pieces are copied by their own lane, long ones by the whole wave
   constexpr int kOwnLaneMax = 4;
   if (width > 0 && width <= kOwnLaneMax) copy_piece(a, lo, l, width, dst, 0, 1);
@@ -236,7 +241,7 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
 struct CellShape {
   int32_t c, k, nb;
   int32_t log2_rb, n_rb, ppg, n_phases;
-  int32_t long_len;  // pieces with more entries are set aside for the long-row launches
+  int32_t long_len;  // pieces with more real entries are not in the lists (heavy pieces)
   int64_t R;
 };
 
@@ -296,7 +301,7 @@ constexpr uint32_t kChunkIsQueue = 1u << 14;
 __device__ __forceinline__ int chunks_of_length(int len) { return (len + kChunkSlots - 1) / kChunkSlots; }
 
 // Walks the row pieces of partition p in row block rb and tells the visitor what becomes of each:
-//   v.on_long(bin, q, len)                 set aside for the long-row launch
+//   (pieces of more than cs.long_len entries are not part of the lists: the heavy-piece launch sums them)
 //   v.on_wide(bin, q, len)                 cut into 64-entry chunks
 //   v.on_queued(bin, q, len, g, start)     entries start .. start + len - 1 of queue g
 //   v.on_dealt(load, chunks)               at the end: entries per queue, chunks of the queue cell
@@ -320,7 +325,7 @@ __device__ __forceinline__ int deal_partition(const CellShape& cs, const int32_t
     const int32_t* ptr = bin_rb_ptr + ((int64_t)p * cs.nb + bin) * per_bin + rb;
     for (int32_t q = ptr[0]; q < ptr[1]; ++q) {
       const int len = row_len[q];
-      if (len > cs.long_len) { v.on_long(bin, q, len); continue; }
+      if (len > cs.long_len) continue;
       const long long share = (to_deal + 7) >> 3;
       to_deal -= len;
       if (len > kChunkSlots && len > share) { v.on_wide(bin, q, len); continue; }
@@ -344,16 +349,13 @@ __device__ __forceinline__ int deal_partition(const CellShape& cs, const int32_t
 // One thread per (group, partition of its phase): chunk counts of that partition's cells.
 struct CountVisitor {
   long long* cell;  // the partition's nb + 1 counts
-  unsigned long long* n_long;
-  __device__ void on_long(int, int32_t, int) { atomicAdd(n_long, 1ull); }
   __device__ void on_wide(int bin, int32_t, int len) { cell[bin] += chunks_of_length(len); }
   __device__ void on_queued(int, int32_t, int, int, int) {}
   __device__ void on_dealt(const int (&)[8], int) {}
 };
 
 __global__ void k_part_chunk_counts(CellShape cs, int64_t n_parts, const int32_t* __restrict__ bin_rb_ptr,
-                                    const int32_t* __restrict__ row_len, long long* cell_chunks,
-                                    unsigned long long* n_long) {
+                                    const int32_t* __restrict__ row_len, long long* cell_chunks) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= n_parts) return;
   const int64_t grp = t / cs.ppg;
@@ -363,7 +365,7 @@ __global__ void k_part_chunk_counts(CellShape cs, int64_t n_parts, const int32_t
   long long* cell = cell_chunks + grp * cells_per_group(cs) + (int64_t)p_local * cells_per_part(cs);
   for (int i = 0; i <= cs.nb; ++i) cell[i] = 0;
   if (p >= cs.c) return;  // a partition past the last one
-  CountVisitor v{cell, n_long};
+  CountVisitor v{cell};
   cell[cs.nb] = deal_partition(cs, bin_rb_ptr, row_len, p, rb, v);
 }
 
@@ -453,8 +455,6 @@ struct FillVisitor {
   int64_t S;
   Chunk* chunks;
   PiecePlace* place;
-  LongPiece* long_pieces;
-  unsigned long long* long_cursor;
   int wide_bin;                 // bin whose wide rows are being written, and the next free chunk of its cell
   int64_t wide_it;
 
@@ -465,11 +465,6 @@ struct FillVisitor {
       return bucket_slot_ptr[b] + (((int64_t)q - bucket_row_ptr[b]) << bin);
     }
     return S + rem_ptr[q - cs.R];
-  }
-  __device__ void on_long(int bin, int32_t q, int len) {  // listed in no particular order
-    LongPiece lp;
-    lp.slot0 = slot_of(bin, q); lp.row = row_ids[q]; lp.len = len; lp.q = q; lp.pad_ = 0;
-    long_pieces[atomicAdd(long_cursor, 1ull)] = lp;
   }
   __device__ void on_wide(int bin, int32_t q, int len) {
     if (bin != wide_bin) { wide_bin = bin; wide_it = cell_first(bin); }
@@ -511,8 +506,7 @@ __global__ void k_part_fill_chunks(CellShape cs, StreamShape ss, int64_t n_parts
                                    const int32_t* __restrict__ row_len, const int32_t* __restrict__ row_ids,
                                    const int64_t* __restrict__ bucket_row_ptr,
                                    const int64_t* __restrict__ bucket_slot_ptr, const int64_t* __restrict__ rem_ptr,
-                                   int64_t S, Chunk* chunks, PiecePlace* place, int64_t* rb_chunk_ptr,
-                                   LongPiece* long_pieces, unsigned long long* long_cursor) {
+                                   int64_t S, Chunk* chunks, PiecePlace* place, int64_t* rb_chunk_ptr) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= n_parts) return;
   const int64_t grp = t / cs.ppg;
@@ -524,7 +518,7 @@ __global__ void k_part_fill_chunks(CellShape cs, StreamShape ss, int64_t n_parts
   if (p_local == 0) rb_chunk_ptr[(int64_t)phase * cs.n_rb + rb] = group_first;
   if (p >= cs.c) return;
   FillVisitor v{cs, ss, p, group_first + cell[0], cell, cell[0], row_ids, bucket_row_ptr, bucket_slot_ptr, rem_ptr, S,
-                chunks, place, long_pieces, long_cursor, -1, 0};
+                chunks, place, -1, 0};
   deal_partition(cs, bin_rb_ptr, row_len, p, rb, v);
 }
 
@@ -559,7 +553,7 @@ __global__ __launch_bounds__(256) void k_pack_pieces(int64_t n_pieces, StreamSha
 
 // One wavefront per chunk of a wide row (and per padding chunk of a group); reads the canonical arrays
 // through the descriptor.  Queue chunks are written by k_pack_pieces and k_part_fill_chunks.
-__global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, StreamShape ss,
+__global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, int64_t first_heavy, StreamShape ss,
                                                      const Chunk* __restrict__ chunks,
                                                      const int32_t* __restrict__ row_ids,
                                                      const int32_t* __restrict__ cols,
@@ -583,7 +577,8 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, StreamSha
   const float val = vals[src];
   const int local_row = rid & ((1 << ss.log2_rb) - 1);
   if (ss.compact) {
-    const uint32_t col_rel = (uint32_t)(col - (col / ss.phase_width) * ss.phase_width);
+    // (the chunks of heavy pieces, from first_heavy on, hold absolute columns: a heavy list may cross partitions)
+    const uint32_t col_rel = q >= first_heavy ? (uint32_t)col : (uint32_t)(col - (col / ss.phase_width) * ss.phase_width);
     put_slot(ss, q, lane,
              (int32_t)(col_rel | ((uint32_t)local_row << kCompactColBits) | ((uint32_t)real << 27) |
                        ((uint32_t)(lw > 6 ? 7 : lw) << 28) | ((uint32_t)hand_over << 31)),
@@ -591,6 +586,131 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, StreamSha
   } else {
     put_slot(ss, q, lane, col, real ? __float_as_int(val) : 0,
              real ? (local_row | (lw << 16) | (hand_over << 22)) : -1);
+  }
+}
+
+// ------------------------------------------------------------ heavy pieces
+// A piece of more than heavy_len real entries is "heavy".  Exclusive prefixes over the pieces in the order of
+// row_ids (buckets in bucket order, then the remainder: partition-major):
+//   unit_before[q]   heavy pieces before piece q
+//   hchunk_before[q] 64-slot chunks of heavy pieces before piece q
+// Both arrays have one element more than there are pieces, so that after the scan the last one is the total.
+__global__ void k_heavy_counts(int64_t n_pieces, const int32_t* __restrict__ row_len, int32_t heavy_len,
+                               int32_t* unit_before, int32_t* hchunk_before) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q > n_pieces) return;
+  const int len = q < n_pieces ? row_len[q] : 0;
+  const bool heavy = len > heavy_len;
+  unit_before[q] = heavy ? 1 : 0;
+  hchunk_before[q] = heavy ? chunks_of_length(len) : 0;
+}
+
+constexpr int kScanSeq = 4096;  // elements per sequence of the device-wide scan
+
+// dst[i] = src[at[i]]
+__global__ void k_pick(int32_t n, const int64_t* __restrict__ at, const int32_t* __restrict__ src, int32_t* dst) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[at[i]];
+}
+
+// data[i] += seq_base[i / kScanSeq]: the last step of the device-wide exclusive scan
+__global__ void k_add_seq_base(int64_t n, int32_t* data, const int32_t* __restrict__ seq_base) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) data[i] += seq_base[i / kScanSeq];
+}
+
+// first slot of piece q in the fused (cols, vals) arrays
+__device__ __forceinline__ int64_t piece_slot0(int64_t q, int64_t B, int32_t k, int64_t R, int64_t S,
+                                               const int64_t* __restrict__ bucket_row_ptr,
+                                               const int64_t* __restrict__ bucket_slot_ptr,
+                                               const int64_t* __restrict__ rem_ptr) {
+  if (q >= R) return S + rem_ptr[q - R];
+  int64_t lo = 0, hi = B;  // last bucket b with bucket_row_ptr[b] <= q
+  while (hi - lo > 1) {
+    const int64_t mid = lo + ((hi - lo) >> 1);
+    if (bucket_row_ptr[mid] <= q) lo = mid; else hi = mid;
+  }
+  const int bin = (int)(lo % (k + 1));
+  return bucket_slot_ptr[lo] + ((q - bucket_row_ptr[lo]) << bin);
+}
+
+// One thread per piece: a heavy piece writes the descriptors of its chunks (the stream is packed from them).
+__global__ void k_heavy_chunks(int64_t n_pieces, const int32_t* __restrict__ row_len,
+                               const int32_t* __restrict__ unit_before, const int32_t* __restrict__ hchunk_before,
+                               int64_t B, int32_t k, int64_t R, int64_t S,
+                               const int64_t* __restrict__ bucket_row_ptr,
+                               const int64_t* __restrict__ bucket_slot_ptr, const int64_t* __restrict__ rem_ptr,
+                               Chunk* heavy_chunks) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= n_pieces || unit_before[q + 1] == unit_before[q]) return;
+  const int len = row_len[q];
+  const int64_t slot0 = piece_slot0(q, B, k, R, S, bucket_row_ptr, bucket_slot_ptr, rem_ptr);
+  Chunk* out = heavy_chunks + hchunk_before[q];
+  for (int off = 0; off < len; off += kChunkSlots) {
+    Chunk ck;
+    ck.slot0 = slot0 + off; ck.row0 = (int32_t)q;
+    const int count = len - off < kChunkSlots ? len - off : kChunkSlots;
+    ck.meta = (uint32_t)kRowLog2W | ((uint32_t)count << 6) | (off + kChunkSlots >= len ? (1u << 13) : 0u);
+    *out++ = ck;
+  }
+}
+
+// Heavy list w covers heavy chunks [w*L, (w+1)*L).  A wavefront writes a partial-sum row at every piece end and
+// one more where its list ends, so its first write goes to row (pieces that end before chunk w*L) + w.
+__global__ void k_heavy_list_slots(int32_t n_lists, int64_t n_pieces, const int32_t* __restrict__ unit_before,
+                                   const int32_t* __restrict__ hchunk_before, int32_t* hlist_first_slot) {
+  const int w = blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= n_lists) return;
+  const int64_t x = (int64_t)w * kHeavyListChunks;
+  // pieces q with hchunk_before[q + 1] <= x end before chunk x: find the first q with hchunk_before[q + 1] > x
+  int64_t lo = 0, hi = n_pieces;
+  while (lo < hi) {
+    const int64_t mid = lo + ((hi - lo) >> 1);
+    if ((int64_t)hchunk_before[mid + 1] <= x) lo = mid + 1; else hi = mid;
+  }
+  // (light pieces before that q add no chunks, so they never end the run early; heavy pieces before it: unit_before)
+  hlist_first_slot[w] = unit_before[lo] + w;
+}
+
+// The partial-sum rows of a heavy piece whose chunks are [f0, f1) and that has `u` heavy pieces before it:
+// rows u + w for every heavy list w that holds one of its chunks (see k_heavy_list_slots).
+__device__ __forceinline__ void piece_slots(int u, int f0, int f1, int* first, int* count) {
+  const int w0 = f0 / kHeavyListChunks, w1 = (f1 - 1) / kHeavyListChunks;
+  *first = u + w0;
+  *count = w1 - w0 + 1;
+}
+
+// One thread per row: how many partial-sum rows the heavy pieces of the row have (row_slot_ptr before its scan)
+__global__ void k_row_slot_counts(int32_t n_rows, int32_t c, const int32_t* __restrict__ piece_of,
+                                  const int32_t* __restrict__ unit_before, const int32_t* __restrict__ hchunk_before,
+                                  int32_t* row_slot_ptr) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r > n_rows) return;
+  int n = 0;
+  if (r < n_rows) {
+    for (int p = 0; p < c; ++p) {
+      const int32_t q = piece_of[(int64_t)p * n_rows + r];
+      if (q < 0 || unit_before[q + 1] == unit_before[q]) continue;
+      int first, count;
+      piece_slots(unit_before[q], hchunk_before[q], hchunk_before[q + 1], &first, &count);
+      n += count;
+    }
+  }
+  row_slot_ptr[r] = n;
+}
+
+__global__ void k_row_slot_fill(int32_t n_rows, int32_t c, const int32_t* __restrict__ piece_of,
+                                const int32_t* __restrict__ unit_before, const int32_t* __restrict__ hchunk_before,
+                                const int32_t* __restrict__ row_slot_ptr, int32_t* row_slots) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_rows) return;
+  int32_t* out = row_slots + row_slot_ptr[r];
+  for (int p = 0; p < c; ++p) {
+    const int32_t q = piece_of[(int64_t)p * n_rows + r];
+    if (q < 0 || unit_before[q + 1] == unit_before[q]) continue;
+    int first, count;
+    piece_slots(unit_before[q], hchunk_before[q], hchunk_before[q + 1], &first, &count);
+    for (int i = 0; i < count; ++i) *out++ = first + i;
   }
 }
 
@@ -605,23 +725,36 @@ struct Blob {  // bump allocator over one device allocation
   }
 };
 
-// Tuning knobs (environment, read when a hyb object is built):
-//   SPTIR_ROW_BLOCK        rows of Y one wavefront keeps in LDS (power of two, 8..256)
-//   SPTIR_PARTS_PER_PHASE  column partitions swept per SpMM launch (default: chosen from the sizes)
-//   SPTIR_WIDE_STREAM      non-zero: always write the 12-byte stream records
-int log2_row_block_setting(int32_t n_rows, int32_t feat_hint) {
-  const char* e = getenv("SPTIR_ROW_BLOCK");
-  long v = e ? atol(e) : 0;
+// Exclusive scan of data[0 .. n) in place on `stream`; data must have room for n rounded up to whole sequences
+// (the tail is zeroed here), seq_base for one int per sequence plus one.
+sptir_status_t device_exclusive_scan(int32_t* data, int64_t n, int32_t* seq_base, hipStream_t stream) {
+  if (n <= 0) return SPTIR_OK;
+  const int64_t n_seq = (n + kScanSeq - 1) / kScanSeq;
+  if (n_seq * kScanSeq > n)
+    SPTIR_HIP(hipMemsetAsync(data + n, 0, sizeof(int32_t) * (size_t)(n_seq * kScanSeq - n), stream));
+  hipLaunchKernelGGL(k_scan_sequences<int32_t>, dim3((unsigned)n_seq), dim3(kBuildBlock), 0, stream, data,
+                     (int32_t)kScanSeq, seq_base);
+  hipLaunchKernelGGL(k_scan_sequences<int32_t>, dim3(1), dim3(kBuildBlock), 0, stream, seq_base, (int32_t)n_seq,
+                     seq_base + n_seq);
+  hipLaunchKernelGGL(k_add_seq_base, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, n, data, seq_base);
+  SPTIR_HIP(hipGetLastError());
+  return SPTIR_OK;
+}
+size_t scan_room(int64_t n) { return (size_t)((n + kScanSeq - 1) / kScanSeq) * kScanSeq; }
+
+int log2_row_block_setting(int32_t n_rows, bool rounds, const sptir_build_options_t& opt) {
+  long v = opt.row_block;
   if (v < 8 || v > 256 || (v & (v - 1))) {
-    // A wavefront walks the list of one (launch, row block) alone and keeps the block's tile of Y in LDS:
+    // A wavefront walks the list of one row block alone and keeps the block's tile of Y in LDS:
     // 64 rows x 128 bytes = 8 KB next to its 4 KB (6 KB) chunk ring allow 12 wavefronts per CU.  Measured on
-    // the two large graphs: 32 rows cost 3 % (more lists, each rounded up to whole chunks), 128 rows 12 - 25 %
-    // (fewer wavefronts per CU); the low-degree graphs do not care.  128 rows is the most a compact record
-    // can address.
-    v = 64;
+    // the two large graphs with a launch per partition: 32 rows cost 3 % (more lists, each rounded up to whole
+    // chunks), 128 rows 12 - 25 % (fewer wavefronts per CU); the low-degree graphs do not care.  In rounds the
+    // lists hold short pieces only and 128 rows win (fewer, longer lists: 6 % on the largest graph).  128 rows is
+    // the most a compact record can address.
+    v = rounds ? 128 : 64;
     // A launch has (row blocks x feature tiles) wavefronts.  With one or two tiles (feat <= 64) that is too few
     // to balance 3,000 wavefront slots, and smaller row blocks win (measured at feat = 32: 32 rows 21 % faster).
-    const long tiles = feat_hint > 0 ? (feat_hint + 31) / 32 : 4;
+    const long tiles = opt.feat_hint > 0 ? (opt.feat_hint + 31) / 32 : 4;
     while (v > 16 && (n_rows / v) * tiles < 6144) v >>= 1;
     // ... but keep at least ~1024 row blocks, or the 256 CUs do not fill
     while (v > 8 && n_rows / v < 1024) v >>= 1;
@@ -631,55 +764,70 @@ int log2_row_block_setting(int32_t n_rows, int32_t feat_hint) {
   return l;
 }
 
-// Column partitions swept by one SpMM launch.  Sweeping them one (or a few)
-// at a time keeps the gathered slice of X inside an XCD's 4 MB L2 (the reason
-// section 4.2.1 gives for column partitioning) but costs a read-modify-write
-// of Y per extra launch, so it only pays when rows are long: with P launches
-// the extra Y traffic is 2*(P-1) lines per row and tile, against one X line
-// per stored slot served from L2 instead of from memory (about 4x faster).
-int parts_per_phase_setting(int32_t c, int32_t w, int32_t n_rows, int64_t slots) {
-  const char* e = getenv("SPTIR_PARTS_PER_PHASE");
-  long v = e ? atol(e) : 0;
-  if (v >= 1 && v <= c) return (int)v;
+// Do the X rows of a column partition have to be kept L2-resident while they are gathered (section 4.2.1's reason
+// for column partitions)?  Only when rows are long: the gathers of a low-degree graph come from beyond L2 either
+// way (measured: 8 slots per row and 4 partitions run 1.7x faster without any ordering by partition).  `fit`
+// receives the partitions whose 128-byte-wide slices fit 2.5 MB of an XCD's 4 MB L2 together.
+bool partitions_matter(int32_t c, int32_t w, int32_t n_rows, int64_t slots, long* fit_out) {
   const double slice_bytes = (double)w * 128.0;               // one 32-float tile of a partition's X rows
   long fit = (long)(2.5 * 1024 * 1024 / (slice_bytes > 1 ? slice_bytes : 1));
   if (fit < 1) fit = 1;
-  if (fit >= c) return c;
-  long phases = (c + fit - 1) / fit;
+  *fit_out = fit;
+  if (fit >= c) return false;
+  const long phases = (c + fit - 1) / fit;
   const double slots_per_row = n_rows > 0 ? (double)slots / n_rows : 0.0;
-  // measured: 8 slots per row and 4 partitions run 1.7x faster in one launch, 420 slots per row and 8 partitions
-  // 1.5x faster in 8 launches
-  if (slots_per_row < 16.0 * (double)(phases - 1)) return c;   // Y traffic would outweigh the L2 hits
-  return (int)fit;
+  return slots_per_row >= 16.0 * (double)(phases - 1);
 }
 
-// A wavefront walks a chunk list alone, so the longest list bounds the launch from below.  A piece with more
-// entries than two average lists (at least 256, at most kLongRowSlots) leaves the lists for the long-row
-// launches, where a workgroup per 1024 entries sums it (measured on the 169,343-row graph with rows of up to
-// 13,000 entries: SpMM 0.134 -> 0.11 ms).
-//   SPTIR_LONG_LEN  overrides the threshold
-int32_t long_piece_setting(int64_t nnz, int64_t n_lists) {
-  const char* e = getenv("SPTIR_LONG_LEN");
-  long v = e ? atol(e) : 0;
-  if (v >= 1 && v <= kLongRowSlots) return (int32_t)v;
-  // (the long-row launches cost some 8 microseconds of their own: not worth it on a graph that is done in 10)
-  if (nnz < (1 << 19)) return kLongRowSlots;
+// A wavefront walks a chunk list alone, so the longest list bounds a launch from below, and the lists of a round
+// run only as fast as the longest of them.  A piece with more entries than two average lists (at least 256, at
+// most kHeavyLenMax) therefore leaves the lists (measured on the 169,343-row graph with rows of up to 13,000
+// entries: SpMM 0.134 -> 0.11 ms).  In rounds every piece longer than one chunk does: what stays in the lists is
+// then so even that the wavefronts of a round sweep the column partitions nearly in step.
+int32_t heavy_len_setting(int64_t nnz, int64_t n_lists, bool rounds, const sptir_build_options_t& opt) {
+  if (opt.heavy_len >= 1) return opt.heavy_len;
+  if (rounds) return kChunkSlots;
+  // (the heavy-piece launches cost some 8 microseconds of their own: not worth it on a graph that is done in 10)
+  if (nnz < (1 << 19)) return kHeavyLenMax;
   const int64_t per_list = n_lists > 0 ? nnz / n_lists : 0;
-  return (int32_t)std::min<int64_t>(kLongRowSlots, std::max<int64_t>(256, 2 * per_list));
+  return (int32_t)std::min<int64_t>(kHeavyLenMax, std::max<int64_t>(256, 2 * per_list));
 }
 
 }  // namespace
 
-LaunchShape decide_launch_shape(int32_t n_rows, int32_t c, int32_t w, int64_t stored_slots, int32_t feat_hint) {
+sptir_build_options_t complete_options(const sptir_build_options_t* given) {
+  sptir_build_options_t o;
+  memset(&o, 0, sizeof(o));
+  if (given) {
+    size_t n = given->struct_size > 0 ? (size_t)given->struct_size : 0;
+    if (n > sizeof(o)) n = sizeof(o);
+    memcpy(&o, given, n);
+  }
+  o.struct_size = (int32_t)sizeof(o);
+  return o;
+}
+
+LaunchShape decide_launch_shape(int32_t n_rows, int32_t n_cols, int32_t c, int32_t w, int64_t stored_slots,
+                                const sptir_build_options_t& opt) {
   LaunchShape ls;
-  ls.parts_per_phase = parts_per_phase_setting(c, w, n_rows, stored_slots);
-  ls.log2_row_block = log2_row_block_setting(n_rows, feat_hint);
-  // the compact stream needs the columns of one launch to fit kCompactColBits and the row block 7 bits
-  const char* e = getenv("SPTIR_WIDE_STREAM");
+  long fit = 1;
+  const bool matter = partitions_matter(c, w, n_rows, stored_slots, &fit);
+  // rounds: every list sweeps all partitions, Y stays on chip and is written once; otherwise a launch per group
+  // of partitions that reads back what the one before it wrote
+  const bool parts_given = opt.parts_per_launch >= 1 && opt.parts_per_launch <= c;
+  // (rounds pay when the pieces that stay in the lists are short: a read-modify-write of Y per partition then
+  //  costs as much as the pieces themselves; with long pieces the wavefronts of a round, which nothing holds in
+  //  step, lose more by drifting onto different partitions.  Measured: mean piece of 8 entries, 1.54 -> 1.04 ms;
+  //  of 37 entries, 1.11 -> 1.39 ms.)
+  const bool short_pieces = opt.light_piece_len == 0 || opt.light_piece_len < 16;
+  ls.rounds = opt.rounds == 1 ? 1 : opt.rounds == 2 ? 0 : (matter && !parts_given && short_pieces ? 1 : 0);
+  ls.log2_row_block = log2_row_block_setting(n_rows, ls.rounds != 0, opt);
+  if (ls.rounds) ls.parts_per_phase = c;
+  else if (parts_given) ls.parts_per_phase = opt.parts_per_launch;
+  else ls.parts_per_phase = matter ? (int32_t)fit : c;
+  // a compact record holds a column in kCompactColBits bits and a row of the row block in 7
   const int64_t max_span = (int64_t)1 << kCompactColBits;
-  const bool compact = !(e && atoi(e) != 0) && w <= max_span && ls.log2_row_block <= kCompactMaxLog2RowBlock;
-  if (compact && (int64_t)ls.parts_per_phase * w > max_span) ls.parts_per_phase = (int32_t)(max_span / w);
-  ls.compact = compact ? 1 : 0;
+  ls.compact = (!opt.wide_stream && n_cols <= max_span && ls.log2_row_block <= kCompactMaxLog2RowBlock) ? 1 : 0;
   ls.n_phases = (c + ls.parts_per_phase - 1) / ls.parts_per_phase;
   return ls;
 }
@@ -690,11 +838,23 @@ using namespace sptir;
 
 extern "C" sptir_status_t sptir_hyb_build(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
                                           void* stream_, sptir_hyb_t** out) {
-  return sptir::hyb_build_impl(csr, n_col_parts, max_bucket_log2, stream_, out, true, 0);
+  return sptir::hyb_build_impl(csr, n_col_parts, max_bucket_log2, sptir::complete_options(nullptr), stream_, out);
+}
+
+extern "C" sptir_status_t sptir_hyb_build_ex(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
+                                             const sptir_build_options_t* options, void* stream_, sptir_hyb_t** out) {
+  const sptir_build_options_t opt = sptir::complete_options(options);
+  if (opt.row_block != 0 && (opt.row_block < 8 || opt.row_block > 256 || (opt.row_block & (opt.row_block - 1))))
+    return SPTIR_ERR_INVALID_ARG;
+  if (opt.parts_per_launch < 0 || opt.rounds < 0 || opt.rounds > 2 || opt.heavy_len < 0 || opt.sweep_kb < 0 ||
+      opt.feat_hint < 0)
+    return SPTIR_ERR_INVALID_ARG;
+  return sptir::hyb_build_impl(csr, n_col_parts, max_bucket_log2, opt, stream_, out);
 }
 
 sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
-                                     void* stream_, sptir_hyb_t** out, bool with_spmm_plan, int32_t feat_hint) {
+                                     const sptir_build_options_t& opt, void* stream_, sptir_hyb_t** out) {
+  const bool with_spmm_plan = !opt.no_spmm_plan;
   if (!csr || !out) return SPTIR_ERR_INVALID_ARG;
   if (csr->n_rows < 0 || csr->n_cols < 0 || csr->nnz < 0) return SPTIR_ERR_INVALID_ARG;
   if (n_col_parts < 1 || max_bucket_log2 < 0 || max_bucket_log2 > 30) return SPTIR_ERR_INVALID_ARG;
@@ -815,18 +975,35 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     h->R = row_ptr[B]; h->S = slot_ptr[B]; h->M = M; h->T = T;
     if (h->R + h->M > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
 
-    // ---- launch shape of the SpMM: row blocks and phases
+    // ---- launch shape of the SpMM: row blocks, lists, heavy pieces
     CellShape cs;
     cs.c = s.c; cs.k = s.k; cs.nb = s.nb; cs.R = h->R;
-    const LaunchShape ls = decide_launch_shape(s.n_rows, s.c, s.w, h->S + h->T, feat_hint);
+    // mean real length of the pieces of at most kChunkSlots entries, estimated from the bucket sizes
+    // (bucket i holds lengths 2^(i-1)+1 .. 2^i)
+    sptir_build_options_t opt_here = opt;
+    if (opt_here.light_piece_len == 0) {
+      double pieces = 0, entries = 0;
+      for (int32_t p = 0; p < s.c; ++p)
+        for (int32_t i = 0; i <= s.k && (1 << i) <= kChunkSlots; ++i) {
+          const double n = tot_bins[(size_t)p * s.nb + i];
+          pieces += n;
+          entries += n * (i == 0 ? 1.0 : 0.5 * ((1 << (i - 1)) + 1 + (1 << i)));
+        }
+      opt_here.light_piece_len = pieces > 0 ? std::max(1, (int)(entries / pieces + 0.5)) : 0;
+    }
+    const LaunchShape ls = decide_launch_shape(s.n_rows, s.n_cols, s.c, s.w, h->S + h->T, opt_here);
     cs.ppg = ls.parts_per_phase; cs.log2_rb = ls.log2_row_block; cs.n_phases = ls.n_phases;
     h->compact_stream = ls.compact;
+    h->rounds = ls.rounds;
+    h->sweep_kb = opt.sweep_kb > 0 ? opt.sweep_kb : 160 * 1024;
     cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
-    cs.long_len = long_piece_setting(csr->nnz, (int64_t)cs.n_phases * cs.n_rb);
+    cs.long_len = heavy_len_setting(csr->nnz, (int64_t)cs.n_phases * cs.n_rb, ls.rounds != 0, opt);
+    h->heavy_len = cs.long_len;
     if (!with_spmm_plan) cs.n_rb = 0;  // no row blocks, no cells, no chunks: only the canonical arrays are built
     h->spmm_plan = with_spmm_plan ? 1 : 0;
     h->log2_row_block = cs.log2_rb; h->n_row_blocks = cs.n_rb;
     h->parts_per_phase = cs.ppg; h->n_phases = cs.n_phases;
+    const int64_t n_pieces = h->R + M;
     const int64_t n_groups = (int64_t)cs.n_phases * cs.n_rb;
     const int64_t n_cells = n_groups * ((int64_t)cs.ppg * (cs.nb + 1) + 1);
     const int64_t n_parts = n_groups * cs.ppg;
@@ -837,8 +1014,15 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     const int64_t n_seq = (n_groups + kGroupSeq - 1) / kGroupSeq;
     const size_t o_group_tot = tmp2.reserve(sizeof(long long) * (size_t)(n_seq ? n_seq * kGroupSeq : 1));
     const size_t o_seq_tot = tmp2.reserve(sizeof(long long) * (size_t)(n_seq ? n_seq : 1));
-    const size_t o_cell_total = tmp2.reserve(2 * sizeof(long long));  // chunks in all, long pieces in all
-    const size_t o_long_cursor = tmp2.reserve(sizeof(long long));
+    const size_t o_cell_total = tmp2.reserve(sizeof(long long));  // chunks of all lists
+    // heavy pieces: the two prefix arrays over the pieces, the (row, partition) -> piece map, scan scratch
+    const bool want_heavy = with_spmm_plan && n_pieces > 0;
+    const size_t o_unit = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room(n_pieces + 1) : 1));
+    const size_t o_hchunk = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room(n_pieces + 1) : 1));
+    const size_t o_piece_of = tmp2.reserve(sizeof(int32_t) * (want_heavy ? (size_t)s.c * (size_t)s.n_rows : 1));
+    const size_t o_seg_at = tmp2.reserve(sizeof(int64_t) * (2 * (size_t)s.c + 1));
+    const size_t o_seg_hc = tmp2.reserve(sizeof(int32_t) * (2 * (size_t)s.c + 1));
+    const size_t o_seq_base = tmp2.reserve(sizeof(int32_t) * 2 * (scan_room(std::max<int64_t>(n_pieces + 1, s.n_rows + 1)) / kScanSeq + 2));
     tmp2.base = (char*)alloc(tmp2.size, actx, stream);
     if (!tmp2.base) { st = SPTIR_ERR_ALLOC; goto fail; }
     int32_t* d_bounds = (int32_t*)(tmp2.base + o_bounds);
@@ -846,7 +1030,12 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     long long* d_group_tot = (long long*)(tmp2.base + o_group_tot);
     long long* d_seq_tot = (long long*)(tmp2.base + o_seq_tot);
     long long* d_cell_total = (long long*)(tmp2.base + o_cell_total);
-    unsigned long long* d_long_cursor = (unsigned long long*)(tmp2.base + o_long_cursor);
+    int32_t* d_unit = (int32_t*)(tmp2.base + o_unit);
+    int32_t* d_hchunk = (int32_t*)(tmp2.base + o_hchunk);
+    int32_t* d_piece_of = want_heavy ? (int32_t*)(tmp2.base + o_piece_of) : nullptr;
+    int32_t* d_seq_base = (int32_t*)(tmp2.base + o_seq_base);
+    int64_t* d_seg_at = (int64_t*)(tmp2.base + o_seg_at);
+    int32_t* d_seg_hc = (int32_t*)(tmp2.base + o_seg_hc);
 
     // ---- the handle's device arrays (the chunk list follows further down)
     struct { void** p; size_t bytes; } wanted[] = {
@@ -854,8 +1043,8 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
         {(void**)&h->bucket_slot_ptr, sizeof(int64_t) * (size_t)(B + 1)},
         {(void**)&h->rem_part_ptr, sizeof(int32_t) * (size_t)(s.c + 1)},
         {(void**)&h->rem_ptr, sizeof(int64_t) * (size_t)(M + 1)},
-        // (row_ids, cols and vals end in kChunkSlots spare zero entries: the SpMM kernel
-        //  reads whole 64-slot chunks, the last one of an array may be shorter)
+        // (row_ids, cols and vals end in kChunkSlots spare zero entries: whole 64-slot chunks are read from them
+        //  when the stream is packed, the last one of an array may be shorter)
         {(void**)&h->row_ids, sizeof(int32_t) * (size_t)(h->R + M + kChunkSlots)},
         {(void**)&h->row_len, sizeof(int32_t) * (size_t)(h->R + M)},
         {(void**)&h->cols, sizeof(int32_t) * (size_t)(h->S + T + kChunkSlots)},
@@ -887,6 +1076,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       a.bucket_row_ptr = h->bucket_row_ptr; a.bucket_slot_ptr = h->bucket_slot_ptr;
       a.rem_part_ptr = h->rem_part_ptr; a.rem_nnz_base = d_rnnz_base;
       a.row_ids = h->row_ids; a.cols = h->cols; a.vals = h->vals; a.rem_ptr = h->rem_ptr; a.row_len = h->row_len;
+      a.piece_of = d_piece_of;
       a.R = h->R; a.S = h->S; a.M = M; a.T = T;
       hipLaunchKernelGGL(k_scatter, dim3((unsigned)n_pair_blocks), dim3(kBuildBlock), 0, stream, s, a);
     } else {
@@ -895,17 +1085,27 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     }
     BUILD_HIP(hipGetLastError());
 
-    // ---- chunk descriptors, grouped by (phase, row block)
-    long long n_chunks = 0, n_long = 0;
+    // ---- heavy pieces: how many, and how many chunks (prefixes over the pieces in row_ids order)
+    if (want_heavy) {
+      hipLaunchKernelGGL(k_heavy_counts, dim3((unsigned)((n_pieces + 256) / 256)), dim3(256), 0, stream, n_pieces,
+                         h->row_len, cs.long_len, d_unit, d_hchunk);
+      BUILD_HIP(hipGetLastError());
+      st = device_exclusive_scan(d_unit, n_pieces + 1, d_seq_base, stream);
+      if (st != SPTIR_OK) goto fail;
+      st = device_exclusive_scan(d_hchunk, n_pieces + 1, d_seq_base, stream);
+      if (st != SPTIR_OK) goto fail;
+    }
+
+    // ---- chunk descriptors of the lists, grouped by (phase, row block)
+    long long n_chunks = 0;
+    int32_t heavy_totals[2] = {0, 0};  // heavy pieces, their chunks
     if (n_cells > 0) {
-      long long totals[2] = {0, 0};
       BUILD_HIP(hipMemsetAsync(d_group_tot, 0, sizeof(long long) * (size_t)n_seq * kGroupSeq, stream));
-      BUILD_HIP(hipMemsetAsync(d_cell_total, 0, 2 * sizeof(long long), stream));
-      BUILD_HIP(hipMemsetAsync(d_long_cursor, 0, sizeof(long long), stream));
+      BUILD_HIP(hipMemsetAsync(d_cell_total, 0, sizeof(long long), stream));
       hipLaunchKernelGGL(k_cell_bounds, dim3((unsigned)((n_bounds + 255) / 256)), dim3(256), 0, stream, cs,
                          h->bucket_row_ptr, h->rem_part_ptr, h->row_ids, d_bounds);
       hipLaunchKernelGGL(k_part_chunk_counts, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs,
-                         n_parts, d_bounds, h->row_len, d_cell_chunks, (unsigned long long*)(d_cell_total + 1));
+                         n_parts, d_bounds, h->row_len, d_cell_chunks);
       hipLaunchKernelGGL(k_group_scan, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, stream, cs, n_groups,
                          d_cell_chunks, d_group_tot);
       // chunks before a cell = its prefix inside the group + the group's inside its sequence + the sequence's
@@ -914,32 +1114,57 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       hipLaunchKernelGGL(k_scan_sequences<long long>, dim3(1), dim3(kBuildBlock), 0, stream, d_seq_tot,
                          (int32_t)n_seq, d_cell_total);
       BUILD_HIP(hipGetLastError());
-      BUILD_HIP(hipMemcpyAsync(totals, d_cell_total, 2 * sizeof(long long), hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipStreamSynchronize(stream));
-      n_chunks = totals[0];
-      n_long = totals[1];
+      BUILD_HIP(hipMemcpyAsync(&n_chunks, d_cell_total, sizeof(long long), hipMemcpyDeviceToHost, stream));
     }
+    // heavy chunks before the pieces of every segment: the ELL pieces of partition 0 .. c-1, then their remainder pieces
+    std::vector<int64_t> seg_at(2 * (size_t)s.c + 1, 0);
+    std::vector<int32_t> seg_hc(2 * (size_t)s.c + 1, 0);
+    if (want_heavy) {
+      for (int32_t p = 0; p < s.c; ++p) {
+        seg_at[p] = row_ptr[(size_t)p * (s.k + 1)];
+        seg_at[(size_t)s.c + p] = h->R + rem_part_ptr[p];
+      }
+      seg_at[2 * (size_t)s.c] = n_pieces;
+      BUILD_HIP(hipMemcpyAsync(d_seg_at, seg_at.data(), sizeof(int64_t) * seg_at.size(), hipMemcpyHostToDevice, stream));
+      hipLaunchKernelGGL(k_pick, dim3((unsigned)((seg_at.size() + 255) / 256)), dim3(256), 0, stream,
+                         (int32_t)seg_at.size(), d_seg_at, d_hchunk, d_seg_hc);
+      BUILD_HIP(hipGetLastError());
+      BUILD_HIP(hipMemcpyAsync(seg_hc.data(), d_seg_hc, sizeof(int32_t) * seg_hc.size(), hipMemcpyDeviceToHost, stream));
+      BUILD_HIP(hipMemcpyAsync(&heavy_totals[0], d_unit + n_pieces, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+      BUILD_HIP(hipMemcpyAsync(&heavy_totals[1], d_hchunk + n_pieces, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    }
+    BUILD_HIP(hipStreamSynchronize(stream));
+    // the lists' chunks come first in the stream (each list a whole number of quads), then the heavy chunks
+    const int64_t n_heavy_chunks =
+        ((int64_t)heavy_totals[1] + kChunksPerQuad - 1) / kChunksPerQuad * kChunksPerQuad;
     h->n_chunks = n_chunks;
-    if (n_long > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
+    h->n_heavy = heavy_totals[0];
+    h->heavy_chunk0 = n_chunks;
+    h->n_heavy_chunks = n_heavy_chunks;
+    h->n_heavy_lists = (int32_t)((n_heavy_chunks + kHeavyListChunks - 1) / kHeavyListChunks);
+    h->n_partial_rows = h->n_heavy + h->n_heavy_lists;
+    if (h->n_heavy > 0) {
+      h->n_heavy_segs = 2 * s.c;
+      h->hseg_list = (int32_t*)malloc(sizeof(int32_t) * (size_t)(h->n_heavy_segs + 1));
+      if (!h->hseg_list) { st = SPTIR_ERR_ALLOC; goto fail; }
+      for (int32_t i = 0; i <= h->n_heavy_segs; ++i)
+        h->hseg_list[i] = (int32_t)(((int64_t)seg_hc[i] + kHeavyListChunks - 1) / kHeavyListChunks);
+    }
+    const int64_t all_chunks = n_chunks + n_heavy_chunks;
+    if (h->n_partial_rows > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
     {
-      size_t bytes = sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1);
+      size_t bytes = sizeof(Chunk) * (size_t)(all_chunks ? all_chunks : 1);
       tmp_chunks = alloc(bytes, actx, stream);  // descriptors are only needed until the stream is packed
       if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
       BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, bytes, stream));  // count 0 marks the padding chunks
-      bytes = sizeof(PiecePlace) * (size_t)(h->R + M ? h->R + M : 1);
+      bytes = sizeof(PiecePlace) * (size_t)(n_pieces ? n_pieces : 1);
       tmp_place = alloc(bytes, actx, stream);
       if (!tmp_place) { st = SPTIR_ERR_ALLOC; goto fail; }
       BUILD_HIP(hipMemsetAsync(tmp_place, 0, bytes, stream));  // len 0: not queued
-      bytes = sizeof(int32_t) * (h->compact_stream ? 2 : 3) * kChunkSlots * (size_t)(n_chunks ? n_chunks : 1);
+      bytes = sizeof(int32_t) * (h->compact_stream ? 2 : 3) * kChunkSlots * (size_t)(all_chunks ? all_chunks : 1);
       h->stream = (int32_t*)alloc(bytes, actx, stream);
       if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += bytes;
-      if (n_long > 0) {
-        bytes = sizeof(LongPiece) * (size_t)n_long;
-        h->long_pieces = (LongPiece*)alloc(bytes, actx, stream);
-        if (!h->long_pieces) { st = SPTIR_ERR_ALLOC; goto fail; }
-        h->device_bytes += bytes;
-      }
     }
     StreamShape ss;
     ss.stream = h->stream; ss.compact = h->compact_stream; ss.log2_rb = cs.log2_rb;
@@ -948,64 +1173,49 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       hipLaunchKernelGGL(k_part_fill_chunks, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs, ss,
                          n_parts, d_bounds, d_cell_chunks, d_group_tot, d_seq_tot, h->row_len, h->row_ids,
                          h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_ptr, h->S, (Chunk*)tmp_chunks,
-                         (PiecePlace*)tmp_place, h->rb_chunk_ptr, h->long_pieces, d_long_cursor);
-    if (n_long > 0) {
-      // The long pieces arrive in no particular order: sort them by (row, partition) on the host, so that
-      // one workgroup sums all pieces of a row in a fixed order.  There are few of them by construction
-      // (each holds more non-zeros than two average chunk lists).
-      std::vector<LongPiece> lp((size_t)n_long);
-      BUILD_HIP(hipMemcpyAsync(lp.data(), h->long_pieces, sizeof(LongPiece) * lp.size(), hipMemcpyDeviceToHost,
+                         (PiecePlace*)tmp_place, h->rb_chunk_ptr);
+    if (h->n_heavy > 0) {
+      // ---- heavy pieces: chunk descriptors, first partial-sum row of every heavy list, the rows' partial sums
+      struct { void** p; size_t bytes; } more[] = {
+          {(void**)&h->hlist_first_slot, sizeof(int32_t) * (size_t)h->n_heavy_lists},
+          {(void**)&h->row_slot_ptr, sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1)},
+          {(void**)&h->partial, sizeof(float) * kPartialFeat * (size_t)h->n_partial_rows},
+      };
+      for (auto& wnt : more) {
+        *wnt.p = alloc(wnt.bytes, actx, stream);
+        if (!*wnt.p) { st = SPTIR_ERR_ALLOC; goto fail; }
+        h->device_bytes += wnt.bytes;
+      }
+      hipLaunchKernelGGL(k_heavy_chunks, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream, n_pieces,
+                         h->row_len, d_unit, d_hchunk, B, s.k, h->R, h->S, h->bucket_row_ptr, h->bucket_slot_ptr,
+                         h->rem_ptr, (Chunk*)tmp_chunks + n_chunks);
+      hipLaunchKernelGGL(k_heavy_list_slots, dim3((unsigned)((h->n_heavy_lists + 255) / 256)), dim3(256), 0, stream,
+                         h->n_heavy_lists, n_pieces, d_unit, d_hchunk, h->hlist_first_slot);
+      hipLaunchKernelGGL(k_row_slot_counts, dim3((unsigned)((s.n_rows + 256) / 256)), dim3(256), 0, stream, s.n_rows,
+                         s.c, d_piece_of, d_unit, d_hchunk, h->row_slot_ptr);
+      BUILD_HIP(hipGetLastError());
+      st = device_exclusive_scan(h->row_slot_ptr, (int64_t)s.n_rows + 1, d_seq_base, stream);
+      if (st != SPTIR_OK) goto fail;
+      int32_t n_row_slots = 0;
+      BUILD_HIP(hipMemcpyAsync(&n_row_slots, h->row_slot_ptr + s.n_rows, sizeof(int32_t), hipMemcpyDeviceToHost,
                                stream));
       BUILD_HIP(hipStreamSynchronize(stream));
-      std::sort(lp.begin(), lp.end(), [](const LongPiece& x, const LongPiece& y) {
-        return x.row != y.row ? x.row < y.row : x.q < y.q;
-      });
-      std::vector<int32_t> rows, ptr;
-      for (size_t i = 0; i < lp.size(); ++i) {
-        if (i == 0 || lp[i].row != lp[i - 1].row) { rows.push_back(lp[i].row); ptr.push_back((int32_t)i); }
-      }
-      ptr.push_back((int32_t)lp.size());
-      h->n_long_rows = (int32_t)rows.size();
-      h->long_rows = (int32_t*)alloc(sizeof(int32_t) * rows.size(), actx, stream);
-      h->long_piece_ptr = (int32_t*)alloc(sizeof(int32_t) * ptr.size(), actx, stream);
-      if (!h->long_rows || !h->long_piece_ptr) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += sizeof(int32_t) * (rows.size() + ptr.size());
-      // segments: one workgroup's worth of a long piece each
-      std::vector<LongSegment> segs;
-      std::vector<int32_t> seg_ptr;
-      for (size_t i = 0; i < rows.size(); ++i) {
-        seg_ptr.push_back((int32_t)segs.size());
-        for (int32_t j = ptr[i]; j < ptr[i + 1]; ++j)
-          for (int32_t off = 0; off < lp[j].len; off += kLongSegSlots)
-            segs.push_back(LongSegment{lp[j].slot0 + off, std::min<int32_t>(kLongSegSlots, lp[j].len - off), 0});
-        if (segs.size() > 0x3FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
-      }
-      seg_ptr.push_back((int32_t)segs.size());
-      h->n_long_segs = (int32_t)segs.size();
-      h->long_seg_ptr = (int32_t*)alloc(sizeof(int32_t) * seg_ptr.size(), actx, stream);
-      h->long_segs = (LongSegment*)alloc(sizeof(LongSegment) * segs.size(), actx, stream);
-      h->long_partial = (float*)alloc(sizeof(float) * kLongPartialFeat * segs.size(), actx, stream);
-      if (!h->long_seg_ptr || !h->long_segs || !h->long_partial) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += sizeof(int32_t) * seg_ptr.size() + (sizeof(LongSegment) + sizeof(float) * kLongPartialFeat) * segs.size();
-      BUILD_HIP(hipMemcpyAsync(h->long_seg_ptr, seg_ptr.data(), sizeof(int32_t) * seg_ptr.size(), hipMemcpyHostToDevice,
-                               stream));
-      BUILD_HIP(hipMemcpyAsync(h->long_segs, segs.data(), sizeof(LongSegment) * segs.size(), hipMemcpyHostToDevice,
-                               stream));
-      BUILD_HIP(hipMemcpyAsync(h->long_pieces, lp.data(), sizeof(LongPiece) * lp.size(), hipMemcpyHostToDevice,
-                               stream));
-      BUILD_HIP(hipMemcpyAsync(h->long_rows, rows.data(), sizeof(int32_t) * rows.size(), hipMemcpyHostToDevice,
-                               stream));
-      BUILD_HIP(hipMemcpyAsync(h->long_piece_ptr, ptr.data(), sizeof(int32_t) * ptr.size(), hipMemcpyHostToDevice,
-                               stream));
-      BUILD_HIP(hipStreamSynchronize(stream));  // the host vectors go out of scope
+      const size_t bytes = sizeof(int32_t) * (size_t)(n_row_slots ? n_row_slots : 1);
+      h->row_slots = (int32_t*)alloc(bytes, actx, stream);
+      if (!h->row_slots) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += bytes;
+      hipLaunchKernelGGL(k_row_slot_fill, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
+                         s.c, d_piece_of, d_unit, d_hchunk, h->row_slot_ptr, h->row_slots);
+      BUILD_HIP(hipGetLastError());
     }
-    if (n_chunks > 0) {
-      int64_t blocks = (n_chunks + 3) / 4;
+    if (all_chunks > 0) {
+      int64_t blocks = (all_chunks + 3) / 4;
       if (blocks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
-      hipLaunchKernelGGL(k_pack_stream, dim3((unsigned)blocks), dim3(256), 0, stream, (int64_t)n_chunks, ss,
-                         (const Chunk*)tmp_chunks, h->row_ids, h->cols, h->vals);
-      const int64_t n_pieces = h->R + M;
-      if (n_pieces > 0)
+      // the heavy chunks hold absolute columns: one heavy list may cross partitions
+      StreamShape ss_all = ss;
+      hipLaunchKernelGGL(k_pack_stream, dim3((unsigned)blocks), dim3(256), 0, stream, (int64_t)all_chunks, n_chunks,
+                         ss_all, (const Chunk*)tmp_chunks, h->row_ids, h->cols, h->vals);
+      if (n_pieces > 0 && n_chunks > 0)
         hipLaunchKernelGGL(k_pack_pieces, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream, n_pieces, ss,
                            (const PiecePlace*)tmp_place, h->row_ids, h->cols, h->vals);
     }
@@ -1024,6 +1234,14 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       if (st != SPTIR_OK) goto fail;
     }
     BUILD_HIP(hipStreamSynchronize(stream));
+    if (opt.release_canonical && with_spmm_plan) {
+      // sptir_spmm reads the stream only
+      const size_t bytes = (sizeof(int32_t) + sizeof(float)) * (size_t)(h->S + T + kChunkSlots);
+      free_(h->cols, actx); free_(h->vals, actx);
+      h->cols = nullptr; h->vals = nullptr;
+      h->canonical_released = 1;
+      h->device_bytes -= bytes;
+    }
   }
   free_(tmp.base, actx);
   if (tmp2.base) free_(tmp2.base, actx);

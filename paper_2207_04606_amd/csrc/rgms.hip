@@ -349,7 +349,9 @@ extern "C" sptir_status_t sptir_rgms_build(const sptir_csr_t* stacked, int32_t n
   current_allocator(&p->alloc, &p->free_, &p->alloc_ctx);
   p->n_rel = n_relations; p->n_rows = stacked->n_rows / n_relations; p->n_cols = stacked->n_cols; p->k = k;
   p->nnz = stacked->nnz;
-  sptir_status_t st = hyb_build_impl(stacked, 1, k, stream_, &p->hyb, false, 0);
+  sptir_build_options_t opt = complete_options(nullptr);
+  opt.no_spmm_plan = 1;
+  sptir_status_t st = hyb_build_impl(stacked, 1, k, opt, stream_, &p->hyb);
   if (st != SPTIR_OK) { delete p; return st; }
 
   const sptir_hyb* h = p->hyb;

@@ -39,7 +39,9 @@ extern "C" sptir_status_t sptir_hyb_search(const sptir_csr_t* csr, const int32_t
   }
   for (int32_t i = 0; i < n_candidates; ++i) {
     sptir_hyb_t* h = nullptr;
-    st = hyb_build_impl(csr, c_candidates[i], k, stream_, &h, true, feat);  // launch plan sized for `feat`
+    sptir_build_options_t opt = complete_options(nullptr);
+    opt.feat_hint = feat;  // launch plan sized for `feat`
+    st = hyb_build_impl(csr, c_candidates[i], k, opt, stream_, &h);
     if (st != SPTIR_OK) goto done;
     float ms = 0.f;
     st = sptir_spmm(h, X, Y, feat, stream_);  // warm-up

@@ -22,11 +22,20 @@
 // round-robin to the 8 XCDs, each with a private L2.  Tiles are bound to
 // blockIdx.x % 8 where the tile count allows it, so an XCD's L2 only ever holds
 // its own feature tile of X; the chunks of a row block sweep the column
-// partitions in ascending order, and long-row matrices get one launch per
-// partition, which keeps the X slice in flight L2-sized (the purpose section
-// 4.2.1 gives for column partitioning).
+// partitions in ascending order.  Where rows are long enough for the cache
+// locality of X to matter (the purpose section 4.2.1 gives for column
+// partitioning) the lists run in rounds: a launch takes as many row blocks as
+// the GPU holds wavefronts, chosen with lists of like length, so that all of
+// them sweep the partitions nearly in step and the X slice in flight stays
+// L2-sized while Y never leaves the chip before it is complete.
+//
+// Row pieces too long for that (more than a chunk's worth of entries in
+// rounds) are summed by k_spmm_heavy: their chunks form one sequence in
+// partition order, cut into lists of 32 chunks, a wavefront each, which leave
+// partial sums in memory; k_heavy_reduce adds them to Y in a fixed order.
 #include <cstdio>
 #include <cstdlib>
+#include <atomic>
 #include <mutex>
 #include "sptir_internal.h"
 
@@ -78,10 +87,11 @@ __device__ __forceinline__ int tile_index(int r, int fl) {
 // read-add-write is enough (LDS float atomics cost several times more).
 template <int VEC, int LG>
 struct TileSink {
+  static constexpr bool kQueues = true;  // the lists it serves hold queue chunks
   float* tile;     // [row_block][kTile] in LDS
   int fl;
   bool f_active;
-  __device__ __forceinline__ void operator()(int r, bool valid, const float (&acc)[VEC]) const {
+  __device__ __forceinline__ void operator()(int r, bool valid, const float (&acc)[VEC]) {
     if (valid && f_active) {
       float* p = tile + tile_index<VEC, LG>(r, fl);
       float t[VEC];
@@ -90,6 +100,20 @@ struct TileSink {
       for (int e = 0; e < VEC; ++e) t[e] += acc[e];
       store_vec<VEC>(p, t);
     }
+  }
+};
+
+// Stores a finished sum as the next partial-sum row (heavy pieces): every call takes one row, whether or not
+// this lane has something to store, so the row number stays the same in all lanes.
+template <int VEC, int LG>
+struct PartialSink {
+  static constexpr bool kQueues = false;  // heavy lists hold chunks cut from one long piece only
+  float* out;      // partial + this lane's feature offset inside a partial-sum row
+  int slot;        // next row
+  bool f_active;
+  __device__ __forceinline__ void operator()(int, bool valid, const float (&acc)[VEC]) {
+    if (valid && f_active) store_vec<VEC>(out + (size_t)slot * kPartialFeat, acc);
+    ++slot;
   }
 };
 
@@ -269,7 +293,7 @@ constexpr int kHybBlock = 64 * kHybWaves;
 // finished row sum into the wavefront's LDS tile of Y; the lane groups that
 // share a chunk of one long row add their partial sums up with cross-lane moves
 // at the row's end, and the leading group hands the sum over.
-template <int VEC, int LG, bool IDX32, bool WIDE>
+template <int VEC, int LG, bool IDX32, bool WIDE, typename Sink>
 struct HybWalker {
   using S = Shape<VEC, LG>;
   static constexpr int UB = S::kSteps, CS = S::kChunk;
@@ -284,13 +308,13 @@ struct HybWalker {
     int col[4], val[4], row[WIDE ? 4 : 1];
   };
 
-  const SpmmArgs& a;
-  const int32_t* quads;  // stream of this (phase, row block)
+  const float* X;        // first row of X the stream's columns count from
+  const int32_t* quads;  // stream of this list
   int n_quads;
   int lane, g;
   int* ring;             // this wave's LDS ring
   unsigned row_bytes, lane_bytes;  // bytes per row of X, byte offset of this lane's features
-  TileSink<VEC, LG> sink;
+  Sink sink;
   float acc[VEC];
 
   __device__ __forceinline__ void fetch(int q, Fetched& f) const {
@@ -353,9 +377,9 @@ struct HybWalker {
       if constexpr (IDX32) {
         // column ids are below 2^24 here, so the 24-bit multiply-add is exact
         unsigned off = __umul24(col, row_bytes) + lane_bytes;
-        load_vec<VEC>(x[j], reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.X) + off));
+        load_vec<VEC>(x[j], reinterpret_cast<const float*>(reinterpret_cast<const char*>(X) + off));
       } else {
-        load_vec<VEC>(x[j], reinterpret_cast<const float*>(reinterpret_cast<const char*>(a.X) +
+        load_vec<VEC>(x[j], reinterpret_cast<const float*>(reinterpret_cast<const char*>(X) +
                                                             (size_t)col * row_bytes + lane_bytes));
       }
     }
@@ -373,7 +397,7 @@ struct HybWalker {
     const bool hand_over = ((meta >> (WIDE ? 6 : 4)) & 1) != 0;
     const int sub = s & (SUB - 1);
     const int* rows = st + (WIDE ? 2 * kQuadSlots : 0);
-    if (lw < 6) {
+    if (Sink::kQueues && lw < 6) {
       int r[UB];
       read_ints(rows + first_slot(s), r);
 #pragma unroll
@@ -422,6 +446,11 @@ struct HybWalker {
     Fetched f, f_first;
     fetch(0, f_first);
     fetch(1, f);
+    // The request for quad 1 has to be issued before the first gathers, as the request for quad Q+2 is issued
+    // before the last gathers of quad Q in the loop.  Loads return in order; if the compiler moved this one behind
+    // the gathers here, the wait for it at the top of the loop (entered from here as well as from its own end)
+    // would have to cover every gather in flight, in every iteration.
+    __builtin_amdgcn_sched_barrier(0);
     int m_cur[kChunksPerQuad], m_next[kChunksPerQuad];
     park(0, f_first, m_cur);
     float xa[UB][VEC], xb[UB][VEC];
@@ -479,7 +508,7 @@ struct HybWalker {
 template <int VEC, int LG, bool IDX32, bool WIDE>
 __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   using S = Shape<VEC, LG>;
-  using W = HybWalker<VEC, LG, IDX32, WIDE>;
+  using W = HybWalker<VEC, LG, IDX32, WIDE, TileSink<VEC, LG>>;
   extern __shared__ __align__(16) float smem[];  // per wavefront: [row_block][kTile] tile of Y, then its quad ring
   int64_t unit;
   int tile_id;
@@ -512,7 +541,7 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   const int64_t c0 = a.rb_chunk_ptr[rb];
   const int n_list = (int)(a.rb_chunk_ptr[rb + 1] - c0);  // a multiple of kChunksPerQuad
   const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
-  W wk{a, a.stream + (size_t)c0 * (W::kArrays * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
+  W wk{a.X, a.stream + (size_t)c0 * (W::kArrays * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
        (unsigned)a.feat * 4u, (unsigned)f_read * 4u, TileSink<VEC, LG>{tile, fl, f_active}, {}};
   wk.run();
 
@@ -524,6 +553,87 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
       store_vec<VEC>(y0 + (size_t)r * (size_t)a.feat, out);
     }
   }
+}
+
+// ------------------------------------------------------------ heavy pieces
+struct HeavyArgs {
+  const int32_t* stream;       // the whole chunk stream
+  const int32_t* first_slot;   // [n_lists] partial-sum row of each list's first write
+  const float* X;
+  float* partial;              // [n_partial_rows][kPartialFeat]
+  int64_t chunk0;              // first heavy chunk in the stream
+  int64_t n_chunks;            // heavy chunks (a multiple of kChunksPerQuad)
+  int32_t list0;               // this launch sums lists list0 .. list0 + n_lists - 1
+  int32_t n_lists;
+  int32_t feat;
+  int32_t feat0;               // first feature of this sweep (partial-sum rows hold kPartialFeat features)
+  int32_t n_tiles;             // feature tiles of this sweep
+  int32_t map_mode;
+  int32_t map_param;
+};
+
+// One wavefront per (heavy list, feature tile): the list's kHeavyListChunks chunks are walked like any other
+// list, but a finished piece goes to the next partial-sum row instead of an LDS tile, and so does, at the end,
+// what has been summed of the piece the list stops in (zeros if it stops at a piece end: every wavefront takes
+// that row, so that the row numbers follow from counting alone).
+template <int VEC, int LG, bool IDX32, bool WIDE>
+__global__ __launch_bounds__(kHybBlock) void k_spmm_heavy(HeavyArgs a) {
+  using S = Shape<VEC, LG>;
+  using W = HybWalker<VEC, LG, IDX32, WIDE, PartialSink<VEC, LG>>;
+  extern __shared__ __align__(16) float smem[];  // per wavefront: its quad ring
+  int64_t unit;
+  int tile_id;
+  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (unit * kHybWaves + wave >= a.n_lists) return;
+  const int64_t list = a.list0 + unit * kHybWaves + wave;
+  const int g = lane / LG, fl = lane & (LG - 1);
+  const int f_in_sweep = tile_id * S::kTile + fl * VEC;
+  const int f0 = a.feat0 + f_in_sweep;
+  const bool f_active = f0 < a.feat;
+  int* ring = reinterpret_cast<int*>(smem) + wave * W::kRingInts;
+  const int64_t c0 = list * kHeavyListChunks;
+  const int64_t left = a.n_chunks - c0;
+  const int n_list = (int)(left < kHeavyListChunks ? left : kHeavyListChunks);
+  const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
+  W wk{a.X, a.stream + (size_t)(a.chunk0 + c0) * (W::kArrays * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
+       (unsigned)a.feat * 4u, (unsigned)f_read * 4u,
+       PartialSink<VEC, LG>{a.partial + f_in_sweep, __builtin_amdgcn_readfirstlane(a.first_slot[list]), f_active}, {}};
+  wk.run();
+  sum_groups<VEC, LG>(wk.acc, S::kGroups);
+  wk.sink(0, g == 0, wk.acc);
+}
+
+// Y[r, feat0 + f] += the partial sums of row r's heavy pieces, in the order of row_slots (partition by partition):
+// one thread per (row, VEC features).  Runs after the chunk-list launches have written Y.
+template <int VEC>
+__global__ __launch_bounds__(256) void k_heavy_reduce(const int32_t* __restrict__ row_slot_ptr,
+                                                      const int32_t* __restrict__ row_slots,
+                                                      const float* __restrict__ partial, float* Y, int32_t n_rows,
+                                                      int32_t feat, int32_t feat0, int32_t width) {
+  const int per_row = width / VEC;
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t r = t / per_row;
+  if (r >= n_rows) return;
+  const int f = (int)(t % per_row) * VEC;
+  const int b = row_slot_ptr[r], e = row_slot_ptr[r + 1];
+  if (b == e) return;
+  float sum[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) sum[i] = 0.f;
+  for (int j = b; j < e; ++j) {
+    float v[VEC];
+    load_vec<VEC>(v, partial + (size_t)row_slots[j] * kPartialFeat + f);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) sum[i] += v[i];
+  }
+  float* y = Y + (size_t)r * (size_t)feat + feat0 + f;
+  float out[VEC];
+  load_vec<VEC>(out, y);
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) out[i] += sum[i];
+  store_vec<VEC>(y, out);
 }
 
 struct CsrArgs {
@@ -569,158 +679,6 @@ __global__ __launch_bounds__(64 * kCsrWaves) void k_spmm_csr(CsrArgs a) {
   walk_row<VEC, LG>(a.indices + begin, a.values + begin, a.X + f0, a.feat, end - begin, lane, f_active, sink);
 }
 
-// ---------------------------------------------------------------- long rows
-// A row piece with more than kLongRowSlots real entries would keep one wavefront busy long after the rest of
-// the launch has drained, so the builder sets such pieces aside.  Here one workgroup of kLongWaves wavefronts
-// takes all long pieces of one row: every wavefront sums a contiguous share of every piece, the shares meet
-// in LDS in wavefront order (fixed, so the result does not change from run to run), and wavefront 0 adds
-// the total to the row of Y, which the chunk-list launches have written before (same stream).
-struct LongArgs {
-  const int32_t* long_rows;
-  const int32_t* long_piece_ptr;
-  const LongPiece* long_pieces;
-  const int32_t* cols;
-  const float* vals;
-  const float* X;
-  float* Y;
-  int32_t n_long_rows;
-  int32_t feat;
-  int32_t n_tiles;
-  int32_t map_mode;
-  int32_t map_param;
-};
-
-constexpr int kLongWaves = 16;
-
-template <int VEC>
-struct RegisterSink {  // adds the row sum the walk hands over to a running total in registers
-  float* total;
-  __device__ __forceinline__ void operator()(int, bool valid, const float (&acc)[VEC]) const {
-    if (valid) {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) total[e] += acc[e];
-    }
-  }
-};
-
-template <int VEC, int LG>
-__global__ __launch_bounds__(64 * kLongWaves) void k_spmm_long(LongArgs a) {
-  using S = Shape<VEC, LG>;
-  __shared__ float partial[kLongWaves][S::kTile];
-  int64_t unit;
-  int tile_id;
-  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
-  if (unit >= a.n_long_rows) return;  // (whole workgroup)
-  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const int lane = threadIdx.x & 63;
-  const int fl = lane & (LG - 1);
-  const int f0 = tile_id * S::kTile + fl * VEC;
-  const bool f_active = f0 < a.feat;
-  float total[VEC];
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) total[e] = 0.f;
-  RegisterSink<VEC> sink{total};
-  const int p_lo = a.long_piece_ptr[unit], p_hi = a.long_piece_ptr[unit + 1];
-  for (int p = p_lo; p < p_hi; ++p) {
-    const LongPiece lp = a.long_pieces[p];
-    // shares are whole chunks, so that every wavefront reads aligned runs of the piece
-    const int n_chunks = (lp.len + S::kChunk - 1) / S::kChunk;
-    const int per_wave = (n_chunks + kLongWaves - 1) / kLongWaves;
-    const int first = wave * per_wave * S::kChunk;
-    const int count = min(lp.len - first, per_wave * S::kChunk);
-    if (count > 0)
-      walk_row<VEC, LG>(a.cols + lp.slot0 + first, a.vals + lp.slot0 + first, a.X + f0, a.feat, count, lane,
-                        f_active, sink);
-  }
-  if (lane < LG) {  // the walk leaves a row's sum in the lanes of the first lane group
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) partial[wave][fl * VEC + e] = total[e];
-  }
-  __syncthreads();
-  if (wave == 0 && lane < LG && f_active) {
-    float* y = a.Y + (size_t)a.long_rows[unit] * (size_t)a.feat + f0;
-    float out[VEC];
-    load_vec<VEC>(out, y);
-    for (int w = 0; w < kLongWaves; ++w) {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) out[e] += partial[w][fl * VEC + e];
-    }
-    store_vec<VEC>(y, out);
-  }
-}
-
-// The same sum with more workgroups, for Y no wider than kLongPartialFeat: one workgroup of kSegWaves wavefronts
-// per segment of a long piece leaves the segment's sum in `partial`, then k_long_reduce adds the segments of a
-// row to its row of Y in segment order (fixed, so the result is again the same from run to run).  A hub row of
-// 20,000 non-zeros is 20 workgroups' work instead of one's.
-struct SegmentArgs {
-  const LongSegment* segs;
-  const int32_t* cols;
-  const float* vals;
-  const float* X;
-  float* partial;  // [n_segs][feat]
-  int32_t n_segs;
-  int32_t feat;
-  int32_t n_tiles;
-  int32_t map_mode;
-  int32_t map_param;
-};
-
-constexpr int kSegWaves = 4;
-
-template <int VEC, int LG>
-__global__ __launch_bounds__(64 * kSegWaves) void k_long_segments(SegmentArgs a) {
-  using S = Shape<VEC, LG>;
-  __shared__ float share[kSegWaves][S::kTile];
-  int64_t unit;
-  int tile_id;
-  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
-  if (unit >= a.n_segs) return;  // (whole workgroup)
-  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const int lane = threadIdx.x & 63;
-  const int fl = lane & (LG - 1);
-  const int f0 = tile_id * S::kTile + fl * VEC;
-  const bool f_active = f0 < a.feat;
-  float total[VEC];
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) total[e] = 0.f;
-  RegisterSink<VEC> sink{total};
-  const LongSegment sg = a.segs[unit];
-  const int n_chunks = (sg.len + S::kChunk - 1) / S::kChunk;
-  const int per_wave = (n_chunks + kSegWaves - 1) / kSegWaves;
-  const int first = wave * per_wave * S::kChunk;
-  const int count = min(sg.len - first, per_wave * S::kChunk);
-  if (count > 0)
-    walk_row<VEC, LG>(a.cols + sg.slot0 + first, a.vals + sg.slot0 + first, a.X + f0, a.feat, count, lane, f_active,
-                      sink);
-  if (lane < LG) {
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) share[wave][fl * VEC + e] = total[e];
-  }
-  __syncthreads();
-  if (wave == 0 && lane < LG && f_active) {
-    float out[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) out[e] = share[0][fl * VEC + e];
-    for (int w = 1; w < kSegWaves; ++w) {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) out[e] += share[w][fl * VEC + e];
-    }
-    store_vec<VEC>(a.partial + (size_t)unit * (size_t)a.feat + f0, out);
-  }
-}
-
-// one thread per (long row, feature)
-__global__ void k_long_reduce(const int32_t* __restrict__ long_rows, const int32_t* __restrict__ long_seg_ptr,
-                              const float* __restrict__ partial, float* Y, int32_t n_long_rows, int32_t feat) {
-  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= (int64_t)n_long_rows * feat) return;
-  const int i = (int)(t / feat), f = (int)(t % feat);
-  float sum = 0.f;
-  for (int sgm = long_seg_ptr[i]; sgm < long_seg_ptr[i + 1]; ++sgm) sum += partial[(size_t)sgm * feat + f];
-  Y[(size_t)long_rows[i] * (size_t)feat + f] += sum;
-}
-
 // launch geometry shared by both SpMM entry points
 struct Geometry {
   int vec, lg, n_tiles, map_mode, map_param;
@@ -755,27 +713,63 @@ bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   return a0 < b0 + nb && b0 < a0 + na;
 }
 
+// the template arguments of the two hyb kernels as a value
 template <int VEC, int LG, bool IDX32, bool WIDE>
-void launch_hyb_one(const Geometry& g, size_t lds_bytes, hipStream_t stream, const SpmmArgs& a) {
-  static bool raised = false;  // row blocks of 1024 rows need more than the default 64 KB of dynamic LDS
-  if (!raised && lds_bytes > 48 * 1024) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_hyb<VEC, LG, IDX32, WIDE>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
-    raised = true;
+struct Variant {
+  static constexpr int vec = VEC, lg = LG;
+  static constexpr bool idx32 = IDX32, wide = WIDE;
+};
+
+template <int VEC, int LG, typename F>
+void with_flags(bool idx32, bool wide, F&& f) {
+  if (wide) {
+    if (idx32) f(Variant<VEC, LG, true, true>{}); else f(Variant<VEC, LG, false, true>{});
+  } else {
+    if (idx32) f(Variant<VEC, LG, true, false>{}); else f(Variant<VEC, LG, false, false>{});
   }
-  hipLaunchKernelGGL((k_spmm_hyb<VEC, LG, IDX32, WIDE>), dim3((unsigned)g.grid), dim3(kHybBlock), lds_bytes, stream,
-                     a);
 }
 
-template <int VEC, int LG>
-void launch_hyb(const Geometry& g, size_t lds_bytes, hipStream_t stream, const SpmmArgs& a, bool idx32, bool wide) {
-  if (wide) {
-    if (idx32) launch_hyb_one<VEC, LG, true, true>(g, lds_bytes, stream, a);
-    else launch_hyb_one<VEC, LG, false, true>(g, lds_bytes, stream, a);
-  } else {
-    if (idx32) launch_hyb_one<VEC, LG, true, false>(g, lds_bytes, stream, a);
-    else launch_hyb_one<VEC, LG, false, false>(g, lds_bytes, stream, a);
+// calls f with the Variant that matches the lane geometry and the stream's record form
+template <typename F>
+void with_variant(int vec, int lg, bool idx32, bool wide, F&& f) {
+  if (vec == 4 && lg == 8) with_flags<4, 8>(idx32, wide, f);
+  else if (vec == 4) with_flags<4, 4>(idx32, wide, f);
+  else if (vec == 2) with_flags<2, 16>(idx32, wide, f);
+  else with_flags<1, 32>(idx32, wide, f);
+}
+
+template <typename V>
+void launch_lists(V, const Geometry& g, size_t lds_bytes, hipStream_t stream, const SpmmArgs& a) {
+  auto* kernel = &k_spmm_hyb<V::vec, V::lg, V::idx32, V::wide>;
+  static std::once_flag raised;  // row blocks of 256 rows need more than the default 64 KB of dynamic LDS
+  std::call_once(raised, [&] {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              160 * 1024 - 1024);
+  });
+  hipLaunchKernelGGL(kernel, dim3((unsigned)g.grid), dim3(kHybBlock), lds_bytes, stream, a);
+}
+
+// workgroups of k_spmm_hyb the GPU holds at once (0: unknown)
+template <typename V>
+int resident_workgroups(V, size_t lds_bytes) {
+  int per_cu = 0, n_cu = 0, dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_spmm_hyb<V::vec, V::lg, V::idx32, V::wide>, kHybBlock,
+                                                   lds_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
   }
+  const int by_lds = lds_bytes ? (int)((160 * 1024) / lds_bytes) : per_cu;
+  if (per_cu > by_lds) per_cu = by_lds;
+  return per_cu > 0 && n_cu > 0 ? per_cu * n_cu : 0;
+}
+
+template <typename V>
+void launch_heavy(V, const Geometry& g, hipStream_t stream, const HeavyArgs& a) {
+  const size_t lds_bytes = (size_t)kHybWaves * sizeof(int) * 2 * (V::wide ? 3 : 2) * kChunkSlots * kChunksPerQuad;
+  hipLaunchKernelGGL((k_spmm_heavy<V::vec, V::lg, V::idx32, V::wide>), dim3((unsigned)g.grid), dim3(kHybBlock),
+                     lds_bytes, stream, a);
 }
 
 }  // namespace
@@ -787,13 +781,12 @@ void lane_shape(int32_t feat, bool aligned16, bool aligned8, int* vec, int* lg) 
   else { *vec = 1; *lg = 32; }
 }
 
-// Feature tiles per sweep over the launches of a call.  Every launch but the first reads back what the one
-// before it wrote to Y; that round trip stays inside the 256 MB memory-side cache only if the part of Y a sweep
-// touches is well below its size.  So a wide Y is produced in several sweeps, each over a group of feature tiles
-// (4 or 8, which still map whole XCDs to a tile).
-int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches) {
-  const char* e = std::getenv("SPTIR_SWEEP_MB");  // tuning knob, read at every call
-  const double limit_mb = e ? std::atof(e) : 160.0;
+// Feature tiles per sweep over the launches of a call when every launch but the first reads back what the one
+// before it wrote to Y (no rounds): that round trip stays inside the 256 MB memory-side cache only if the part of
+// Y a sweep touches is well below its size.  So a wide Y is produced in several sweeps, each over a group of
+// feature tiles (4 or 8, which still map whole XCDs to a tile).
+int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches, int sweep_kb) {
+  const double limit_mb = (double)sweep_kb / 1024.0;
   if (n_launches < 2 || n_tiles % 4 != 0) return n_tiles;
   const double tile_mb = (double)n_rows * tile_floats * sizeof(float) / (1024.0 * 1024.0);
   if (tile_mb * n_tiles <= limit_mb) return n_tiles;
@@ -801,14 +794,22 @@ int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches
   return 4;
 }
 
+// May the gather offsets of a launch be formed with the 24-bit multiply (column x bytes per row of X)?
+// Both factors must fit 24 bits and the product, plus a lane's offset inside the row, 32.
+bool offsets_fit_32(int64_t n_cols_spanned, int32_t feat) {
+  const uint64_t row_bytes = (uint64_t)feat * sizeof(float);
+  return row_bytes < (1u << 24) && n_cols_spanned < (1 << 24) &&
+         (uint64_t)n_cols_spanned * row_bytes < ((uint64_t)1 << 32);
+}
+
 }  // namespace sptir
 
 using namespace sptir;
 
-// The work of sptir_spmm; long_partial is where the segment sums of rows with very long pieces meet
-// ([n_long_segs][feat] floats; only read when such rows exist and feat <= kLongPartialFeat).
+// The work of sptir_spmm; `partial` is where the sums of heavy pieces meet ([n_partial_rows][kPartialFeat] floats;
+// only touched when the matrix has heavy pieces).
 static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat, void* stream_,
-                                  float* long_partial) {
+                                  float* partial) {
   if (!h || feat < 1) return SPTIR_ERR_INVALID_ARG;
   if ((h->n_cols > 0 && !X) || (h->n_rows > 0 && !Y)) return SPTIR_ERR_INVALID_ARG;
   const size_t x_bytes = sizeof(float) * (size_t)h->n_cols * feat, y_bytes = sizeof(float) * (size_t)h->n_rows * feat;
@@ -818,7 +819,8 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
   if (!h->spmm_plan) return SPTIR_ERR_UNSUPPORTED;
 
   Geometry g;
-  if (!plan(((int64_t)h->n_row_blocks + kHybWaves - 1) / kHybWaves, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
+  const int64_t n_units = ((int64_t)h->n_row_blocks + kHybWaves - 1) / kHybWaves;
+  if (!plan(n_units, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
   SpmmArgs a;
   a.stream = h->stream;
   a.X = X; a.Y = Y; a.n_rows = h->n_rows; a.n_row_blocks = h->n_row_blocks; a.log2_row_block = h->log2_row_block;
@@ -827,66 +829,94 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
   const bool wide = !h->compact_stream;
   const size_t lds_bytes = (size_t)kHybWaves * (sizeof(float) * ((size_t)g.vec * g.lg << h->log2_row_block) +
                                                 sizeof(int) * 2 * (wide ? 3 : 2) * kChunkSlots * kChunksPerQuad);
-  // A compact stream holds columns relative to the first column of its launch, which moves into the X pointer.
-  const size_t span = (size_t)h->parts_per_phase * (size_t)h->w;
-  const bool idx32 = wide ? (h->n_cols < (1 << 24) && x_bytes < ((size_t)1 << 32))
-                          : (span * feat * sizeof(float) < ((size_t)1 << 32));
+  // A compact list holds columns relative to the first column of its launch, which moves into the X pointer.
+  const int64_t span = (int64_t)h->parts_per_phase * (int64_t)h->w;
+  const bool idx32 = offsets_fit_32(wide ? (int64_t)h->n_cols : (span < h->n_cols ? span : (int64_t)h->n_cols), feat);
   const int all_tiles = g.n_tiles;
-  const int per_sweep = tiles_per_sweep(all_tiles, g.vec * g.lg, h->n_rows, h->n_phases);
-  for (int tile0 = 0; tile0 < all_tiles; tile0 += per_sweep) {
-    g.n_tiles = all_tiles - tile0 < per_sweep ? all_tiles - tile0 : per_sweep;
-    if (!plan_tiles(((int64_t)h->n_row_blocks + kHybWaves - 1) / kHybWaves, &g)) return SPTIR_ERR_OVERFLOW;
-    a.n_tiles = g.n_tiles; a.tile0 = tile0; a.map_mode = g.map_mode; a.map_param = g.map_param;
-    for (int phase = 0; phase < h->n_phases; ++phase) {
-      a.rb_chunk_ptr = h->rb_chunk_ptr + (size_t)phase * h->n_row_blocks;
-      a.rb_order = h->rb_order + (size_t)phase * h->n_row_blocks;
-      a.accumulate = phase > 0;
-      a.X = wide ? X : X + (size_t)phase * span * (size_t)feat;
-      if (g.vec == 4 && g.lg == 8) launch_hyb<4, 8>(g, lds_bytes, stream, a, idx32, wide);
-      else if (g.vec == 4) launch_hyb<4, 4>(g, lds_bytes, stream, a, idx32, wide);
-      else if (g.vec == 2) launch_hyb<2, 16>(g, lds_bytes, stream, a, idx32, wide);
-      else launch_hyb<1, 32>(g, lds_bytes, stream, a, idx32, wide);
+  if (h->rounds) {
+    // Rounds: a launch takes as many row blocks, in the order of their list lengths, as the GPU holds wavefronts.
+    // All of them start together, their lists are about equally long and sweep the column partitions in the same
+    // order, so they stay nearly in step; the Y tiles stay in LDS from the first partition to the last.
+    int capacity = 0;
+    with_variant(g.vec, g.lg, idx32, wide, [&](auto v) { capacity = resident_workgroups(v, lds_bytes); });
+    if (capacity <= 0) capacity = 3 * 256;
+    int64_t per_round = (int64_t)capacity / all_tiles * kHybWaves;  // row blocks
+    if (per_round < 8 * kHybWaves) per_round = 8 * kHybWaves;
+    const int64_t n_rounds = (h->n_row_blocks + per_round - 1) / per_round;
+    per_round = ((h->n_row_blocks + n_rounds - 1) / n_rounds + 7) / 8 * 8;  // rounds of equal size
+    a.rb_chunk_ptr = h->rb_chunk_ptr; a.accumulate = 0; a.tile0 = 0;
+    for (int64_t first = 0; first < h->n_row_blocks; first += per_round) {
+      const int64_t here = h->n_row_blocks - first < per_round ? h->n_row_blocks - first : per_round;
+      a.rb_order = h->rb_order + first;
+      a.n_row_blocks = (int32_t)here;
+      if (!plan_tiles((here + kHybWaves - 1) / kHybWaves, &g)) return SPTIR_ERR_OVERFLOW;
+      a.map_mode = g.map_mode; a.map_param = g.map_param;
+      with_variant(g.vec, g.lg, idx32, wide, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
+    }
+  } else {
+    const int per_sweep = tiles_per_sweep(all_tiles, g.vec * g.lg, h->n_rows, h->n_phases, h->sweep_kb);
+    for (int tile0 = 0; tile0 < all_tiles; tile0 += per_sweep) {
+      g.n_tiles = all_tiles - tile0 < per_sweep ? all_tiles - tile0 : per_sweep;
+      if (!plan_tiles(n_units, &g)) return SPTIR_ERR_OVERFLOW;
+      a.n_tiles = g.n_tiles; a.tile0 = tile0; a.map_mode = g.map_mode; a.map_param = g.map_param;
+      for (int phase = 0; phase < h->n_phases; ++phase) {
+        a.rb_chunk_ptr = h->rb_chunk_ptr + (size_t)phase * h->n_row_blocks;
+        a.rb_order = h->rb_order + (size_t)phase * h->n_row_blocks;
+        a.accumulate = phase > 0;
+        a.X = wide ? X : X + (size_t)phase * (size_t)span * (size_t)feat;
+        with_variant(g.vec, g.lg, idx32, wide, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
+      }
     }
   }
-  if (h->n_long_rows > 0 && feat <= kLongPartialFeat) {
-    Geometry gl;
-    if (!plan(h->n_long_segs, feat, X, Y, &gl)) return SPTIR_ERR_OVERFLOW;
-    SegmentArgs sa;
-    sa.segs = h->long_segs; sa.cols = h->cols; sa.vals = h->vals; sa.X = X; sa.partial = long_partial;
-    sa.n_segs = h->n_long_segs; sa.feat = feat;
-    sa.n_tiles = gl.n_tiles; sa.map_mode = gl.map_mode; sa.map_param = gl.map_param;
-    dim3 grid((unsigned)gl.grid), block(64 * kSegWaves);
-    if (gl.vec == 4 && gl.lg == 8) hipLaunchKernelGGL((k_long_segments<4, 8>), grid, block, 0, stream, sa);
-    else if (gl.vec == 4) hipLaunchKernelGGL((k_long_segments<4, 4>), grid, block, 0, stream, sa);
-    else if (gl.vec == 2) hipLaunchKernelGGL((k_long_segments<2, 16>), grid, block, 0, stream, sa);
-    else hipLaunchKernelGGL((k_long_segments<1, 32>), grid, block, 0, stream, sa);
-    const int64_t n_out = (int64_t)h->n_long_rows * feat;
-    hipLaunchKernelGGL(k_long_reduce, dim3((unsigned)((n_out + 255) / 256)), dim3(256), 0, stream, h->long_rows,
-                       h->long_seg_ptr, long_partial, Y, h->n_long_rows, feat);
-  } else if (h->n_long_rows > 0) {
-    Geometry gl;
-    if (!plan(h->n_long_rows, feat, X, Y, &gl)) return SPTIR_ERR_OVERFLOW;
-    LongArgs la;
-    la.long_rows = h->long_rows; la.long_piece_ptr = h->long_piece_ptr; la.long_pieces = h->long_pieces;
-    la.cols = h->cols; la.vals = h->vals; la.X = X; la.Y = Y;
-    la.n_long_rows = h->n_long_rows; la.feat = feat;
-    la.n_tiles = gl.n_tiles; la.map_mode = gl.map_mode; la.map_param = gl.map_param;
-    dim3 grid((unsigned)gl.grid), block(64 * kLongWaves);
-    if (gl.vec == 4 && gl.lg == 8) hipLaunchKernelGGL((k_spmm_long<4, 8>), grid, block, 0, stream, la);
-    else if (gl.vec == 4) hipLaunchKernelGGL((k_spmm_long<4, 4>), grid, block, 0, stream, la);
-    else if (gl.vec == 2) hipLaunchKernelGGL((k_spmm_long<2, 16>), grid, block, 0, stream, la);
-    else hipLaunchKernelGGL((k_spmm_long<1, 32>), grid, block, 0, stream, la);
+  if (h->n_heavy > 0) {
+    // heavy pieces: partial sums of kPartialFeat features at a time, added to the Y the lists have written
+    const bool idx32_all = offsets_fit_32(h->n_cols, feat);
+    const int tile = g.vec * g.lg;
+    const bool y_vec4 = feat % 4 == 0 && ((uintptr_t)Y & 15) == 0;
+    HeavyArgs ha;
+    ha.stream = h->stream; ha.first_slot = h->hlist_first_slot; ha.X = X; ha.partial = partial;
+    ha.chunk0 = h->heavy_chunk0; ha.n_chunks = h->n_heavy_chunks; ha.feat = feat;
+    for (int feat0 = 0; feat0 < feat; feat0 += kPartialFeat) {
+      const int width = feat - feat0 < kPartialFeat ? feat - feat0 : kPartialFeat;
+      Geometry gh = g;
+      gh.n_tiles = (width + tile - 1) / tile;
+      ha.feat0 = feat0; ha.n_tiles = gh.n_tiles;
+      // The heavy chunks are in partition order.  Where the locality of X matters (rounds), a launch ends with
+      // a partition's last list, so that its waves never straddle two slices of X for long; small groups of
+      // lists are not worth a launch of their own.
+      const int32_t min_lists = 2048;
+      int32_t first = 0;
+      for (int32_t sg = 1; sg <= h->n_heavy_segs; ++sg) {
+        const int32_t end = h->hseg_list[sg];
+        if (end == first) continue;
+        if (sg < h->n_heavy_segs && !(h->rounds && end - first >= min_lists)) continue;
+        ha.list0 = first; ha.n_lists = end - first;
+        if (!plan_tiles(((int64_t)ha.n_lists + kHybWaves - 1) / kHybWaves, &gh)) return SPTIR_ERR_OVERFLOW;
+        ha.map_mode = gh.map_mode; ha.map_param = gh.map_param;
+        with_variant(g.vec, g.lg, idx32_all, wide, [&](auto v) { launch_heavy(v, gh, stream, ha); });
+        first = end;
+      }
+      const int64_t n_threads = (int64_t)h->n_rows * (width / (y_vec4 ? 4 : 1));
+      const dim3 grid((unsigned)((n_threads + 255) / 256)), block(256);
+      if ((n_threads + 255) / 256 > 0x7FFFFFFF) return SPTIR_ERR_OVERFLOW;
+      if (y_vec4)
+        hipLaunchKernelGGL(k_heavy_reduce<4>, grid, block, 0, stream, h->row_slot_ptr, h->row_slots, partial, Y,
+                           h->n_rows, feat, feat0, width);
+      else
+        hipLaunchKernelGGL(k_heavy_reduce<1>, grid, block, 0, stream, h->row_slot_ptr, h->row_slots, partial, Y,
+                           h->n_rows, feat, feat0, width);
+    }
   }
   SPTIR_HIP(hipGetLastError());
   return SPTIR_OK;
 }
 
 extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat, void* stream_) {
-  return spmm_on_hyb(h, X, Y, feat, stream_, h ? h->long_partial : nullptr);
+  return spmm_on_hyb(h, X, Y, feat, stream_, h ? h->partial : nullptr);
 }
 
 // ---------------------------------------------------------------- sptir_spmm_noalloc
-// The segment sums of long rows in memory that belongs to the loaded code object instead of the handle: every
+// The partial sums of heavy pieces in memory that belongs to the loaded code object instead of the handle: every
 // GPU the library runs on holds its own copy of this array until the process ends.
 static constexpr size_t kStaticScratchFloats = SPTIR_NOALLOC_SCRATCH_BYTES / sizeof(float);
 static __device__ __align__(256) float scratch[kStaticScratchFloats];
@@ -916,14 +946,14 @@ extern "C" sptir_status_t sptir_spmm_noalloc(const sptir_hyb_t* h, const float* 
                                              void* stream_) {
   if (!h || feat < 1) return SPTIR_ERR_INVALID_ARG;
   float* partial = nullptr;
-  if (h->n_long_rows > 0 && feat <= kLongPartialFeat) {
-    if ((size_t)h->n_long_segs * (size_t)feat > kStaticScratchFloats) {
+  if (h->n_heavy > 0) {
+    const size_t need = (size_t)h->n_partial_rows * kPartialFeat;
+    if (need > kStaticScratchFloats) {
       char msg[256];
       snprintf(msg, sizeof(msg),
-               "sptir_spmm_noalloc: %lld long-row segments x %d features = %zu bytes of partial sums exceed the "
+               "sptir_spmm_noalloc: the partial sums of %lld heavy row pieces need %zu bytes, more than the "
                "static scratch of %zu bytes; use sptir_spmm",
-               (long long)h->n_long_segs, (int)feat, (size_t)h->n_long_segs * feat * sizeof(float),
-               (size_t)SPTIR_NOALLOC_SCRATCH_BYTES);
+               (long long)h->n_heavy, need * sizeof(float), (size_t)SPTIR_NOALLOC_SCRATCH_BYTES);
       note_error_text(msg);
       return SPTIR_ERR_UNSUPPORTED;
     }

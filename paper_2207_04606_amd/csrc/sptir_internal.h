@@ -28,27 +28,14 @@ constexpr int kChunkSlots = 64;
 constexpr int kRowLog2W = 31;
 constexpr int kChunksPerQuad = 4;  // chunks the SpMM kernel fetches with one load per lane and array
 constexpr int kBuildBlock = 256;  // rows per workgroup in the builder kernels
-// A row piece (ELL row or remainder piece) with more real entries than this is kept out of the chunk lists,
-// which one wavefront walks alone, and is summed by a whole workgroup in a launch of its own.
-constexpr int kLongRowSlots = 2048;
-
-// One long row piece: `len` consecutive slots of the fused (cols, vals) arrays starting at slot0.
-struct LongPiece {
-  int64_t slot0;
-  int32_t row;
-  int32_t len;
-  int32_t q;  // position in row_ids (orders the pieces of a row by column partition)
-  int32_t pad_;
-};
-static_assert(sizeof(LongPiece) == 24, "LongPiece must stay 24 bytes");
-// A run of at most kLongSegSlots consecutive entries of a long piece.
-struct LongSegment {
-  int64_t slot0;
-  int32_t len;
-  int32_t pad_;
-};
-constexpr int kLongSegSlots = 1024;
-constexpr int kLongPartialFeat = 512;  // widest Y the per-segment partial sums are kept for
+// Row pieces of more than `heavy_len` real entries leave the chunk lists (a wavefront walks a list alone and keeps
+// the Y rows of its row block on chip).  Their entries form one sequence of 64-slot chunks, piece after piece in the
+// order of the canonical arrays (partition-major); the sequence is cut into "heavy lists" of kHeavyListChunks chunks,
+// a wavefront each, which write one partial sum per finished piece plus one for whatever piece is unfinished where
+// the list ends.  A last launch adds a row's partial sums to Y in a fixed order.
+constexpr int kHeavyLenMax = 2048;      // largest threshold the size rules choose
+constexpr int kHeavyListChunks = 32;    // chunks per heavy list (a multiple of kChunksPerQuad; 16 and 64 measure the same)
+constexpr int kPartialFeat = 128;       // features per partial sum row: wider Y is produced in sweeps of this many
 // Compact stream records spend 8 bytes per slot instead of 12: one word holds the column relative to the first
 // column of the launch (bits 0..19), the row relative to the row block (20..26), "slot is real" (27), the chunk's
 // log2w code (28..30; 3 = queue chunk, 7 = cut from one long row) and the hand-over flag (31; of the chunk, or in a
@@ -79,21 +66,26 @@ struct sptir_hyb {
   int64_t* rb_chunk_ptr;     // device [n_phases * n_row_blocks + 1], first chunk of each group
   int32_t* rb_order;         // device [n_phases * n_row_blocks]: the row blocks of a launch, longest list first
   int64_t n_chunks;
-  // rows with long pieces: the pieces of long_rows[i] are long_pieces[long_piece_ptr[i] .. long_piece_ptr[i+1])
-  int32_t n_long_rows;
-  int32_t* long_rows;        // device [n_long_rows], ascending
-  int32_t* long_piece_ptr;   // device [n_long_rows + 1]
-  sptir::LongPiece* long_pieces;  // device
-  // the long pieces cut into segments of at most kLongSegSlots entries, one workgroup each; the segments of
-  // long_rows[i] are long_segs[long_seg_ptr[i] .. long_seg_ptr[i+1]) and their partial sums meet in long_partial
-  int32_t n_long_segs;
-  int32_t* long_seg_ptr;     // device [n_long_rows + 1]
-  sptir::LongSegment* long_segs;  // device [n_long_segs]
-  float* long_partial;       // device [n_long_segs][kLongPartialFeat]
+  // heavy pieces (see kHeavyListChunks): their chunks sit in `stream` from chunk heavy_chunk0 on
+  int32_t heavy_len;
+  int64_t n_heavy;            // heavy pieces
+  int64_t n_heavy_chunks;     // their chunks, rounded up to whole quads
+  int64_t heavy_chunk0;       // a multiple of kChunksPerQuad
+  int32_t n_heavy_lists;
+  int32_t* hlist_first_slot;  // device [n_heavy_lists]: partial-sum row the list's first write goes to
+  int32_t n_heavy_segs;       // 2c: the ELL pieces of each partition, then its remainder pieces
+  int32_t* hseg_list;         // host (malloc) [n_heavy_segs + 1]: first heavy list that starts in each segment
+  int32_t* row_slot_ptr;      // device [n_rows + 1]: the partial-sum rows of row r are row_slots[row_slot_ptr[r] ..)
+  int32_t* row_slots;         // device, in the order they are added to Y (partition-major)
+  float* partial;             // device [(n_heavy + n_heavy_lists)][kPartialFeat]
+  int64_t n_partial_rows;
   int32_t log2_row_block;    // rows of Y one wavefront accumulates in LDS (power of two)
   int32_t n_row_blocks;
-  int32_t parts_per_phase;   // column partitions swept by one SpMM launch
+  int32_t parts_per_phase;   // column partitions swept by one chunk list
   int32_t n_phases;
+  int32_t rounds;            // 1: the lists sweep all partitions and are launched in rounds (Y written once)
+  int32_t sweep_kb;          // rounds == 0: kilobytes of Y one sweep over the launches may touch
+  int32_t canonical_released;
   size_t device_bytes;
   sptir_alloc_fn alloc;
   sptir_free_fn free_;
@@ -107,24 +99,27 @@ void current_allocator(sptir_alloc_fn* a, sptir_free_fn* f, void** ctx);
 void* default_alloc(size_t bytes, void* ctx, void* stream);
 void default_free(void* p, void* ctx);
 
-// sptir_hyb_build, optionally without the SpMM launch plan (for users of the canonical arrays alone), and with
-// the feature size the launch plan should suit (0: not known)
-sptir_status_t hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2, void* stream,
-                              sptir_hyb_t** out, bool with_spmm_plan, int32_t feat_hint);
+// sptir_hyb_build_ex; `opt` is complete (defaults filled in by the caller)
+sptir_status_t hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
+                              const sptir_build_options_t& opt, void* stream, sptir_hyb_t** out);
+// the options a NULL pointer stands for / a caller's struct with unknown tail fields zeroed
+sptir_build_options_t complete_options(const sptir_build_options_t* given);
 
 // What the builder decides about the SpMM launches from the sizes alone (builder.hip; host code, no device access).
 struct LaunchShape {
   int32_t log2_row_block;   // rows of Y per wavefront
-  int32_t parts_per_phase;  // column partitions per launch
-  int32_t n_phases;         // launches per sweep
+  int32_t parts_per_phase;  // column partitions per chunk list
+  int32_t n_phases;         // chunk-list launches per sweep (1 when rounds)
   int32_t compact;          // 1: 8-byte stream records
+  int32_t rounds;           // 1: lists sweep all partitions, launched in rounds
 };
-LaunchShape decide_launch_shape(int32_t n_rows, int32_t c, int32_t w, int64_t stored_slots, int32_t feat_hint);
+LaunchShape decide_launch_shape(int32_t n_rows, int32_t n_cols, int32_t c, int32_t w, int64_t stored_slots,
+                                const sptir_build_options_t& opt);
 
 // Lane geometry sptir_spmm uses for `feat` when X and Y are 16-byte aligned, and the feature tiles one sweep over
 // the launches covers (spmm.hip; host code).
 void lane_shape(int32_t feat, bool aligned16, bool aligned8, int* vec, int* lg);
-int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches);
+int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches, int sweep_kb);
 
 // rb_order[launch][i] = the row block with the i-th longest chunk list of that launch (order.hip).  Works on
 // `stream`; *scratch_out is device memory the caller frees once the stream has drained.

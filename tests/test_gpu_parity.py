@@ -20,9 +20,12 @@ def say(msg):
     print(msg, flush=True)
 
 
-def build_both(sptir, w, c, k):
+def build_both(sptir, w, c, k, options=None):
     d = upload(w)
-    hyb = sptir.sptir_hyb_build(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, c, k)
+    if options:
+        hyb = sptir.sptir_hyb_build_ex(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, c, k, options)
+    else:
+        hyb = sptir.sptir_hyb_build(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, c, k)
     got, info = fetch_hyb(sptir, hyb)
     want = oracle.hyb_build(w.n_rows, w.n_cols, w.indptr, w.indices, w.values, c, k)
     return d, hyb, got, want, info
@@ -212,45 +215,28 @@ def test_named_configs_full(gpu_lib, name):
 
 
 @pytest.mark.parametrize("name", ["protein", "social"])
-def test_named_configs_full_size_sampled(gpu_lib, name):
-    """Full-size graphs in the launch configuration bench.py times: hyb arrays
-    bit-exact in full, Y on a sample of rows the oracle evaluates one by one
-    (the highest-degree rows, the first and last rows, and random rows)."""
+def test_named_configs_full_size_all_rows(gpu_lib, name):
+    """Full-size graphs in the launch configuration bench.py times: hyb arrays bit-exact in full, and every
+    element of Y against the oracle, at the configuration's own feature size and at the 128 the headline
+    measurement uses."""
     say(f"[config] {name}: generating")
     w = workloads.make_config(name)
     say(f"[config] {name}: building on GPU and in the oracle")
     d, hyb, got, want, info = build_both(gpu_lib, w, w.n_col_parts, w.max_bucket_log2)
     assert_same_hyb(got, want)
     del got, want
-    Y = torch.empty(w.n_rows, w.feat, device="cuda")
-    gpu_lib.sptir_spmm(hyb, d.X, Y)
-    torch.cuda.synchronize()
-    deg = np.diff(w.indptr)
-    rng = np.random.default_rng(0)
-    rows = np.unique(np.concatenate([np.argsort(deg)[-64:], np.argsort(deg)[:64], [0, w.n_rows - 1],
-                                     rng.choice(w.n_rows, 6000, replace=False)])).astype(np.int32)
-    say(f"[config] {name}: oracle on {rows.size} sampled rows")
-    Yr, Sr = oracle.spmm_csr_rows(rows, w.indptr, w.indices, w.values, w.X)
-    Yg = Y[torch.from_numpy(rows.astype(np.int64)).cuda()].cpu().numpy()
-    worst = assert_y_close(Yg, Yr, Sr, what=name)
-    # property that holds at any size: column sums, sum_i Y[i,:] = sum_j (sum_i a_ij) X[j,:]
-    colw = np.bincount(w.indices, weights=w.values.astype(np.float64), minlength=w.n_cols)
-    want_sum = colw @ w.X.astype(np.float64)
-    abs_sum = np.bincount(w.indices, weights=np.abs(w.values.astype(np.float64)), minlength=w.n_cols) @ np.abs(
-        w.X.astype(np.float64))
-    got_sum = Y.double().sum(0).cpu().numpy()
-    assert (np.abs(got_sum - want_sum) <= 1e-5 * abs_sum).all()
-    say(f"[config] {name}: nnz={w.nnz} pads={info['n_pad_slots']} rem_nnz={info['n_rem_nnz']} "
-        f"items={info['n_work_items']} max_err={worst:.2e}")
-    if w.feat != 128:
-        # the same decomposition at the feature size the headline measurement uses (one sweep instead of two)
-        X128 = np.ascontiguousarray(w.X[:, :128])
-        Y128 = torch.empty(w.n_rows, 128, device="cuda")
-        gpu_lib.sptir_spmm(hyb, torch.from_numpy(X128).cuda(), Y128)
-        Yr, Sr = oracle.spmm_csr_rows(rows, w.indptr, w.indices, w.values, X128)
-        Yg = Y128[torch.from_numpy(rows.astype(np.int64)).cuda()].cpu().numpy()
-        worst = assert_y_close(Yg, Yr, Sr, what=f"{name} feat=128")
-        say(f"[config] {name}: feat=128 max_err={worst:.2e}")
+    for feat in sorted({w.feat, 128}):
+        X = w.X if feat == w.feat else np.ascontiguousarray(w.X[:, :feat])
+        Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+        gpu_lib.sptir_spmm(hyb, torch.from_numpy(X).cuda(), Y)
+        torch.cuda.synchronize()
+        say(f"[config] {name}: oracle on all {w.n_rows} rows at feat={feat}")
+        Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, X)
+        worst = assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"{name} feat={feat}")
+        say(f"[config] {name}: feat={feat} nnz={w.nnz} pads={info['n_pad_slots']} rem_nnz={info['n_rem_nnz']} "
+            f"list chunks={info['n_work_items']} heavy pieces={info['n_heavy_pieces']} rounds={info['rounds']} "
+            f"max_err={worst:.2e}")
+        del Yr, Sr
 
 
 def test_spmm_csr_ragged(gpu_lib):
@@ -278,24 +264,41 @@ def test_spmm_on_side_stream_and_repeat(gpu_lib):
 
 
 @pytest.mark.parametrize("knobs", [
-    {"SPTIR_WIDE_STREAM": "1"}, {"SPTIR_PARTS_PER_PHASE": "1"}, {"SPTIR_PARTS_PER_PHASE": "2", "SPTIR_WIDE_STREAM": "1"},
-    {"SPTIR_ROW_BLOCK": "8"}, {"SPTIR_ROW_BLOCK": "64", "SPTIR_PARTS_PER_PHASE": "3"}, {"SPTIR_ROW_BLOCK": "128"},
-    {"SPTIR_ROW_BLOCK": "256"}])
-def test_spmm_launch_plan_knobs(gpu_lib, monkeypatch, knobs):
-    """Every launch plan the builder can choose (record form, partitions per launch, rows per wavefront) computes
-    the same Y; two runs on one handle agree bit for bit (no atomics anywhere on the path)."""
+    {"wide_stream": 1}, {"parts_per_launch": 1}, {"parts_per_launch": 2, "wide_stream": 1},
+    {"row_block": 8}, {"row_block": 64, "parts_per_launch": 3}, {"row_block": 128}, {"row_block": 256},
+    {"rounds": 1}, {"rounds": 1, "heavy_len": 64}, {"rounds": 1, "heavy_len": 16, "wide_stream": 1},
+    {"rounds": 1, "row_block": 16, "heavy_len": 1}, {"rounds": 2, "parts_per_launch": 1, "heavy_len": 100},
+    {"rounds": 2, "heavy_len": 5000}, {"release_canonical": 1, "heavy_len": 70}])
+def test_spmm_launch_plan_knobs(gpu_lib, knobs):
+    """Every launch plan the builder can choose (record form, partitions per launch, rounds, rows per wavefront,
+    which pieces count as heavy) computes the same Y; two runs on one handle agree bit for bit (no atomics
+    anywhere on the path)."""
     say(f"[knobs] {knobs}")
-    for key, value in knobs.items():
-        monkeypatch.setenv(key, value)
     for feat, c, k in ((32, 5, 4), (7, 3, 2), (128, 4, 7)):
         w = ragged_workload(300 + feat, 2300, 2100, feat, max_deg=1500, long_rows=8)
-        d, hyb, got, want, info = build_both(gpu_lib, w, c, k)
-        assert_same_hyb(got, want)
-        if "SPTIR_PARTS_PER_PHASE" in knobs:
-            ppg = int(knobs["SPTIR_PARTS_PER_PHASE"])
-            assert info["n_phases"] == -(-c // ppg)
-        if "SPTIR_ROW_BLOCK" in knobs:
-            assert info["row_block"] == int(knobs["SPTIR_ROW_BLOCK"])
+        d = upload(w)
+        hyb = gpu_lib.sptir_hyb_build_ex(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, c, k, knobs)
+        info = gpu_lib.sptir_hyb_info(hyb)
+        if knobs.get("release_canonical"):
+            for name in ("ell_col", "ell_val", "rem_col", "rem_val"):
+                with pytest.raises(gpu_lib.SptirError) as e:
+                    gpu_lib.sptir_hyb_array(hyb, name)
+                assert e.value.status == 6
+            assert np.array_equal(gpu_lib.sptir_hyb_array(hyb, "ell_row"),
+                                  oracle.hyb_build(w.n_rows, w.n_cols, w.indptr, w.indices, w.values, c, k).ell_row)
+        else:
+            got, _ = fetch_hyb(gpu_lib, hyb)
+            assert_same_hyb(got, oracle.hyb_build(w.n_rows, w.n_cols, w.indptr, w.indices, w.values, c, k))
+        if "parts_per_launch" in knobs:
+            assert info["n_phases"] == -(-c // knobs["parts_per_launch"]) and info["rounds"] == 0
+        if knobs.get("rounds") == 1:
+            assert info["rounds"] == 1 and info["n_phases"] == 1
+        if "row_block" in knobs:
+            assert info["row_block"] == knobs["row_block"]
+        if "heavy_len" in knobs:
+            assert info["heavy_len"] == knobs["heavy_len"]
+            lens = np.diff(w.indptr)   # an upper bound: a heavy piece needs a row longer than heavy_len
+            assert (info["n_heavy_pieces"] > 0) == bool((lens > knobs["heavy_len"]).any()) or c > 1
         Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
         gpu_lib.sptir_spmm(hyb, d.X, Y)
         Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
@@ -305,31 +308,48 @@ def test_spmm_launch_plan_knobs(gpu_lib, monkeypatch, knobs):
         assert torch.equal(Y, Y2)
 
 
+def test_build_options_are_validated(gpu_lib):
+    w = ragged_workload(1, 50, 60, 4, max_deg=20)
+    d = upload(w)
+    for bad in ({"row_block": 48}, {"row_block": 512}, {"rounds": 3}, {"heavy_len": -1}, {"parts_per_launch": -2}):
+        with pytest.raises(gpu_lib.SptirError) as e:
+            gpu_lib.sptir_hyb_build_ex(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 2, 2, bad)
+        assert e.value.status == 1, bad
+    with pytest.raises(KeyError):
+        gpu_lib.sptir_hyb_build_ex(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 2, 2, {"no_such_field": 1})
+
+
 @pytest.mark.parametrize("feat", [128, 256, 320, 384, 520])
-def test_spmm_feature_sweeps(gpu_lib, monkeypatch, feat):
-    """A Y too wide for the memory-side cache is produced in several sweeps over the launches, each over a group
-    of 4 or 8 feature tiles; the limit is lowered here so that a small Y takes that path (feat = 320 and 520
-    have tile counts that do not split and run as one sweep)."""
+def test_spmm_feature_sweeps(gpu_lib, feat):
+    """Where every launch reads back the Y of the one before it (no rounds), a Y too wide for the memory-side
+    cache is produced in several sweeps over the launches, each over a group of 4 or 8 feature tiles; the limit
+    is lowered here so that a small Y takes that path (feat = 320 and 520 have tile counts that do not split and
+    run as one sweep)."""
     say(f"[feature sweeps] feat={feat}")
-    monkeypatch.setenv("SPTIR_PARTS_PER_PHASE", "1")
     w = ragged_workload(1300 + feat, 1500, 1800, feat, max_deg=900, long_rows=3)
-    d, hyb, got, want, info = build_both(gpu_lib, w, 3, 6)
-    assert info["n_phases"] == 3
     Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+    d, hyb, got, want, info = build_both(gpu_lib, w, 3, 6, {"parts_per_launch": 1})
+    assert info["n_phases"] == 3 and info["rounds"] == 0
     Y_one = torch.full((w.n_rows, feat), float("nan"), device="cuda")
     gpu_lib.sptir_spmm(hyb, d.X, Y_one)
     assert_y_close(Y_one.cpu().numpy(), Yr, Sr, what=f"one sweep feat={feat}")
-    for limit_mb in ("0.5", "0.0001"):   # 8 tiles of 1500 rows are 0.73 MB: sweeps of 4 tiles, then the same
-        monkeypatch.setenv("SPTIR_SWEEP_MB", limit_mb)
+    for limit_kb in (512, 1):   # 8 tiles of 1500 rows are 0.73 MB: sweeps of 4 tiles, then the same
+        hyb2 = gpu_lib.sptir_hyb_build_ex(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 3, 6,
+                                          {"parts_per_launch": 1, "sweep_kb": limit_kb})
         Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
-        gpu_lib.sptir_spmm(hyb, d.X, Y)
-        assert torch.equal(Y, Y_one), f"feat={feat} limit={limit_mb}"
+        gpu_lib.sptir_spmm(hyb2, d.X, Y)
+        assert torch.equal(Y, Y_one), f"feat={feat} limit={limit_kb} KB"
+    # the same matrix in rounds, wider than one partial-sum row of the heavy pieces
+    d, hyb3, got, want, info = build_both(gpu_lib, w, 3, 6, {"rounds": 1})
+    assert info["rounds"] == 1 and info["n_heavy_pieces"] > 0
+    Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+    gpu_lib.sptir_spmm(hyb3, d.X, Y)
+    assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"rounds feat={feat}")
 
 
 @pytest.mark.parametrize("c", [1, 2, 4, 9])
 def test_spmm_many_columns(gpu_lib, c):
-    """More than 2^20 columns per partition (c = 1, 2) cannot use launch-relative 20-bit columns; c = 4 can, but
-    only one partition per launch; c = 9 fits three."""
+    """More than 2^20 columns do not fit the 20-bit column field of the 8-byte stream records: 12-byte records."""
     n_rows, n_cols, feat = 700, 2_500_000, 4
     say(f"[many columns] c={c}")
     w = ragged_workload(900 + c, n_rows, n_cols, feat, max_deg=400, long_rows=4)
@@ -344,8 +364,8 @@ def test_spmm_many_columns(gpu_lib, c):
 @pytest.mark.parametrize("c,k,feat", [(1, 3, 32), (3, 5, 64), (2, 30, 8), (4, 11, 100), (1, 0, 3), (2, 4, 516)])
 def test_spmm_long_rows(gpu_lib, c, k, feat):
     """Rows with far more non-zeros than a wavefront's list should hold (remainder pieces, and ELL rows when k is
-    large) are cut into segments that a workgroup each sums (one workgroup per row when Y is wider than 512
-    floats); several long pieces of one row (c > 1) land in the same row of Y."""
+    large) are heavy pieces: their chunks run through many heavy lists, whose partial sums (also of several
+    heavy pieces of one row, c > 1, and of Y wider than one partial-sum row) land in the same row of Y."""
     say(f"[long rows] c={c} k={k} feat={feat}")
     w = ragged_workload(500 + c + k, 900, 40_000, feat, max_deg=30_000, long_rows=7)
     d, hyb, got, want, info = build_both(gpu_lib, w, c, k)
@@ -404,7 +424,7 @@ def test_launch_plan_query_matches_what_is_built(gpu_lib, name, feat):
                                          c_candidates=(w.n_col_parts,), max_bucket_log2=w.max_bucket_log2, reps=1)
     info = gpu_lib.sptir_hyb_info(hyb)
     plan = gpu_lib.sptir_launch_plan(w.n_rows, w.n_cols, info["n_ell_slots"] + info["n_rem_nnz"], w.n_col_parts, feat)
-    assert (plan["row_block"], plan["n_launches"]) == (info["row_block"], info["n_phases"])
+    assert (plan["row_block"], plan["n_launches"], plan["rounds"]) == (info["row_block"], info["n_phases"], info["rounds"])
 
 
 def test_spmm_and_sddmm_replay_in_a_hip_graph(gpu_lib):

@@ -18,26 +18,45 @@ MEDIUM = dict(n_rows=169343, n_cols=169343, stored_slots=1389517, n_col_parts=4)
 TINY = dict(n_rows=2708, n_cols=2708, stored_slots=11753, n_col_parts=1)
 
 
-def test_largest_configuration_takes_one_launch_per_partition():
-    # a partition's 128-byte column of X is 14,561 rows x 128 B = 1.86 MB: one fits an XCD's L2, two do not
+def test_largest_configuration_runs_in_rounds():
+    # a partition's 128-byte column of X is 14,561 rows x 128 B = 1.86 MB: one fits an XCD's L2, two do not, and
+    # with ~700 stored slots per row that locality is worth keeping: every list sweeps all 16 partitions in order
+    # and the lists run in rounds, Y written once
     p = sptir.sptir_launch_plan(feat=128, **SOCIAL)
-    assert p == dict(row_block=64, parts_per_launch=1, n_launches=16, compact_stream=1, n_feature_tiles=4,
-                     tiles_per_sweep=4, n_sweeps=1)
+    assert p == dict(row_block=128, parts_per_launch=16, n_launches=1, compact_stream=1, n_feature_tiles=4,
+                     tiles_per_sweep=4, n_sweeps=1, rounds=1)
+    # asked for explicitly, the older plan: a launch per partition, each reading back the Y of the one before
+    p = sptir.sptir_launch_plan(feat=128, options={"rounds": 2}, **SOCIAL)
+    assert (p["row_block"], p["parts_per_launch"], p["n_launches"], p["rounds"]) == (64, 1, 16, 0)
+    # the same when the pieces that would stay in the lists are long (the caller's knowledge of the matrix, or
+    # the builder's own histogram): nothing keeps the wavefronts of a round in step, and with long pieces that
+    # costs more than the round trips of Y
+    p = sptir.sptir_launch_plan(feat=128, options={"light_piece_len": 37}, **SOCIAL)
+    assert (p["parts_per_launch"], p["n_launches"], p["rounds"]) == (1, 16, 0)
+    p = sptir.sptir_launch_plan(feat=128, options={"light_piece_len": 8}, **SOCIAL)
+    assert p["rounds"] == 1
+    # naming the partitions per launch implies it
+    p = sptir.sptir_launch_plan(feat=128, options={"parts_per_launch": 1}, **SOCIAL)
+    assert (p["parts_per_launch"], p["n_launches"], p["rounds"]) == (1, 16, 0)
 
 
-def test_wide_y_is_swept_in_groups_of_feature_tiles():
+def test_wide_y_is_swept_in_groups_of_feature_tiles_without_rounds():
     # Y of 232,965 x 256 floats is 239 MB, more than the memory-side cache keeps between launches: two sweeps of
     # four tiles; 512 columns: four sweeps
-    assert sptir.sptir_launch_plan(feat=256, **SOCIAL)["tiles_per_sweep"] == 4
-    assert sptir.sptir_launch_plan(feat=256, **SOCIAL)["n_sweeps"] == 2
-    assert sptir.sptir_launch_plan(feat=512, **SOCIAL)["n_sweeps"] == 4
+    old = {"rounds": 2}
+    assert sptir.sptir_launch_plan(feat=256, options=old, **SOCIAL)["tiles_per_sweep"] == 4
+    assert sptir.sptir_launch_plan(feat=256, options=old, **SOCIAL)["n_sweeps"] == 2
+    assert sptir.sptir_launch_plan(feat=512, options=old, **SOCIAL)["n_sweeps"] == 4
     # 132,534 rows x 256 floats = 136 MB stays in one sweep, x 512 takes two of eight tiles
     protein = dict(n_rows=132534, n_cols=132534, stored_slots=56233393, n_col_parts=8)
-    assert sptir.sptir_launch_plan(feat=256, **protein)["n_sweeps"] == 1
-    p = sptir.sptir_launch_plan(feat=512, **protein)
+    assert sptir.sptir_launch_plan(feat=256, options=old, **protein)["n_sweeps"] == 1
+    p = sptir.sptir_launch_plan(feat=512, options=old, **protein)
     assert (p["tiles_per_sweep"], p["n_sweeps"]) == (8, 2)
     # a tile count that does not split into fours is not swept
-    assert sptir.sptir_launch_plan(feat=320, **SOCIAL)["n_sweeps"] == 1
+    assert sptir.sptir_launch_plan(feat=320, options=old, **SOCIAL)["n_sweeps"] == 1
+    # in rounds Y never makes a round trip, so nothing is swept
+    assert sptir.sptir_launch_plan(feat=512, **SOCIAL)["n_sweeps"] == 1
+    assert sptir.sptir_launch_plan(feat=512, **protein)["rounds"] == 1      # (piece lengths unknown to the query)
 
 
 def test_few_feature_tiles_take_smaller_row_blocks():
@@ -48,43 +67,40 @@ def test_few_feature_tiles_take_smaller_row_blocks():
 def test_low_degree_graphs_run_as_one_launch():
     # 8 stored slots per row do not pay for a read-modify-write of Y per partition
     p = sptir.sptir_launch_plan(feat=128, **MEDIUM)
-    assert (p["parts_per_launch"], p["n_launches"]) == (4, 1)
+    assert (p["parts_per_launch"], p["n_launches"], p["rounds"]) == (4, 1, 0)
     p = sptir.sptir_launch_plan(feat=64, **TINY)
     assert (p["n_launches"], p["n_sweeps"]) == (1, 1)
     assert p["row_block"] == 8          # 2,708 rows: small blocks, or the chip does not fill
 
 
 def test_many_columns_fall_back_to_wide_records():
-    # more than 2^20 columns in one partition do not fit the compact record
-    assert sptir.sptir_launch_plan(700, 2_500_000, 20000, 1, 4)["compact_stream"] == 0
-    assert sptir.sptir_launch_plan(700, 2_500_000, 20000, 2, 4)["compact_stream"] == 0
-    p = sptir.sptir_launch_plan(700, 2_500_000, 20000, 4, 4)
-    assert (p["compact_stream"], p["parts_per_launch"]) == (1, 1)
-    p = sptir.sptir_launch_plan(700, 2_500_000, 20000, 9, 4)
-    assert p["compact_stream"] == 1 and p["parts_per_launch"] * 277_778 <= 1 << 20
+    # a compact record holds a column in 20 bits (heavy lists cross partitions, so it is the absolute column)
+    for c in (1, 2, 4, 9):
+        assert sptir.sptir_launch_plan(700, 2_500_000, 20000, c, 4)["compact_stream"] == 0
+    assert sptir.sptir_launch_plan(700, 1 << 20, 20000, 2, 4)["compact_stream"] == 1
+    assert sptir.sptir_launch_plan(700, (1 << 20) + 1, 20000, 2, 4)["compact_stream"] == 0
 
 
-def test_environment_knobs(monkeypatch):
-    monkeypatch.setenv("SPTIR_ROW_BLOCK", "128")
-    monkeypatch.setenv("SPTIR_PARTS_PER_PHASE", "4")
-    p = sptir.sptir_launch_plan(feat=128, **SOCIAL)
-    assert (p["row_block"], p["parts_per_launch"], p["n_launches"]) == (128, 4, 4)
-    monkeypatch.setenv("SPTIR_ROW_BLOCK", "256")       # more rows than a compact record can address
-    assert sptir.sptir_launch_plan(feat=128, **SOCIAL)["compact_stream"] == 0
-    monkeypatch.delenv("SPTIR_ROW_BLOCK")
-    monkeypatch.setenv("SPTIR_WIDE_STREAM", "1")
-    assert sptir.sptir_launch_plan(feat=128, **SOCIAL)["compact_stream"] == 0
-    monkeypatch.delenv("SPTIR_WIDE_STREAM")
-    monkeypatch.delenv("SPTIR_PARTS_PER_PHASE")
-    monkeypatch.setenv("SPTIR_SWEEP_MB", "1")
-    assert sptir.sptir_launch_plan(feat=256, **SOCIAL)["tiles_per_sweep"] == 4
+def test_build_options_steer_the_plan():
+    p = sptir.sptir_launch_plan(feat=128, options={"row_block": 128, "parts_per_launch": 4}, **SOCIAL)
+    assert (p["row_block"], p["parts_per_launch"], p["n_launches"], p["rounds"]) == (128, 4, 4, 0)
+    # more rows than a compact record can address
+    assert sptir.sptir_launch_plan(feat=128, options={"row_block": 256}, **SOCIAL)["compact_stream"] == 0
+    assert sptir.sptir_launch_plan(feat=128, options={"wide_stream": 1}, **SOCIAL)["compact_stream"] == 0
+    p = sptir.sptir_launch_plan(feat=256, options={"rounds": 2, "sweep_kb": 1024}, **SOCIAL)
+    assert p["tiles_per_sweep"] == 4
+    # rounds can be forced on a graph that would not choose them
+    p = sptir.sptir_launch_plan(feat=128, options={"rounds": 1}, **MEDIUM)
+    assert (p["rounds"], p["parts_per_launch"], p["n_launches"]) == (1, 4, 1)
+    # the feature size hint sizes the row blocks: the query takes it from feat unless told otherwise
+    assert sptir.sptir_launch_plan(feat=128, options={"feat_hint": 32}, **SOCIAL)["row_block"] == 32
 
 
 def test_invalid_arguments():
     for args in ((-1, 5, 5, 1, 4), (5, -1, 5, 1, 4), (5, 5, -1, 1, 4), (5, 5, 5, 0, 4), (5, 5, 5, 1, 0)):
         with pytest.raises(sptir.SptirError):
             sptir.sptir_launch_plan(*args)
-    assert sptir.load_library().sptir_launch_plan(5, 5, 5, 1, 4, None) == 1
+    assert sptir.load_library().sptir_launch_plan(5, 5, 5, 1, 4, None, None) == 1
 
 
 def test_sddmm_partition_rule():
