@@ -12,6 +12,9 @@ smaller configurations are reported in extra keys of the same JSON line.
 from __future__ import annotations
 
 import argparse
+import ctypes
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -21,8 +24,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
-GATHER_PEAK_GBS = 39300.0  # 256 CUs x 64 B/clk x 2.4 GHz vector-memory return path (measured ~38.7 TB/s)
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+GATHER_THEORY_GBS = 39300.0    # 256 CUs x 64 B/clk x 2.4 GHz: what the vector-memory return path could carry
+FMA_PEAK_TFLOPS = 157.3        # fp32 vector, published (plain v_fma_f32 measures ~129 here: the packed forms are not needed)
 
 
 def bytes_min(nnz, n_rows, n_cols, feat):
@@ -35,6 +39,23 @@ def bytes_hyb(info, n_rows, n_cols, feat):
     every remainder non-zero and piece descriptor, X once, Y once."""
     return (8.0 * info["n_ell_slots"] + 4.0 * info["n_ell_rows"] + 8.0 * info["n_rem_nnz"] + 12.0 * info["n_rem_pieces"]
             + 4.0 * n_cols * feat + 4.0 * n_rows * feat)
+
+
+def bytes_build(info, nnz, n_rows):
+    """Algorithmic bytes of sptir_hyb_build: the CSR read twice (validation; count and scatter share a pass over
+    the column ids, the scatter also reads the values), the canonical slots written, read again and written as
+    the SpMM stream (real entries only)."""
+    slots = info["n_ell_slots"] + info["n_rem_nnz"]
+    return 4.0 * nnz + 4.0 * nnz + 8.0 * nnz + 8.0 * slots + 8.0 * nnz + 8.0 * nnz + 8.0 * n_rows
+
+
+def source_fingerprint():
+    """Hash of the HIP sources: a profile summary taken on other sources says nothing about this build."""
+    h = hashlib.sha1()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2207_04606_amd", "csrc", "*"))):
+        if path.endswith((".hip", ".h")):
+            h.update(open(path, "rb").read())
+    return h.hexdigest()[:12]
 
 
 def time_spmm(sptir, torch, hyb, X, Y, steps, warmup):
@@ -52,6 +73,34 @@ def time_spmm(sptir, torch, hyb, X, Y, steps, warmup):
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     event_ms = e0.elapsed_time(e1) / steps
     return wall_ms, event_ms
+
+
+def median_spmm_ms(sptir, torch, hyb, X, Y, steps):
+    """Median over single steps, each bracketed by its own pair of events (no host synchronisation in between)."""
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for e0, e1 in events:
+        e0.record()
+        sptir.sptir_spmm(hyb, X, Y)
+        e1.record()
+    torch.cuda.synchronize()
+    times = sorted(e0.elapsed_time(e1) for e0, e1 in events)
+    return times[len(times) // 2]
+
+
+def kernel_times(sptir, torch, hyb, X, Y, reps):
+    """Mean time of each group of launches inside sptir_spmm (HIP events on the launch stream, recorded by the
+    library between its launches) and the launch counts."""
+    acc = None
+    for _ in range(reps):
+        t = sptir.sptir_spmm_timed(hyb, X, Y)
+        if acc is None:
+            acc = dict(t)
+        else:
+            for k in ("ms_lists", "ms_heavy", "ms_reduce"):
+                acc[k] += t[k]
+    for k in ("ms_lists", "ms_heavy", "ms_reduce"):
+        acc[k] /= reps
+    return acc
 
 
 def time_graph_replay(sptir, torch, hyb, X, Y, calls_per_graph, replays):
@@ -96,20 +145,59 @@ def upload(torch, w):
             torch.from_numpy(w.values).to(dev))
 
 
-def read_traffic(key):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, if one covers `key`."""
+def read_traffic(key, fingerprint):
+    """Bytes that crossed the L2 boundary per launch of the dominant kernel, from the committed rocprofv3 counter
+    summary.  Returns (bytes or None, note): the figure only counts if the summary was taken on these sources."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if not os.path.exists(path):
-        return None
+        return None, "no profiles/hbm_traffic.txt"
+    stamp, value = None, None
     for line in open(path):
         parts = line.split()
+        if len(parts) >= 2 and parts[0] == "sources":
+            stamp = parts[1]
         if len(parts) >= 2 and parts[0] == key:
-            return float(parts[1])
-    return None
+            value = float(parts[1])
+    if value is None:
+        return None, "profiles/hbm_traffic.txt has no line for " + key
+    if stamp != fingerprint:
+        return None, f"profiles/hbm_traffic.txt was taken on sources {stamp}, this build is {fingerprint}: stale"
+    return value, f"profiles/hbm_traffic.txt, sources {stamp}"
 
 
-def cpu_baseline(oracle, np, w, X_host, feat, budget_s=12.0):
-    """The fp64 oracle, untuned, on a bounded sample of rows of the same workload."""
+def gather_roof(sptir, torch, dev, quick=True):
+    """Measured rate of random 128-byte row gathers (the access every stored non-zero costs) for working sets that
+    sit in L1, in one XCD's L2 (the case of the SpMM kernels: a partition's slice of one feature tile), in the
+    memory-side cache and in HBM, and over wavefronts per SIMD; plus the float32 FMA rate."""
+    rows_max = 1 << (18 if quick else 21)
+    X = torch.zeros(rows_max, 128, device=dev)
+    sink = torch.zeros(16, device=dev)
+    out = {"working_set_sweep": [], "occupancy_sweep": []}
+
+    def run(n_rows, tiles, wgs, iters):
+        ms, nbytes = sptir.sptir_roof_gather(X, n_rows, tiles, wgs, iters, sink)
+        return nbytes / ms / 1e6
+
+    sets = [(64, "L1: 8 KB per XCD and tile"), (1024, "0.13 MB"), (14561, "1.86 MB: one partition of the largest graph"),
+            (32768, "4.2 MB"), (1 << 18, "33.5 MB: memory-side cache")]
+    if not quick:
+        sets.append((1 << 21, "268 MB per tile: HBM"))
+    for n_rows, what in sets:
+        gbs = run(n_rows, 4, 4096, 128)
+        out["working_set_sweep"].append({"rows": n_rows, "bytes_per_xcd": n_rows * 128, "what": what,
+                                         "gbs": round(gbs, 1)})
+    for wgs in (256, 512, 768, 1024, 2048, 4096):
+        out["occupancy_sweep"].append({"workgroups": wgs, "wavefronts_per_simd": wgs * 4 / 1024.0,
+                                       "gbs_at_1.86MB": round(run(14561, 4, wgs, 512), 1)})
+    out["l2_resident_gbs"] = max(p["gbs_at_1.86MB"] for p in out["occupancy_sweep"])
+    out["theory_gbs"] = GATHER_THEORY_GBS
+    ms, flops = sptir.sptir_roof_fma(8192, 4096, sink)
+    out["fma_tflops"] = round(flops / ms / 1e9, 2)
+    return out
+
+
+def cpu_baseline(oracle, np, w, X_host, feat, budget_s=10.0):
+    """The fp64 oracle, untuned, on a bounded sample of rows of the same workload: all host threads, then one."""
     rng = np.random.default_rng(1)
     rows = rng.permutation(w.n_rows).astype(np.int32)
     deg = np.diff(w.indptr)
@@ -126,9 +214,25 @@ def cpu_baseline(oracle, np, w, X_host, feat, budget_s=12.0):
     Yr, Sr = oracle.spmm_csr_rows(sel, w.indptr, w.indices, w.values, X_host)
     dt = time.perf_counter() - t0
     nnz_sel = int(deg[sel].sum())
-    return dict(value=2.0 * nnz_sel * feat / dt / 1e9, unit="GFLOP/s", cores=oracle.num_threads(), kind="oracle",
+    threads = oracle.num_threads()
+    base = dict(value=2.0 * nnz_sel * feat / dt / 1e9, unit="GFLOP/s", cores=threads, kind="oracle",
                 sample=f"{n_sel} random rows ({nnz_sel} non-zeros) of the same graph and X, feat={feat}, "
-                       f"{dt:.1f} s, fp64, OpenMP over rows"), sel, Yr, Sr
+                       f"{dt:.1f} s, fp64, OpenMP over rows")
+    # one thread, on a sample a thread's worth as large (the OpenMP runtime the oracle links is told so; the
+    # oracle itself is untouched)
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+        gomp.omp_set_num_threads(1)
+        one = rows[:max(500, n_sel // max(threads, 1))]
+        t0 = time.perf_counter()
+        oracle.spmm_csr_rows(one, w.indptr, w.indices, w.values, X_host)
+        dt1 = time.perf_counter() - t0
+        gomp.omp_set_num_threads(threads)
+        base["one_thread_gflops"] = round(2.0 * int(deg[one].sum()) * feat / dt1 / 1e9, 2)
+        base["one_thread_sample"] = f"{one.size} of those rows, {dt1:.1f} s"
+    except OSError:
+        base["one_thread_gflops"] = None
+    return base, sel, Yr, Sr
 
 
 def main():
@@ -140,6 +244,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM bytes) to scale profiler byte counters")
+    ap.add_argument("--gather-roof", action="store_true",
+                    help="only the gather / FMA roof microbenchmarks (full sweep), one JSON line")
+    ap.add_argument("--workload", default="social", help="headline workload for profiling runs (default: social)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (every box has one); run with --gpus 1", file=sys.stderr)
@@ -157,6 +264,10 @@ def main():
     sptir.load_library()   # no fallback: raises if the HIP library is not built
     dev = torch.device("cuda:0")
 
+    if args.gather_roof:
+        print(json.dumps({"gather_roof": gather_roof(sptir, torch, dev, quick=False)}))
+        return
+
     if args.copy_calibration:
         src = torch.ones(256 * 1024 * 1024, device=dev)   # 1 GiB written by the fill kernel
         dst = torch.empty_like(src)
@@ -165,24 +276,27 @@ def main():
         del src, dst
 
     # ---------------------------------------------------------------- headline
-    w = workloads.make_config("social")
+    w = workloads.make_config(args.workload)
     indptr, indices, values = upload(torch, w)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     hyb = sptir.sptir_hyb_build(w.n_rows, w.n_cols, indptr, indices, values, w.n_col_parts, w.max_bucket_log2)
     torch.cuda.synchronize()
     build_first_ms = (time.perf_counter() - t0) * 1e3
-    t0 = time.perf_counter()
-    hyb2 = sptir.sptir_hyb_build(w.n_rows, w.n_cols, indptr, indices, values, w.n_col_parts, w.max_bucket_log2)
-    torch.cuda.synchronize()
-    build_ms = (time.perf_counter() - t0) * 1e3
-    hyb2.destroy()
+    build_times = []
+    for _ in range(3):
+        t0 = time.perf_counter()
+        hyb2 = sptir.sptir_hyb_build(w.n_rows, w.n_cols, indptr, indices, values, w.n_col_parts, w.max_bucket_log2)
+        torch.cuda.synchronize()
+        build_times.append((time.perf_counter() - t0) * 1e3)
+        hyb2.destroy()
+    build_ms = sorted(build_times)[1]
     info = sptir.sptir_hyb_info(hyb)
 
     results = {}
     X_host_128 = None
     for feat in (128, 256):
-        if feat == 256 and args.no_extras:
+        if feat == 256 and (args.no_extras or args.workload != "social"):
             continue
         if feat == w.feat:
             Xh = w.X
@@ -196,9 +310,11 @@ def main():
         flops = 2.0 * w.nnz * feat
         bmin = bytes_min(w.nnz, w.n_rows, w.n_cols, feat)
         results[feat] = dict(wall_ms=wall_ms, event_ms=event_ms, gflops=flops / wall_ms / 1e6,
+                             median_ms=median_spmm_ms(sptir, torch, hyb, X, Y, args.steps),
                              bmin_gbs=bmin / event_ms / 1e6, bmin=bmin,
                              # one row of X (feat * 4 bytes) is gathered per non-zero; bucket pads are not walked
                              gather_gbs=w.nnz * feat * 4.0 / event_ms / 1e6,
+                             kernels=kernel_times(sptir, torch, hyb, X, Y, 5) if feat == 128 else None,
                              Y=Y if feat == 128 else None)
         if feat == 256:
             del X, Y
@@ -207,40 +323,89 @@ def main():
     out = {
         "metric": "SpMM GFLOP/s and achieved HBM GB/s (% of peak) at feat=128, 1 MI355X",
         "value": round(head["gflops"], 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(head["wall_ms"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(head["wall_ms"], 4), "median_ms_per_step": round(head["median_ms"], 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "largest graph of the set (social-like: 232,965 rows, %d non-zeros, power-law "
                                "degrees, values 1/deg) decomposed as hyb(c=16, k=11), X 232,965 x 128 fp32 N(0,1); "
-                               "Y = A X per step" % w.nnz,
+                               "Y = A X per step" % w.nnz if args.workload == "social" else args.workload,
                    "n_rows": w.n_rows, "nnz": w.nnz, "feat": 128, "n_col_parts": w.n_col_parts,
                    "max_bucket_log2": w.max_bucket_log2, "stored_slots": info["n_ell_slots"] + info["n_rem_nnz"],
-                   "pad_slots": info["n_pad_slots"], "walked_slots": info["n_work_items"] * info["item_slots"],
-                   "kernel_launches_per_step": info["n_phases"],
-                   "row_block": info["row_block"]},
+                   "pad_slots": info["n_pad_slots"],
+                   "walked_slots": (info["n_work_items"] + info["n_heavy_items"]) * info["item_slots"],
+                   "rounds": info["rounds"], "row_block": info["row_block"], "heavy_len": info["heavy_len"],
+                   "heavy_pieces": info["n_heavy_pieces"], "heavy_nnz": info["n_heavy_nnz"],
+                   "values_per_row": info["values_per_row"]},
         "hbm_gbs_min_model": round(head["bmin_gbs"], 1),
         "hbm_gbs_hyb_model": round(bytes_hyb(info, w.n_rows, w.n_cols, 128) / head["event_ms"] / 1e6, 1),
-        "hbm_gbs_measured": None,
         "hbm_pct_of_peak": round(100.0 * head["bmin_gbs"] / HBM_PEAK_GBS, 2),
+        "target_note": "the 60 %-of-HBM target under the minimal byte model is missed: the path is a cache-served "
+                       "gather (one 128-byte row of X per non-zero and feature tile through the vector-memory path), "
+                       "see roofline.binding_roof",
         "hyb_build_ms": round(build_ms, 3), "hyb_build_first_call_ms": round(build_first_ms, 3),
-    }
-    # dominant kernel: k_spmm_hyb, launched once per phase; events bracket all launches of a step
-    per_launch_ms = head["event_ms"] / info["n_phases"]
-    per_launch_bytes = head["bmin"] / info["n_phases"]
-    out["roofline"] = {
-        "bound": "hbm", "achieved": round(per_launch_bytes / per_launch_ms / 1e6, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(per_launch_bytes / per_launch_ms / 1e6 / HBM_PEAK_GBS, 4),
-        "traffic": read_traffic("social_feat128"),
-        "kernel": "k_spmm_hyb<4, 8, true, false>", "launches_per_step": info["n_phases"],
-        "avg_launch_ms": round(per_launch_ms, 4), "algorithmic_bytes_per_launch": per_launch_bytes,
-        # the path is a cache-served gather, not an HBM stream: each non-zero pulls feat*4 bytes of X
-        # through the vector-memory return path, whose peak is 64 B/clk/CU
-        "binding_roof": {"name": "vector-memory gather (L2 -> VGPR)", "achieved_gbs": round(head["gather_gbs"], 1),
-                         "peak_gbs": GATHER_PEAK_GBS, "frac": round(head["gather_gbs"] / GATHER_PEAK_GBS, 4)},
+        "hyb_build": {"ms": round(build_ms, 3), "algorithmic_bytes": bytes_build(info, w.nnz, w.n_rows),
+                      "gbs": round(bytes_build(info, w.nnz, w.n_rows) / build_ms / 1e6, 1),
+                      "frac_of_hbm_peak": round(bytes_build(info, w.nnz, w.n_rows) / build_ms / 1e6 / HBM_PEAK_GBS, 4),
+                      "device_bytes": info["device_bytes"]},
     }
 
-    if out["roofline"]["traffic"]:
-        # bytes that crossed the L2 boundary per second (rocprofv3 counters of the committed profile run)
-        out["hbm_gbs_measured"] = round(out["roofline"]["traffic"] / per_launch_ms / 1e6, 1)
+    # ------------------------------------------------------------- roofline
+    # The dominant kernel is whichever group of launches takes longer inside a call; its launches are timed live
+    # by HIP events the library records on the launch stream between its launches.
+    kt = head["kernels"]
+    fingerprint = source_fingerprint()
+    feat = 128
+    if kt["ms_heavy"] >= kt["ms_lists"]:
+        kernel, n_launch, ms = "k_spmm_heavy<4, 8, true, false, %s>" % ("true" if info["values_per_row"] else "false"), \
+            kt["n_heavy_launches"], kt["ms_heavy"]
+        # its share of the minimal byte model: the heavy pieces' entries once, X once, its partial sums written
+        alg_bytes = (8.0 * info["n_heavy_nnz"] + 4.0 * w.n_cols * feat +
+                     4.0 * feat * (info["n_heavy_pieces"] + info["n_heavy_lists"]))
+        gathered = info["n_heavy_nnz"] * feat * 4.0
+        key = args.workload + "_feat128_k_spmm_heavy"
+    else:
+        kernel, n_launch, ms = "k_spmm_hyb<4, 8, true, false, %s>" % ("true" if info["values_per_row"] else "false"), \
+            kt["n_list_launches"], kt["ms_lists"]
+        light_nnz = w.nnz - info["n_heavy_nnz"]
+        x_reads = kt["n_list_launches"] if info["rounds"] else 1     # every round sweeps all of X
+        alg_bytes = 8.0 * light_nnz + 4.0 * w.n_cols * feat * x_reads + 4.0 * w.n_rows * feat
+        gathered = light_nnz * feat * 4.0
+        key = args.workload + "_feat128_k_spmm_hyb"
+    per_launch_ms = ms / max(n_launch, 1)
+    traffic, traffic_note = read_traffic(key, fingerprint)
+    out["roofline"] = {
+        "bound": "hbm", "achieved": round(alg_bytes / ms / 1e6, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(alg_bytes / ms / 1e6 / HBM_PEAK_GBS, 4),
+        "traffic": traffic, "traffic_source": traffic_note,
+        "kernel": kernel, "launches_per_step": n_launch,
+        "avg_launch_ms": round(per_launch_ms, 4), "algorithmic_bytes_per_launch": alg_bytes / max(n_launch, 1),
+        "kernel_ms_per_step": {"k_spmm_hyb": round(kt["ms_lists"], 4), "k_spmm_heavy": round(kt["ms_heavy"], 4),
+                               "k_heavy_reduce": round(kt["ms_reduce"], 4),
+                               "launches": [kt["n_list_launches"], kt["n_heavy_launches"], kt["n_reduce_launches"]]},
+        "whole_call": {"achieved": round(head["bmin_gbs"], 1), "frac": round(head["bmin_gbs"] / HBM_PEAK_GBS, 4),
+                       "algorithmic_bytes": head["bmin"]},
+        "sources": fingerprint,
+    }
+    # the path is a cache-served gather, not an HBM stream: each non-zero pulls feat*4 bytes of X through the
+    # vector-memory return path.  Its roof is measured here, on this GPU, by the library's microbenchmark.
+    roof = gather_roof(sptir, torch, dev, quick=True)
+    out["roofline"]["binding_roof"] = {
+        "name": "vector-memory gather of 128-byte rows of X out of an XCD's L2",
+        "kernel_gathered_gbs": round(gathered / ms / 1e6, 1),
+        "measured_l2_resident_gbs": roof["l2_resident_gbs"], "theory_gbs": GATHER_THEORY_GBS,
+        "frac_of_measured": round(gathered / ms / 1e6 / roof["l2_resident_gbs"], 4),
+        "frac_of_theory": round(gathered / ms / 1e6 / GATHER_THEORY_GBS, 4),
+        "whole_call_gathered_gbs": round(head["gather_gbs"], 1),
+        "whole_call_frac_of_measured": round(head["gather_gbs"] / roof["l2_resident_gbs"], 4),
+        "fma_tflops_measured": roof["fma_tflops"], "fma_tflops_peak": FMA_PEAK_TFLOPS,
+        "fma_frac": round(2.0 * w.nnz * feat / head["event_ms"] / 1e9 / FMA_PEAK_TFLOPS, 4),
+    }
+    out["gather_roof"] = roof
+    if traffic:
+        # bytes that crossed the L2 boundary per second during the dominant kernel
+        out["hbm_gbs_measured"] = round(traffic / per_launch_ms / 1e6, 1)
+    else:
+        out["hbm_gbs_measured"] = None
 
     # ------------------------------------------------- CPU oracle beside it
     if not args.no_cpu:
@@ -252,15 +417,23 @@ def main():
         out["max_normalised_error_vs_oracle"] = float((np.abs(Yg - Yr)[nz] / Sr[nz]).max())
     head["Y"] = None
 
-    if not args.no_extras:
+    if not args.no_extras and args.workload == "social":
         r256 = results[256]
         out["as_written_feat256"] = {"gflops": round(r256["gflops"], 1), "ms_per_step": round(r256["wall_ms"], 4),
+                                     "median_ms_per_step": round(r256["median_ms"], 4),
                                      "hbm_gbs_min_model": round(r256["bmin_gbs"], 1),
                                      "gather_gbs": round(r256["gather_gbs"], 1)}
         scratch = torch.zeros(256 * 1024 * 1024, device=dev)
         X = torch.from_numpy(X_host_128).to(dev)
         Y = torch.empty(w.n_rows, 128, device=dev)
         out["cold_ms_per_step"] = round(time_cold(sptir, torch, hyb, X, Y, 10, scratch), 4)
+        # the same matrix with a value stored per entry, and with a launch per partition instead of rounds
+        for name, opts in (("values_kept", {"keep_values": 1}), ("launch_per_partition", {"rounds": 2})):
+            hv = sptir.sptir_hyb_build_ex(w.n_rows, w.n_cols, indptr, indices, values, w.n_col_parts,
+                                          w.max_bucket_log2, opts)
+            vw, _ = time_spmm(sptir, torch, hv, X, Y, 20, 3)
+            out[name] = {"ms_per_step": round(vw, 4), "gflops": round(2.0 * w.nnz * 128 / vw / 1e6, 1)}
+            hv.destroy()
         # the single-pass CSR kernel ("no-hyb") on the same graph and X, for the comparison section 4.2.1 makes
         for _ in range(3):
             sptir.sptir_spmm_csr(w.n_rows, w.n_cols, indptr, indices, values, X, Y)
@@ -313,24 +486,34 @@ def main():
                                 "gather_gbs": round(w.nnz * 512.0 / sddmm_ms / 1e6, 1),
                                 "csr_order_ms_per_step": round(sddmm_csr_ms, 4)}
         del Xl, Bv
-        # relational gather-matmul-scatter on a synthetic heterogeneous graph (51 relations, feature size 32)
-        hw = workloads.make_hetero("hetero_d")
-        hip_, hix, hva = (torch.from_numpy(a).to(dev) for a in (hw.indptr, hw.indices, hw.values))
-        t0 = time.perf_counter()
-        rg = sptir.sptir_rgms_build(hw.n_rel, hw.n, hw.n, hip_, hix, hva)
-        torch.cuda.synchronize()
-        rg_build_ms = (time.perf_counter() - t0) * 1e3
-        rinfo = sptir.sptir_rgms_info(rg)
-        hX, hW = torch.from_numpy(hw.X).to(dev), torch.from_numpy(hw.W).to(dev)
-        hY = torch.empty(hw.n, 32, device=dev)
-        rg_ms = timed(lambda: sptir.sptir_rgms(rg, hX, hW, hY), reps=20)
-        pairs = rinfo["n_stacked_rows_stored"]
-        out["rgms_feat32"] = {"workload": "%d nodes, %d relations, %d non-zeros, d_in = d_out = 32" % (hw.n, hw.n_rel, hw.nnz),
-                              "ms_per_step": round(rg_ms, 4), "build_ms": round(rg_build_ms, 3),
-                              "gflops": round((2.0 * hw.nnz * 32 + 2.0 * pairs * 32 * 32) / rg_ms / 1e6, 1),
-                              "scatter_gbs": round(pairs * 128.0 / rg_ms / 1e6, 1), "tiles": rinfo["n_tiles"]}
-        rg.destroy()
-        del hX, hW, hY, hip_, hix, hva
+        # relational gather-matmul-scatter on two synthetic heterogeneous graphs (feature size 32)
+        out["rgms_feat32"] = []
+        for hname in ("hetero_d", "hetero_e"):
+            hw = workloads.make_hetero(hname)
+            hip_, hix, hva = (torch.from_numpy(a).to(dev) for a in (hw.indptr, hw.indices, hw.values))
+            t0 = time.perf_counter()
+            rg = sptir.sptir_rgms_build(hw.n_rel, hw.n, hw.n, hip_, hix, hva)
+            torch.cuda.synchronize()
+            rg_build_ms = (time.perf_counter() - t0) * 1e3
+            rinfo = sptir.sptir_rgms_info(rg)
+            hX, hW = torch.from_numpy(hw.X).to(dev), torch.from_numpy(hw.W).to(dev)
+            hY = torch.empty(hw.n, 32, device=dev)
+            rg_ms = timed(lambda: sptir.sptir_rgms(rg, hX, hW, hY), reps=20)
+            pairs = rinfo["n_stacked_rows_stored"]
+            # algorithmic bytes: a 128-byte row of X in per non-zero, a 128-byte row of Y out per (relation, row)
+            # pair, 8 bytes per stored slot, W once
+            slots = hw.nnz + rinfo["n_pad_slots"]
+            rg_bytes = 128.0 * hw.nnz + 128.0 * pairs + 8.0 * slots + 4.0 * hw.W.size
+            out["rgms_feat32"].append({
+                "workload": "%s: %d nodes, %d relations, %d non-zeros, d_in = d_out = 32" % (hname, hw.n, hw.n_rel, hw.nnz),
+                "ms_per_step": round(rg_ms, 4), "build_ms": round(rg_build_ms, 3),
+                "gflops": round((2.0 * hw.nnz * 32 + 2.0 * pairs * 32 * 32) / rg_ms / 1e6, 1),
+                "scatter_gbs": round(pairs * 128.0 / rg_ms / 1e6, 1), "tiles": rinfo["n_tiles"],
+                "roofline": {"bound": "hbm", "achieved": round(rg_bytes / rg_ms / 1e6, 1), "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": round(rg_bytes / rg_ms / 1e6 / HBM_PEAK_GBS, 4),
+                             "algorithmic_bytes": rg_bytes}})
+            rg.destroy()
+            del hX, hW, hY, hip_, hix, hva
         del X, Y
         hyb.destroy()
         del indptr, indices, values
@@ -338,13 +521,13 @@ def main():
         for name in ("tiny", "small", "medium", "protein"):
             wc = workloads.make_config(name)
             ip, ix, va = upload(torch, wc)
-            # (the first build at a new size loads kernels of the sort library: time the second)
             sptir.sptir_hyb_build(wc.n_rows, wc.n_cols, ip, ix, va, wc.n_col_parts, wc.max_bucket_log2).destroy()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             hc = sptir.sptir_hyb_build(wc.n_rows, wc.n_cols, ip, ix, va, wc.n_col_parts, wc.max_bucket_log2)
             torch.cuda.synchronize()
             b_ms = (time.perf_counter() - t0) * 1e3
+            ci = sptir.sptir_hyb_info(hc)
             X = torch.from_numpy(wc.X).to(dev)
             Y = torch.empty(wc.n_rows, wc.feat, device=dev)
             wall_ms, event_ms = time_spmm(sptir, torch, hc, X, Y, 100, 10)
@@ -353,9 +536,13 @@ def main():
             others.append({"config": name, "nnz": wc.nnz, "feat": wc.feat,
                            "gflops": round(2.0 * wc.nnz * wc.feat / wall_ms / 1e6, 1),
                            "ms_per_step": round(wall_ms, 4),
+                           "median_ms_per_step": round(median_spmm_ms(sptir, torch, hc, X, Y, 50), 4),
                            "graph_replay_ms_per_step": round(time_graph_replay(sptir, torch, hc, X, Y, 10, 20), 4),
                            "cold_ms_per_step": round(cold, 4),
-                           "hbm_gbs_min_model_cold": round(bm / cold / 1e6, 1), "hyb_build_ms": round(b_ms, 3)})
+                           "hbm_gbs_min_model_cold": round(bm / cold / 1e6, 1),
+                           "hbm_frac_cold": round(bm / cold / 1e6 / HBM_PEAK_GBS, 4),
+                           "rounds": ci["rounds"], "launches": ci["n_phases"], "heavy_pieces": ci["n_heavy_pieces"],
+                           "hyb_build_ms": round(b_ms, 3)})
             hc.destroy()
         out["other_configs"] = others
     print(json.dumps(out))

@@ -108,8 +108,11 @@ typedef struct {
                                partitions, each adding to the Y of the one before */
   int64_t n_heavy_pieces;   /* row pieces with more than heavy_len real entries: summed by a launch of their own */
   int64_t n_heavy_items;    /* their 64-slot chunks */
+  int64_t n_heavy_nnz;      /* their real entries */
   int32_t heavy_len;
   int32_t n_heavy_lists;    /* wavefronts of that launch per feature tile */
+  int32_t values_per_row;   /* 1: every row of A has one value for all its entries and the SpMM stream holds none */
+  int32_t reserved;
   int64_t device_bytes;     /* device memory the handle owns */
 } sptir_hyb_info_t;
 
@@ -157,6 +160,9 @@ typedef struct {
   int32_t release_canonical;  /* 1: free ELL_COL, ELL_VAL, REM_COL and REM_VAL once the SpMM stream is packed
                                  (sptir_hyb_array then reports SPTIR_ERR_UNSUPPORTED for them) */
   int32_t no_spmm_plan;       /* 1: canonical arrays only; sptir_spmm refuses the handle */
+  int32_t keep_values;        /* 1: the SpMM stream stores a value per entry even where every row of A has one
+                                 value for all its entries (otherwise such a matrix is stored without values and
+                                 the rows of Y are scaled at the end: half the stream bytes) */
   int32_t light_piece_len;    /* mean real length of the row pieces of at most 64 entries, if the caller knows it
                                  (sptir_hyb_build takes it from its histogram); 0: unknown, taken to be short.
                                  Rounds are chosen when it is below 16: Y round trips then cost more than the
@@ -236,6 +242,38 @@ sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_
  * 2^31 workgroups), HIP.
  */
 sptir_status_t sptir_spmm(const sptir_hyb_t* hyb, const float* X, float* Y, int32_t feat, void* stream);
+
+/*
+ * Measurement aid: sptir_spmm with HIP events recorded on `stream` between its groups of launches, so that a
+ * benchmark can price each kernel by the time it really took inside the call.  Synchronises `stream` before it
+ * returns; creates and destroys a few events.  Same results as sptir_spmm.
+ *   ms_lists   the chunk-list launches (k_spmm_hyb), n_list_launches of them
+ *   ms_heavy   the heavy-piece launches (k_spmm_heavy)
+ *   ms_reduce  the launches that add the heavy pieces' partial sums to Y (k_heavy_reduce)
+ */
+typedef struct {
+  float ms_lists, ms_heavy, ms_reduce;
+  int32_t n_list_launches, n_heavy_launches, n_reduce_launches;
+} sptir_spmm_times_t;
+sptir_status_t sptir_spmm_timed(const sptir_hyb_t* hyb, const float* X, float* Y, int32_t feat, void* stream,
+                                sptir_spmm_times_t* out);
+
+/*
+ * The two on-chip roofs the SpMM kernels are priced against, measured on the current device (Section 4.2.1
+ * names the cache hit rate of X as what column partitions buy; what a hit then costs is this gather rate).
+ * sptir_roof_gather: every group of 8 lanes of n_workgroups x 4 wavefronts reads one 128-byte line (16 bytes a
+ * lane, 8 loads in flight) of a random row of X[0 .. n_rows) (row_floats floats per row, 16-byte aligned),
+ * iters x 8 times; `tiles` > 1 spreads the lines over that many 32-float feature tiles, bound to workgroup id
+ * modulo 8 like the SpMM kernels bind tiles to XCDs.  *ms_out receives the time of one launch (after one
+ * untimed launch), *bytes_out the bytes it gathered.  sptir_roof_fma: n_workgroups x 256 lanes issue iters x 8
+ * independent float32 FMAs; *flops_out receives 2 flops per FMA.  `sink` is a device float the kernels may
+ * write (they all but never do).  Both create two events and synchronise `stream`.
+ */
+sptir_status_t sptir_roof_gather(const float* X, int64_t n_rows, int32_t row_floats, int32_t tiles,
+                                 int32_t n_workgroups, int32_t iters, float* sink, void* stream, float* ms_out,
+                                 double* bytes_out);
+sptir_status_t sptir_roof_fma(int32_t n_workgroups, int32_t iters, float* sink, void* stream, float* ms_out,
+                              double* flops_out);
 
 /*
  * sptir_spmm for callers that cannot allocate device memory or let a library do so: code under HIP graph

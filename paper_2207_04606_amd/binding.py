@@ -46,15 +46,16 @@ class _Info(ctypes.Structure):
                 ("n_rem_pieces", ctypes.c_int64), ("n_rem_nnz", ctypes.c_int64),
                 ("n_work_items", ctypes.c_int64), ("item_slots", ctypes.c_int32),
                 ("row_block", ctypes.c_int32), ("n_phases", ctypes.c_int32), ("rounds", ctypes.c_int32),
-                ("n_heavy_pieces", ctypes.c_int64), ("n_heavy_items", ctypes.c_int64),
-                ("heavy_len", ctypes.c_int32), ("n_heavy_lists", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
+                ("n_heavy_pieces", ctypes.c_int64), ("n_heavy_items", ctypes.c_int64), ("n_heavy_nnz", ctypes.c_int64),
+                ("heavy_len", ctypes.c_int32), ("n_heavy_lists", ctypes.c_int32), ("values_per_row", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
 
 
 class _BuildOptions(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_int32), ("feat_hint", ctypes.c_int32), ("row_block", ctypes.c_int32),
                 ("parts_per_launch", ctypes.c_int32), ("rounds", ctypes.c_int32), ("wide_stream", ctypes.c_int32),
                 ("heavy_len", ctypes.c_int32), ("sweep_kb", ctypes.c_int32), ("release_canonical", ctypes.c_int32),
-                ("no_spmm_plan", ctypes.c_int32), ("light_piece_len", ctypes.c_int32)]
+                ("no_spmm_plan", ctypes.c_int32), ("keep_values", ctypes.c_int32), ("light_piece_len", ctypes.c_int32)]
 
 
 def _options(options):
@@ -97,7 +98,13 @@ _FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 _lib = None
 _hip = None
 
-EXPORTED_SYMBOLS = ("sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_build_ex", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
+class _SpmmTimes(ctypes.Structure):
+    _fields_ = [("ms_lists", ctypes.c_float), ("ms_heavy", ctypes.c_float), ("ms_reduce", ctypes.c_float),
+                ("n_list_launches", ctypes.c_int32), ("n_heavy_launches", ctypes.c_int32),
+                ("n_reduce_launches", ctypes.c_int32)]
+
+
+EXPORTED_SYMBOLS = ("sptir_spmm_timed", "sptir_roof_gather", "sptir_roof_fma", "sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_build_ex", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
                     "sptir_spmm_noalloc",
                     "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_sddmm_plan_build", "sptir_sddmm",
                     "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_rgms_build", "sptir_rgms", "sptir_rgms_info",
@@ -126,6 +133,15 @@ def load_library(path: str | None = None):
     lib.sptir_default_bucket_log2.argtypes = [ctypes.c_int64, ctypes.c_int32]
     lib.sptir_spmm.restype = ctypes.c_int
     lib.sptir_spmm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+    lib.sptir_spmm_timed.restype = ctypes.c_int
+    lib.sptir_spmm_timed.argtypes = lib.sptir_spmm.argtypes + [ctypes.POINTER(_SpmmTimes)]
+    lib.sptir_roof_gather.restype = ctypes.c_int
+    lib.sptir_roof_gather.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                      ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
+    lib.sptir_roof_fma.restype = ctypes.c_int
+    lib.sptir_roof_fma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                   ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
     lib.sptir_spmm_noalloc.restype = ctypes.c_int
     lib.sptir_spmm_noalloc.argtypes = lib.sptir_spmm.argtypes
     lib.sptir_sddmm_csr.restype = ctypes.c_int
@@ -350,6 +366,43 @@ def sptir_spmm(hyb: Hyb, X, Y, stream=None) -> None:
                                    _stream_ptr(stream))
     if st != SPTIR_OK:
         raise SptirError(st, "sptir_spmm")
+
+
+def sptir_spmm_timed(hyb: Hyb, X, Y, stream=None) -> dict:
+    """sptir_spmm with HIP events between its groups of launches; returns their times (ms) and launch counts."""
+    _dev(X, torch.float32, "X"); _dev(Y, torch.float32, "Y")
+    if X.dim() != 2 or Y.dim() != 2 or X.shape[1] != Y.shape[1]:
+        raise ValueError("X and Y must be 2-D with the same number of columns")
+    if X.shape[0] != hyb.n_cols or Y.shape[0] != hyb.n_rows:
+        raise ValueError("X / Y row counts do not match the matrix")
+    out = _SpmmTimes()
+    st = load_library().sptir_spmm_timed(hyb.handle, X.data_ptr() or None, Y.data_ptr() or None, X.shape[1],
+                                         _stream_ptr(stream), ctypes.byref(out))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_spmm_timed")
+    return {name: getattr(out, name) for name, _ in _SpmmTimes._fields_}
+
+
+def sptir_roof_gather(X, n_rows: int, tiles: int, n_workgroups: int, iters: int, sink, stream=None):
+    """(milliseconds, bytes gathered) of one launch of the gather-roof microbenchmark over X[0:n_rows]."""
+    _dev(X, torch.float32, "X"); _dev(sink, torch.float32, "sink")
+    ms = ctypes.c_float(0.0); nbytes = ctypes.c_double(0.0)
+    st = load_library().sptir_roof_gather(X.data_ptr(), n_rows, X.shape[1], tiles, n_workgroups, iters,
+                                          sink.data_ptr(), _stream_ptr(stream), ctypes.byref(ms), ctypes.byref(nbytes))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_roof_gather")
+    return float(ms.value), float(nbytes.value)
+
+
+def sptir_roof_fma(n_workgroups: int, iters: int, sink, stream=None):
+    """(milliseconds, flops) of one launch of the float32 FMA microbenchmark."""
+    _dev(sink, torch.float32, "sink")
+    ms = ctypes.c_float(0.0); flops = ctypes.c_double(0.0)
+    st = load_library().sptir_roof_fma(n_workgroups, iters, sink.data_ptr(), _stream_ptr(stream), ctypes.byref(ms),
+                                       ctypes.byref(flops))
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_roof_fma")
+    return float(ms.value), float(flops.value)
 
 
 def sptir_spmm_noalloc(hyb: Hyb, X, Y, stream=None) -> None:

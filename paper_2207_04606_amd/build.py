@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsptir.so")
-SOURCES = ["api.hip", "builder.hip", "order.hip", "spmm.hip", "sddmm.hip", "search.hip", "rgms.hip"]
+SOURCES = ["api.hip", "builder.hip", "order.hip", "spmm.hip", "sddmm.hip", "search.hip", "rgms.hip", "roof.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

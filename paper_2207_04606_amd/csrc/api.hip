@@ -62,7 +62,7 @@ sptir_status_t sptir_hyb_destroy(sptir_hyb_t* h) {
   if (!h) return SPTIR_OK;
   void* ptrs[] = {h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_part_ptr, h->rem_ptr,
                   h->row_ids, h->row_len, h->cols, h->vals, h->stream, h->rb_chunk_ptr, h->rb_order,
-                  h->hlist_first_slot, h->row_slot_ptr, h->row_slots, h->partial};
+                  h->hlist_first_slot, h->row_slot_ptr, h->row_slots, h->partial, h->row_val};
   for (void* p : ptrs)
     if (p) h->free_(p, h->alloc_ctx);
   free(h->hseg_list);
@@ -84,8 +84,9 @@ sptir_status_t sptir_hyb_info(const sptir_hyb_t* h, sptir_hyb_info_t* out) {
   o.n_work_items = h->n_chunks; o.item_slots = sptir::kChunkSlots; o.row_block = 1 << h->log2_row_block;
   o.n_phases = h->n_phases;
   o.rounds = h->rounds;
-  o.n_heavy_pieces = h->n_heavy; o.n_heavy_items = h->n_heavy_chunks;
+  o.n_heavy_pieces = h->n_heavy; o.n_heavy_items = h->n_heavy_chunks; o.n_heavy_nnz = h->n_heavy_nnz;
   o.heavy_len = h->heavy_len; o.n_heavy_lists = h->n_heavy_lists;
+  o.values_per_row = h->row_val ? 1 : 0;
   o.device_bytes = (int64_t)h->device_bytes;
   *out = o;
   return SPTIR_OK;

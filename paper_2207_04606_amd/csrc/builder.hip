@@ -53,43 +53,64 @@ __device__ __forceinline__ int bin_of_length(int l, int k) {
 // flags[3]: number of non-empty rows whose first column does not exceed the
 //           column stored just before it (descents that are legal)
 // Columns ascend strictly inside every row iff flags[2] == flags[3].
+// flags[4]: number of positions q >= 1 whose value differs (as a bit pattern) from the one stored before it
+// flags[5]: number of non-empty rows whose first value differs from the value stored just before it
+// Every row has one value for all of its entries iff flags[4] == flags[5] (only counted when `values` is given).
 __global__ void k_validate_rows(int32_t n_rows, int64_t nnz, const int32_t* __restrict__ indptr,
-                                const int32_t* __restrict__ indices, unsigned long long* flags) {
+                                const int32_t* __restrict__ indices, const int32_t* __restrict__ values,
+                                unsigned long long* flags) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  unsigned int legal_descents = 0;
+  unsigned int legal_descents = 0, legal_changes = 0;
   bool bad = false;
   for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < n_rows; r += stride) {
     int64_t a = indptr[r], b = indptr[r + 1];
     const bool bad_here = (a < 0) || (b > nnz) || (a > b) || (r == 0 && a != 0) || (r == n_rows - 1 && b != nnz);
     bad |= bad_here;
     legal_descents += !bad_here && a < b && a > 0 && indices[a] <= indices[a - 1];
+    if (values) legal_changes += !bad_here && a < b && a > 0 && values[a] != values[a - 1];
   }
   // a grid-wide count through one address: one atomic per wavefront, a few thousand in all
-  for (int d = 32; d > 0; d >>= 1) legal_descents += __shfl_down(legal_descents, d, 64);
+  for (int d = 32; d > 0; d >>= 1) {
+    legal_descents += __shfl_down(legal_descents, d, 64);
+    legal_changes += __shfl_down(legal_changes, d, 64);
+  }
   const unsigned long long any_bad = __ballot(bad);
   if ((threadIdx.x & 63) == 0) {
+    if (legal_changes) atomicAdd(&flags[5], (unsigned long long)legal_changes);
     if (legal_descents) atomicAdd(&flags[3], (unsigned long long)legal_descents);
     if (any_bad) flags[0] = 1;
   }
 }
 
 __global__ void k_validate_elems(int64_t nnz, int32_t n_cols, const int32_t* __restrict__ indices,
-                                 unsigned long long* flags) {
+                                 const int32_t* __restrict__ values, unsigned long long* flags) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  unsigned int descents = 0;
+  unsigned int descents = 0, changes = 0;
   bool range = false;
   for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nnz; q += stride) {
     int32_t col = indices[q];
     range |= (col < 0) || (col >= n_cols);
     descents += (q > 0) && (col <= indices[q - 1]);
+    if (values) changes += (q > 0) && (values[q] != values[q - 1]);
   }
   // a grid-wide count through one address: one atomic per wavefront, a few thousand in all
-  for (int d = 32; d > 0; d >>= 1) descents += __shfl_down(descents, d, 64);
+  for (int d = 32; d > 0; d >>= 1) {
+    descents += __shfl_down(descents, d, 64);
+    changes += __shfl_down(changes, d, 64);
+  }
   unsigned long long any_range = __ballot(range);
   if ((threadIdx.x & 63) == 0) {
+    if (changes) atomicAdd(&flags[4], (unsigned long long)changes);
     if (descents) atomicAdd(&flags[2], (unsigned long long)descents);
     if (any_range) flags[1] = 1;
   }
+}
+
+// row_val[r] = the value of row r's first entry (0 for an empty row)
+__global__ void k_row_values(int32_t n_rows, const int32_t* __restrict__ indptr, const float* __restrict__ values,
+                             float* row_val) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r < n_rows) row_val[r] = indptr[r + 1] > indptr[r] ? values[indptr[r]] : 0.f;
 }
 
 // --------------------------------------------------------------------- count
@@ -407,6 +428,7 @@ constexpr int kGroupSeq = 1024;  // groups per sequence of the two-level scan ov
 //   quad[256..511]  values
 struct StreamShape {
   int32_t* stream;
+  int32_t unit;   // 1: no values array (every row of A has one value, kept aside)
   int32_t compact;
   int32_t log2_rb;
   int32_t phase_width;  // columns a launch covers
@@ -415,11 +437,12 @@ struct StreamShape {
 __device__ __forceinline__ void put_slot(const StreamShape& ss, int64_t chunk, int slot, int32_t col_word,
                                          int32_t val_bits, int32_t row_word) {
   constexpr int kQuadSlots = kChunkSlots * kChunksPerQuad;
-  int32_t* quad = ss.stream + (chunk / kChunksPerQuad) * ((ss.compact ? 2 : 3) * kQuadSlots);
+  const int n_arrays = (ss.compact ? 2 : 3) - (ss.unit ? 1 : 0);  // [cols][vals unless unit][row words unless compact]
+  int32_t* quad = ss.stream + (chunk / kChunksPerQuad) * (n_arrays * kQuadSlots);
   const int at = (int)(chunk % kChunksPerQuad) * kChunkSlots + slot;
   quad[at] = col_word;
-  quad[kQuadSlots + at] = val_bits;
-  if (!ss.compact) quad[2 * kQuadSlots + at] = row_word;
+  if (!ss.unit) quad[kQuadSlots + at] = val_bits;
+  if (!ss.compact) quad[(n_arrays - 1) * kQuadSlots + at] = row_word;
 }
 
 // entry e of a queued piece
@@ -595,14 +618,19 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, int64_t f
 //   unit_before[q]   heavy pieces before piece q
 //   hchunk_before[q] 64-slot chunks of heavy pieces before piece q
 // Both arrays have one element more than there are pieces, so that after the scan the last one is the total.
+// *heavy_nnz receives the real entries of all heavy pieces.
 __global__ void k_heavy_counts(int64_t n_pieces, const int32_t* __restrict__ row_len, int32_t heavy_len,
-                               int32_t* unit_before, int32_t* hchunk_before) {
+                               int32_t* unit_before, int32_t* hchunk_before, unsigned long long* heavy_nnz) {
   const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (q > n_pieces) return;
   const int len = q < n_pieces ? row_len[q] : 0;
   const bool heavy = len > heavy_len;
-  unit_before[q] = heavy ? 1 : 0;
-  hchunk_before[q] = heavy ? chunks_of_length(len) : 0;
+  if (q <= n_pieces) {
+    unit_before[q] = heavy ? 1 : 0;
+    hchunk_before[q] = heavy ? chunks_of_length(len) : 0;
+  }
+  unsigned long long mine = heavy ? (unsigned long long)len : 0ull;
+  for (int d = 32; d > 0; d >>= 1) mine += __shfl_down(mine, d, 64);
+  if ((threadIdx.x & 63) == 0 && mine) atomicAdd(heavy_nnz, mine);
 }
 
 constexpr int kScanSeq = 4096;  // elements per sequence of the device-wide scan
@@ -916,15 +944,17 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     int64_t* d_rnnz_base = (int64_t*)(tmp.base + o_rnnz_base);
 
     // ---- validation of the CSR input
-    unsigned long long flags[4] = {0, 0, 0, 0};
+    unsigned long long flags[6] = {0, 0, 0, 0, 0, 0};
+    // (values are only looked at when a value-less stream is an option)
+    const int32_t* value_bits = (with_spmm_plan && !opt.keep_values) ? (const int32_t*)csr->values : nullptr;
     BUILD_HIP(hipMemsetAsync(d_flags, 0, sizeof(flags), stream));
     if (s.n_rows > 0)
       hipLaunchKernelGGL(k_validate_rows, dim3((unsigned)std::min<int64_t>(((int64_t)s.n_rows + 255) / 256, 4096)),
                          dim3(256), 0, stream, s.n_rows, csr->nnz,
-                         csr->indptr, csr->indices, d_flags);
+                         csr->indptr, csr->indices, value_bits, d_flags);
     if (csr->nnz > 0)
       hipLaunchKernelGGL(k_validate_elems, dim3((unsigned)std::min<int64_t>((csr->nnz + 255) / 256, 4096)), dim3(256),
-                         0, stream, csr->nnz, s.n_cols, csr->indices, d_flags);
+                         0, stream, csr->nnz, s.n_cols, csr->indices, value_bits, d_flags);
     BUILD_HIP(hipGetLastError());
     BUILD_HIP(hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, stream));
     BUILD_HIP(hipStreamSynchronize(stream));
@@ -995,6 +1025,16 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     cs.ppg = ls.parts_per_phase; cs.log2_rb = ls.log2_row_block; cs.n_phases = ls.n_phases;
     h->compact_stream = ls.compact;
     h->rounds = ls.rounds;
+    if (value_bits && csr->nnz > 0 && flags[4] == flags[5]) {
+      // Every row has one value for all its entries (a row-normalised adjacency matrix, say): the stream
+      // carries no values, the kernels sum rows of X and scale each row of Y once.
+      h->row_val = (float*)alloc(sizeof(float) * (size_t)s.n_rows, actx, stream);
+      if (!h->row_val) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += sizeof(float) * (size_t)s.n_rows;
+      hipLaunchKernelGGL(k_row_values, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
+                         csr->indptr, csr->values, h->row_val);
+      BUILD_HIP(hipGetLastError());
+    }
     h->sweep_kb = opt.sweep_kb > 0 ? opt.sweep_kb : 160 * 1024;
     cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
     cs.long_len = heavy_len_setting(csr->nnz, (int64_t)cs.n_phases * cs.n_rb, ls.rounds != 0, opt);
@@ -1014,7 +1054,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     const int64_t n_seq = (n_groups + kGroupSeq - 1) / kGroupSeq;
     const size_t o_group_tot = tmp2.reserve(sizeof(long long) * (size_t)(n_seq ? n_seq * kGroupSeq : 1));
     const size_t o_seq_tot = tmp2.reserve(sizeof(long long) * (size_t)(n_seq ? n_seq : 1));
-    const size_t o_cell_total = tmp2.reserve(sizeof(long long));  // chunks of all lists
+    const size_t o_cell_total = tmp2.reserve(2 * sizeof(long long));  // chunks of all lists; entries of heavy pieces
     // heavy pieces: the two prefix arrays over the pieces, the (row, partition) -> piece map, scan scratch
     const bool want_heavy = with_spmm_plan && n_pieces > 0;
     const size_t o_unit = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room(n_pieces + 1) : 1));
@@ -1087,8 +1127,9 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
 
     // ---- heavy pieces: how many, and how many chunks (prefixes over the pieces in row_ids order)
     if (want_heavy) {
+      BUILD_HIP(hipMemsetAsync(d_cell_total + 1, 0, sizeof(long long), stream));
       hipLaunchKernelGGL(k_heavy_counts, dim3((unsigned)((n_pieces + 256) / 256)), dim3(256), 0, stream, n_pieces,
-                         h->row_len, cs.long_len, d_unit, d_hchunk);
+                         h->row_len, cs.long_len, d_unit, d_hchunk, (unsigned long long*)(d_cell_total + 1));
       BUILD_HIP(hipGetLastError());
       st = device_exclusive_scan(d_unit, n_pieces + 1, d_seq_base, stream);
       if (st != SPTIR_OK) goto fail;
@@ -1130,6 +1171,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
                          (int32_t)seg_at.size(), d_seg_at, d_hchunk, d_seg_hc);
       BUILD_HIP(hipGetLastError());
       BUILD_HIP(hipMemcpyAsync(seg_hc.data(), d_seg_hc, sizeof(int32_t) * seg_hc.size(), hipMemcpyDeviceToHost, stream));
+      BUILD_HIP(hipMemcpyAsync(&h->n_heavy_nnz, d_cell_total + 1, sizeof(long long), hipMemcpyDeviceToHost, stream));
       BUILD_HIP(hipMemcpyAsync(&heavy_totals[0], d_unit + n_pieces, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
       BUILD_HIP(hipMemcpyAsync(&heavy_totals[1], d_hchunk + n_pieces, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
     }
@@ -1161,13 +1203,14 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       tmp_place = alloc(bytes, actx, stream);
       if (!tmp_place) { st = SPTIR_ERR_ALLOC; goto fail; }
       BUILD_HIP(hipMemsetAsync(tmp_place, 0, bytes, stream));  // len 0: not queued
-      bytes = sizeof(int32_t) * (h->compact_stream ? 2 : 3) * kChunkSlots * (size_t)(all_chunks ? all_chunks : 1);
+      bytes = sizeof(int32_t) * ((h->compact_stream ? 2 : 3) - (h->row_val ? 1 : 0)) * kChunkSlots *
+              (size_t)(all_chunks ? all_chunks : 1);
       h->stream = (int32_t*)alloc(bytes, actx, stream);
       if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += bytes;
     }
     StreamShape ss;
-    ss.stream = h->stream; ss.compact = h->compact_stream; ss.log2_rb = cs.log2_rb;
+    ss.stream = h->stream; ss.compact = h->compact_stream; ss.log2_rb = cs.log2_rb; ss.unit = h->row_val ? 1 : 0;
     ss.phase_width = (int32_t)((int64_t)cs.ppg * s.w > 0x7FFFFFFF ? 0x7FFFFFFF : (int64_t)cs.ppg * s.w);
     if (n_parts > 0)
       hipLaunchKernelGGL(k_part_fill_chunks, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs, ss,

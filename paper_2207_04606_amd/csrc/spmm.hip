@@ -35,8 +35,10 @@
 // partial sums in memory; k_heavy_reduce adds them to Y in a fixed order.
 #include <cstdio>
 #include <cstdlib>
-#include <atomic>
+#include <cstring>
 #include <mutex>
+#include <utility>
+#include <vector>
 #include "sptir_internal.h"
 
 namespace sptir {
@@ -269,6 +271,7 @@ struct SpmmArgs {
   int32_t map_mode;
   int32_t map_param;
   int32_t accumulate;  // 0: Y tile is overwritten, 1: added to (a later phase)
+  const float* row_val;  // UNIT kernels: the value of every entry of row r
 };
 
 constexpr int kHybWaves = 4;
@@ -293,19 +296,24 @@ constexpr int kHybBlock = 64 * kHybWaves;
 // finished row sum into the wavefront's LDS tile of Y; the lane groups that
 // share a chunk of one long row add their partial sums up with cross-lane moves
 // at the row's end, and the leading group hands the sum over.
-template <int VEC, int LG, bool IDX32, bool WIDE, typename Sink>
+//
+// UNIT: the stream holds no values (every row of A has one value for all its entries, which the caller of the
+// walk multiplies in at the end): a real slot counts 1, any other 0.
+template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT, typename Sink>
 struct HybWalker {
   using S = Shape<VEC, LG>;
   static constexpr int UB = S::kSteps, CS = S::kChunk;
   static constexpr int SUB = kChunkSlots / CS;              // steps per chunk
   static constexpr int kQuadSteps = kChunksPerQuad * SUB;   // steps per quad
   static constexpr int kQuadSlots = kChunksPerQuad * kChunkSlots;
-  static constexpr int kArrays = WIDE ? 3 : 2;              // [cols | vals | row words] or [col+row words | vals]
+  // [cols | vals | row words] or [col+row words | vals]; no vals when UNIT
+  static constexpr int kArrays = (WIDE ? 3 : 2) - (UNIT ? 1 : 0);
+  static constexpr int kRowArray = kArrays - 1;             // WIDE: which array holds the row words
   static constexpr int kQuadInts = kArrays * kQuadSlots;
   static constexpr int kRingInts = 2 * kQuadInts;           // two quads parked per wave
 
   struct Fetched {  // a quad on its way from memory: slots 4*lane .. 4*lane+3 of each array
-    int col[4], val[4], row[WIDE ? 4 : 1];
+    int col[4], val[UNIT ? 1 : 4], row[WIDE ? 4 : 1];
   };
 
   const float* X;        // first row of X the stream's columns count from
@@ -320,11 +328,14 @@ struct HybWalker {
   __device__ __forceinline__ void fetch(int q, Fetched& f) const {
     q = q < n_quads ? q : n_quads - 1;
     const int4* rec = reinterpret_cast<const int4*>(quads + (size_t)q * kQuadInts);
-    const int4 c = rec[lane], v = rec[kQuadSlots / 4 + lane];
+    const int4 c = rec[lane];
     f.col[0] = c.x; f.col[1] = c.y; f.col[2] = c.z; f.col[3] = c.w;
-    f.val[0] = v.x; f.val[1] = v.y; f.val[2] = v.z; f.val[3] = v.w;
+    if constexpr (!UNIT) {
+      const int4 v = rec[kQuadSlots / 4 + lane];
+      f.val[0] = v.x; f.val[1] = v.y; f.val[2] = v.z; f.val[3] = v.w;
+    }
     if constexpr (WIDE) {
-      const int4 r = rec[2 * kQuadSlots / 4 + lane];
+      const int4 r = rec[kRowArray * kQuadSlots / 4 + lane];
       f.row[0] = r.x; f.row[1] = r.y; f.row[2] = r.z; f.row[3] = r.w;
     }
   }
@@ -345,8 +356,8 @@ struct HybWalker {
   __device__ __forceinline__ void park(int q, const Fetched& f, int (&m)[kChunksPerQuad]) const {
     int4* st = reinterpret_cast<int4*>(slot_of(q));
     st[lane] = make_int4(f.col[0], f.col[1], f.col[2], f.col[3]);
-    st[kQuadSlots / 4 + lane] = make_int4(f.val[0], f.val[1], f.val[2], f.val[3]);
-    if constexpr (WIDE) st[2 * kQuadSlots / 4 + lane] = make_int4(f.row[0], f.row[1], f.row[2], f.row[3]);
+    if constexpr (!UNIT) st[kQuadSlots / 4 + lane] = make_int4(f.val[0], f.val[1], f.val[2], f.val[3]);
+    if constexpr (WIDE) st[kRowArray * kQuadSlots / 4 + lane] = make_int4(f.row[0], f.row[1], f.row[2], f.row[3]);
 #pragma unroll
     for (int i = 0; i < kChunksPerQuad; ++i) {
       if constexpr (WIDE) m[i] = __builtin_amdgcn_readlane(f.row[0], i * (kChunkSlots / 4)) >> 16;
@@ -390,16 +401,22 @@ struct HybWalker {
   //    names its row and the last entry of a row piece carries the hand-over flag;
   //  * chunks cut from one wide row (log2w >= 6), which all lane groups share; the chunk's hand-over flag
   //    says whether the row ends with it.
+  // (w: with UNIT the row words of the step's slots, which step() has read to tell real slots from others)
   __device__ __forceinline__ void consume(const int* st, int s, int meta, const float (&v)[UB],
-                                          const float (&x)[UB][VEC]) {
+                                          const float (&x)[UB][VEC], const int (&w)[UB]) {
     // (compact: a chunk cut from a row wider than 64 slots carries code 7; the test below only asks lw >= 6)
     const int lw = WIDE ? (meta & 63) : ((meta >> 1) & 7);
     const bool hand_over = ((meta >> (WIDE ? 6 : 4)) & 1) != 0;
     const int sub = s & (SUB - 1);
-    const int* rows = st + (WIDE ? 2 * kQuadSlots : 0);
+    const int* rows = st + (WIDE ? kRowArray * kQuadSlots : 0);
     if (Sink::kQueues && lw < 6) {
       int r[UB];
-      read_ints(rows + first_slot(s), r);
+      if constexpr (UNIT) {
+#pragma unroll
+        for (int j = 0; j < UB; ++j) r[j] = w[j];
+      } else {
+        read_ints(rows + first_slot(s), r);
+      }
 #pragma unroll
       for (int j = 0; j < UB; ++j) {
 #pragma unroll
@@ -466,15 +483,22 @@ struct HybWalker {
       const int* st = slot_of(Q);
       int t[UB];
       float v[UB];
-      read_ints(st + kQuadSlots + first_slot(s), t);  // LDS reads first: their latency hides behind what follows
+      // LDS reads first: their latency hides behind what follows
+      if constexpr (UNIT) {
+        read_ints(st + (WIDE ? kRowArray * kQuadSlots : 0) + first_slot(s), t);
 #pragma unroll
-      for (int j = 0; j < UB; ++j) v[j] = __int_as_float(t[j]);
+        for (int j = 0; j < UB; ++j) v[j] = row_valid(t[j]) ? 1.f : 0.f;
+      } else {
+        read_ints(st + kQuadSlots + first_slot(s), t);
+#pragma unroll
+        for (int j = 0; j < UB; ++j) v[j] = __int_as_float(t[j]);
+      }
       int c[UB];
       if (refill) {
         const int s2 = s + 2;
         read_ints((s2 < kQuadSteps ? st : slot_of(Q + 1)) + first_slot(s2 & (kQuadSteps - 1)), c);
       }
-      consume(st, s, m_cur[s / SUB], v, x);
+      consume(st, s, m_cur[s / SUB], v, x, t);
       if (refill) issue(c, x);
     };
     int Q = 0;
@@ -505,10 +529,10 @@ struct HybWalker {
   }
 };
 
-template <int VEC, int LG, bool IDX32, bool WIDE>
+template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT>
 __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   using S = Shape<VEC, LG>;
-  using W = HybWalker<VEC, LG, IDX32, WIDE, TileSink<VEC, LG>>;
+  using W = HybWalker<VEC, LG, IDX32, WIDE, UNIT, TileSink<VEC, LG>>;
   extern __shared__ __align__(16) float smem[];  // per wavefront: [row_block][kTile] tile of Y, then its quad ring
   int64_t unit;
   int tile_id;
@@ -528,13 +552,14 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   float* tile = smem + wave * wave_floats;
   int* ring = reinterpret_cast<int*>(tile + row_block * S::kTile);
 
-  // the tile starts from zero, or from what earlier launches (column partitions) left in Y
+  // the tile starts from zero, or from what earlier launches (column partitions) left in Y; with UNIT what it
+  // sums still has to be multiplied by the row's value, so the earlier Y joins at the end instead
   float* y0 = a.Y + (size_t)rb_first * (size_t)a.feat + f0;
   for (int r = g; r < row_block; r += S::kGroups) {
     float init[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) init[e] = 0.f;
-    if (a.accumulate && f_active && r < rows_here) load_vec<VEC>(init, y0 + (size_t)r * (size_t)a.feat);
+    if (!UNIT && a.accumulate && f_active && r < rows_here) load_vec<VEC>(init, y0 + (size_t)r * (size_t)a.feat);
     store_vec<VEC>(tile + tile_index<VEC, LG>(r, fl), init);
   }
 
@@ -550,6 +575,15 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
     for (int r = g; r < rows_here; r += S::kGroups) {
       float out[VEC];
       load_vec<VEC>(out, tile + tile_index<VEC, LG>(r, fl));
+      if constexpr (UNIT) {
+        const float v = a.row_val[rb_first + r];
+        float before[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) before[e] = 0.f;
+        if (a.accumulate) load_vec<VEC>(before, y0 + (size_t)r * (size_t)a.feat);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) out[e] = fmaf(v, out[e], before[e]);
+      }
       store_vec<VEC>(y0 + (size_t)r * (size_t)a.feat, out);
     }
   }
@@ -576,10 +610,10 @@ struct HeavyArgs {
 // list, but a finished piece goes to the next partial-sum row instead of an LDS tile, and so does, at the end,
 // what has been summed of the piece the list stops in (zeros if it stops at a piece end: every wavefront takes
 // that row, so that the row numbers follow from counting alone).
-template <int VEC, int LG, bool IDX32, bool WIDE>
+template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT>
 __global__ __launch_bounds__(kHybBlock) void k_spmm_heavy(HeavyArgs a) {
   using S = Shape<VEC, LG>;
-  using W = HybWalker<VEC, LG, IDX32, WIDE, PartialSink<VEC, LG>>;
+  using W = HybWalker<VEC, LG, IDX32, WIDE, UNIT, PartialSink<VEC, LG>>;
   extern __shared__ __align__(16) float smem[];  // per wavefront: its quad ring
   int64_t unit;
   int tile_id;
@@ -605,12 +639,13 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_heavy(HeavyArgs a) {
   wk.sink(0, g == 0, wk.acc);
 }
 
-// Y[r, feat0 + f] += the partial sums of row r's heavy pieces, in the order of row_slots (partition by partition):
+// Y[r, feat0 + f] += (row_val[r] *) the partial sums of row r's heavy pieces, in the order of row_slots (partition by partition):
 // one thread per (row, VEC features).  Runs after the chunk-list launches have written Y.
 template <int VEC>
 __global__ __launch_bounds__(256) void k_heavy_reduce(const int32_t* __restrict__ row_slot_ptr,
                                                       const int32_t* __restrict__ row_slots,
-                                                      const float* __restrict__ partial, float* Y, int32_t n_rows,
+                                                      const float* __restrict__ partial,
+                                                      const float* __restrict__ row_val, float* Y, int32_t n_rows,
                                                       int32_t feat, int32_t feat0, int32_t width) {
   const int per_row = width / VEC;
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -628,11 +663,12 @@ __global__ __launch_bounds__(256) void k_heavy_reduce(const int32_t* __restrict_
 #pragma unroll
     for (int i = 0; i < VEC; ++i) sum[i] += v[i];
   }
+  const float scale = row_val ? row_val[r] : 1.f;  // (the heavy lists of a value-less stream sum rows of X only)
   float* y = Y + (size_t)r * (size_t)feat + feat0 + f;
   float out[VEC];
   load_vec<VEC>(out, y);
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) out[i] += sum[i];
+  for (int i = 0; i < VEC; ++i) out[i] = fmaf(scale, sum[i], out[i]);
   store_vec<VEC>(y, out);
 }
 
@@ -714,33 +750,39 @@ bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
 }
 
 // the template arguments of the two hyb kernels as a value
-template <int VEC, int LG, bool IDX32, bool WIDE>
+template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT>
 struct Variant {
   static constexpr int vec = VEC, lg = LG;
-  static constexpr bool idx32 = IDX32, wide = WIDE;
+  static constexpr bool idx32 = IDX32, wide = WIDE, unit = UNIT;
 };
 
-template <int VEC, int LG, typename F>
+template <int VEC, int LG, bool UNIT, typename F>
 void with_flags(bool idx32, bool wide, F&& f) {
   if (wide) {
-    if (idx32) f(Variant<VEC, LG, true, true>{}); else f(Variant<VEC, LG, false, true>{});
+    if (idx32) f(Variant<VEC, LG, true, true, UNIT>{}); else f(Variant<VEC, LG, false, true, UNIT>{});
   } else {
-    if (idx32) f(Variant<VEC, LG, true, false>{}); else f(Variant<VEC, LG, false, false>{});
+    if (idx32) f(Variant<VEC, LG, true, false, UNIT>{}); else f(Variant<VEC, LG, false, false, UNIT>{});
   }
+}
+
+template <bool UNIT, typename F>
+void with_shape(int vec, int lg, bool idx32, bool wide, F&& f) {
+  if (vec == 4 && lg == 8) with_flags<4, 8, UNIT>(idx32, wide, f);
+  else if (vec == 4) with_flags<4, 4, UNIT>(idx32, wide, f);
+  else if (vec == 2) with_flags<2, 16, UNIT>(idx32, wide, f);
+  else with_flags<1, 32, UNIT>(idx32, wide, f);
 }
 
 // calls f with the Variant that matches the lane geometry and the stream's record form
 template <typename F>
-void with_variant(int vec, int lg, bool idx32, bool wide, F&& f) {
-  if (vec == 4 && lg == 8) with_flags<4, 8>(idx32, wide, f);
-  else if (vec == 4) with_flags<4, 4>(idx32, wide, f);
-  else if (vec == 2) with_flags<2, 16>(idx32, wide, f);
-  else with_flags<1, 32>(idx32, wide, f);
+void with_variant(int vec, int lg, bool idx32, bool wide, bool unit, F&& f) {
+  if (unit) with_shape<true>(vec, lg, idx32, wide, f);
+  else with_shape<false>(vec, lg, idx32, wide, f);
 }
 
 template <typename V>
 void launch_lists(V, const Geometry& g, size_t lds_bytes, hipStream_t stream, const SpmmArgs& a) {
-  auto* kernel = &k_spmm_hyb<V::vec, V::lg, V::idx32, V::wide>;
+  auto* kernel = &k_spmm_hyb<V::vec, V::lg, V::idx32, V::wide, V::unit>;
   static std::once_flag raised;  // row blocks of 256 rows need more than the default 64 KB of dynamic LDS
   std::call_once(raised, [&] {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -755,7 +797,7 @@ int resident_workgroups(V, size_t lds_bytes) {
   int per_cu = 0, n_cu = 0, dev = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_spmm_hyb<V::vec, V::lg, V::idx32, V::wide>, kHybBlock,
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_spmm_hyb<V::vec, V::lg, V::idx32, V::wide, V::unit>, kHybBlock,
                                                    lds_bytes) != hipSuccess) {
     (void)hipGetLastError();
     return 0;
@@ -767,8 +809,9 @@ int resident_workgroups(V, size_t lds_bytes) {
 
 template <typename V>
 void launch_heavy(V, const Geometry& g, hipStream_t stream, const HeavyArgs& a) {
-  const size_t lds_bytes = (size_t)kHybWaves * sizeof(int) * 2 * (V::wide ? 3 : 2) * kChunkSlots * kChunksPerQuad;
-  hipLaunchKernelGGL((k_spmm_heavy<V::vec, V::lg, V::idx32, V::wide>), dim3((unsigned)g.grid), dim3(kHybBlock),
+  const size_t lds_bytes =
+      (size_t)kHybWaves * sizeof(int) * 2 * ((V::wide ? 3 : 2) - (V::unit ? 1 : 0)) * kChunkSlots * kChunksPerQuad;
+  hipLaunchKernelGGL((k_spmm_heavy<V::vec, V::lg, V::idx32, V::wide, V::unit>), dim3((unsigned)g.grid), dim3(kHybBlock),
                      lds_bytes, stream, a);
 }
 
@@ -806,10 +849,27 @@ bool offsets_fit_32(int64_t n_cols_spanned, int32_t feat) {
 
 using namespace sptir;
 
+// Events between the groups of launches of one call (sptir_spmm_timed)
+struct LaunchTimers {
+  enum Tag { kStart = 0, kLists = 1, kHeavy = 2, kReduce = 3 };
+  std::vector<std::pair<hipEvent_t, int>> marks;
+  int launches[4] = {0, 0, 0, 0};
+  bool failed = false;
+  void mark(hipStream_t stream, int tag, int n_launches) {
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess || hipEventRecord(e, stream) != hipSuccess) { failed = true; return; }
+    marks.emplace_back(e, tag);
+    launches[tag] += n_launches;
+  }
+  ~LaunchTimers() {
+    for (auto& m : marks) (void)hipEventDestroy(m.first);
+  }
+};
+
 // The work of sptir_spmm; `partial` is where the sums of heavy pieces meet ([n_partial_rows][kPartialFeat] floats;
 // only touched when the matrix has heavy pieces).
 static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat, void* stream_,
-                                  float* partial) {
+                                  float* partial, LaunchTimers* timers = nullptr) {
   if (!h || feat < 1) return SPTIR_ERR_INVALID_ARG;
   if ((h->n_cols > 0 && !X) || (h->n_rows > 0 && !Y)) return SPTIR_ERR_INVALID_ARG;
   const size_t x_bytes = sizeof(float) * (size_t)h->n_cols * feat, y_bytes = sizeof(float) * (size_t)h->n_rows * feat;
@@ -826,19 +886,23 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
   a.X = X; a.Y = Y; a.n_rows = h->n_rows; a.n_row_blocks = h->n_row_blocks; a.log2_row_block = h->log2_row_block;
   a.feat = feat; a.n_tiles = g.n_tiles; a.map_mode = g.map_mode; a.map_param = g.map_param;
   // per wavefront: its Y tile and its ring of two quads
-  const bool wide = !h->compact_stream;
-  const size_t lds_bytes = (size_t)kHybWaves * (sizeof(float) * ((size_t)g.vec * g.lg << h->log2_row_block) +
-                                                sizeof(int) * 2 * (wide ? 3 : 2) * kChunkSlots * kChunksPerQuad);
+  const bool wide = !h->compact_stream, unit = h->row_val != nullptr;
+  a.row_val = h->row_val;
+  const size_t lds_bytes =
+      (size_t)kHybWaves * (sizeof(float) * ((size_t)g.vec * g.lg << h->log2_row_block) +
+                           sizeof(int) * 2 * ((wide ? 3 : 2) - (unit ? 1 : 0)) * kChunkSlots * kChunksPerQuad);
   // A compact list holds columns relative to the first column of its launch, which moves into the X pointer.
   const int64_t span = (int64_t)h->parts_per_phase * (int64_t)h->w;
   const bool idx32 = offsets_fit_32(wide ? (int64_t)h->n_cols : (span < h->n_cols ? span : (int64_t)h->n_cols), feat);
   const int all_tiles = g.n_tiles;
+  int n_list_launches = 0;
+  if (timers) timers->mark(stream, LaunchTimers::kStart, 0);
   if (h->rounds) {
     // Rounds: a launch takes as many row blocks, in the order of their list lengths, as the GPU holds wavefronts.
     // All of them start together, their lists are about equally long and sweep the column partitions in the same
     // order, so they stay nearly in step; the Y tiles stay in LDS from the first partition to the last.
     int capacity = 0;
-    with_variant(g.vec, g.lg, idx32, wide, [&](auto v) { capacity = resident_workgroups(v, lds_bytes); });
+    with_variant(g.vec, g.lg, idx32, wide, unit, [&](auto v) { capacity = resident_workgroups(v, lds_bytes); });
     if (capacity <= 0) capacity = 3 * 256;
     int64_t per_round = (int64_t)capacity / all_tiles * kHybWaves;  // row blocks
     if (per_round < 8 * kHybWaves) per_round = 8 * kHybWaves;
@@ -851,7 +915,8 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
       a.n_row_blocks = (int32_t)here;
       if (!plan_tiles((here + kHybWaves - 1) / kHybWaves, &g)) return SPTIR_ERR_OVERFLOW;
       a.map_mode = g.map_mode; a.map_param = g.map_param;
-      with_variant(g.vec, g.lg, idx32, wide, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
+      with_variant(g.vec, g.lg, idx32, wide, unit, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
+      ++n_list_launches;
     }
   } else {
     const int per_sweep = tiles_per_sweep(all_tiles, g.vec * g.lg, h->n_rows, h->n_phases, h->sweep_kb);
@@ -864,10 +929,12 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
         a.rb_order = h->rb_order + (size_t)phase * h->n_row_blocks;
         a.accumulate = phase > 0;
         a.X = wide ? X : X + (size_t)phase * (size_t)span * (size_t)feat;
-        with_variant(g.vec, g.lg, idx32, wide, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
+        with_variant(g.vec, g.lg, idx32, wide, unit, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
+        ++n_list_launches;
       }
     }
   }
+  if (timers) timers->mark(stream, LaunchTimers::kLists, n_list_launches);
   if (h->n_heavy > 0) {
     // heavy pieces: partial sums of kPartialFeat features at a time, added to the Y the lists have written
     const bool idx32_all = offsets_fit_32(h->n_cols, feat);
@@ -886,6 +953,7 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
       // lists are not worth a launch of their own.
       const int32_t min_lists = 2048;
       int32_t first = 0;
+      int n_heavy_launches = 0;
       for (int32_t sg = 1; sg <= h->n_heavy_segs; ++sg) {
         const int32_t end = h->hseg_list[sg];
         if (end == first) continue;
@@ -893,18 +961,21 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
         ha.list0 = first; ha.n_lists = end - first;
         if (!plan_tiles(((int64_t)ha.n_lists + kHybWaves - 1) / kHybWaves, &gh)) return SPTIR_ERR_OVERFLOW;
         ha.map_mode = gh.map_mode; ha.map_param = gh.map_param;
-        with_variant(g.vec, g.lg, idx32_all, wide, [&](auto v) { launch_heavy(v, gh, stream, ha); });
+        with_variant(g.vec, g.lg, idx32_all, wide, unit, [&](auto v) { launch_heavy(v, gh, stream, ha); });
+        ++n_heavy_launches;
         first = end;
       }
+      if (timers) timers->mark(stream, LaunchTimers::kHeavy, n_heavy_launches);
       const int64_t n_threads = (int64_t)h->n_rows * (width / (y_vec4 ? 4 : 1));
       const dim3 grid((unsigned)((n_threads + 255) / 256)), block(256);
       if ((n_threads + 255) / 256 > 0x7FFFFFFF) return SPTIR_ERR_OVERFLOW;
       if (y_vec4)
-        hipLaunchKernelGGL(k_heavy_reduce<4>, grid, block, 0, stream, h->row_slot_ptr, h->row_slots, partial, Y,
-                           h->n_rows, feat, feat0, width);
+        hipLaunchKernelGGL(k_heavy_reduce<4>, grid, block, 0, stream, h->row_slot_ptr, h->row_slots, partial,
+                           h->row_val, Y, h->n_rows, feat, feat0, width);
       else
-        hipLaunchKernelGGL(k_heavy_reduce<1>, grid, block, 0, stream, h->row_slot_ptr, h->row_slots, partial, Y,
-                           h->n_rows, feat, feat0, width);
+        hipLaunchKernelGGL(k_heavy_reduce<1>, grid, block, 0, stream, h->row_slot_ptr, h->row_slots, partial,
+                           h->row_val, Y, h->n_rows, feat, feat0, width);
+      if (timers) timers->mark(stream, LaunchTimers::kReduce, 1);
     }
   }
   SPTIR_HIP(hipGetLastError());
@@ -913,6 +984,30 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
 
 extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat, void* stream_) {
   return spmm_on_hyb(h, X, Y, feat, stream_, h ? h->partial : nullptr);
+}
+
+extern "C" sptir_status_t sptir_spmm_timed(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat,
+                                           void* stream_, sptir_spmm_times_t* out) {
+  if (!out) return SPTIR_ERR_INVALID_ARG;
+  LaunchTimers timers;
+  const sptir_status_t st = spmm_on_hyb(h, X, Y, feat, stream_, h ? h->partial : nullptr, &timers);
+  if (st != SPTIR_OK) return st;
+  SPTIR_HIP(hipStreamSynchronize((hipStream_t)stream_));
+  if (timers.failed) return note_hip_error(hipGetLastError(), "recording events");
+  sptir_spmm_times_t t;
+  memset(&t, 0, sizeof(t));
+  for (size_t i = 1; i < timers.marks.size(); ++i) {
+    float ms = 0.f;
+    SPTIR_HIP(hipEventElapsedTime(&ms, timers.marks[i - 1].first, timers.marks[i].first));
+    if (timers.marks[i].second == LaunchTimers::kLists) t.ms_lists += ms;
+    else if (timers.marks[i].second == LaunchTimers::kHeavy) t.ms_heavy += ms;
+    else if (timers.marks[i].second == LaunchTimers::kReduce) t.ms_reduce += ms;
+  }
+  t.n_list_launches = timers.launches[LaunchTimers::kLists];
+  t.n_heavy_launches = timers.launches[LaunchTimers::kHeavy];
+  t.n_reduce_launches = timers.launches[LaunchTimers::kReduce];
+  *out = t;
+  return SPTIR_OK;
 }
 
 // ---------------------------------------------------------------- sptir_spmm_noalloc

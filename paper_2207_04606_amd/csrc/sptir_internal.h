@@ -60,6 +60,8 @@ struct sptir_hyb {
   int32_t* cols;             // device [S+T]
   float* vals;               // device [S+T]
   int32_t* row_len;          // device [R+M], real length of every ELL row / remainder piece
+  float* row_val;            // device [n_rows] or NULL: set when every row of A has one value for all its entries;
+                             // the stream then holds no values and Y is scaled row by row at the end
   int32_t* stream;           // device [n_chunks * 128 or 192]: the chunks as fixed records, grouped by (phase, row block)
   int32_t spmm_plan;         // 0: built without the chunk stream (canonical arrays only); sptir_spmm refuses it
   int32_t compact_stream;    // 1: 8-byte slots (columns relative to the launch), 0: 12-byte slots (global columns)
@@ -69,6 +71,7 @@ struct sptir_hyb {
   // heavy pieces (see kHeavyListChunks): their chunks sit in `stream` from chunk heavy_chunk0 on
   int32_t heavy_len;
   int64_t n_heavy;            // heavy pieces
+  int64_t n_heavy_nnz;        // their real entries
   int64_t n_heavy_chunks;     // their chunks, rounded up to whole quads
   int64_t heavy_chunk0;       // a multiple of kChunksPerQuad
   int32_t n_heavy_lists;

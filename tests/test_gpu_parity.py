@@ -308,6 +308,61 @@ def test_spmm_launch_plan_knobs(gpu_lib, knobs):
         assert torch.equal(Y, Y2)
 
 
+@pytest.mark.parametrize("knobs", [
+    {}, {"keep_values": 1}, {"rounds": 1, "heavy_len": 64}, {"rounds": 1, "wide_stream": 1, "heavy_len": 20},
+    {"rounds": 2, "parts_per_launch": 1}, {"rounds": 2, "parts_per_launch": 2, "wide_stream": 1, "heavy_len": 300},
+    {"row_block": 256}])
+def test_spmm_one_value_per_row(gpu_lib, knobs):
+    """A matrix whose rows each repeat one value (a row-normalised adjacency matrix) is stored without values in
+    the SpMM stream, and the rows of Y are scaled at the end; keep_values turns that off.  Both must meet the
+    oracle, in every launch plan."""
+    say(f"[one value per row] {knobs}")
+    for feat, c, k in ((32, 5, 4), (6, 3, 2), (128, 4, 7), (200, 2, 3)):
+        w = ragged_workload(700 + feat, 2300, 2100, feat, max_deg=1500, long_rows=8)
+        deg = np.diff(w.indptr)
+        per_row = np.random.default_rng(feat).standard_normal(w.n_rows).astype(np.float32)
+        w.values[:] = np.repeat(per_row, deg)
+        d, hyb, got, want, info = build_both(gpu_lib, w, c, k, dict(knobs) or None)
+        assert_same_hyb(got, want)
+        assert info["values_per_row"] == (0 if knobs.get("keep_values") else 1)
+        Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+        gpu_lib.sptir_spmm(hyb, d.X, Y)
+        Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+        assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"one value per row {knobs} feat={feat}")
+    # one entry that differs, at the end of a row, and the matrix is stored with its values
+    w.values[w.indptr[w.n_rows // 2 + 1] - 1] += 1.0
+    d, hyb, got, want, info = build_both(gpu_lib, w, c, k, dict(knobs) or None)
+    assert info["values_per_row"] == 0
+    Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+    gpu_lib.sptir_spmm(hyb, d.X, Y)
+    Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+    assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"almost one value per row {knobs}")
+
+
+def test_timed_call_and_roof_microbenchmarks(gpu_lib):
+    """The measurement aids of the C ABI: sptir_spmm_timed gives the same Y as sptir_spmm and times that add up;
+    the roof microbenchmarks return plausible rates and reject bad arguments."""
+    sptir = gpu_lib
+    w = ragged_workload(5, 3000, 2500, 64, max_deg=1200, long_rows=10)
+    d, hyb, got, want, info = build_both(sptir, w, 3, 4, {"rounds": 1, "heavy_len": 64})
+    Y = torch.empty(w.n_rows, 64, device="cuda"); Yt = torch.empty_like(Y)
+    sptir.sptir_spmm(hyb, d.X, Y)
+    t = sptir.sptir_spmm_timed(hyb, d.X, Yt)
+    assert torch.equal(Y, Yt)
+    assert t["n_list_launches"] >= 1 and t["n_heavy_launches"] >= 1 and t["n_reduce_launches"] == 1
+    assert t["ms_lists"] > 0 and t["ms_heavy"] > 0 and t["ms_reduce"] > 0
+    X = torch.zeros(4096, 128, device="cuda"); sink = torch.zeros(4, device="cuda")
+    ms, nbytes = sptir.sptir_roof_gather(X, 4096, 4, 1024, 64, sink)
+    assert ms > 0 and nbytes == 1024 * 4 * 64 * 8 * 1024
+    assert 1e3 < nbytes / ms / 1e6 < 45e3            # GB/s: above one CU's share, below the 39.3 TB/s of the return path + slack
+    ms, flops = sptir.sptir_roof_fma(2048, 1024, sink)
+    assert ms > 0 and 5.0 < flops / ms / 1e9 < 320.0  # TFLOP/s
+    assert float(sink.sum()) == 0.0
+    for bad in ((X, 0, 4, 8, 8), (X, 4096, 9, 8, 8), (X, 4096, 4, 0, 8), (X, 4096, 4, 8, 0)):
+        with pytest.raises(sptir.SptirError):
+            sptir.sptir_roof_gather(*bad, sink)
+
+
 def test_build_options_are_validated(gpu_lib):
     w = ragged_workload(1, 50, 60, 4, max_deg=20)
     d = upload(w)
