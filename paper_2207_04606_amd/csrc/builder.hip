@@ -320,6 +320,7 @@ static_assert(sizeof(PiecePlace) == 24, "PiecePlace must stay 24 bytes");
 constexpr uint32_t kChunkIsQueue = 1u << 14;
 
 __device__ __forceinline__ int chunks_of_length(int len) { return (len + kChunkSlots - 1) / kChunkSlots; }
+inline int64_t chunks_of_slots(int64_t slots) { return (slots + kChunkSlots - 1) / kChunkSlots; }
 
 // Walks the row pieces of partition p in row block rb and tells the visitor what becomes of each:
 //   (pieces of more than cs.long_len entries are not part of the lists: the heavy-piece launch sums them)
@@ -576,7 +577,7 @@ __global__ __launch_bounds__(256) void k_pack_pieces(int64_t n_pieces, StreamSha
 
 // One wavefront per chunk of a wide row (and per padding chunk of a group); reads the canonical arrays
 // through the descriptor.  Queue chunks are written by k_pack_pieces and k_part_fill_chunks.
-__global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, int64_t first_heavy, StreamShape ss,
+__global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, StreamShape ss,
                                                      const Chunk* __restrict__ chunks,
                                                      const int32_t* __restrict__ row_ids,
                                                      const int32_t* __restrict__ cols,
@@ -600,8 +601,7 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, int64_t f
   const float val = vals[src];
   const int local_row = rid & ((1 << ss.log2_rb) - 1);
   if (ss.compact) {
-    // (the chunks of heavy pieces, from first_heavy on, hold absolute columns: a heavy list may cross partitions)
-    const uint32_t col_rel = q >= first_heavy ? (uint32_t)col : (uint32_t)(col - (col / ss.phase_width) * ss.phase_width);
+    const uint32_t col_rel = (uint32_t)(col - (col / ss.phase_width) * ss.phase_width);
     put_slot(ss, q, lane,
              (int32_t)(col_rel | ((uint32_t)local_row << kCompactColBits) | ((uint32_t)real << 27) |
                        ((uint32_t)(lw > 6 ? 7 : lw) << 28) | ((uint32_t)hand_over << 31)),
@@ -613,20 +613,27 @@ __global__ __launch_bounds__(256) void k_pack_stream(int64_t n_chunks, int64_t f
 }
 
 // ------------------------------------------------------------ heavy pieces
-// A piece of more than heavy_len real entries is "heavy".  Exclusive prefixes over the pieces in the order of
-// row_ids (buckets in bucket order, then the remainder: partition-major):
-//   unit_before[q]   heavy pieces before piece q
-//   hchunk_before[q] 64-slot chunks of heavy pieces before piece q
+// A piece of more than heavy_len real entries is "heavy".  The entries of all heavy pieces form one sequence, in
+// the order of row_ids (buckets in bucket order, then the remainder: partition-major), which is cut into 64-slot
+// chunks.  When heavy_len >= kChunkSlots the pieces follow each other without a gap (a chunk then holds the end
+// of at most one piece, which is what the kernel can hand over per chunk); shorter heavy pieces each start a
+// chunk of their own.  Exclusive prefixes over the pieces:
+//   unit_before[q]  heavy pieces before piece q
+//   hent_before[q]  slots of the heavy sequence before piece q
 // Both arrays have one element more than there are pieces, so that after the scan the last one is the total.
 // *heavy_nnz receives the real entries of all heavy pieces.
+__device__ __forceinline__ int heavy_footprint(int len, int heavy_len) {
+  return heavy_len >= kChunkSlots ? len : chunks_of_length(len) * kChunkSlots;
+}
+
 __global__ void k_heavy_counts(int64_t n_pieces, const int32_t* __restrict__ row_len, int32_t heavy_len,
-                               int32_t* unit_before, int32_t* hchunk_before, unsigned long long* heavy_nnz) {
+                               int32_t* unit_before, int32_t* hent_before, unsigned long long* heavy_nnz) {
   const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int len = q < n_pieces ? row_len[q] : 0;
   const bool heavy = len > heavy_len;
   if (q <= n_pieces) {
     unit_before[q] = heavy ? 1 : 0;
-    hchunk_before[q] = heavy ? chunks_of_length(len) : 0;
+    hent_before[q] = heavy ? heavy_footprint(len, heavy_len) : 0;
   }
   unsigned long long mine = heavy ? (unsigned long long)len : 0ull;
   for (int d = 32; d > 0; d >>= 1) mine += __shfl_down(mine, d, 64);
@@ -662,56 +669,102 @@ __device__ __forceinline__ int64_t piece_slot0(int64_t q, int64_t B, int32_t k, 
   return bucket_slot_ptr[lo] + ((q - bucket_row_ptr[lo]) << bin);
 }
 
-// One thread per piece: a heavy piece writes the descriptors of its chunks (the stream is packed from them).
-__global__ void k_heavy_chunks(int64_t n_pieces, const int32_t* __restrict__ row_len,
-                               const int32_t* __restrict__ unit_before, const int32_t* __restrict__ hchunk_before,
-                               int64_t B, int32_t k, int64_t R, int64_t S,
-                               const int64_t* __restrict__ bucket_row_ptr,
-                               const int64_t* __restrict__ bucket_slot_ptr, const int64_t* __restrict__ rem_ptr,
-                               Chunk* heavy_chunks) {
+// One thread per piece: heavy piece number u notes which piece it is, where its slots start and where its real
+// entries end (unit_piece, unit_start, unit_end; unit_start has one more element, the total).
+__global__ void k_heavy_units(int64_t n_pieces, const int32_t* __restrict__ row_len,
+                              const int32_t* __restrict__ unit_before, const int32_t* __restrict__ hent_before,
+                              int32_t* unit_piece, int32_t* unit_start, int32_t* unit_end) {
   const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (q >= n_pieces || unit_before[q + 1] == unit_before[q]) return;
-  const int len = row_len[q];
+  if (q > n_pieces) return;
+  if (q == n_pieces) { unit_start[unit_before[q]] = hent_before[q]; return; }
+  if (unit_before[q + 1] == unit_before[q]) return;
+  const int u = unit_before[q];
+  unit_piece[u] = (int32_t)q;
+  unit_start[u] = hent_before[q];
+  unit_end[u] = hent_before[q] + row_len[q];
+}
+
+// One wavefront per chunk of the heavy sequence, a lane per slot: writes the chunk's stream record.  The slot
+// words of a chunk all name the slot at which a piece ends in it (in the place of the local row of the list
+// records), with the hand-over flag set if one does.
+__global__ __launch_bounds__(256) void k_pack_heavy(int64_t n_heavy_chunks, int64_t first_chunk, StreamShape ss,
+                                                    int32_t n_units, const int32_t* __restrict__ unit_piece,
+                                                    const int32_t* __restrict__ unit_start,
+                                                    const int32_t* __restrict__ unit_end, int64_t B, int32_t k,
+                                                    int64_t R, int64_t S,
+                                                    const int64_t* __restrict__ bucket_row_ptr,
+                                                    const int64_t* __restrict__ bucket_slot_ptr,
+                                                    const int64_t* __restrict__ rem_ptr,
+                                                    const int32_t* __restrict__ cols, const float* __restrict__ vals) {
+  const int64_t ck = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (ck >= n_heavy_chunks) return;
+  const int lane = threadIdx.x & 63;
+  const int64_t e0 = ck * kChunkSlots;
+  if (n_units == 0 || e0 >= unit_start[n_units]) {  // past the last piece: padding up to a whole quad
+    put_slot(ss, first_chunk + ck, lane, ss.compact ? (int32_t)0xF0000000u : 0, 0, -1);
+    return;
+  }
+  // the last unit that starts at or before the chunk's first slot
+  int lo = 0, hi = n_units;
+  while (hi - lo > 1) {
+    const int mid = lo + ((hi - lo) >> 1);
+    if ((int64_t)unit_start[mid] <= e0) lo = mid; else hi = mid;
+  }
+  const int64_t e = e0 + lane;
+  const int u = (lo + 1 < n_units && e >= unit_start[lo + 1]) ? lo + 1 : lo;
+  const int32_t q = unit_piece[u];
   const int64_t slot0 = piece_slot0(q, B, k, R, S, bucket_row_ptr, bucket_slot_ptr, rem_ptr);
-  Chunk* out = heavy_chunks + hchunk_before[q];
-  for (int off = 0; off < len; off += kChunkSlots) {
-    Chunk ck;
-    ck.slot0 = slot0 + off; ck.row0 = (int32_t)q;
-    const int count = len - off < kChunkSlots ? len - off : kChunkSlots;
-    ck.meta = (uint32_t)kRowLog2W | ((uint32_t)count << 6) | (off + kChunkSlots >= len ? (1u << 13) : 0u);
-    *out++ = ck;
+  const int len = unit_end[u] - unit_start[u];
+  const int64_t j = e - unit_start[u];
+  const bool real = j < len;
+  const int64_t src = slot0 + (real ? j : len - 1);
+  const int32_t col = cols[src];
+  const float val = real ? vals[src] : 0.f;
+  // the piece that ends inside this chunk, if any, is the one the chunk starts in (a later one would have to
+  // start and end here: heavy pieces are longer than that, or start a chunk of their own)
+  const int64_t end_lo = (int64_t)unit_end[lo] - 1 - e0;
+  const int hand_over = end_lo >= 0 && end_lo < kChunkSlots;
+  const int end_slot = hand_over ? (int)end_lo : 0;
+  if (ss.compact) {
+    put_slot(ss, first_chunk + ck, lane,
+             (int32_t)((uint32_t)col | ((uint32_t)end_slot << kCompactColBits) | ((uint32_t)real << 27) | (7u << 28) |
+                       ((uint32_t)hand_over << 31)),
+             __float_as_int(val), 0);
+  } else {
+    put_slot(ss, first_chunk + ck, lane, col, __float_as_int(val),
+             real ? (end_slot | (kRowLog2W << 16) | (hand_over << 22)) : -1);
   }
 }
 
-// Heavy list w covers heavy chunks [w*L, (w+1)*L).  A wavefront writes a partial-sum row at every piece end and
-// one more where its list ends, so its first write goes to row (pieces that end before chunk w*L) + w.
-__global__ void k_heavy_list_slots(int32_t n_lists, int64_t n_pieces, const int32_t* __restrict__ unit_before,
-                                   const int32_t* __restrict__ hchunk_before, int32_t* hlist_first_slot) {
+// Heavy list w covers the chunks [w*L, (w+1)*L) of the heavy sequence.  A wavefront writes a partial-sum row at
+// every piece end and one more where its list ends, so its first write goes to row (pieces that end before
+// chunk w*L) + w.
+__global__ void k_heavy_list_slots(int32_t n_lists, int32_t n_units, const int32_t* __restrict__ unit_end,
+                                   int32_t* hlist_first_slot) {
   const int w = blockIdx.x * blockDim.x + threadIdx.x;
   if (w >= n_lists) return;
-  const int64_t x = (int64_t)w * kHeavyListChunks;
-  // pieces q with hchunk_before[q + 1] <= x end before chunk x: find the first q with hchunk_before[q + 1] > x
-  int64_t lo = 0, hi = n_pieces;
+  const int64_t x = (int64_t)w * kHeavyListChunks * kChunkSlots;
+  int lo = 0, hi = n_units;  // first unit whose real entries end beyond slot x
   while (lo < hi) {
-    const int64_t mid = lo + ((hi - lo) >> 1);
-    if ((int64_t)hchunk_before[mid + 1] <= x) lo = mid + 1; else hi = mid;
+    const int mid = lo + ((hi - lo) >> 1);
+    if ((int64_t)unit_end[mid] <= x) lo = mid + 1; else hi = mid;
   }
-  // (light pieces before that q add no chunks, so they never end the run early; heavy pieces before it: unit_before)
-  hlist_first_slot[w] = unit_before[lo] + w;
+  hlist_first_slot[w] = lo + w;
 }
 
-// The partial-sum rows of a heavy piece whose chunks are [f0, f1) and that has `u` heavy pieces before it:
-// rows u + w for every heavy list w that holds one of its chunks (see k_heavy_list_slots).
-__device__ __forceinline__ void piece_slots(int u, int f0, int f1, int* first, int* count) {
-  const int w0 = f0 / kHeavyListChunks, w1 = (f1 - 1) / kHeavyListChunks;
+// The partial-sum rows of heavy piece number u whose real entries are the slots [e0, e1) of the heavy sequence:
+// rows u + w for every heavy list w that holds one of them (see k_heavy_list_slots).
+__device__ __forceinline__ void piece_slots(int u, int e0, int e1, int* first, int* count) {
+  const int per_list = kHeavyListChunks * kChunkSlots;
+  const int w0 = e0 / per_list, w1 = (e1 - 1) / per_list;
   *first = u + w0;
   *count = w1 - w0 + 1;
 }
 
 // One thread per row: how many partial-sum rows the heavy pieces of the row have (row_slot_ptr before its scan)
 __global__ void k_row_slot_counts(int32_t n_rows, int32_t c, const int32_t* __restrict__ piece_of,
-                                  const int32_t* __restrict__ unit_before, const int32_t* __restrict__ hchunk_before,
-                                  int32_t* row_slot_ptr) {
+                                  const int32_t* __restrict__ row_len, const int32_t* __restrict__ unit_before,
+                                  const int32_t* __restrict__ hent_before, int32_t* row_slot_ptr) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r > n_rows) return;
   int n = 0;
@@ -720,7 +773,7 @@ __global__ void k_row_slot_counts(int32_t n_rows, int32_t c, const int32_t* __re
       const int32_t q = piece_of[(int64_t)p * n_rows + r];
       if (q < 0 || unit_before[q + 1] == unit_before[q]) continue;
       int first, count;
-      piece_slots(unit_before[q], hchunk_before[q], hchunk_before[q + 1], &first, &count);
+      piece_slots(unit_before[q], hent_before[q], hent_before[q] + row_len[q], &first, &count);
       n += count;
     }
   }
@@ -728,8 +781,9 @@ __global__ void k_row_slot_counts(int32_t n_rows, int32_t c, const int32_t* __re
 }
 
 __global__ void k_row_slot_fill(int32_t n_rows, int32_t c, const int32_t* __restrict__ piece_of,
-                                const int32_t* __restrict__ unit_before, const int32_t* __restrict__ hchunk_before,
-                                const int32_t* __restrict__ row_slot_ptr, int32_t* row_slots) {
+                                const int32_t* __restrict__ row_len, const int32_t* __restrict__ unit_before,
+                                const int32_t* __restrict__ hent_before, const int32_t* __restrict__ row_slot_ptr,
+                                int32_t* row_slots) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= n_rows) return;
   int32_t* out = row_slots + row_slot_ptr[r];
@@ -737,9 +791,22 @@ __global__ void k_row_slot_fill(int32_t n_rows, int32_t c, const int32_t* __rest
     const int32_t q = piece_of[(int64_t)p * n_rows + r];
     if (q < 0 || unit_before[q + 1] == unit_before[q]) continue;
     int first, count;
-    piece_slots(unit_before[q], hchunk_before[q], hchunk_before[q + 1], &first, &count);
+    piece_slots(unit_before[q], hent_before[q], hent_before[q] + row_len[q], &first, &count);
     for (int i = 0; i < count; ++i) *out++ = first + i;
   }
+}
+
+// heavy_rows (compacted): flags, then after their scan the rows themselves
+__global__ void k_heavy_row_flags(int32_t n_rows, const int32_t* __restrict__ row_slot_ptr, int32_t* flag) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r > n_rows) return;
+  flag[r] = (r < n_rows && row_slot_ptr[r + 1] > row_slot_ptr[r]) ? 1 : 0;
+}
+__global__ void k_heavy_row_fill(int32_t n_rows, const int32_t* __restrict__ row_slot_ptr,
+                                 const int32_t* __restrict__ before, int32_t* heavy_rows) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_rows) return;
+  if (row_slot_ptr[r + 1] > row_slot_ptr[r]) heavy_rows[before[r]] = r;
 }
 
 // --------------------------------------------------------------- host helpers
@@ -919,6 +986,8 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   void* tmp_chunks = nullptr;
   void* tmp_place = nullptr;
   void* tmp_order = nullptr;
+  void* tmp_units = nullptr;
+  void* tmp_row_flags = nullptr;
 
   sptir_hyb* h = new (std::nothrow) sptir_hyb();
   if (!h) { free_(tmp.base, actx); return SPTIR_ERR_ALLOC; }
@@ -1058,7 +1127,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     // heavy pieces: the two prefix arrays over the pieces, the (row, partition) -> piece map, scan scratch
     const bool want_heavy = with_spmm_plan && n_pieces > 0;
     const size_t o_unit = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room(n_pieces + 1) : 1));
-    const size_t o_hchunk = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room(n_pieces + 1) : 1));
+    const size_t o_hent = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room(n_pieces + 1) : 1));
     const size_t o_piece_of = tmp2.reserve(sizeof(int32_t) * (want_heavy ? (size_t)s.c * (size_t)s.n_rows : 1));
     const size_t o_seg_at = tmp2.reserve(sizeof(int64_t) * (2 * (size_t)s.c + 1));
     const size_t o_seg_hc = tmp2.reserve(sizeof(int32_t) * (2 * (size_t)s.c + 1));
@@ -1071,7 +1140,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     long long* d_seq_tot = (long long*)(tmp2.base + o_seq_tot);
     long long* d_cell_total = (long long*)(tmp2.base + o_cell_total);
     int32_t* d_unit = (int32_t*)(tmp2.base + o_unit);
-    int32_t* d_hchunk = (int32_t*)(tmp2.base + o_hchunk);
+    int32_t* d_hent = (int32_t*)(tmp2.base + o_hent);
     int32_t* d_piece_of = want_heavy ? (int32_t*)(tmp2.base + o_piece_of) : nullptr;
     int32_t* d_seq_base = (int32_t*)(tmp2.base + o_seq_base);
     int64_t* d_seg_at = (int64_t*)(tmp2.base + o_seg_at);
@@ -1129,11 +1198,11 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     if (want_heavy) {
       BUILD_HIP(hipMemsetAsync(d_cell_total + 1, 0, sizeof(long long), stream));
       hipLaunchKernelGGL(k_heavy_counts, dim3((unsigned)((n_pieces + 256) / 256)), dim3(256), 0, stream, n_pieces,
-                         h->row_len, cs.long_len, d_unit, d_hchunk, (unsigned long long*)(d_cell_total + 1));
+                         h->row_len, cs.long_len, d_unit, d_hent, (unsigned long long*)(d_cell_total + 1));
       BUILD_HIP(hipGetLastError());
       st = device_exclusive_scan(d_unit, n_pieces + 1, d_seq_base, stream);
       if (st != SPTIR_OK) goto fail;
-      st = device_exclusive_scan(d_hchunk, n_pieces + 1, d_seq_base, stream);
+      st = device_exclusive_scan(d_hent, n_pieces + 1, d_seq_base, stream);
       if (st != SPTIR_OK) goto fail;
     }
 
@@ -1168,17 +1237,18 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       seg_at[2 * (size_t)s.c] = n_pieces;
       BUILD_HIP(hipMemcpyAsync(d_seg_at, seg_at.data(), sizeof(int64_t) * seg_at.size(), hipMemcpyHostToDevice, stream));
       hipLaunchKernelGGL(k_pick, dim3((unsigned)((seg_at.size() + 255) / 256)), dim3(256), 0, stream,
-                         (int32_t)seg_at.size(), d_seg_at, d_hchunk, d_seg_hc);
+                         (int32_t)seg_at.size(), d_seg_at, d_hent, d_seg_hc);
       BUILD_HIP(hipGetLastError());
       BUILD_HIP(hipMemcpyAsync(seg_hc.data(), d_seg_hc, sizeof(int32_t) * seg_hc.size(), hipMemcpyDeviceToHost, stream));
       BUILD_HIP(hipMemcpyAsync(&h->n_heavy_nnz, d_cell_total + 1, sizeof(long long), hipMemcpyDeviceToHost, stream));
       BUILD_HIP(hipMemcpyAsync(&heavy_totals[0], d_unit + n_pieces, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipMemcpyAsync(&heavy_totals[1], d_hchunk + n_pieces, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+      BUILD_HIP(hipMemcpyAsync(&heavy_totals[1], d_hent + n_pieces, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
     }
     BUILD_HIP(hipStreamSynchronize(stream));
     // the lists' chunks come first in the stream (each list a whole number of quads), then the heavy chunks
+    // (heavy_totals[1]: slots of the heavy sequence)
     const int64_t n_heavy_chunks =
-        ((int64_t)heavy_totals[1] + kChunksPerQuad - 1) / kChunksPerQuad * kChunksPerQuad;
+        (chunks_of_slots(heavy_totals[1]) + kChunksPerQuad - 1) / kChunksPerQuad * kChunksPerQuad;
     h->n_chunks = n_chunks;
     h->n_heavy = heavy_totals[0];
     h->heavy_chunk0 = n_chunks;
@@ -1189,14 +1259,17 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       h->n_heavy_segs = 2 * s.c;
       h->hseg_list = (int32_t*)malloc(sizeof(int32_t) * (size_t)(h->n_heavy_segs + 1));
       if (!h->hseg_list) { st = SPTIR_ERR_ALLOC; goto fail; }
+      // the first heavy list that starts at or after the chunk in which the segment's first piece starts
       for (int32_t i = 0; i <= h->n_heavy_segs; ++i)
-        h->hseg_list[i] = (int32_t)(((int64_t)seg_hc[i] + kHeavyListChunks - 1) / kHeavyListChunks);
+        h->hseg_list[i] = i == h->n_heavy_segs
+                              ? h->n_heavy_lists
+                              : (int32_t)(((int64_t)seg_hc[i] / kChunkSlots + kHeavyListChunks - 1) / kHeavyListChunks);
     }
     const int64_t all_chunks = n_chunks + n_heavy_chunks;
     if (h->n_partial_rows > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
     {
-      size_t bytes = sizeof(Chunk) * (size_t)(all_chunks ? all_chunks : 1);
-      tmp_chunks = alloc(bytes, actx, stream);  // descriptors are only needed until the stream is packed
+      size_t bytes = sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1);
+      tmp_chunks = alloc(bytes, actx, stream);  // descriptors (of the lists' chunks) are only needed until the stream is packed
       if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
       BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, bytes, stream));  // count 0 marks the padding chunks
       bytes = sizeof(PiecePlace) * (size_t)(n_pieces ? n_pieces : 1);
@@ -1218,47 +1291,67 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
                          h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_ptr, h->S, (Chunk*)tmp_chunks,
                          (PiecePlace*)tmp_place, h->rb_chunk_ptr);
     if (h->n_heavy > 0) {
-      // ---- heavy pieces: chunk descriptors, first partial-sum row of every heavy list, the rows' partial sums
+      // ---- heavy pieces: their stream records, first partial-sum row of every heavy list, the rows' partial sums
       struct { void** p; size_t bytes; } more[] = {
           {(void**)&h->hlist_first_slot, sizeof(int32_t) * (size_t)h->n_heavy_lists},
           {(void**)&h->row_slot_ptr, sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1)},
           {(void**)&h->partial, sizeof(float) * kPartialFeat * (size_t)h->n_partial_rows},
+          {(void**)&tmp_units, sizeof(int32_t) * (3 * (size_t)h->n_heavy + 1)},
+          {(void**)&tmp_row_flags, sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1)},
       };
       for (auto& wnt : more) {
         *wnt.p = alloc(wnt.bytes, actx, stream);
         if (!*wnt.p) { st = SPTIR_ERR_ALLOC; goto fail; }
-        h->device_bytes += wnt.bytes;
       }
-      hipLaunchKernelGGL(k_heavy_chunks, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream, n_pieces,
-                         h->row_len, d_unit, d_hchunk, B, s.k, h->R, h->S, h->bucket_row_ptr, h->bucket_slot_ptr,
-                         h->rem_ptr, (Chunk*)tmp_chunks + n_chunks);
+      h->device_bytes += more[0].bytes + more[1].bytes + more[2].bytes;
+      const int32_t n_units = (int32_t)h->n_heavy;
+      int32_t* unit_piece = (int32_t*)tmp_units;
+      int32_t* unit_end = unit_piece + n_units;
+      int32_t* unit_start = unit_end + n_units;  // [n_units + 1]
+      hipLaunchKernelGGL(k_heavy_units, dim3((unsigned)((n_pieces + 256) / 256)), dim3(256), 0, stream, n_pieces,
+                         h->row_len, d_unit, d_hent, unit_piece, unit_start, unit_end);
+      hipLaunchKernelGGL(k_pack_heavy, dim3((unsigned)((n_heavy_chunks + 3) / 4)), dim3(256), 0, stream,
+                         n_heavy_chunks, (int64_t)n_chunks, ss, n_units, unit_piece, unit_start, unit_end, B, s.k,
+                         h->R, h->S, h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_ptr, h->cols, h->vals);
       hipLaunchKernelGGL(k_heavy_list_slots, dim3((unsigned)((h->n_heavy_lists + 255) / 256)), dim3(256), 0, stream,
-                         h->n_heavy_lists, n_pieces, d_unit, d_hchunk, h->hlist_first_slot);
+                         h->n_heavy_lists, n_units, unit_end, h->hlist_first_slot);
       hipLaunchKernelGGL(k_row_slot_counts, dim3((unsigned)((s.n_rows + 256) / 256)), dim3(256), 0, stream, s.n_rows,
-                         s.c, d_piece_of, d_unit, d_hchunk, h->row_slot_ptr);
+                         s.c, d_piece_of, h->row_len, d_unit, d_hent, h->row_slot_ptr);
       BUILD_HIP(hipGetLastError());
       st = device_exclusive_scan(h->row_slot_ptr, (int64_t)s.n_rows + 1, d_seq_base, stream);
+      if (st != SPTIR_OK) goto fail;
+      // the rows that have heavy pieces, compacted: the launch that adds their partial sums to Y visits only them
+      hipLaunchKernelGGL(k_heavy_row_flags, dim3((unsigned)((s.n_rows + 256) / 256)), dim3(256), 0, stream, s.n_rows,
+                         h->row_slot_ptr, (int32_t*)tmp_row_flags);
+      BUILD_HIP(hipGetLastError());
+      st = device_exclusive_scan((int32_t*)tmp_row_flags, (int64_t)s.n_rows + 1, d_seq_base, stream);
       if (st != SPTIR_OK) goto fail;
       int32_t n_row_slots = 0;
       BUILD_HIP(hipMemcpyAsync(&n_row_slots, h->row_slot_ptr + s.n_rows, sizeof(int32_t), hipMemcpyDeviceToHost,
                                stream));
+      BUILD_HIP(hipMemcpyAsync(&h->n_heavy_rows, (int32_t*)tmp_row_flags + s.n_rows, sizeof(int32_t),
+                               hipMemcpyDeviceToHost, stream));
       BUILD_HIP(hipStreamSynchronize(stream));
-      const size_t bytes = sizeof(int32_t) * (size_t)(n_row_slots ? n_row_slots : 1);
+      size_t bytes = sizeof(int32_t) * (size_t)(n_row_slots ? n_row_slots : 1);
       h->row_slots = (int32_t*)alloc(bytes, actx, stream);
       if (!h->row_slots) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += bytes;
+      bytes = sizeof(int32_t) * (size_t)(h->n_heavy_rows ? h->n_heavy_rows : 1);
+      h->heavy_rows = (int32_t*)alloc(bytes, actx, stream);
+      if (!h->heavy_rows) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += bytes;
       hipLaunchKernelGGL(k_row_slot_fill, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
-                         s.c, d_piece_of, d_unit, d_hchunk, h->row_slot_ptr, h->row_slots);
+                         s.c, d_piece_of, h->row_len, d_unit, d_hent, h->row_slot_ptr, h->row_slots);
+      hipLaunchKernelGGL(k_heavy_row_fill, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
+                         h->row_slot_ptr, (const int32_t*)tmp_row_flags, h->heavy_rows);
       BUILD_HIP(hipGetLastError());
     }
-    if (all_chunks > 0) {
-      int64_t blocks = (all_chunks + 3) / 4;
+    if (n_chunks > 0) {
+      int64_t blocks = (n_chunks + 3) / 4;
       if (blocks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
-      // the heavy chunks hold absolute columns: one heavy list may cross partitions
-      StreamShape ss_all = ss;
-      hipLaunchKernelGGL(k_pack_stream, dim3((unsigned)blocks), dim3(256), 0, stream, (int64_t)all_chunks, n_chunks,
-                         ss_all, (const Chunk*)tmp_chunks, h->row_ids, h->cols, h->vals);
-      if (n_pieces > 0 && n_chunks > 0)
+      hipLaunchKernelGGL(k_pack_stream, dim3((unsigned)blocks), dim3(256), 0, stream, (int64_t)n_chunks, ss,
+                         (const Chunk*)tmp_chunks, h->row_ids, h->cols, h->vals);
+      if (n_pieces > 0)
         hipLaunchKernelGGL(k_pack_pieces, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream, n_pieces, ss,
                            (const PiecePlace*)tmp_place, h->row_ids, h->cols, h->vals);
     }
@@ -1291,6 +1384,8 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   if (tmp_chunks) free_(tmp_chunks, actx);
   if (tmp_place) free_(tmp_place, actx);
   if (tmp_order) free_(tmp_order, actx);
+  if (tmp_units) free_(tmp_units, actx);
+  if (tmp_row_flags) free_(tmp_row_flags, actx);
   *out = h;
   return SPTIR_OK;
 
@@ -1301,6 +1396,8 @@ fail:
   if (tmp_chunks) free_(tmp_chunks, actx);
   if (tmp_place) free_(tmp_place, actx);
   if (tmp_order) free_(tmp_order, actx);
+  if (tmp_units) free_(tmp_units, actx);
+  if (tmp_row_flags) free_(tmp_row_flags, actx);
   sptir_hyb_destroy(h);
   return st;
 #undef BUILD_HIP

@@ -324,6 +324,7 @@ struct HybWalker {
   unsigned row_bytes, lane_bytes;  // bytes per row of X, byte offset of this lane's features
   Sink sink;
   float acc[VEC];
+  float next_acc[VEC];   // heavy lists: what a chunk holds of the piece after the one that ends in it
 
   __device__ __forceinline__ void fetch(int q, Fetched& f) const {
     q = q < n_quads ? q : n_quads - 1;
@@ -439,6 +440,36 @@ struct HybWalker {
       for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
       return;
     }
+    if constexpr (!Sink::kQueues) {
+      // Heavy lists: pieces follow each other without a gap, so a chunk may hold the end of one piece (at the
+      // slot its words name) and the start of the next.  What lies past the end is summed apart and becomes
+      // the running sum once the finished piece has been handed over.
+      if (!hand_over) {
+#pragma unroll
+        for (int j = 0; j < UB; ++j)
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
+        return;
+      }
+      const int end_slot = local_row(rows[(s - sub) * CS]);
+      const int slot0 = sub * CS + g * UB;  // this lane group's first slot of the chunk in this step
+#pragma unroll
+      for (int j = 0; j < UB; ++j) {
+        const bool before = slot0 + j <= end_slot;
+        const float va = before ? v[j] : 0.f, vb = before ? 0.f : v[j];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          acc[e] = fmaf(va, x[j][e], acc[e]);
+          next_acc[e] = fmaf(vb, x[j][e], next_acc[e]);
+        }
+      }
+      if (sub != SUB - 1) return;
+      sum_groups<VEC, LG>(acc, S::kGroups);
+      sink(0, g == 0, acc);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { acc[e] = next_acc[e]; next_acc[e] = 0.f; }
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < UB; ++j)
 #pragma unroll
@@ -455,7 +486,7 @@ struct HybWalker {
 
   __device__ __forceinline__ void run() {
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    for (int e = 0; e < VEC; ++e) { acc[e] = 0.f; next_acc[e] = 0.f; }
     if (n_quads <= 0) return;
     // Quads 0 and 1 are requested at once and quad 0 is parked.  From then on, at the start of quad Q, quad Q+1
     // (requested a whole quad earlier, so long arrived: a load that is waited for too early stalls every load
@@ -567,7 +598,7 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   const int n_list = (int)(a.rb_chunk_ptr[rb + 1] - c0);  // a multiple of kChunksPerQuad
   const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
   W wk{a.X, a.stream + (size_t)c0 * (W::kArrays * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
-       (unsigned)a.feat * 4u, (unsigned)f_read * 4u, TileSink<VEC, LG>{tile, fl, f_active}, {}};
+       (unsigned)a.feat * 4u, (unsigned)f_read * 4u, TileSink<VEC, LG>{tile, fl, f_active}, {}, {}};
   wk.run();
 
   // write the tile: a lane group per row, one 128-byte line per group
@@ -633,27 +664,27 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_heavy(HeavyArgs a) {
   const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
   W wk{a.X, a.stream + (size_t)(a.chunk0 + c0) * (W::kArrays * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
        (unsigned)a.feat * 4u, (unsigned)f_read * 4u,
-       PartialSink<VEC, LG>{a.partial + f_in_sweep, __builtin_amdgcn_readfirstlane(a.first_slot[list]), f_active}, {}};
+       PartialSink<VEC, LG>{a.partial + f_in_sweep, __builtin_amdgcn_readfirstlane(a.first_slot[list]), f_active}, {}, {}};
   wk.run();
   sum_groups<VEC, LG>(wk.acc, S::kGroups);
   wk.sink(0, g == 0, wk.acc);
 }
 
 // Y[r, feat0 + f] += (row_val[r] *) the partial sums of row r's heavy pieces, in the order of row_slots (partition by partition):
-// one thread per (row, VEC features).  Runs after the chunk-list launches have written Y.
+// one thread per (row with heavy pieces, VEC features).  Runs after the chunk-list launches have written Y.
 template <int VEC>
-__global__ __launch_bounds__(256) void k_heavy_reduce(const int32_t* __restrict__ row_slot_ptr,
+__global__ __launch_bounds__(256) void k_heavy_reduce(const int32_t* __restrict__ heavy_rows,
+                                                      const int32_t* __restrict__ row_slot_ptr,
                                                       const int32_t* __restrict__ row_slots,
                                                       const float* __restrict__ partial,
                                                       const float* __restrict__ row_val, float* Y, int32_t n_rows,
                                                       int32_t feat, int32_t feat0, int32_t width) {
   const int per_row = width / VEC;
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t r = t / per_row;
-  if (r >= n_rows) return;
+  if (t / per_row >= n_rows) return;  // (n_rows: rows with heavy pieces)
+  const int64_t r = heavy_rows[t / per_row];
   const int f = (int)(t % per_row) * VEC;
   const int b = row_slot_ptr[r], e = row_slot_ptr[r + 1];
-  if (b == e) return;
   float sum[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) sum[i] = 0.f;
@@ -966,15 +997,15 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
         first = end;
       }
       if (timers) timers->mark(stream, LaunchTimers::kHeavy, n_heavy_launches);
-      const int64_t n_threads = (int64_t)h->n_rows * (width / (y_vec4 ? 4 : 1));
+      const int64_t n_threads = (int64_t)h->n_heavy_rows * (width / (y_vec4 ? 4 : 1));
       const dim3 grid((unsigned)((n_threads + 255) / 256)), block(256);
       if ((n_threads + 255) / 256 > 0x7FFFFFFF) return SPTIR_ERR_OVERFLOW;
       if (y_vec4)
-        hipLaunchKernelGGL(k_heavy_reduce<4>, grid, block, 0, stream, h->row_slot_ptr, h->row_slots, partial,
-                           h->row_val, Y, h->n_rows, feat, feat0, width);
+        hipLaunchKernelGGL(k_heavy_reduce<4>, grid, block, 0, stream, h->heavy_rows, h->row_slot_ptr, h->row_slots,
+                           partial, h->row_val, Y, h->n_heavy_rows, feat, feat0, width);
       else
-        hipLaunchKernelGGL(k_heavy_reduce<1>, grid, block, 0, stream, h->row_slot_ptr, h->row_slots, partial,
-                           h->row_val, Y, h->n_rows, feat, feat0, width);
+        hipLaunchKernelGGL(k_heavy_reduce<1>, grid, block, 0, stream, h->heavy_rows, h->row_slot_ptr, h->row_slots,
+                           partial, h->row_val, Y, h->n_heavy_rows, feat, feat0, width);
       if (timers) timers->mark(stream, LaunchTimers::kReduce, 1);
     }
   }
