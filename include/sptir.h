@@ -84,7 +84,27 @@ typedef enum {
   SPTIR_HYB_REM_PTR = 7,
   SPTIR_HYB_REM_COL = 8,
   SPTIR_HYB_REM_VAL = 9,
-  SPTIR_HYB_N_ARRAYS = 10
+  SPTIR_HYB_N_ARRAYS = 10,
+  /* What sptir_spmm reads instead of the canonical arrays (derived from them at build time; exported so that a
+   * test can decode it and find every non-zero of A exactly once).  The chunk stream: fixed records of four
+   * 64-slot chunks ("quads"), each [256 column words][256 values unless values_per_row][256 row words unless
+   * compact_stream]; first the chunk lists, list (launch l, row block b) at chunks RB_CHUNK_PTR[l * n_row_blocks
+   * + b] .. [.. + 1), then from chunk n_work_items on the heavy sequence, heavy list w at its chunks 32 w ...
+   * A compact column word holds the column relative to the first column of the launch in bits 0..19 (heavy
+   * chunks: the column itself), bits 20..26 the row relative to the row block (heavy chunks: the slot at which a
+   * piece ends in the chunk), bit 27 "the slot holds an entry", bits 28..30 the chunk kind (3: eight queues of
+   * eight slots, slot 8q + j continuing queue q; 7: 64 slots of one row piece), bit 31 the hand-over flag (queue
+   * chunk: this slot is the last entry of a row piece; otherwise the chunk's: a piece ends in it).  Without
+   * compact_stream the column word is the column and the row word holds bits 0..15 row (or end slot), 16..21 kind
+   * (3 or 31), bit 22 hand-over, bit 23 / the value -1 "no entry". */
+  SPTIR_PLAN_STREAM = 100,            /* int32 */
+  SPTIR_PLAN_RB_CHUNK_PTR = 101,      /* int64 [n_phases * n_row_blocks + 1] */
+  SPTIR_PLAN_RB_ORDER = 102,          /* int32 [n_phases * n_row_blocks]: launch order of the row blocks */
+  SPTIR_PLAN_HLIST_FIRST_SLOT = 103,  /* int32 [n_heavy_lists]: partial-sum row of each heavy list's first write */
+  SPTIR_PLAN_ROW_SLOT_PTR = 104,      /* int32 [n_rows + 1] */
+  SPTIR_PLAN_ROW_SLOTS = 105,         /* int32: the partial-sum rows that are added to row r of Y */
+  SPTIR_PLAN_HEAVY_ROWS = 106,        /* int32: the rows with heavy pieces, ascending */
+  SPTIR_PLAN_ROW_VAL = 107            /* float [n_rows], only with values_per_row */
 } sptir_hyb_array_id;
 
 typedef struct {
@@ -112,7 +132,9 @@ typedef struct {
   int32_t heavy_len;
   int32_t n_heavy_lists;    /* wavefronts of that launch per feature tile */
   int32_t values_per_row;   /* 1: every row of A has one value for all its entries and the SpMM stream holds none */
-  int32_t reserved;
+  int32_t compact_stream;   /* 1: 8-byte stream records (4 with values_per_row), 0: 12-byte (8) */
+  int32_t n_row_blocks;
+  int32_t parts_per_launch; /* column partitions one chunk list sweeps */
   int64_t device_bytes;     /* device memory the handle owns */
 } sptir_hyb_info_t;
 

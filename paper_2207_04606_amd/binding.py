@@ -18,10 +18,15 @@ LIB_PATH = os.path.join(_HERE, "libsptir.so")
 
 SPTIR_OK = 0
 ARRAY_IDS = {"bucket_row_ptr": 0, "bucket_slot_ptr": 1, "ell_row": 2, "ell_col": 3, "ell_val": 4,
-             "rem_part_ptr": 5, "rem_row": 6, "rem_ptr": 7, "rem_col": 8, "rem_val": 9}
+             "rem_part_ptr": 5, "rem_row": 6, "rem_ptr": 7, "rem_col": 8, "rem_val": 9,
+             "plan_stream": 100, "plan_rb_chunk_ptr": 101, "plan_rb_order": 102, "plan_hlist_first_slot": 103,
+             "plan_row_slot_ptr": 104, "plan_row_slots": 105, "plan_heavy_rows": 106, "plan_row_val": 107}
 ARRAY_DTYPES = {"bucket_row_ptr": np.int64, "bucket_slot_ptr": np.int64, "ell_row": np.int32,
                 "ell_col": np.int32, "ell_val": np.float32, "rem_part_ptr": np.int32,
-                "rem_row": np.int32, "rem_ptr": np.int64, "rem_col": np.int32, "rem_val": np.float32}
+                "rem_row": np.int32, "rem_ptr": np.int64, "rem_col": np.int32, "rem_val": np.float32,
+                "plan_stream": np.int32, "plan_rb_chunk_ptr": np.int64, "plan_rb_order": np.int32,
+                "plan_hlist_first_slot": np.int32, "plan_row_slot_ptr": np.int32, "plan_row_slots": np.int32,
+                "plan_heavy_rows": np.int32, "plan_row_val": np.float32}
 
 
 class SptirError(RuntimeError):
@@ -48,7 +53,8 @@ class _Info(ctypes.Structure):
                 ("row_block", ctypes.c_int32), ("n_phases", ctypes.c_int32), ("rounds", ctypes.c_int32),
                 ("n_heavy_pieces", ctypes.c_int64), ("n_heavy_items", ctypes.c_int64), ("n_heavy_nnz", ctypes.c_int64),
                 ("heavy_len", ctypes.c_int32), ("n_heavy_lists", ctypes.c_int32), ("values_per_row", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
+                ("compact_stream", ctypes.c_int32), ("n_row_blocks", ctypes.c_int32),
+                ("parts_per_launch", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
 
 
 class _BuildOptions(ctypes.Structure):

@@ -87,6 +87,7 @@ sptir_status_t sptir_hyb_info(const sptir_hyb_t* h, sptir_hyb_info_t* out) {
   o.n_heavy_pieces = h->n_heavy; o.n_heavy_items = h->n_heavy_chunks; o.n_heavy_nnz = h->n_heavy_nnz;
   o.heavy_len = h->heavy_len; o.n_heavy_lists = h->n_heavy_lists;
   o.values_per_row = h->row_val ? 1 : 0;
+  o.compact_stream = h->compact_stream; o.n_row_blocks = h->n_row_blocks; o.parts_per_launch = h->parts_per_phase;
   o.device_bytes = (int64_t)h->device_bytes;
   *out = o;
   return SPTIR_OK;
@@ -107,6 +108,17 @@ sptir_status_t sptir_hyb_array(const sptir_hyb_t* h, int32_t which, const void**
     case SPTIR_HYB_REM_PTR: p = h->rem_ptr; n = h->M + 1; break;
     case SPTIR_HYB_REM_COL: p = h->cols + h->S; n = h->T; break;
     case SPTIR_HYB_REM_VAL: p = h->vals + h->S; n = h->T; break;
+    case SPTIR_PLAN_STREAM:
+      p = h->stream;
+      n = (h->n_chunks + h->n_heavy_chunks) * sptir::kChunkSlots * ((h->compact_stream ? 2 : 3) - (h->row_val ? 1 : 0));
+      break;
+    case SPTIR_PLAN_RB_CHUNK_PTR: p = h->rb_chunk_ptr; n = h->spmm_plan ? (int64_t)h->n_phases * h->n_row_blocks + 1 : 0; break;
+    case SPTIR_PLAN_RB_ORDER: p = h->rb_order; n = h->spmm_plan ? (int64_t)h->n_phases * h->n_row_blocks : 0; break;
+    case SPTIR_PLAN_HLIST_FIRST_SLOT: p = h->hlist_first_slot; n = h->n_heavy > 0 ? h->n_heavy_lists : 0; break;
+    case SPTIR_PLAN_ROW_SLOT_PTR: p = h->row_slot_ptr; n = h->n_heavy > 0 ? (int64_t)h->n_rows + 1 : 0; break;
+    case SPTIR_PLAN_ROW_SLOTS: p = h->row_slots; n = h->n_heavy > 0 ? h->n_row_slots : 0; break;
+    case SPTIR_PLAN_HEAVY_ROWS: p = h->heavy_rows; n = h->n_heavy > 0 ? h->n_heavy_rows : 0; break;
+    case SPTIR_PLAN_ROW_VAL: p = h->row_val; n = h->row_val ? h->n_rows : 0; break;
     default: return SPTIR_ERR_INVALID_ARG;
   }
   if (h->canonical_released && (which == SPTIR_HYB_ELL_COL || which == SPTIR_HYB_ELL_VAL ||

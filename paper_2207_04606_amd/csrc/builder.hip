@@ -1332,6 +1332,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       BUILD_HIP(hipMemcpyAsync(&h->n_heavy_rows, (int32_t*)tmp_row_flags + s.n_rows, sizeof(int32_t),
                                hipMemcpyDeviceToHost, stream));
       BUILD_HIP(hipStreamSynchronize(stream));
+      h->n_row_slots = n_row_slots;
       size_t bytes = sizeof(int32_t) * (size_t)(n_row_slots ? n_row_slots : 1);
       h->row_slots = (int32_t*)alloc(bytes, actx, stream);
       if (!h->row_slots) { st = SPTIR_ERR_ALLOC; goto fail; }

@@ -81,6 +81,7 @@ struct sptir_hyb {
   int32_t* row_slot_ptr;      // device [n_rows + 1]: the partial-sum rows of row r are row_slots[row_slot_ptr[r] ..)
   int32_t* row_slots;         // device, in the order they are added to Y (partition-major)
   int32_t n_heavy_rows;       // rows with at least one heavy piece
+  int32_t n_row_slots;        // elements of row_slots
   int32_t* heavy_rows;        // device [n_heavy_rows], ascending
   float* partial;             // device [(n_heavy + n_heavy_lists)][kPartialFeat]
   int64_t n_partial_rows;
