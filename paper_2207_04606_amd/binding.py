@@ -443,8 +443,12 @@ _torch_blocks: dict[int, torch.Tensor] = {}
 
 @_ALLOC_FN
 def _torch_alloc(nbytes, ctx, stream):
+    # The block is taken from torch's caching allocator under the stream the library will first use it on, so that
+    # the allocator orders its reuse (of this block now, and of its memory after the free) against that stream.
     try:
-        t = torch.empty(max(int(nbytes), 1), dtype=torch.uint8, device="cuda")
+        on = torch.cuda.ExternalStream(int(stream)) if stream else torch.cuda.default_stream()
+        with torch.cuda.stream(on):
+            t = torch.empty(max(int(nbytes), 1), dtype=torch.uint8, device="cuda")
     except Exception:
         return None
     _torch_blocks[t.data_ptr()] = t
@@ -458,7 +462,9 @@ def _torch_free(ptr, ctx):
 
 def sptir_set_allocator(use_torch: bool) -> None:
     """Routes the library's device allocations through torch's caching allocator
-    (True) or back to hipMalloc/hipFree (False)."""
+    (True) or back to hipMalloc/hipFree (False).  A block belongs to the stream of the call that allocated it
+    (the build's stream for a handle's arrays): a handle used on other streams as well must not be destroyed
+    while work on them is pending, as with any torch tensor shared between streams."""
     lib = load_library()
     if use_torch:
         st = lib.sptir_set_allocator(_torch_alloc, _torch_free, None)

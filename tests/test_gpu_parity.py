@@ -111,6 +111,32 @@ def test_hyb_build_through_torch_allocator(gpu_lib):
         gpu_lib.sptir_set_allocator(False)
 
 
+def test_torch_allocator_on_a_side_stream(gpu_lib):
+    """Build, SpMM and destroy on a side stream with the library's memory coming from torch's allocator, while the
+    default stream keeps allocating, filling and freeing blocks of the sizes in play: blocks the library took
+    under the side stream must not be handed to the default stream while the side stream still uses them."""
+    w = workloads.make_config("small")
+    d = upload(w)
+    Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    gpu_lib.sptir_set_allocator(True)
+    try:
+        for rep in range(4):
+            with torch.cuda.stream(s):
+                hyb = gpu_lib.sptir_hyb_build_ex(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 2, 4,
+                                                 {"rounds": 1, "heavy_len": 8}, stream=s)
+                Y = torch.empty(w.n_rows, w.feat, device="cuda")
+                gpu_lib.sptir_spmm(hyb, d.X, Y, stream=s)
+                hyb.destroy()
+            for nbytes in (1 << 12, 1 << 16, 1 << 20, 1 << 22):      # default stream: churn
+                torch.full((nbytes,), 255, dtype=torch.uint8, device="cuda")
+            s.synchronize()
+            assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"torch allocator, side stream, repeat {rep}")
+    finally:
+        gpu_lib.sptir_set_allocator(False)
+
+
 def test_error_paths(gpu_lib):
     sptir = gpu_lib
     dev = "cuda"

@@ -106,24 +106,40 @@ def test_rgms_edge_cases_and_errors(gpu_lib):
         gpu_lib.sptir_rgms(h, torch.zeros(10, 48, device=dev), torch.zeros(3, 48, 32, device=dev), Y)
     with pytest.raises(ValueError):
         gpu_lib.sptir_rgms(h, torch.zeros(10, 32, device=dev), torch.zeros(2, 32, 32, device=dev), Y)
-    with pytest.raises(gpu_lib.SptirError):        # stacked rows not a multiple of the relation count
-        gpu_lib.sptir_rgms_build(4, 10, 10, ip[:31], ix, va) if False else gpu_lib.sptir_rgms_build(
-            7, 10, 10, torch.zeros(7 * 10 + 1, dtype=torch.int32, device=dev), ix, va, 9)
+    with pytest.raises(gpu_lib.SptirError):        # a bucket count beyond what the builder supports
+        gpu_lib.sptir_rgms_build(7, 10, 10, torch.zeros(7 * 10 + 1, dtype=torch.int32, device=dev), ix, va, 9)
     with pytest.raises(gpu_lib.SptirError):        # workspace width not a multiple of 32
         gpu_lib.sptir_rgms_build(3, 10, 10, ip, ix, va, -1, 48)
     h.destroy()
 
 
+def capped_hetero(seed, n, n_rel, cap, d=32):
+    """A heterogeneous graph whose every (relation, row) pair has between 0 and `cap` entries."""
+    rng = np.random.default_rng(seed)
+    counts = rng.integers(0, cap + 1, n_rel * n)
+    counts[rng.random(n_rel * n) < 0.5] = 0
+    counts[rng.integers(0, n_rel * n, 8)] = cap          # the cap is reached
+    indptr = np.zeros(n_rel * n + 1, dtype=np.int64); np.cumsum(counts, out=indptr[1:])
+    indices = np.concatenate([np.sort(rng.choice(n, int(m), replace=False)) for m in counts if m] or [np.zeros(0)])
+    return workloads.HeteroWorkload("capped", n, n_rel, indptr.astype(np.int32), indices.astype(np.int32),
+                                    rng.uniform(-1, 1, indices.shape[0]).astype(np.float32),
+                                    rng.standard_normal((n, d)).astype(np.float32),
+                                    rng.standard_normal((n_rel, d, d)).astype(np.float32))
+
+
 def test_rgms_workspace_path_is_reproducible(gpu_lib):
-    """With the workspace every sum has a fixed order (no remainder pieces in this graph): two calls agree bit for bit."""
+    """With the workspace, and no (relation, row) pair longer than the widest bucket (so nothing goes to the
+    remainder, whose pieces meet in atomic adds), every sum has a fixed order: calls agree bit for bit."""
+    wl = capped_hetero(9, 700, 5, 32)
+    assert np.diff(wl.indptr).max() == 32
+    (Y1, Y2, Y3), info = run_rgms(gpu_lib, wl, workspace_d_out=32, repeat=3)
+    assert info["max_bucket_log2"] == 5
+    assert np.array_equal(Y1, Y2) and np.array_equal(Y1, Y3)
+    Yr, Sr = oracle.rgms(wl.n_rel, wl.n, wl.indptr, wl.indices, wl.values, wl.X, wl.W)
+    assert_y_close(Y1, Yr, Sr, "capped workspace")
+    # and on a graph with remainder pieces the two paths agree with the oracle to rounding
     w = workloads.make_hetero("hetero_a")
     assert np.diff(w.indptr).max() > 32
-    w2 = workloads.make_hetero("hetero_tiny", seed=3, scale=0.5)
-    for wl in (w2,):
-        if np.diff(wl.indptr).max() <= 32:
-            (Y1, Y2), info = run_rgms(gpu_lib, wl, workspace_d_out=32, repeat=2)
-            assert np.array_equal(Y1, Y2)
-    # and on a graph with remainder pieces the two paths agree with each other to rounding
     Ya, _ = run_rgms(gpu_lib, w, workspace_d_out=0)
     Yb, _ = run_rgms(gpu_lib, w, workspace_d_out=32)
     Yr, Sr = oracle.rgms(w.n_rel, w.n, w.indptr, w.indices, w.values, w.X, w.W)
@@ -131,7 +147,7 @@ def test_rgms_workspace_path_is_reproducible(gpu_lib):
 
 
 @pytest.mark.parametrize("workspace", [0, 32])
-@pytest.mark.parametrize("name", ["hetero_a", "hetero_b", "hetero_c", "hetero_d"])
+@pytest.mark.parametrize("name", ["hetero_a", "hetero_b", "hetero_c", "hetero_d", "hetero_e"])
 def test_rgms_named_configs(gpu_lib, name, workspace):
     w = workloads.make_hetero(name)
     Y, info = run_rgms(gpu_lib, w, workspace_d_out=workspace)
