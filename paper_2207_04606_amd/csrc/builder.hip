@@ -13,6 +13,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -30,12 +31,42 @@ struct BuildShape {
   int32_t NB;  // row blocks = ceil(n_rows / 256)
 };
 
+// bound[(p - 1) * n_rows + r] = first position of row r whose column is >= p * w, for p = 1 .. c-1.  A workgroup
+// takes kBoundRows rows x up to kBoundParts partitions with the partition index running fastest over the lanes, so
+// that the searches of a wavefront probe the entries of a few rows only (they are in cache after the first
+// probes), and writes its results through an LDS tile, so that consecutive lanes write consecutive rows.
+constexpr int kBoundRows = 64, kBoundParts = 64;
+
+__global__ __launch_bounds__(256) void k_piece_bounds(BuildShape s, int32_t nnz,
+                                                      const int32_t* __restrict__ indptr,
+                                                      const int32_t* __restrict__ indices,
+                                                      int32_t* __restrict__ bound) {
+  __shared__ int32_t tile[kBoundParts][kBoundRows + 1];
+  const int n_pc = (s.c - 1 + kBoundParts - 1) / kBoundParts;
+  const int rb = blockIdx.x / n_pc, pc = blockIdx.x % n_pc;
+  const int r0 = rb * kBoundRows, p0 = 1 + pc * kBoundParts;
+  const int np = s.c - p0 < kBoundParts ? s.c - p0 : kBoundParts;
+  const int nr = s.n_rows - r0 < kBoundRows ? s.n_rows - r0 : kBoundRows;
+  for (int idx = threadIdx.x; idx < nr * np; idx += blockDim.x) {
+    const int rl = idx / np, pl = idx - rl * np;
+    // (this runs before the host has seen the verdict on indptr: whatever it holds, no read leaves `indices`)
+    int a = indptr[r0 + rl], b = indptr[r0 + rl + 1];
+    a = a < 0 ? 0 : (a > nnz ? nnz : a);
+    b = b < a ? a : (b > nnz ? nnz : b);
+    tile[pl][rl] = lower_bound_col(indices, a, b, (int64_t)(p0 + pl) * s.w);
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < nr * np; idx += blockDim.x) {
+    const int pl = idx / nr, rl = idx - pl * nr;
+    bound[(int64_t)(p0 + pl - 1) * s.n_rows + r0 + rl] = tile[pl][rl];
+  }
+}
+
 // start and length of row r's piece in partition p
 __device__ __forceinline__ void row_piece(const BuildShape& s, const int32_t* __restrict__ indptr,
-                                          const int32_t* __restrict__ indices, int r, int p, int* lo, int* len) {
-  int a = indptr[r], b = indptr[r + 1];
-  int first = (p == 0) ? a : lower_bound_col(indices, a, b, (int64_t)p * s.w);
-  int last = (p == s.c - 1) ? b : lower_bound_col(indices, first, b, (int64_t)(p + 1) * s.w);
+                                          const int32_t* __restrict__ bound, int r, int p, int* lo, int* len) {
+  const int first = (p == 0) ? indptr[r] : bound[(int64_t)(p - 1) * s.n_rows + r];
+  const int last = (p == s.c - 1) ? indptr[r + 1] : bound[(int64_t)p * s.n_rows + r];
   *lo = first;
   *len = last - first;
 }
@@ -56,6 +87,12 @@ __device__ __forceinline__ int bin_of_length(int l, int k) {
 // flags[4]: number of positions q >= 1 whose value differs (as a bit pattern) from the one stored before it
 // flags[5]: number of non-empty rows whose first value differs from the value stored just before it
 // Every row has one value for all of its entries iff flags[4] == flags[5] (only counted when `values` is given).
+// The counters exist kFlagSlots times, 64 bytes apart, and a wavefront adds to the copy its workgroup id picks:
+// tens of thousands of atomic adds to one address would take longer than reading the matrix.  The host adds up.
+constexpr int kFlagSlots = 64, kFlagStride = 8;
+__device__ __forceinline__ unsigned long long* flag_slot(unsigned long long* flags) {
+  return flags + (blockIdx.x & (kFlagSlots - 1)) * kFlagStride;
+}
 __global__ void k_validate_rows(int32_t n_rows, int64_t nnz, const int32_t* __restrict__ indptr,
                                 const int32_t* __restrict__ indices, const int32_t* __restrict__ values,
                                 unsigned long long* flags) {
@@ -75,6 +112,7 @@ __global__ void k_validate_rows(int32_t n_rows, int64_t nnz, const int32_t* __re
     legal_changes += __shfl_down(legal_changes, d, 64);
   }
   const unsigned long long any_bad = __ballot(bad);
+  flags = flag_slot(flags);
   if ((threadIdx.x & 63) == 0) {
     if (legal_changes) atomicAdd(&flags[5], (unsigned long long)legal_changes);
     if (legal_descents) atomicAdd(&flags[3], (unsigned long long)legal_descents);
@@ -82,16 +120,56 @@ __global__ void k_validate_rows(int32_t n_rows, int64_t nnz, const int32_t* __re
   }
 }
 
-__global__ void k_validate_elems(int64_t nnz, int32_t n_cols, const int32_t* __restrict__ indices,
-                                 const int32_t* __restrict__ values, unsigned long long* flags) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+// One thread checks 8 consecutive positions per step (two 16-byte loads per array when `vec` says that the arrays
+// are 16-byte aligned, 4-byte loads otherwise; all loads of a step are issued before any is used); position q is
+// compared with position q - 1, which the lane below holds (the first lane of a wavefront loads it).
+__device__ __forceinline__ int4 load4(const int32_t* __restrict__ p, int vec) {
+  if (vec) return *reinterpret_cast<const int4*>(p);
+  return make_int4(p[0], p[1], p[2], p[3]);
+}
+__device__ __forceinline__ int ascents_not(int prev, const int4& a, const int4& b, bool has_prev) {
+  return (has_prev && a.x <= prev) + (a.y <= a.x) + (a.z <= a.y) + (a.w <= a.z) + (b.x <= a.w) + (b.y <= b.x) +
+         (b.z <= b.y) + (b.w <= b.z);
+}
+__device__ __forceinline__ int changes_of(int prev, const int4& a, const int4& b, bool has_prev) {
+  return (has_prev && a.x != prev) + (a.y != a.x) + (a.z != a.y) + (a.w != a.z) + (b.x != a.w) + (b.y != b.x) +
+         (b.z != b.y) + (b.w != b.z);
+}
+
+__global__ __launch_bounds__(256) void k_validate_elems(int64_t nnz, int32_t n_cols, int vec,
+                                                        const int32_t* __restrict__ indices,
+                                                        const int32_t* __restrict__ values,
+                                                        unsigned long long* flags) {
+  constexpr int kPer = 8;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * kPer;
+  const int lane = threadIdx.x & 63;
+  const bool with_values = values != nullptr;
   unsigned int descents = 0, changes = 0;
   bool range = false;
-  for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nnz; q += stride) {
-    int32_t col = indices[q];
-    range |= (col < 0) || (col >= n_cols);
-    descents += (q > 0) && (col <= indices[q - 1]);
-    if (values) changes += (q > 0) && (values[q] != values[q - 1]);
+  int64_t q = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * kPer;
+  for (; q + kPer <= nnz; q += stride) {  // whole groups
+    const int64_t q_prev = q > 0 ? q - 1 : 0;
+    const int4 c0 = load4(indices + q, vec), c1 = load4(indices + q + 4, vec);
+    int4 v0 = make_int4(0, 0, 0, 0), v1 = v0;
+    if (with_values) { v0 = load4(values + q, vec); v1 = load4(values + q + 4, vec); }
+    int first_c = 0, first_v = 0;
+    if (lane == 0) {
+      first_c = indices[q_prev];
+      if (with_values) first_v = values[q_prev];
+    }
+    int prev_c = __shfl_up(c1.w, 1, 64), prev_v = __shfl_up(v1.w, 1, 64);
+    if (lane == 0) { prev_c = first_c; prev_v = first_v; }
+    const unsigned n = (unsigned)n_cols;
+    range |= ((unsigned)c0.x >= n) | ((unsigned)c0.y >= n) | ((unsigned)c0.z >= n) | ((unsigned)c0.w >= n) |
+             ((unsigned)c1.x >= n) | ((unsigned)c1.y >= n) | ((unsigned)c1.z >= n) | ((unsigned)c1.w >= n);
+    descents += ascents_not(prev_c, c0, c1, q > 0);
+    if (with_values) changes += changes_of(prev_v, v0, v1, q > 0);
+  }
+  for (int i = 0; i < kPer && q + i < nnz; ++i) {  // the thread that holds the last, partial group
+    const int32_t col = indices[q + i];
+    range |= (unsigned)col >= (unsigned)n_cols;
+    descents += (q + i > 0) && col <= indices[q + i > 0 ? q + i - 1 : 0];
+    if (with_values) changes += (q + i > 0) && values[q + i] != values[q + i > 0 ? q + i - 1 : 0];
   }
   // a grid-wide count through one address: one atomic per wavefront, a few thousand in all
   for (int d = 32; d > 0; d >>= 1) {
@@ -99,6 +177,7 @@ __global__ void k_validate_elems(int64_t nnz, int32_t n_cols, const int32_t* __r
     changes += __shfl_down(changes, d, 64);
   }
   unsigned long long any_range = __ballot(range);
+  flags = flag_slot(flags);
   if ((threadIdx.x & 63) == 0) {
     if (changes) atomicAdd(&flags[4], (unsigned long long)changes);
     if (descents) atomicAdd(&flags[2], (unsigned long long)descents);
@@ -117,7 +196,7 @@ __global__ void k_row_values(int32_t n_rows, const int32_t* __restrict__ indptr,
 // counts   [c][nb][NB] int32 : pieces of each bin per row block
 // rem_nnz  [c][NB]     int64 : non-zeros sent to the remainder per row block
 __global__ __launch_bounds__(kBuildBlock) void k_count(BuildShape s, const int32_t* __restrict__ indptr,
-                                                       const int32_t* __restrict__ indices, int32_t* counts,
+                                                       const int32_t* __restrict__ bound, int32_t* counts,
                                                        int64_t* rem_nnz) {
   __shared__ int hist[kMaxBins];
   __shared__ unsigned long long sum_nnz;
@@ -129,7 +208,7 @@ __global__ __launch_bounds__(kBuildBlock) void k_count(BuildShape s, const int32
   int r = rb * kBuildBlock + tid;
   if (r < s.n_rows) {
     int lo, l;
-    row_piece(s, indptr, indices, r, p, &lo, &l);
+    row_piece(s, indptr, bound, r, p, &lo, &l);
     if (l > 0) {
       int bin = bin_of_length(l, s.k);
       atomicAdd(&hist[bin], 1);
@@ -146,6 +225,7 @@ struct ScatterArgs {
   const int32_t* indptr;
   const int32_t* indices;
   const float* values;
+  const int32_t* bound;        // piece boundaries (k_piece_bounds)
   const int32_t* counts;       // scanned: rank of the block's first piece of each bin
   const int64_t* rem_nnz;      // scanned
   const int64_t* bucket_row_ptr;
@@ -161,33 +241,38 @@ struct ScatterArgs {
   int64_t R, S, M, T;
 };
 
-// copies one row piece to `dst`: `len` real entries, then pads up to `width`
-// (a pad repeats the last real column and holds +0.0f); lanes stride the piece
-__device__ __forceinline__ void copy_piece(const ScatterArgs& a, int lo, int len, int width, int64_t dst, int first,
-                                           int step) {
-  for (int j = first; j < width; j += step) {
-    int32_t col;
-    float val;
-    if (j < len) { col = a.indices[lo + j]; val = a.values[lo + j]; }
-    else { col = a.indices[lo + len - 1]; val = 0.0f; }
-    a.cols[dst + j] = col;
-    a.vals[dst + j] = val;
-  }
-}
-
 __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterArgs a) {
   __shared__ int wave_cnt[kWaves][kMaxBins];
   __shared__ long long wave_sums[kWaves];
+  // the pieces of a wavefront, for the copy: slots before each piece, where it lies in the input, its real
+  // length, where it goes
+  __shared__ long long pre[kWaves][65];
+  __shared__ long long piece_dst[kWaves][64];
+  __shared__ int piece_lo[kWaves][64], piece_len[kWaves][64];
   int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int p = blockIdx.x / s.NB, rb = blockIdx.x % s.NB;
+  // The c workgroups that copy the pieces of one block of rows read the same cache lines of the input (a piece
+  // ends in the middle of a line, the next partition's starts there), so they are made neighbours in time and
+  // share an XCD: workgroup ids go round the 8 XCDs, hence ids b, b + 8, b + 16, .. take consecutive work numbers.
+  const long long n_work = (long long)gridDim.x, per_xcd = (n_work + 7) / 8;
+  long long work = (long long)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  // (when the grid is not a multiple of 8 the last XCDs have one workgroup less: the numbers past the end wrap
+  //  into the gaps those leave)
+  const int full = (int)(n_work & 7);  // XCDs that have per_xcd workgroups (0: all of them)
+  if (full != 0 && (int)(blockIdx.x & 7) >= full) work -= (int)(blockIdx.x & 7) - full;
+  int rb = (int)(work / s.c), p = (int)(work % s.c);
   if (tid < kWaves * kMaxBins) (&wave_cnt[0][0])[tid] = 0;
   if (blockIdx.x == 0 && tid == 0) a.rem_ptr[a.M] = a.T;
+  if (blockIdx.x == 0 && tid < kChunkSlots) {  // the spare entries past the end of the arrays
+    a.row_ids[a.R + a.M + tid] = 0;
+    a.cols[a.S + a.T + tid] = 0;
+    a.vals[a.S + a.T + tid] = 0.f;
+  }
   __syncthreads();
 
   int r = rb * kBuildBlock + tid;
   int lo = 0, l = 0, bin = -1;
   if (r < s.n_rows) {
-    row_piece(s, a.indptr, a.indices, r, p, &lo, &l);
+    row_piece(s, a.indptr, a.bound, r, p, &lo, &l);
     if (l > 0) bin = bin_of_length(l, s.k);
   }
   // rank among the lanes of this wave that hold the same bin (stable: lower lanes first)
@@ -235,16 +320,49 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
     }
   }
   if (a.piece_of && r < s.n_rows) a.piece_of[(int64_t)p * s.n_rows + r] = where;
-  // short pieces are copied by their own lane, long ones by the whole wave
-  constexpr int kOwnLaneMax = 4;
-  if (width > 0 && width <= kOwnLaneMax) copy_piece(a, lo, l, width, dst, 0, 1);
-  unsigned long long wide = __ballot(width > kOwnLaneMax);
-  while (wide) {
-    int src = __ffsll((long long)wide) - 1;
-    wide &= wide - 1;
-    int lo_s = __shfl(lo, src, 64), l_s = __shfl(l, src, 64), width_s = __shfl(width, src, 64);
-    long long dst_s = __shfl((long long)dst, src, 64);
-    copy_piece(a, lo_s, l_s, width_s, dst_s, lane, 64);
+  // ---- the copy.  The pieces of a wavefront, `width` slots each (real entries, then pads: a pad repeats the last
+  // real column and holds +0.0f), form one sequence; every step the 64 lanes take 64 consecutive slots of it, so
+  // that lanes are busy whatever the lengths of the pieces and neighbouring lanes touch neighbouring addresses.
+  long long inc = width;
+  for (int d = 1; d < 64; d <<= 1) {
+    const long long t = __shfl_up(inc, d, 64);
+    if (lane >= d) inc += t;
+  }
+  if (lane == 0) pre[wave][0] = 0;
+  pre[wave][lane + 1] = inc;
+  piece_lo[wave][lane] = lo; piece_len[wave][lane] = l; piece_dst[wave][lane] = dst;
+  __syncthreads();
+  const long long total = pre[wave][64];
+  const int32_t* __restrict__ indices = a.indices;
+  const float* __restrict__ values = a.values;
+  int32_t* __restrict__ cols = a.cols;
+  float* __restrict__ vals = a.vals;
+  constexpr int kUnroll = 4;
+  for (long long f0 = 0; f0 < total; f0 += 64 * kUnroll) {
+    int32_t col[kUnroll];
+    float val[kUnroll];
+    long long at[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const long long f = f0 + u * 64 + lane;
+      at[u] = -1; col[u] = 0; val[u] = 0.f;
+      if (f < total) {
+        int i = 0;  // the piece with pre[i] <= f < pre[i + 1]
+#pragma unroll
+        for (int step = 32; step > 0; step >>= 1)
+          if (pre[wave][i + step] <= f) i += step;
+        const long long j = f - pre[wave][i];
+        const int len_i = piece_len[wave][i];
+        const bool real = j < len_i;
+        const long long src = piece_lo[wave][i] + (real ? j : (long long)len_i - 1);
+        col[u] = indices[src];
+        val[u] = real ? values[src] : 0.0f;
+        at[u] = piece_dst[wave][i] + j;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      if (at[u] >= 0) { cols[at[u]] = col[u]; vals[at[u]] = val[u]; }
   }
 }
 
@@ -393,19 +511,30 @@ __global__ void k_part_chunk_counts(CellShape cs, int64_t n_parts, const int32_t
 
 // One thread per (phase, row block) group: the pad cell gets what is missing to a multiple of kChunksPerQuad,
 // the group's counts become their exclusive prefix inside the group, group_total[grp] their sum.
-__global__ void k_group_scan(CellShape cs, int64_t n_groups, long long* cell_chunks, long long* group_total) {
-  int64_t grp = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void k_group_scan(CellShape cs, int64_t n_groups, long long* cell_chunks,
+                                                    long long* group_total, unsigned long long* longest) {
+  // one wavefront per group: an exclusive scan over the group's cells, 64 at a time
+  const int64_t grp = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (grp >= n_groups) return;
+  const int lane = threadIdx.x & 63;
   const int cpg = cells_per_group(cs);
   long long* c = cell_chunks + grp * cpg;
-  long long total = 0;
-  for (int i = 0; i < cpg - 1; ++i) {
-    long long n = c[i];
-    c[i] = total;
-    total += n;
+  long long carry = 0;
+  for (int i0 = 0; i0 < cpg - 1; i0 += 64) {
+    const int i = i0 + lane;
+    const long long n = i < cpg - 1 ? c[i] : 0;
+    const long long incl = wave_inclusive_scan(n, lane);
+    if (i < cpg - 1) c[i] = carry + incl - n;
+    carry += __shfl(incl, 63, 64);
   }
-  c[cpg - 1] = total;
-  group_total[grp] = total + (kChunksPerQuad - total % kChunksPerQuad) % kChunksPerQuad;
+  if (lane == 0) {
+    c[cpg - 1] = carry;
+    const long long padded = carry + (kChunksPerQuad - carry % kChunksPerQuad) % kChunksPerQuad;
+    group_total[grp] = padded;
+    // the longest list (the sort of the launch order needs to know how many digits can differ)
+    // (one of kFlagSlots counters, for the reason given there; the report takes their maximum)
+    if (padded > 0) atomicMax(longest + (grp & (kFlagSlots - 1)) * kFlagStride, (unsigned long long)padded);
+  }
 }
 
 constexpr int kGroupSeq = 1024;  // groups per sequence of the two-level scan over group totals
@@ -530,7 +659,8 @@ __global__ void k_part_fill_chunks(CellShape cs, StreamShape ss, int64_t n_parts
                                    const int32_t* __restrict__ row_len, const int32_t* __restrict__ row_ids,
                                    const int64_t* __restrict__ bucket_row_ptr,
                                    const int64_t* __restrict__ bucket_slot_ptr, const int64_t* __restrict__ rem_ptr,
-                                   int64_t S, Chunk* chunks, PiecePlace* place, int64_t* rb_chunk_ptr) {
+                                   int64_t S, Chunk* chunks, PiecePlace* place, int64_t* rb_chunk_ptr,
+                                   int64_t n_chunks_total) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= n_parts) return;
   const int64_t grp = t / cs.ppg;
@@ -540,38 +670,68 @@ __global__ void k_part_fill_chunks(CellShape cs, StreamShape ss, int64_t n_parts
   const long long* cell = cell_first_chunk + grp * cells_per_group(cs) + (int64_t)p_local * cells_per_part(cs);
   const int64_t group_first = group_first_chunk[grp] + seq_first_chunk[grp / kGroupSeq];
   if (p_local == 0) rb_chunk_ptr[(int64_t)phase * cs.n_rb + rb] = group_first;
+  if (grp == 0 && p_local == 0) rb_chunk_ptr[(int64_t)cs.n_phases * cs.n_rb] = n_chunks_total;
   if (p >= cs.c) return;
   FillVisitor v{cs, ss, p, group_first + cell[0], cell, cell[0], row_ids, bucket_row_ptr, bucket_slot_ptr, rem_ptr, S,
                 chunks, place, -1, 0};
   deal_partition(cs, bin_rb_ptr, row_len, p, rb, v);
 }
 
-// One thread per row piece: copies the entries of a queued piece to its place in the stream; short pieces
-// by their own lane, longer ones by the whole wavefront.
+// One lane per row piece, 64 pieces per wavefront: the entries of the wavefront's queued pieces form one
+// sequence of which every step the lanes take 64 consecutive ones (as in k_scatter), each going to its place in
+// its queue.
 __global__ __launch_bounds__(256) void k_pack_pieces(int64_t n_pieces, StreamShape ss,
                                                      const PiecePlace* __restrict__ place,
                                                      const int32_t* __restrict__ row_ids,
                                                      const int32_t* __restrict__ cols,
                                                      const float* __restrict__ vals) {
+  __shared__ int pre[4][65];
+  __shared__ PiecePlace pl_of[4][64];
+  __shared__ int32_t row_of[4][64];
   const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int lane = threadIdx.x & 63;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   PiecePlace pl;
   pl.slot0 = 0; pl.first_chunk = 0; pl.where = 0; pl.len = 0;
   int32_t row = 0;
   if (q < n_pieces) { pl = place[q]; row = row_ids[q]; }
-  constexpr int kOwnLaneMax = 4;
-  if (pl.len <= kOwnLaneMax)
-    for (int e = 0; e < pl.len; ++e)
-      put_queue_entry(ss, pl.first_chunk, pl.where, e, cols[pl.slot0 + e], vals[pl.slot0 + e], row, e == pl.len - 1);
-  unsigned long long wide = __ballot(pl.len > kOwnLaneMax);
-  while (wide) {
-    const int src = __ffsll((long long)wide) - 1;
-    wide &= wide - 1;
-    const long long slot0 = __shfl((long long)pl.slot0, src, 64);
-    const long long first_chunk = __shfl((long long)pl.first_chunk, src, 64);
-    const int where = __shfl(pl.where, src, 64), len = __shfl(pl.len, src, 64), row_s = __shfl(row, src, 64);
-    for (int e = lane; e < len; e += 64)
-      put_queue_entry(ss, first_chunk, where, e, cols[slot0 + e], vals[slot0 + e], row_s, e == len - 1);
+  int inc = pl.len;
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(inc, d, 64);
+    if (lane >= d) inc += t;
+  }
+  if (lane == 0) pre[wave][0] = 0;
+  pre[wave][lane + 1] = inc;
+  pl_of[wave][lane] = pl;
+  row_of[wave][lane] = row;
+  __syncthreads();
+  const int total = pre[wave][64];
+  constexpr int kUnroll = 4;
+  for (int f0 = 0; f0 < total; f0 += 64 * kUnroll) {
+    int32_t col[kUnroll];
+    float val[kUnroll];
+    int piece[kUnroll], e[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int f = f0 + u * 64 + lane;
+      piece[u] = -1; e[u] = 0; col[u] = 0; val[u] = 0.f;
+      if (f < total) {
+        int i = 0;  // the piece with pre[i] <= f < pre[i + 1]
+#pragma unroll
+        for (int step = 32; step > 0; step >>= 1)
+          if (pre[wave][i + step] <= f) i += step;
+        piece[u] = i;
+        e[u] = f - pre[wave][i];
+        const int64_t src = pl_of[wave][i].slot0 + e[u];
+        col[u] = cols[src];
+        val[u] = ss.unit ? 0.f : vals[src];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      if (piece[u] >= 0) {
+        const PiecePlace& w = pl_of[wave][piece[u]];
+        put_queue_entry(ss, w.first_chunk, w.where, e[u], col[u], val[u], row_of[wave][piece[u]], e[u] == w.len - 1);
+      }
   }
 }
 
@@ -637,15 +797,38 @@ __global__ void k_heavy_counts(int64_t n_pieces, const int32_t* __restrict__ row
   }
   unsigned long long mine = heavy ? (unsigned long long)len : 0ull;
   for (int d = 32; d > 0; d >>= 1) mine += __shfl_down(mine, d, 64);
-  if ((threadIdx.x & 63) == 0 && mine) atomicAdd(heavy_nnz, mine);
+  if ((threadIdx.x & 63) == 0 && mine) atomicAdd(flag_slot(heavy_nnz), mine);  // (kFlagSlots counters, see there)
 }
 
 constexpr int kScanSeq = 4096;  // elements per sequence of the device-wide scan
 
-// dst[i] = src[at[i]]
-__global__ void k_pick(int32_t n, const int64_t* __restrict__ at, const int32_t* __restrict__ src, int32_t* dst) {
+// What the host needs to know before it can size the stream, in one array: report[0] = chunks of all lists,
+// [1] = entries of heavy pieces (the sum of the counters k_heavy_counts added to; the longest list is the maximum
+// of the counters next to them), [2] = heavy pieces, [3] = slots of the heavy sequence, [4] = chunks of the longest
+// list, [5 + i] = slots of the heavy sequence before the pieces of segment i (seg_at[i]: its first piece).
+__global__ void k_report(const long long* totals, const long long* heavy_nnz_slots, const int32_t* unit_before,
+                         const int32_t* hent_before,
+                         int64_t n_pieces, int32_t n_segs, const int64_t* __restrict__ seg_at, long long* report) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) dst[i] = src[at[i]];
+  if (i >= 5 + n_segs) return;
+  long long v;
+  if (i == 0) v = totals[0];
+  else if (i == 1) { v = 0; for (int slot = 0; slot < kFlagSlots; ++slot) v += heavy_nnz_slots[slot * kFlagStride]; }
+  else if (i == 2) v = unit_before ? unit_before[n_pieces] : 0;
+  else if (i == 3) v = hent_before ? hent_before[n_pieces] : 0;
+  else if (i == 4) {
+    v = 0;
+    for (int slot = 0; slot < kFlagSlots; ++slot) {
+      const long long o = heavy_nnz_slots[slot * kFlagStride + 1];
+      v = o > v ? o : v;
+    }
+  }
+  else v = hent_before ? hent_before[seg_at[i - 5]] : 0;
+  report[i] = v;
+}
+
+__global__ void k_pick2(const int32_t* a, const int32_t* b, int32_t* dst) {
+  if (threadIdx.x == 0) { dst[0] = *a; dst[1] = *b; }
 }
 
 // data[i] += seq_base[i / kScanSeq]: the last step of the device-wide exclusive scan
@@ -669,70 +852,102 @@ __device__ __forceinline__ int64_t piece_slot0(int64_t q, int64_t B, int32_t k, 
   return bucket_slot_ptr[lo] + ((q - bucket_row_ptr[lo]) << bin);
 }
 
-// One thread per piece: heavy piece number u notes which piece it is, where its slots start and where its real
-// entries end (unit_piece, unit_start, unit_end; unit_start has one more element, the total).
+// One thread per piece: heavy piece number u notes where its slots start in the heavy sequence, where its real
+// entries end there, and where its entries lie in the fused (cols, vals) arrays (unit_start, unit_end, unit_slot0;
+// unit_start has one more element, the total).
 __global__ void k_heavy_units(int64_t n_pieces, const int32_t* __restrict__ row_len,
                               const int32_t* __restrict__ unit_before, const int32_t* __restrict__ hent_before,
-                              int32_t* unit_piece, int32_t* unit_start, int32_t* unit_end) {
+                              int64_t B, int32_t k, int64_t R, int64_t S,
+                              const int64_t* __restrict__ bucket_row_ptr,
+                              const int64_t* __restrict__ bucket_slot_ptr, const int64_t* __restrict__ rem_ptr,
+                              int32_t heavy_len, int32_t* __restrict__ unit_start,
+                              int32_t* __restrict__ unit_end, int64_t* __restrict__ unit_slot0,
+                              int32_t* __restrict__ quad_unit) {
   const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (q > n_pieces) return;
   if (q == n_pieces) { unit_start[unit_before[q]] = hent_before[q]; return; }
   if (unit_before[q + 1] == unit_before[q]) return;
   const int u = unit_before[q];
-  unit_piece[u] = (int32_t)q;
-  unit_start[u] = hent_before[q];
-  unit_end[u] = hent_before[q] + row_len[q];
+  const int64_t start = hent_before[q], len = row_len[q];
+  unit_start[u] = (int32_t)start;
+  unit_end[u] = (int32_t)(start + len);
+  unit_slot0[u] = piece_slot0(q, B, k, R, S, bucket_row_ptr, bucket_slot_ptr, rem_ptr);
+  // every quad of the heavy sequence whose first slot lies in this piece learns so (the pieces follow each other
+  // without a gap, so every quad that starts before the end of the sequence hears from exactly one piece)
+  constexpr int kQuadSlots = kChunkSlots * kChunksPerQuad;
+  const int64_t end = start + heavy_footprint((int)len, heavy_len);
+  for (int64_t quad = (start + kQuadSlots - 1) / kQuadSlots; quad * kQuadSlots < end; ++quad) quad_unit[quad] = u;
 }
 
-// One wavefront per chunk of the heavy sequence, a lane per slot: writes the chunk's stream record.  The slot
-// words of a chunk all name the slot at which a piece ends in it (in the place of the local row of the list
-// records), with the hand-over flag set if one does.
+// One wavefront per kPackRun consecutive chunks of the heavy sequence (a whole quad), a lane per slot: writes the
+// chunks' stream records.  The slot words of a chunk all name the slot at which a piece ends in it (in the place of
+// the local row of the list records), with the hand-over flag set if one does.  Which pieces a chunk covers is the
+// same for all lanes: quad_unit names the piece the quad starts in, the walk over unit_start from there runs on
+// wave-uniform values.
+constexpr int kPackRun = kChunksPerQuad;
+
 __global__ __launch_bounds__(256) void k_pack_heavy(int64_t n_heavy_chunks, int64_t first_chunk, StreamShape ss,
-                                                    int32_t n_units, const int32_t* __restrict__ unit_piece,
-                                                    const int32_t* __restrict__ unit_start,
-                                                    const int32_t* __restrict__ unit_end, int64_t B, int32_t k,
-                                                    int64_t R, int64_t S,
-                                                    const int64_t* __restrict__ bucket_row_ptr,
-                                                    const int64_t* __restrict__ bucket_slot_ptr,
-                                                    const int64_t* __restrict__ rem_ptr,
+                                                    int32_t n_units, const int32_t* __restrict__ unit_start,
+                                                    const int32_t* __restrict__ unit_end,
+                                                    const int64_t* __restrict__ unit_slot0,
+                                                    const int32_t* __restrict__ quad_unit,
                                                     const int32_t* __restrict__ cols, const float* __restrict__ vals) {
-  const int64_t ck = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (ck >= n_heavy_chunks) return;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int64_t ck0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + wave) * kPackRun;
+  if (ck0 >= n_heavy_chunks) return;  // (n_heavy_chunks is a whole number of quads)
   const int lane = threadIdx.x & 63;
-  const int64_t e0 = ck * kChunkSlots;
-  if (n_units == 0 || e0 >= unit_start[n_units]) {  // past the last piece: padding up to a whole quad
-    put_slot(ss, first_chunk + ck, lane, ss.compact ? (int32_t)0xF0000000u : 0, 0, -1);
-    return;
+  const int64_t total = n_units > 0 ? (int64_t)unit_start[n_units] : 0;
+  // the last unit that starts at or before the first slot of the run
+  int lo = ck0 * kChunkSlots < total ? quad_unit[ck0 / kPackRun] : 0;
+  int64_t src[kPackRun];
+  int32_t word[kPackRun];  // everything of the record but the column
+  bool pad[kPackRun];
+#pragma unroll
+  for (int i = 0; i < kPackRun; ++i) {
+    const int64_t e0 = (ck0 + i) * kChunkSlots;
+    pad[i] = e0 >= total;  // past the last piece: padding up to a whole quad
+    src[i] = 0; word[i] = 0;
+    if (pad[i]) continue;
+    while (lo + 1 < n_units && (int64_t)unit_start[lo + 1] <= e0) ++lo;
+    const int64_t start_lo = unit_start[lo], end_lo = unit_end[lo], slot0_lo = unit_slot0[lo];
+    const bool has_next = lo + 1 < n_units;
+    const int64_t start_hi = unit_start[lo + 1];  // (the total when lo is the last unit)
+    const int64_t end_hi = has_next ? unit_end[lo + 1] : 0, slot0_hi = has_next ? unit_slot0[lo + 1] : 0;
+    const int64_t e = e0 + lane;
+    const bool second = has_next && e >= start_hi;
+    const int64_t start = second ? start_hi : start_lo, len = (second ? end_hi : end_lo) - start;
+    const int64_t j = e - start;
+    const bool real = j < len;
+    src[i] = (second ? slot0_hi : slot0_lo) + (real ? j : len - 1);
+    // the piece that ends inside this chunk, if any, is the one the chunk starts in (a later one would have to
+    // start and end here: heavy pieces are longer than that, or start a chunk of their own)
+    const int64_t last = end_lo - 1 - e0;
+    const int hand_over = last >= 0 && last < kChunkSlots;
+    const int end_slot = hand_over ? (int)last : 0;
+    if (ss.compact)
+      word[i] = (int32_t)(((uint32_t)end_slot << kCompactColBits) | ((uint32_t)real << 27) | (7u << 28) |
+                          ((uint32_t)hand_over << 31));
+    else
+      word[i] = real ? (end_slot | (kRowLog2W << 16) | (hand_over << 22)) : -1;
   }
-  // the last unit that starts at or before the chunk's first slot
-  int lo = 0, hi = n_units;
-  while (hi - lo > 1) {
-    const int mid = lo + ((hi - lo) >> 1);
-    if ((int64_t)unit_start[mid] <= e0) lo = mid; else hi = mid;
+  int32_t col[kPackRun];
+  float val[kPackRun];
+#pragma unroll
+  for (int i = 0; i < kPackRun; ++i) {
+    col[i] = cols[src[i]];
+    val[i] = ss.unit ? 0.f : vals[src[i]];
   }
-  const int64_t e = e0 + lane;
-  const int u = (lo + 1 < n_units && e >= unit_start[lo + 1]) ? lo + 1 : lo;
-  const int32_t q = unit_piece[u];
-  const int64_t slot0 = piece_slot0(q, B, k, R, S, bucket_row_ptr, bucket_slot_ptr, rem_ptr);
-  const int len = unit_end[u] - unit_start[u];
-  const int64_t j = e - unit_start[u];
-  const bool real = j < len;
-  const int64_t src = slot0 + (real ? j : len - 1);
-  const int32_t col = cols[src];
-  const float val = real ? vals[src] : 0.f;
-  // the piece that ends inside this chunk, if any, is the one the chunk starts in (a later one would have to
-  // start and end here: heavy pieces are longer than that, or start a chunk of their own)
-  const int64_t end_lo = (int64_t)unit_end[lo] - 1 - e0;
-  const int hand_over = end_lo >= 0 && end_lo < kChunkSlots;
-  const int end_slot = hand_over ? (int)end_lo : 0;
-  if (ss.compact) {
-    put_slot(ss, first_chunk + ck, lane,
-             (int32_t)((uint32_t)col | ((uint32_t)end_slot << kCompactColBits) | ((uint32_t)real << 27) | (7u << 28) |
-                       ((uint32_t)hand_over << 31)),
-             __float_as_int(val), 0);
-  } else {
-    put_slot(ss, first_chunk + ck, lane, col, __float_as_int(val),
-             real ? (end_slot | (kRowLog2W << 16) | (hand_over << 22)) : -1);
+#pragma unroll
+  for (int i = 0; i < kPackRun; ++i) {
+    if (pad[i]) {
+      put_slot(ss, first_chunk + ck0 + i, lane, ss.compact ? (int32_t)0xF0000000u : 0, 0, -1);
+    } else if (ss.compact) {
+      const bool real = (word[i] >> 27) & 1;
+      put_slot(ss, first_chunk + ck0 + i, lane, (int32_t)((uint32_t)col[i] | (uint32_t)word[i]),
+               real ? __float_as_int(val[i]) : 0, 0);
+    } else {
+      put_slot(ss, first_chunk + ck0 + i, lane, col[i], word[i] >= 0 ? __float_as_int(val[i]) : 0, word[i]);
+    }
   }
 }
 
@@ -810,6 +1025,46 @@ __global__ void k_heavy_row_fill(int32_t n_rows, const int32_t* __restrict__ row
 }
 
 // --------------------------------------------------------------- host helpers
+// Pinned host memory for the few small arrays a build exchanges with the device.  The blocks are kept for the life
+// of the process (pinning memory costs more than a small build) and lent to one build at a time.
+class PinnedPool {
+ public:
+  struct Buf { char* p = nullptr; size_t size = 0; };
+  Buf acquire(size_t bytes) {
+    {
+      std::lock_guard<std::mutex> g(m_);
+      for (size_t i = 0; i < free_.size(); ++i)
+        if (free_[i].size >= bytes) {
+          Buf b = free_[i];
+          free_.erase(free_.begin() + (long)i);
+          return b;
+        }
+    }
+    Buf b;
+    b.size = std::max<size_t>(bytes, 64 * 1024);
+    void* p = nullptr;
+    if (hipHostMalloc(&p, b.size, hipHostMallocPortable) != hipSuccess) { (void)hipGetLastError(); b.size = 0; return b; }
+    b.p = (char*)p;
+    return b;
+  }
+  void release(Buf b) {
+    if (!b.p) return;
+    {
+      std::lock_guard<std::mutex> g(m_);
+      if (free_.size() < 8) { free_.push_back(b); return; }
+    }
+    (void)hipHostFree(b.p);
+  }
+
+ private:
+  std::mutex m_;
+  std::vector<Buf> free_;
+};
+PinnedPool& pinned_pool() {
+  static PinnedPool* pool = new PinnedPool();  // never destroyed: no HIP call at process exit
+  return *pool;
+}
+
 struct Blob {  // bump allocator over one device allocation
   char* base = nullptr;
   size_t size = 0;
@@ -971,17 +1226,46 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   sptir_alloc_fn alloc; sptir_free_fn free_; void* actx;
   current_allocator(&alloc, &free_, &actx);
 
-  // ---- temporary device storage: one blob now, a second one once the cell count is known
+  // ---- temporary storage: one device blob now, a second one once the cell count is known; one pinned host block
+  // for everything that crosses to or from the host (pageable memory would make every small copy a blocking one)
   const size_t nbk = (size_t)(s.NB ? s.NB : 1);
+  const size_t n_segs = 2 * (size_t)s.c + 1;  // heavy segments: the ELL pieces of each partition, then its remainder pieces
   Blob tmp;
-  const size_t o_flags = tmp.reserve(4 * sizeof(unsigned long long));
+  // (flags, tot_rnnz and tot_bins lie next to each other: one copy brings them to the host)
+  const size_t o_flags = tmp.size;
+  tmp.size += kFlagSlots * kFlagStride * sizeof(unsigned long long);
+  const size_t o_tot_rnnz = tmp.size;
+  tmp.size += sizeof(int64_t) * (size_t)s.c;
+  const size_t o_tot_bins = tmp.size;
+  const size_t report1_bytes = tmp.reserve(sizeof(int32_t) * (size_t)s.c * s.nb) + sizeof(int32_t) * (size_t)s.c * s.nb;
   const size_t o_counts = tmp.reserve(sizeof(int32_t) * (size_t)s.c * s.nb * nbk);
   const size_t o_rnnz = tmp.reserve(sizeof(int64_t) * (size_t)s.c * nbk);
-  const size_t o_tot_bins = tmp.reserve(sizeof(int32_t) * (size_t)s.c * s.nb);
-  const size_t o_tot_rnnz = tmp.reserve(sizeof(int64_t) * (size_t)s.c);
   const size_t o_rnnz_base = tmp.reserve(sizeof(int64_t) * (size_t)s.c);
+  const size_t o_bound = tmp.reserve(sizeof(int32_t) * (size_t)(s.c - 1) * (size_t)(s.n_rows ? s.n_rows : 1) + 16);
+  const size_t o_seg_at = tmp.reserve(sizeof(int64_t) * n_segs);
+  const size_t o_totals = tmp.reserve(sizeof(long long) * 4);  // chunks of all lists; -; longest list
+  const size_t o_nnz_slots = tmp.reserve(sizeof(long long) * kFlagSlots * kFlagStride);  // entries of heavy pieces
+  const size_t report2_count = 5 + n_segs;
+  const size_t o_report2 = tmp.reserve(sizeof(long long) * report2_count);
+  const size_t o_report3 = tmp.reserve(sizeof(int32_t) * 2);
+  const int64_t n_bound_blocks =
+      (((int64_t)s.n_rows + kBoundRows - 1) / kBoundRows) * (((int64_t)s.c - 1 + kBoundParts - 1) / kBoundParts);
+  if (n_bound_blocks > 0x7FFFFFFF) return SPTIR_ERR_OVERFLOW;
+  Blob host;
+  const size_t h_report1 = host.reserve(report1_bytes);
+  const size_t h_row_ptr = host.reserve(sizeof(int64_t) * (size_t)(B + 1));
+  const size_t h_slot_ptr = host.reserve(sizeof(int64_t) * (size_t)(B + 1));
+  const size_t h_rem_part_ptr = host.reserve(sizeof(int32_t) * (size_t)(s.c + 1));
+  const size_t h_rnnz_base = host.reserve(sizeof(int64_t) * (size_t)s.c);
+  const size_t h_seg_at = host.reserve(sizeof(int64_t) * n_segs);
+  const size_t h_report2 = host.reserve(sizeof(long long) * report2_count);
+  const size_t h_report3 = host.reserve(sizeof(int32_t) * 4);
+  const size_t h_misc = host.reserve(64);
+  PinnedPool::Buf pinned = pinned_pool().acquire(host.size);
+  if (!pinned.p) return SPTIR_ERR_ALLOC;
+  host.base = pinned.p;
   tmp.base = (char*)alloc(tmp.size, actx, stream);
-  if (!tmp.base) return SPTIR_ERR_ALLOC;
+  if (!tmp.base) { pinned_pool().release(pinned); return SPTIR_ERR_ALLOC; }
   Blob tmp2;
   void* tmp_chunks = nullptr;
   void* tmp_place = nullptr;
@@ -990,7 +1274,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   void* tmp_row_flags = nullptr;
 
   sptir_hyb* h = new (std::nothrow) sptir_hyb();
-  if (!h) { free_(tmp.base, actx); return SPTIR_ERR_ALLOC; }
+  if (!h) { free_(tmp.base, actx); pinned_pool().release(pinned); return SPTIR_ERR_ALLOC; }
   memset(h, 0, sizeof(*h));
   h->alloc = alloc; h->free_ = free_; h->alloc_ctx = actx;
   h->n_rows = s.n_rows; h->n_cols = s.n_cols; h->c = s.c; h->k = s.k; h->w = s.w;
@@ -1011,53 +1295,64 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     int32_t* d_tot_bins = (int32_t*)(tmp.base + o_tot_bins);
     int64_t* d_tot_rnnz = (int64_t*)(tmp.base + o_tot_rnnz);
     int64_t* d_rnnz_base = (int64_t*)(tmp.base + o_rnnz_base);
+    int32_t* d_bound = (int32_t*)(tmp.base + o_bound);
+    int64_t* d_seg_at = (int64_t*)(tmp.base + o_seg_at);
+    long long* d_totals = (long long*)(tmp.base + o_totals);
+    long long* d_nnz_slots = (long long*)(tmp.base + o_nnz_slots);
+    long long* d_report2 = (long long*)(tmp.base + o_report2);
+    int32_t* d_report3 = (int32_t*)(tmp.base + o_report3);
 
-    // ---- validation of the CSR input
+    // ---- validation of the CSR input, and with it (their results are only used if the input is valid, and they
+    // read nothing at a position the input names without clamping it) the piece boundaries, histogram and scans
+    const unsigned long long* flag_slots = (const unsigned long long*)(host.base + h_report1);
     unsigned long long flags[6] = {0, 0, 0, 0, 0, 0};
+    const int64_t* tot_rnnz = (const int64_t*)(host.base + h_report1 + (o_tot_rnnz - o_flags));
+    const int32_t* tot_bins = (const int32_t*)(host.base + h_report1 + (o_tot_bins - o_flags));
     // (values are only looked at when a value-less stream is an option)
     const int32_t* value_bits = (with_spmm_plan && !opt.keep_values) ? (const int32_t*)csr->values : nullptr;
-    BUILD_HIP(hipMemsetAsync(d_flags, 0, sizeof(flags), stream));
+    BUILD_HIP(hipMemsetAsync(d_flags, 0, report1_bytes, stream));
     if (s.n_rows > 0)
       hipLaunchKernelGGL(k_validate_rows, dim3((unsigned)std::min<int64_t>(((int64_t)s.n_rows + 255) / 256, 4096)),
                          dim3(256), 0, stream, s.n_rows, csr->nnz,
                          csr->indptr, csr->indices, value_bits, d_flags);
     if (csr->nnz > 0)
-      hipLaunchKernelGGL(k_validate_elems, dim3((unsigned)std::min<int64_t>((csr->nnz + 255) / 256, 4096)), dim3(256),
-                         0, stream, csr->nnz, s.n_cols, csr->indices, value_bits, d_flags);
-    BUILD_HIP(hipGetLastError());
-    BUILD_HIP(hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, stream));
-    BUILD_HIP(hipStreamSynchronize(stream));
-    if (s.n_rows == 0) {
-      int32_t first = 0;
-      BUILD_HIP(hipMemcpyAsync(&first, csr->indptr, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipStreamSynchronize(stream));
-      if (first != 0 || csr->nnz != 0) flags[0] = 1;
-    }
-    if (flags[0]) { st = SPTIR_ERR_INVALID_ARG; goto fail; }
-    if (flags[1] || flags[2] != flags[3]) { st = SPTIR_ERR_UNSORTED; goto fail; }
-
-    // ---- histogram and scans
-    std::vector<int32_t> tot_bins((size_t)s.c * s.nb, 0);
-    std::vector<int64_t> tot_rnnz((size_t)s.c, 0);
+      hipLaunchKernelGGL(k_validate_elems, dim3((unsigned)std::min<int64_t>((csr->nnz + 2047) / 2048, 8192)),
+                         dim3(256), 0, stream, csr->nnz, s.n_cols,
+                         (int)((((uintptr_t)csr->indices | (uintptr_t)csr->values) & 15) == 0), csr->indices,
+                         value_bits, d_flags);
     if (s.NB > 0) {
+      if (n_bound_blocks > 0)
+        hipLaunchKernelGGL(k_piece_bounds, dim3((unsigned)n_bound_blocks), dim3(256), 0, stream, s, (int32_t)csr->nnz,
+                           csr->indptr, csr->indices, d_bound);
       hipLaunchKernelGGL(k_count, dim3((unsigned)n_pair_blocks), dim3(kBuildBlock), 0, stream, s, csr->indptr,
-                         csr->indices, d_counts, d_rnnz);
+                         d_bound, d_counts, d_rnnz);
       hipLaunchKernelGGL(k_scan_sequences<int32_t>, dim3((unsigned)(s.c * s.nb)), dim3(kBuildBlock), 0, stream,
                          d_counts, s.NB, d_tot_bins);
       hipLaunchKernelGGL(k_scan_sequences<long long>, dim3((unsigned)s.c), dim3(kBuildBlock), 0, stream,
                          (long long*)d_rnnz, s.NB, (long long*)d_tot_rnnz);
-      BUILD_HIP(hipGetLastError());
-      BUILD_HIP(hipMemcpyAsync(tot_bins.data(), d_tot_bins, sizeof(int32_t) * tot_bins.size(),
-                               hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipMemcpyAsync(tot_rnnz.data(), d_tot_rnnz, sizeof(int64_t) * s.c, hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipStreamSynchronize(stream));
     }
+    BUILD_HIP(hipGetLastError());
+    BUILD_HIP(hipMemcpyAsync(host.base + h_report1, d_flags, report1_bytes, hipMemcpyDeviceToHost, stream));
+    BUILD_HIP(hipStreamSynchronize(stream));
+    for (int slot = 0; slot < kFlagSlots; ++slot)
+      for (int i = 0; i < 6; ++i) flags[i] += flag_slots[slot * kFlagStride + i];
+    bool bad_indptr = flags[0] != 0;
+    if (s.n_rows == 0) {
+      int32_t* first = (int32_t*)(host.base + h_misc);
+      BUILD_HIP(hipMemcpyAsync(first, csr->indptr, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+      BUILD_HIP(hipStreamSynchronize(stream));
+      if (*first != 0 || csr->nnz != 0) bad_indptr = true;
+    }
+    if (bad_indptr) { st = SPTIR_ERR_INVALID_ARG; goto fail; }
+    if (flags[1] || flags[2] != flags[3]) { st = SPTIR_ERR_UNSORTED; goto fail; }
 
     // ---- sizes and the small prefix arrays (host)
-    std::vector<int64_t> row_ptr((size_t)B + 1, 0), slot_ptr((size_t)B + 1, 0);
-    std::vector<int32_t> rem_part_ptr((size_t)s.c + 1, 0);
-    std::vector<int64_t> rnnz_base((size_t)s.c, 0);
+    int64_t* row_ptr = (int64_t*)(host.base + h_row_ptr);
+    int64_t* slot_ptr = (int64_t*)(host.base + h_slot_ptr);
+    int32_t* rem_part_ptr = (int32_t*)(host.base + h_rem_part_ptr);
+    int64_t* rnnz_base = (int64_t*)(host.base + h_rnnz_base);
     int64_t M = 0, T = 0;
+    row_ptr[0] = 0; slot_ptr[0] = 0; rem_part_ptr[0] = 0;
     for (int32_t p = 0; p < s.c; ++p) {
       for (int32_t i = 0; i <= s.k; ++i) {
         int64_t b = (int64_t)p * (s.k + 1) + i;
@@ -1123,14 +1418,11 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     const int64_t n_seq = (n_groups + kGroupSeq - 1) / kGroupSeq;
     const size_t o_group_tot = tmp2.reserve(sizeof(long long) * (size_t)(n_seq ? n_seq * kGroupSeq : 1));
     const size_t o_seq_tot = tmp2.reserve(sizeof(long long) * (size_t)(n_seq ? n_seq : 1));
-    const size_t o_cell_total = tmp2.reserve(2 * sizeof(long long));  // chunks of all lists; entries of heavy pieces
     // heavy pieces: the two prefix arrays over the pieces, the (row, partition) -> piece map, scan scratch
     const bool want_heavy = with_spmm_plan && n_pieces > 0;
     const size_t o_unit = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room(n_pieces + 1) : 1));
     const size_t o_hent = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room(n_pieces + 1) : 1));
     const size_t o_piece_of = tmp2.reserve(sizeof(int32_t) * (want_heavy ? (size_t)s.c * (size_t)s.n_rows : 1));
-    const size_t o_seg_at = tmp2.reserve(sizeof(int64_t) * (2 * (size_t)s.c + 1));
-    const size_t o_seg_hc = tmp2.reserve(sizeof(int32_t) * (2 * (size_t)s.c + 1));
     const size_t o_seq_base = tmp2.reserve(sizeof(int32_t) * 2 * (scan_room(std::max<int64_t>(n_pieces + 1, s.n_rows + 1)) / kScanSeq + 2));
     tmp2.base = (char*)alloc(tmp2.size, actx, stream);
     if (!tmp2.base) { st = SPTIR_ERR_ALLOC; goto fail; }
@@ -1138,13 +1430,10 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     long long* d_cell_chunks = (long long*)(tmp2.base + o_cell_chunks);
     long long* d_group_tot = (long long*)(tmp2.base + o_group_tot);
     long long* d_seq_tot = (long long*)(tmp2.base + o_seq_tot);
-    long long* d_cell_total = (long long*)(tmp2.base + o_cell_total);
     int32_t* d_unit = (int32_t*)(tmp2.base + o_unit);
     int32_t* d_hent = (int32_t*)(tmp2.base + o_hent);
     int32_t* d_piece_of = want_heavy ? (int32_t*)(tmp2.base + o_piece_of) : nullptr;
     int32_t* d_seq_base = (int32_t*)(tmp2.base + o_seq_base);
-    int64_t* d_seg_at = (int64_t*)(tmp2.base + o_seg_at);
-    int32_t* d_seg_hc = (int32_t*)(tmp2.base + o_seg_hc);
 
     // ---- the handle's device arrays (the chunk list follows further down)
     struct { void** p; size_t bytes; } wanted[] = {
@@ -1166,22 +1455,16 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       if (!*wnt.p) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += bytes;
     }
-    BUILD_HIP(hipMemsetAsync(h->row_ids + h->R + M, 0, sizeof(int32_t) * kChunkSlots, stream));
-    BUILD_HIP(hipMemsetAsync(h->cols + h->S + T, 0, sizeof(int32_t) * kChunkSlots, stream));
-    BUILD_HIP(hipMemsetAsync(h->vals + h->S + T, 0, sizeof(float) * kChunkSlots, stream));
-    BUILD_HIP(hipMemcpyAsync(h->bucket_row_ptr, row_ptr.data(), sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice,
-                             stream));
-    BUILD_HIP(hipMemcpyAsync(h->bucket_slot_ptr, slot_ptr.data(), sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice,
-                             stream));
-    BUILD_HIP(hipMemcpyAsync(h->rem_part_ptr, rem_part_ptr.data(), sizeof(int32_t) * (s.c + 1),
-                             hipMemcpyHostToDevice, stream));
-    BUILD_HIP(hipMemcpyAsync(d_rnnz_base, rnnz_base.data(), sizeof(int64_t) * s.c, hipMemcpyHostToDevice, stream));
+    BUILD_HIP(hipMemcpyAsync(h->bucket_row_ptr, row_ptr, sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice, stream));
+    BUILD_HIP(hipMemcpyAsync(h->bucket_slot_ptr, slot_ptr, sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice, stream));
+    BUILD_HIP(hipMemcpyAsync(h->rem_part_ptr, rem_part_ptr, sizeof(int32_t) * (s.c + 1), hipMemcpyHostToDevice, stream));
+    BUILD_HIP(hipMemcpyAsync(d_rnnz_base, rnnz_base, sizeof(int64_t) * s.c, hipMemcpyHostToDevice, stream));
 
     // ---- stable scatter
     if (s.NB > 0) {
       ScatterArgs a;
       a.indptr = csr->indptr; a.indices = csr->indices; a.values = csr->values;
-      a.counts = d_counts; a.rem_nnz = d_rnnz;
+      a.bound = d_bound; a.counts = d_counts; a.rem_nnz = d_rnnz;
       a.bucket_row_ptr = h->bucket_row_ptr; a.bucket_slot_ptr = h->bucket_slot_ptr;
       a.rem_part_ptr = h->rem_part_ptr; a.rem_nnz_base = d_rnnz_base;
       a.row_ids = h->row_ids; a.cols = h->cols; a.vals = h->vals; a.rem_ptr = h->rem_ptr; a.row_len = h->row_len;
@@ -1189,16 +1472,20 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       a.R = h->R; a.S = h->S; a.M = M; a.T = T;
       hipLaunchKernelGGL(k_scatter, dim3((unsigned)n_pair_blocks), dim3(kBuildBlock), 0, stream, s, a);
     } else {
-      int64_t zero = 0;
-      BUILD_HIP(hipMemcpyAsync(h->rem_ptr, &zero, sizeof(int64_t), hipMemcpyHostToDevice, stream));
+      int64_t* zero = (int64_t*)(host.base + h_misc + 8);
+      *zero = 0;
+      BUILD_HIP(hipMemcpyAsync(h->rem_ptr, zero, sizeof(int64_t), hipMemcpyHostToDevice, stream));
+      BUILD_HIP(hipMemsetAsync(h->row_ids + h->R + M, 0, sizeof(int32_t) * kChunkSlots, stream));
+      BUILD_HIP(hipMemsetAsync(h->cols + h->S + T, 0, sizeof(int32_t) * kChunkSlots, stream));
+      BUILD_HIP(hipMemsetAsync(h->vals + h->S + T, 0, sizeof(float) * kChunkSlots, stream));
     }
     BUILD_HIP(hipGetLastError());
 
     // ---- heavy pieces: how many, and how many chunks (prefixes over the pieces in row_ids order)
+    BUILD_HIP(hipMemsetAsync(d_totals, 0, o_nnz_slots - o_totals + sizeof(long long) * kFlagSlots * kFlagStride, stream));
     if (want_heavy) {
-      BUILD_HIP(hipMemsetAsync(d_cell_total + 1, 0, sizeof(long long), stream));
       hipLaunchKernelGGL(k_heavy_counts, dim3((unsigned)((n_pieces + 256) / 256)), dim3(256), 0, stream, n_pieces,
-                         h->row_len, cs.long_len, d_unit, d_hent, (unsigned long long*)(d_cell_total + 1));
+                         h->row_len, cs.long_len, d_unit, d_hent, (unsigned long long*)d_nnz_slots);
       BUILD_HIP(hipGetLastError());
       st = device_exclusive_scan(d_unit, n_pieces + 1, d_seq_base, stream);
       if (st != SPTIR_OK) goto fail;
@@ -1207,50 +1494,60 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     }
 
     // ---- chunk descriptors of the lists, grouped by (phase, row block)
-    long long n_chunks = 0;
-    int32_t heavy_totals[2] = {0, 0};  // heavy pieces, their chunks
     if (n_cells > 0) {
       BUILD_HIP(hipMemsetAsync(d_group_tot, 0, sizeof(long long) * (size_t)n_seq * kGroupSeq, stream));
-      BUILD_HIP(hipMemsetAsync(d_cell_total, 0, sizeof(long long), stream));
       hipLaunchKernelGGL(k_cell_bounds, dim3((unsigned)((n_bounds + 255) / 256)), dim3(256), 0, stream, cs,
                          h->bucket_row_ptr, h->rem_part_ptr, h->row_ids, d_bounds);
       hipLaunchKernelGGL(k_part_chunk_counts, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs,
                          n_parts, d_bounds, h->row_len, d_cell_chunks);
-      hipLaunchKernelGGL(k_group_scan, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, stream, cs, n_groups,
-                         d_cell_chunks, d_group_tot);
+      hipLaunchKernelGGL(k_group_scan, dim3((unsigned)((n_groups + 3) / 4)), dim3(256), 0, stream, cs, n_groups,
+                         d_cell_chunks, d_group_tot, (unsigned long long*)(d_nnz_slots + 1));
       // chunks before a cell = its prefix inside the group + the group's inside its sequence + the sequence's
       hipLaunchKernelGGL(k_scan_sequences<long long>, dim3((unsigned)n_seq), dim3(kBuildBlock), 0, stream,
                          d_group_tot, (int32_t)kGroupSeq, d_seq_tot);
       hipLaunchKernelGGL(k_scan_sequences<long long>, dim3(1), dim3(kBuildBlock), 0, stream, d_seq_tot,
-                         (int32_t)n_seq, d_cell_total);
+                         (int32_t)n_seq, d_totals);
       BUILD_HIP(hipGetLastError());
-      BUILD_HIP(hipMemcpyAsync(&n_chunks, d_cell_total, sizeof(long long), hipMemcpyDeviceToHost, stream));
     }
-    // heavy chunks before the pieces of every segment: the ELL pieces of partition 0 .. c-1, then their remainder pieces
-    std::vector<int64_t> seg_at(2 * (size_t)s.c + 1, 0);
-    std::vector<int32_t> seg_hc(2 * (size_t)s.c + 1, 0);
-    if (want_heavy) {
+    // one report for the host: the totals, and the slots of the heavy sequence before the pieces of every segment
+    // (the ELL pieces of partition 0 .. c-1, then their remainder pieces)
+    {
+      int64_t* seg_at = (int64_t*)(host.base + h_seg_at);
       for (int32_t p = 0; p < s.c; ++p) {
         seg_at[p] = row_ptr[(size_t)p * (s.k + 1)];
         seg_at[(size_t)s.c + p] = h->R + rem_part_ptr[p];
       }
       seg_at[2 * (size_t)s.c] = n_pieces;
-      BUILD_HIP(hipMemcpyAsync(d_seg_at, seg_at.data(), sizeof(int64_t) * seg_at.size(), hipMemcpyHostToDevice, stream));
-      hipLaunchKernelGGL(k_pick, dim3((unsigned)((seg_at.size() + 255) / 256)), dim3(256), 0, stream,
-                         (int32_t)seg_at.size(), d_seg_at, d_hent, d_seg_hc);
+      BUILD_HIP(hipMemcpyAsync(d_seg_at, seg_at, sizeof(int64_t) * n_segs, hipMemcpyHostToDevice, stream));
+      hipLaunchKernelGGL(k_report, dim3((unsigned)((report2_count + 255) / 256)), dim3(256), 0, stream, d_totals,
+                         d_nnz_slots, want_heavy ? d_unit : nullptr, want_heavy ? d_hent : nullptr, n_pieces, (int32_t)n_segs,
+                         d_seg_at, d_report2);
       BUILD_HIP(hipGetLastError());
-      BUILD_HIP(hipMemcpyAsync(seg_hc.data(), d_seg_hc, sizeof(int32_t) * seg_hc.size(), hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipMemcpyAsync(&h->n_heavy_nnz, d_cell_total + 1, sizeof(long long), hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipMemcpyAsync(&heavy_totals[0], d_unit + n_pieces, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipMemcpyAsync(&heavy_totals[1], d_hent + n_pieces, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+      BUILD_HIP(hipMemcpyAsync(host.base + h_report2, d_report2, sizeof(long long) * report2_count,
+                               hipMemcpyDeviceToHost, stream));
+    }
+    // (the GPU is busy: the allocations whose sizes are known come now)
+    if (with_spmm_plan) {
+      const size_t bytes = sizeof(PiecePlace) * (size_t)(n_pieces ? n_pieces : 1);
+      tmp_place = alloc(bytes, actx, stream);
+      if (!tmp_place) { st = SPTIR_ERR_ALLOC; goto fail; }
+      BUILD_HIP(hipMemsetAsync(tmp_place, 0, bytes, stream));  // len 0: not queued
+    }
+    if (want_heavy) {
+      h->row_slot_ptr = (int32_t*)alloc(sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1), actx, stream);
+      tmp_row_flags = alloc(sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1), actx, stream);
+      if (!h->row_slot_ptr || !tmp_row_flags) { st = SPTIR_ERR_ALLOC; goto fail; }
     }
     BUILD_HIP(hipStreamSynchronize(stream));
+    const long long* report2 = (const long long*)(host.base + h_report2);
+    const long long n_chunks = report2[0];
+    h->n_heavy_nnz = report2[1];
+    const int64_t max_list_len = report2[4];
     // the lists' chunks come first in the stream (each list a whole number of quads), then the heavy chunks
-    // (heavy_totals[1]: slots of the heavy sequence)
-    const int64_t n_heavy_chunks =
-        (chunks_of_slots(heavy_totals[1]) + kChunksPerQuad - 1) / kChunksPerQuad * kChunksPerQuad;
+    // (report2[3]: slots of the heavy sequence)
+    const int64_t n_heavy_chunks = (chunks_of_slots(report2[3]) + kChunksPerQuad - 1) / kChunksPerQuad * kChunksPerQuad;
     h->n_chunks = n_chunks;
-    h->n_heavy = heavy_totals[0];
+    h->n_heavy = report2[2];
     h->heavy_chunk0 = n_chunks;
     h->n_heavy_chunks = n_heavy_chunks;
     h->n_heavy_lists = (int32_t)((n_heavy_chunks + kHeavyListChunks - 1) / kHeavyListChunks);
@@ -1263,56 +1560,44 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       for (int32_t i = 0; i <= h->n_heavy_segs; ++i)
         h->hseg_list[i] = i == h->n_heavy_segs
                               ? h->n_heavy_lists
-                              : (int32_t)(((int64_t)seg_hc[i] / kChunkSlots + kHeavyListChunks - 1) / kHeavyListChunks);
+                              : (int32_t)((report2[5 + i] / kChunkSlots + kHeavyListChunks - 1) / kHeavyListChunks);
+    } else if (h->row_slot_ptr) {
+      free_(h->row_slot_ptr, actx);
+      h->row_slot_ptr = nullptr;
     }
     const int64_t all_chunks = n_chunks + n_heavy_chunks;
     if (h->n_partial_rows > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
-    {
-      size_t bytes = sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1);
-      tmp_chunks = alloc(bytes, actx, stream);  // descriptors (of the lists' chunks) are only needed until the stream is packed
-      if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
-      BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, bytes, stream));  // count 0 marks the padding chunks
-      bytes = sizeof(PiecePlace) * (size_t)(n_pieces ? n_pieces : 1);
-      tmp_place = alloc(bytes, actx, stream);
-      if (!tmp_place) { st = SPTIR_ERR_ALLOC; goto fail; }
-      BUILD_HIP(hipMemsetAsync(tmp_place, 0, bytes, stream));  // len 0: not queued
-      bytes = sizeof(int32_t) * ((h->compact_stream ? 2 : 3) - (h->row_val ? 1 : 0)) * kChunkSlots *
-              (size_t)(all_chunks ? all_chunks : 1);
-      h->stream = (int32_t*)alloc(bytes, actx, stream);
-      if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += bytes;
-    }
-    StreamShape ss;
-    ss.stream = h->stream; ss.compact = h->compact_stream; ss.log2_rb = cs.log2_rb; ss.unit = h->row_val ? 1 : 0;
-    ss.phase_width = (int32_t)((int64_t)cs.ppg * s.w > 0x7FFFFFFF ? 0x7FFFFFFF : (int64_t)cs.ppg * s.w);
-    if (n_parts > 0)
-      hipLaunchKernelGGL(k_part_fill_chunks, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs, ss,
-                         n_parts, d_bounds, d_cell_chunks, d_group_tot, d_seq_tot, h->row_len, h->row_ids,
-                         h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_ptr, h->S, (Chunk*)tmp_chunks,
-                         (PiecePlace*)tmp_place, h->rb_chunk_ptr);
+    const int32_t n_units = (int32_t)h->n_heavy;
+    int64_t* unit_slot0 = nullptr;
+    int32_t *unit_start = nullptr, *unit_end = nullptr, *quad_unit = nullptr;
+    const size_t partial_bytes = sizeof(float) * kPartialFeat * (size_t)h->n_partial_rows;
     if (h->n_heavy > 0) {
-      // ---- heavy pieces: their stream records, first partial-sum row of every heavy list, the rows' partial sums
+      // ---- heavy pieces, the part that needs small arrays only: where every piece lies, the first partial-sum
+      // row of every heavy list, which partial-sum rows each row of Y takes.  A row of Y takes one partial-sum row
+      // per heavy piece it has plus one per list boundary such a piece crosses, so there are at most
+      // n_partial_rows of them; the rows with heavy pieces are at most as many as there are such pieces.
+      const size_t slot_bytes = sizeof(int32_t) * (size_t)h->n_partial_rows;
+      const size_t rows_bytes = sizeof(int32_t) * (size_t)std::min<int64_t>(s.n_rows, h->n_heavy);
       struct { void** p; size_t bytes; } more[] = {
           {(void**)&h->hlist_first_slot, sizeof(int32_t) * (size_t)h->n_heavy_lists},
-          {(void**)&h->row_slot_ptr, sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1)},
-          {(void**)&h->partial, sizeof(float) * kPartialFeat * (size_t)h->n_partial_rows},
-          {(void**)&tmp_units, sizeof(int32_t) * (3 * (size_t)h->n_heavy + 1)},
-          {(void**)&tmp_row_flags, sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1)},
+          {(void**)&tmp_units, (sizeof(int64_t) + 2 * sizeof(int32_t)) * ((size_t)h->n_heavy + 1) +
+                                   sizeof(int32_t) * (size_t)(n_heavy_chunks / kChunksPerQuad + 1)},
+          {(void**)&h->row_slots, slot_bytes},
+          {(void**)&h->heavy_rows, rows_bytes},
       };
       for (auto& wnt : more) {
         *wnt.p = alloc(wnt.bytes, actx, stream);
         if (!*wnt.p) { st = SPTIR_ERR_ALLOC; goto fail; }
       }
-      h->device_bytes += more[0].bytes + more[1].bytes + more[2].bytes;
-      const int32_t n_units = (int32_t)h->n_heavy;
-      int32_t* unit_piece = (int32_t*)tmp_units;
-      int32_t* unit_end = unit_piece + n_units;
-      int32_t* unit_start = unit_end + n_units;  // [n_units + 1]
+      h->device_bytes += more[0].bytes + slot_bytes + rows_bytes + sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1) +
+                         partial_bytes;
+      unit_slot0 = (int64_t*)tmp_units;                  // [n_units]
+      unit_start = (int32_t*)(unit_slot0 + n_units + 1);  // [n_units + 1]
+      unit_end = unit_start + n_units + 1;               // [n_units]
+      quad_unit = unit_end + n_units + 1;                // [quads of the heavy sequence]
       hipLaunchKernelGGL(k_heavy_units, dim3((unsigned)((n_pieces + 256) / 256)), dim3(256), 0, stream, n_pieces,
-                         h->row_len, d_unit, d_hent, unit_piece, unit_start, unit_end);
-      hipLaunchKernelGGL(k_pack_heavy, dim3((unsigned)((n_heavy_chunks + 3) / 4)), dim3(256), 0, stream,
-                         n_heavy_chunks, (int64_t)n_chunks, ss, n_units, unit_piece, unit_start, unit_end, B, s.k,
-                         h->R, h->S, h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_ptr, h->cols, h->vals);
+                         h->row_len, d_unit, d_hent, B, s.k, h->R, h->S, h->bucket_row_ptr, h->bucket_slot_ptr,
+                         h->rem_ptr, cs.long_len, unit_start, unit_end, unit_slot0, quad_unit);
       hipLaunchKernelGGL(k_heavy_list_slots, dim3((unsigned)((h->n_heavy_lists + 255) / 256)), dim3(256), 0, stream,
                          h->n_heavy_lists, n_units, unit_end, h->hlist_first_slot);
       hipLaunchKernelGGL(k_row_slot_counts, dim3((unsigned)((s.n_rows + 256) / 256)), dim3(256), 0, stream, s.n_rows,
@@ -1326,27 +1611,43 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       BUILD_HIP(hipGetLastError());
       st = device_exclusive_scan((int32_t*)tmp_row_flags, (int64_t)s.n_rows + 1, d_seq_base, stream);
       if (st != SPTIR_OK) goto fail;
-      int32_t n_row_slots = 0;
-      BUILD_HIP(hipMemcpyAsync(&n_row_slots, h->row_slot_ptr + s.n_rows, sizeof(int32_t), hipMemcpyDeviceToHost,
-                               stream));
-      BUILD_HIP(hipMemcpyAsync(&h->n_heavy_rows, (int32_t*)tmp_row_flags + s.n_rows, sizeof(int32_t),
-                               hipMemcpyDeviceToHost, stream));
-      BUILD_HIP(hipStreamSynchronize(stream));
-      h->n_row_slots = n_row_slots;
-      size_t bytes = sizeof(int32_t) * (size_t)(n_row_slots ? n_row_slots : 1);
-      h->row_slots = (int32_t*)alloc(bytes, actx, stream);
-      if (!h->row_slots) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += bytes;
-      bytes = sizeof(int32_t) * (size_t)(h->n_heavy_rows ? h->n_heavy_rows : 1);
-      h->heavy_rows = (int32_t*)alloc(bytes, actx, stream);
-      if (!h->heavy_rows) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += bytes;
       hipLaunchKernelGGL(k_row_slot_fill, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
                          s.c, d_piece_of, h->row_len, d_unit, d_hent, h->row_slot_ptr, h->row_slots);
       hipLaunchKernelGGL(k_heavy_row_fill, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
                          h->row_slot_ptr, (const int32_t*)tmp_row_flags, h->heavy_rows);
+      hipLaunchKernelGGL(k_pick2, dim3(1), dim3(64), 0, stream, h->row_slot_ptr + s.n_rows,
+                         (const int32_t*)tmp_row_flags + s.n_rows, d_report3);
       BUILD_HIP(hipGetLastError());
+      BUILD_HIP(hipMemcpyAsync(host.base + h_report3, d_report3, sizeof(int32_t) * 2, hipMemcpyDeviceToHost, stream));
     }
+    {
+      // ---- the large arrays (the GPU is busy meanwhile)
+      size_t bytes = sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1);
+      tmp_chunks = alloc(bytes, actx, stream);  // descriptors (of the lists' chunks) are only needed until the stream is packed
+      if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
+      BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, bytes, stream));  // count 0 marks the padding chunks
+      bytes = sizeof(int32_t) * ((h->compact_stream ? 2 : 3) - (h->row_val ? 1 : 0)) * kChunkSlots *
+              (size_t)(all_chunks ? all_chunks : 1);
+      h->stream = (int32_t*)alloc(bytes, actx, stream);
+      if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += bytes;
+      if (h->n_heavy > 0) {
+        h->partial = (float*)alloc(partial_bytes, actx, stream);
+        if (!h->partial) { st = SPTIR_ERR_ALLOC; goto fail; }
+      }
+    }
+    StreamShape ss;
+    ss.stream = h->stream; ss.compact = h->compact_stream; ss.log2_rb = cs.log2_rb; ss.unit = h->row_val ? 1 : 0;
+    ss.phase_width = (int32_t)((int64_t)cs.ppg * s.w > 0x7FFFFFFF ? 0x7FFFFFFF : (int64_t)cs.ppg * s.w);
+    if (n_parts > 0)
+      hipLaunchKernelGGL(k_part_fill_chunks, dim3((unsigned)((n_parts + 255) / 256)), dim3(256), 0, stream, cs, ss,
+                         n_parts, d_bounds, d_cell_chunks, d_group_tot, d_seq_tot, h->row_len, h->row_ids,
+                         h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_ptr, h->S, (Chunk*)tmp_chunks,
+                         (PiecePlace*)tmp_place, h->rb_chunk_ptr, (int64_t)n_chunks);
+    if (h->n_heavy > 0)
+      hipLaunchKernelGGL(k_pack_heavy, dim3((unsigned)((n_heavy_chunks / kPackRun + 3) / 4)), dim3(256), 0, stream,
+                         n_heavy_chunks, (int64_t)n_chunks, ss, n_units, unit_start, unit_end, unit_slot0, quad_unit,
+                         h->cols, h->vals);
     if (n_chunks > 0) {
       int64_t blocks = (n_chunks + 3) / 4;
       if (blocks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
@@ -1356,21 +1657,27 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
         hipLaunchKernelGGL(k_pack_pieces, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream, n_pieces, ss,
                            (const PiecePlace*)tmp_place, h->row_ids, h->cols, h->vals);
     }
-    {
-      int64_t total = n_chunks;
-      BUILD_HIP(hipMemcpyAsync(h->rb_chunk_ptr + (size_t)cs.n_phases * cs.n_rb, &total, sizeof(int64_t),
-                               hipMemcpyHostToDevice, stream));
-    }
     BUILD_HIP(hipGetLastError());
+    if (n_parts == 0) {  // no lists: the one element of rb_chunk_ptr
+      int64_t* zero = (int64_t*)(host.base + h_misc + 16);
+      *zero = 0;
+      BUILD_HIP(hipMemcpyAsync(h->rb_chunk_ptr, zero, sizeof(int64_t), hipMemcpyHostToDevice, stream));
+    }
     if (n_groups > 0) {
       // ---- launch order of the row blocks: longest list first
       h->rb_order = (int32_t*)alloc(sizeof(int32_t) * (size_t)n_groups, actx, stream);
       if (!h->rb_order) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += sizeof(int32_t) * (size_t)n_groups;
-      st = order_row_blocks(h->rb_chunk_ptr, cs.n_phases, cs.n_rb, h->rb_order, alloc, free_, actx, stream, &tmp_order);
+      st = order_row_blocks(h->rb_chunk_ptr, cs.n_phases, cs.n_rb, max_list_len, h->rb_order, alloc, free_, actx,
+                            stream, &tmp_order);
       if (st != SPTIR_OK) goto fail;
     }
     BUILD_HIP(hipStreamSynchronize(stream));
+    if (h->n_heavy > 0) {
+      const int32_t* report3 = (const int32_t*)(host.base + h_report3);
+      h->n_row_slots = report3[0];
+      h->n_heavy_rows = report3[1];
+    }
     if (opt.release_canonical && with_spmm_plan) {
       // sptir_spmm reads the stream only
       const size_t bytes = (sizeof(int32_t) + sizeof(float)) * (size_t)(h->S + T + kChunkSlots);
@@ -1387,6 +1694,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   if (tmp_order) free_(tmp_order, actx);
   if (tmp_units) free_(tmp_units, actx);
   if (tmp_row_flags) free_(tmp_row_flags, actx);
+  pinned_pool().release(pinned);
   *out = h;
   return SPTIR_OK;
 
@@ -1399,6 +1707,7 @@ fail:
   if (tmp_order) free_(tmp_order, actx);
   if (tmp_units) free_(tmp_units, actx);
   if (tmp_row_flags) free_(tmp_row_flags, actx);
+  pinned_pool().release(pinned);
   sptir_hyb_destroy(h);
   return st;
 #undef BUILD_HIP

@@ -129,9 +129,9 @@ int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches
 
 // rb_order[launch][i] = the row block with the i-th longest chunk list of that launch (order.hip).  Works on
 // `stream`; *scratch_out is device memory the caller frees once the stream has drained.
-sptir_status_t order_row_blocks(const int64_t* rb_chunk_ptr, int32_t n_launches, int32_t n_rb, int32_t* rb_order,
-                                sptir_alloc_fn alloc, sptir_free_fn free_, void* actx, hipStream_t stream,
-                                void** scratch_out);
+sptir_status_t order_row_blocks(const int64_t* rb_chunk_ptr, int32_t n_launches, int32_t n_rb, int64_t max_list_len,
+                                int32_t* rb_order, sptir_alloc_fn alloc, sptir_free_fn free_, void* actx,
+                                hipStream_t stream, void** scratch_out);
 
 // records a failed HIP call for sptir_last_hip_error(); returns SPTIR_ERR_HIP
 sptir_status_t note_hip_error(hipError_t e, const char* what);
