@@ -60,10 +60,7 @@ sptir_status_t sptir_set_allocator(sptir_alloc_fn alloc, sptir_free_fn free_, vo
 
 sptir_status_t sptir_hyb_destroy(sptir_hyb_t* h) {
   if (!h) return SPTIR_OK;
-  void* ptrs[] = {h->bucket_row_ptr, h->bucket_slot_ptr, h->rem_part_ptr, h->rem_ptr,
-                  h->row_ids, h->row_len, h->cols, h->vals, h->stream, h->rb_chunk_ptr, h->rb_order,
-                  h->hlist_first_slot, h->row_slot_ptr, h->row_slots, h->heavy_rows, h->partial, h->row_val};
-  for (void* p : ptrs)
+  for (void* p : h->blobs)
     if (p) h->free_(p, h->alloc_ctx);
   free(h->hseg_list);
   delete h;

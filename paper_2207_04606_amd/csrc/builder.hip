@@ -247,6 +247,7 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
   // the pieces of a wavefront, for the copy: slots before each piece, where it lies in the input, its real
   // length, where it goes
   __shared__ long long pre[kWaves][65];
+  __shared__ unsigned pre32[kWaves][65];
   __shared__ long long piece_dst[kWaves][64];
   __shared__ int piece_lo[kWaves][64], piece_len[kWaves][64];
   int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -328,8 +329,9 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
     const long long t = __shfl_up(inc, d, 64);
     if (lane >= d) inc += t;
   }
-  if (lane == 0) pre[wave][0] = 0;
+  if (lane == 0) { pre[wave][0] = 0; pre32[wave][0] = 0; }
   pre[wave][lane + 1] = inc;
+  pre32[wave][lane + 1] = (unsigned)inc;
   piece_lo[wave][lane] = lo; piece_len[wave][lane] = l; piece_dst[wave][lane] = dst;
   __syncthreads();
   const long long total = pre[wave][64];
@@ -337,24 +339,38 @@ __global__ __launch_bounds__(kBuildBlock) void k_scatter(BuildShape s, ScatterAr
   const float* __restrict__ values = a.values;
   int32_t* __restrict__ cols = a.cols;
   float* __restrict__ vals = a.vals;
+  if (total >= 0x7FFFFFFFll) {
+    // (a wavefront with 2^31 slots or more: piece after piece, the 32-bit positions below do not reach)
+    for (int i = 0; i < 64; ++i) {
+      const long long width_i = pre[wave][i + 1] - pre[wave][i];
+      const int len_i = piece_len[wave][i];
+      for (long long j = lane; j < width_i; j += 64) {
+        const long long src = piece_lo[wave][i] + (j < len_i ? j : (long long)len_i - 1);
+        cols[piece_dst[wave][i] + j] = indices[src];
+        vals[piece_dst[wave][i] + j] = j < len_i ? values[src] : 0.0f;
+      }
+    }
+    return;
+  }
   constexpr int kUnroll = 4;
-  for (long long f0 = 0; f0 < total; f0 += 64 * kUnroll) {
+  const unsigned total32 = (unsigned)total;
+  for (unsigned f0 = 0; f0 < total32; f0 += 64 * kUnroll) {
     int32_t col[kUnroll];
     float val[kUnroll];
     long long at[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      const long long f = f0 + u * 64 + lane;
+      const unsigned f = f0 + u * 64 + lane;
       at[u] = -1; col[u] = 0; val[u] = 0.f;
-      if (f < total) {
+      if (f < total32) {
         int i = 0;  // the piece with pre[i] <= f < pre[i + 1]
 #pragma unroll
         for (int step = 32; step > 0; step >>= 1)
-          if (pre[wave][i + step] <= f) i += step;
-        const long long j = f - pre[wave][i];
+          if (pre32[wave][i + step] <= f) i += step;
+        const int j = (int)(f - pre32[wave][i]);
         const int len_i = piece_len[wave][i];
         const bool real = j < len_i;
-        const long long src = piece_lo[wave][i] + (real ? j : (long long)len_i - 1);
+        const long long src = (long long)piece_lo[wave][i] + (real ? j : len_i - 1);
         col[u] = indices[src];
         val[u] = real ? values[src] : 0.0f;
         at[u] = piece_dst[wave][i] + j;
@@ -429,12 +445,12 @@ __device__ __forceinline__ int cells_per_part(const CellShape& cs) { return cs.n
 __device__ __forceinline__ int cells_per_group(const CellShape& cs) { return cs.ppg * (cs.nb + 1) + 1; }
 
 struct PiecePlace {     // where the entries of a queued row piece go (len 0: the piece is not queued)
-  int64_t slot0;        // its first slot in the fused (cols, vals) arrays
-  int64_t first_chunk;  // first chunk of the queue cell
+  uint32_t slot0;       // its first slot in the fused (cols, vals) arrays (fewer than 2^32: at most 2 * nnz)
+  int32_t first_chunk;  // first chunk of the queue cell
   int32_t where;        // position of its first entry in the queue | queue << 28
   int32_t len;          // real entries
 };
-static_assert(sizeof(PiecePlace) == 24, "PiecePlace must stay 24 bytes");
+static_assert(sizeof(PiecePlace) == 16, "PiecePlace must stay 16 bytes");
 constexpr uint32_t kChunkIsQueue = 1u << 14;
 
 __device__ __forceinline__ int chunks_of_length(int len) { return (len + kChunkSlots - 1) / kChunkSlots; }
@@ -632,7 +648,8 @@ struct FillVisitor {
   }
   __device__ void on_queued(int bin, int32_t q, int len, int g, int start) {
     PiecePlace pl;
-    pl.slot0 = slot_of(bin, q); pl.first_chunk = cell_first(cs.nb); pl.where = start | (g << 28); pl.len = len;
+    pl.slot0 = (uint32_t)slot_of(bin, q); pl.first_chunk = (int32_t)cell_first(cs.nb);
+    pl.where = start | (g << 28); pl.len = len;
     place[q] = pl;
   }
   __device__ void on_dealt(const int (&load)[8], int n_chunks) {
@@ -721,7 +738,7 @@ __global__ __launch_bounds__(256) void k_pack_pieces(int64_t n_pieces, StreamSha
           if (pre[wave][i + step] <= f) i += step;
         piece[u] = i;
         e[u] = f - pre[wave][i];
-        const int64_t src = pl_of[wave][i].slot0 + e[u];
+        const int64_t src = (int64_t)pl_of[wave][i].slot0 + e[u];
         col[u] = cols[src];
         val[u] = ss.unit ? 0.f : vals[src];
       }
@@ -1270,8 +1287,6 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   void* tmp_chunks = nullptr;
   void* tmp_place = nullptr;
   void* tmp_order = nullptr;
-  void* tmp_units = nullptr;
-  void* tmp_row_flags = nullptr;
 
   sptir_hyb* h = new (std::nothrow) sptir_hyb();
   if (!h) { free_(tmp.base, actx); pinned_pool().release(pinned); return SPTIR_ERR_ALLOC; }
@@ -1367,7 +1382,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       rem_part_ptr[p + 1] = (int32_t)M;
     }
     h->R = row_ptr[B]; h->S = slot_ptr[B]; h->M = M; h->T = T;
-    if (h->R + h->M > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
+    if (h->R + h->M > 0x7FFFFFFF || h->S + T >= 0xFFFFFFFFll) { st = SPTIR_ERR_OVERFLOW; goto fail; }
 
     // ---- launch shape of the SpMM: row blocks, lists, heavy pieces
     CellShape cs;
@@ -1389,16 +1404,9 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     cs.ppg = ls.parts_per_phase; cs.log2_rb = ls.log2_row_block; cs.n_phases = ls.n_phases;
     h->compact_stream = ls.compact;
     h->rounds = ls.rounds;
-    if (value_bits && csr->nnz > 0 && flags[4] == flags[5]) {
-      // Every row has one value for all its entries (a row-normalised adjacency matrix, say): the stream
-      // carries no values, the kernels sum rows of X and scale each row of Y once.
-      h->row_val = (float*)alloc(sizeof(float) * (size_t)s.n_rows, actx, stream);
-      if (!h->row_val) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += sizeof(float) * (size_t)s.n_rows;
-      hipLaunchKernelGGL(k_row_values, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
-                         csr->indptr, csr->values, h->row_val);
-      BUILD_HIP(hipGetLastError());
-    }
+    // Every row has one value for all its entries (a row-normalised adjacency matrix, say): the stream
+    // carries no values, the kernels sum rows of X and scale each row of Y once.
+    const bool one_value_per_row = value_bits && csr->nnz > 0 && flags[4] == flags[5];
     h->sweep_kb = opt.sweep_kb > 0 ? opt.sweep_kb : 160 * 1024;
     cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
     cs.long_len = heavy_len_setting(csr->nnz, (int64_t)cs.n_phases * cs.n_rb, ls.rounds != 0, opt);
@@ -1424,6 +1432,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     const size_t o_hent = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room(n_pieces + 1) : 1));
     const size_t o_piece_of = tmp2.reserve(sizeof(int32_t) * (want_heavy ? (size_t)s.c * (size_t)s.n_rows : 1));
     const size_t o_seq_base = tmp2.reserve(sizeof(int32_t) * 2 * (scan_room(std::max<int64_t>(n_pieces + 1, s.n_rows + 1)) / kScanSeq + 2));
+    const size_t o_row_flags = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room((int64_t)s.n_rows + 1) : 1));
     tmp2.base = (char*)alloc(tmp2.size, actx, stream);
     if (!tmp2.base) { st = SPTIR_ERR_ALLOC; goto fail; }
     int32_t* d_bounds = (int32_t*)(tmp2.base + o_bounds);
@@ -1434,26 +1443,44 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     int32_t* d_hent = (int32_t*)(tmp2.base + o_hent);
     int32_t* d_piece_of = want_heavy ? (int32_t*)(tmp2.base + o_piece_of) : nullptr;
     int32_t* d_seq_base = (int32_t*)(tmp2.base + o_seq_base);
+    int32_t* d_row_flags = (int32_t*)(tmp2.base + o_row_flags);
 
-    // ---- the handle's device arrays (the chunk list follows further down)
-    struct { void** p; size_t bytes; } wanted[] = {
-        {(void**)&h->bucket_row_ptr, sizeof(int64_t) * (size_t)(B + 1)},
-        {(void**)&h->bucket_slot_ptr, sizeof(int64_t) * (size_t)(B + 1)},
-        {(void**)&h->rem_part_ptr, sizeof(int32_t) * (size_t)(s.c + 1)},
-        {(void**)&h->rem_ptr, sizeof(int64_t) * (size_t)(M + 1)},
-        // (row_ids, cols and vals end in kChunkSlots spare zero entries: whole 64-slot chunks are read from them
-        //  when the stream is packed, the last one of an array may be shorter)
-        {(void**)&h->row_ids, sizeof(int32_t) * (size_t)(h->R + M + kChunkSlots)},
-        {(void**)&h->row_len, sizeof(int32_t) * (size_t)(h->R + M)},
-        {(void**)&h->cols, sizeof(int32_t) * (size_t)(h->S + T + kChunkSlots)},
-        {(void**)&h->vals, sizeof(float) * (size_t)(h->S + T + kChunkSlots)},
-        {(void**)&h->rb_chunk_ptr, sizeof(int64_t) * ((size_t)cs.n_phases * cs.n_rb + 1)},
-    };
-    for (auto& wnt : wanted) {
-      size_t bytes = wnt.bytes ? wnt.bytes : 16;
-      *wnt.p = alloc(bytes, actx, stream);
-      if (!*wnt.p) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += bytes;
+    // ---- the handle's device arrays whose sizes are known now: two allocations (cols and vals can be released
+    // on their own); the arrays of the SpMM plan follow further down
+    {
+      Blob ba, bb;
+      const size_t a_row_ptr = ba.reserve(sizeof(int64_t) * (size_t)(B + 1));
+      const size_t a_slot_ptr = ba.reserve(sizeof(int64_t) * (size_t)(B + 1));
+      const size_t a_rem_part = ba.reserve(sizeof(int32_t) * (size_t)(s.c + 1));
+      const size_t a_rem_ptr = ba.reserve(sizeof(int64_t) * (size_t)(M + 1));
+      // (row_ids, cols and vals end in kChunkSlots spare zero entries: whole 64-slot chunks are read from them
+      //  when the stream is packed, the last one of an array may be shorter)
+      const size_t a_row_ids = ba.reserve(sizeof(int32_t) * (size_t)(h->R + M + kChunkSlots));
+      const size_t a_row_len = ba.reserve(sizeof(int32_t) * (size_t)(h->R + M + 1));
+      const size_t a_rb_chunk = ba.reserve(sizeof(int64_t) * ((size_t)cs.n_phases * cs.n_rb + 1));
+      const size_t a_row_val = ba.reserve(one_value_per_row ? sizeof(float) * (size_t)s.n_rows : 0);
+      const size_t a_row_slot = ba.reserve(want_heavy ? sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1) : 0);
+      const size_t b_cols = bb.reserve(sizeof(int32_t) * (size_t)(h->S + T + kChunkSlots));
+      const size_t b_vals = bb.reserve(sizeof(float) * (size_t)(h->S + T + kChunkSlots));
+      h->blobs[0] = alloc(ba.size, actx, stream);
+      h->blobs[1] = alloc(bb.size, actx, stream);
+      if (!h->blobs[0] || !h->blobs[1]) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += ba.size + bb.size;
+      char* a0 = (char*)h->blobs[0];
+      char* b0 = (char*)h->blobs[1];
+      h->bucket_row_ptr = (int64_t*)(a0 + a_row_ptr); h->bucket_slot_ptr = (int64_t*)(a0 + a_slot_ptr);
+      h->rem_part_ptr = (int32_t*)(a0 + a_rem_part); h->rem_ptr = (int64_t*)(a0 + a_rem_ptr);
+      h->row_ids = (int32_t*)(a0 + a_row_ids); h->row_len = (int32_t*)(a0 + a_row_len);
+      h->rb_chunk_ptr = (int64_t*)(a0 + a_rb_chunk);
+      if (one_value_per_row) h->row_val = (float*)(a0 + a_row_val);
+      if (want_heavy) h->row_slot_ptr = (int32_t*)(a0 + a_row_slot);
+      h->cols = (int32_t*)(b0 + b_cols); h->vals = (float*)(b0 + b_vals);
+      h->canonical_bytes = bb.size;
+    }
+    if (one_value_per_row) {
+      hipLaunchKernelGGL(k_row_values, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
+                         csr->indptr, csr->values, h->row_val);
+      BUILD_HIP(hipGetLastError());
     }
     BUILD_HIP(hipMemcpyAsync(h->bucket_row_ptr, row_ptr, sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice, stream));
     BUILD_HIP(hipMemcpyAsync(h->bucket_slot_ptr, slot_ptr, sizeof(int64_t) * (B + 1), hipMemcpyHostToDevice, stream));
@@ -1533,11 +1560,6 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       if (!tmp_place) { st = SPTIR_ERR_ALLOC; goto fail; }
       BUILD_HIP(hipMemsetAsync(tmp_place, 0, bytes, stream));  // len 0: not queued
     }
-    if (want_heavy) {
-      h->row_slot_ptr = (int32_t*)alloc(sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1), actx, stream);
-      tmp_row_flags = alloc(sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1), actx, stream);
-      if (!h->row_slot_ptr || !tmp_row_flags) { st = SPTIR_ERR_ALLOC; goto fail; }
-    }
     BUILD_HIP(hipStreamSynchronize(stream));
     const long long* report2 = (const long long*)(host.base + h_report2);
     const long long n_chunks = report2[0];
@@ -1561,40 +1583,52 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
         h->hseg_list[i] = i == h->n_heavy_segs
                               ? h->n_heavy_lists
                               : (int32_t)((report2[5 + i] / kChunkSlots + kHeavyListChunks - 1) / kHeavyListChunks);
-    } else if (h->row_slot_ptr) {
-      free_(h->row_slot_ptr, actx);
-      h->row_slot_ptr = nullptr;
+    } else {
+      h->row_slot_ptr = nullptr;  // (its room in the first allocation stays unused)
     }
     const int64_t all_chunks = n_chunks + n_heavy_chunks;
-    if (h->n_partial_rows > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
+    if (h->n_partial_rows > 0x7FFFFFFF || all_chunks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
     const int32_t n_units = (int32_t)h->n_heavy;
     int64_t* unit_slot0 = nullptr;
     int32_t *unit_start = nullptr, *unit_end = nullptr, *quad_unit = nullptr;
-    const size_t partial_bytes = sizeof(float) * kPartialFeat * (size_t)h->n_partial_rows;
-    if (h->n_heavy > 0) {
-      // ---- heavy pieces, the part that needs small arrays only: where every piece lies, the first partial-sum
-      // row of every heavy list, which partial-sum rows each row of Y takes.  A row of Y takes one partial-sum row
-      // per heavy piece it has plus one per list boundary such a piece crosses, so there are at most
-      // n_partial_rows of them; the rows with heavy pieces are at most as many as there are such pieces.
-      const size_t slot_bytes = sizeof(int32_t) * (size_t)h->n_partial_rows;
-      const size_t rows_bytes = sizeof(int32_t) * (size_t)std::min<int64_t>(s.n_rows, h->n_heavy);
-      struct { void** p; size_t bytes; } more[] = {
-          {(void**)&h->hlist_first_slot, sizeof(int32_t) * (size_t)h->n_heavy_lists},
-          {(void**)&tmp_units, (sizeof(int64_t) + 2 * sizeof(int32_t)) * ((size_t)h->n_heavy + 1) +
-                                   sizeof(int32_t) * (size_t)(n_heavy_chunks / kChunksPerQuad + 1)},
-          {(void**)&h->row_slots, slot_bytes},
-          {(void**)&h->heavy_rows, rows_bytes},
-      };
-      for (auto& wnt : more) {
-        *wnt.p = alloc(wnt.bytes, actx, stream);
-        if (!*wnt.p) { st = SPTIR_ERR_ALLOC; goto fail; }
+    // ---- the arrays of the SpMM plan, one allocation; the temporaries of this stage, another.  A row of Y takes
+    // one partial-sum row per heavy piece it has plus one per list boundary such a piece crosses, so there are at
+    // most n_partial_rows of them; the rows with heavy pieces are at most as many as there are such pieces.
+    {
+      Blob bc, bt;
+      const bool heavy = h->n_heavy > 0;
+      const size_t c_first_slot = bc.reserve(heavy ? sizeof(int32_t) * (size_t)h->n_heavy_lists : 0);
+      const size_t c_row_slots = bc.reserve(heavy ? sizeof(int32_t) * (size_t)h->n_partial_rows : 0);
+      const size_t c_heavy_rows = bc.reserve(heavy ? sizeof(int32_t) * (size_t)std::min<int64_t>(s.n_rows, h->n_heavy) : 0);
+      const size_t c_rb_order = bc.reserve(sizeof(int32_t) * (size_t)(n_groups ? n_groups : 1));
+      const size_t c_stream = bc.reserve(sizeof(int32_t) * ((h->compact_stream ? 2 : 3) - (one_value_per_row ? 1 : 0)) *
+                                         kChunkSlots * (size_t)(all_chunks ? all_chunks : 1));
+      const size_t c_partial = bc.reserve(heavy ? sizeof(float) * kPartialFeat * (size_t)h->n_partial_rows : 0);
+      const size_t t_chunks = bt.reserve(sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1));
+      const size_t t_slot0 = bt.reserve(heavy ? sizeof(int64_t) * (size_t)n_units : 0);
+      const size_t t_start = bt.reserve(heavy ? sizeof(int32_t) * ((size_t)n_units + 1) : 0);
+      const size_t t_end = bt.reserve(heavy ? sizeof(int32_t) * (size_t)n_units : 0);
+      const size_t t_quad = bt.reserve(heavy ? sizeof(int32_t) * (size_t)(n_heavy_chunks / kChunksPerQuad + 1) : 0);
+      h->blobs[2] = alloc(bc.size, actx, stream);
+      tmp_chunks = alloc(bt.size, actx, stream);
+      if (!h->blobs[2] || !tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
+      h->device_bytes += bc.size;
+      char* c0 = (char*)h->blobs[2];
+      char* t0 = (char*)tmp_chunks;
+      if (heavy) {
+        h->hlist_first_slot = (int32_t*)(c0 + c_first_slot); h->row_slots = (int32_t*)(c0 + c_row_slots);
+        h->heavy_rows = (int32_t*)(c0 + c_heavy_rows); h->partial = (float*)(c0 + c_partial);
+        unit_slot0 = (int64_t*)(t0 + t_slot0); unit_start = (int32_t*)(t0 + t_start);
+        unit_end = (int32_t*)(t0 + t_end); quad_unit = (int32_t*)(t0 + t_quad);
       }
-      h->device_bytes += more[0].bytes + slot_bytes + rows_bytes + sizeof(int32_t) * scan_room((int64_t)s.n_rows + 1) +
-                         partial_bytes;
-      unit_slot0 = (int64_t*)tmp_units;                  // [n_units]
-      unit_start = (int32_t*)(unit_slot0 + n_units + 1);  // [n_units + 1]
-      unit_end = unit_start + n_units + 1;               // [n_units]
-      quad_unit = unit_end + n_units + 1;                // [quads of the heavy sequence]
+      if (n_groups > 0) h->rb_order = (int32_t*)(c0 + c_rb_order);
+      h->stream = (int32_t*)(c0 + c_stream);
+      (void)t_chunks;  // (offset 0)
+      BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1), stream));  // count 0 marks the padding chunks
+    }
+    if (h->n_heavy > 0) {
+      // ---- heavy pieces: where every piece lies, the first partial-sum row of every heavy list, which
+      // partial-sum rows each row of Y takes
       hipLaunchKernelGGL(k_heavy_units, dim3((unsigned)((n_pieces + 256) / 256)), dim3(256), 0, stream, n_pieces,
                          h->row_len, d_unit, d_hent, B, s.k, h->R, h->S, h->bucket_row_ptr, h->bucket_slot_ptr,
                          h->rem_ptr, cs.long_len, unit_start, unit_end, unit_slot0, quad_unit);
@@ -1607,34 +1641,18 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       if (st != SPTIR_OK) goto fail;
       // the rows that have heavy pieces, compacted: the launch that adds their partial sums to Y visits only them
       hipLaunchKernelGGL(k_heavy_row_flags, dim3((unsigned)((s.n_rows + 256) / 256)), dim3(256), 0, stream, s.n_rows,
-                         h->row_slot_ptr, (int32_t*)tmp_row_flags);
+                         h->row_slot_ptr, d_row_flags);
       BUILD_HIP(hipGetLastError());
-      st = device_exclusive_scan((int32_t*)tmp_row_flags, (int64_t)s.n_rows + 1, d_seq_base, stream);
+      st = device_exclusive_scan(d_row_flags, (int64_t)s.n_rows + 1, d_seq_base, stream);
       if (st != SPTIR_OK) goto fail;
       hipLaunchKernelGGL(k_row_slot_fill, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
                          s.c, d_piece_of, h->row_len, d_unit, d_hent, h->row_slot_ptr, h->row_slots);
       hipLaunchKernelGGL(k_heavy_row_fill, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
-                         h->row_slot_ptr, (const int32_t*)tmp_row_flags, h->heavy_rows);
+                         h->row_slot_ptr, d_row_flags, h->heavy_rows);
       hipLaunchKernelGGL(k_pick2, dim3(1), dim3(64), 0, stream, h->row_slot_ptr + s.n_rows,
-                         (const int32_t*)tmp_row_flags + s.n_rows, d_report3);
+                         d_row_flags + s.n_rows, d_report3);
       BUILD_HIP(hipGetLastError());
       BUILD_HIP(hipMemcpyAsync(host.base + h_report3, d_report3, sizeof(int32_t) * 2, hipMemcpyDeviceToHost, stream));
-    }
-    {
-      // ---- the large arrays (the GPU is busy meanwhile)
-      size_t bytes = sizeof(Chunk) * (size_t)(n_chunks ? n_chunks : 1);
-      tmp_chunks = alloc(bytes, actx, stream);  // descriptors (of the lists' chunks) are only needed until the stream is packed
-      if (!tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
-      BUILD_HIP(hipMemsetAsync(tmp_chunks, 0, bytes, stream));  // count 0 marks the padding chunks
-      bytes = sizeof(int32_t) * ((h->compact_stream ? 2 : 3) - (h->row_val ? 1 : 0)) * kChunkSlots *
-              (size_t)(all_chunks ? all_chunks : 1);
-      h->stream = (int32_t*)alloc(bytes, actx, stream);
-      if (!h->stream) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += bytes;
-      if (h->n_heavy > 0) {
-        h->partial = (float*)alloc(partial_bytes, actx, stream);
-        if (!h->partial) { st = SPTIR_ERR_ALLOC; goto fail; }
-      }
     }
     StreamShape ss;
     ss.stream = h->stream; ss.compact = h->compact_stream; ss.log2_rb = cs.log2_rb; ss.unit = h->row_val ? 1 : 0;
@@ -1665,9 +1683,6 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     }
     if (n_groups > 0) {
       // ---- launch order of the row blocks: longest list first
-      h->rb_order = (int32_t*)alloc(sizeof(int32_t) * (size_t)n_groups, actx, stream);
-      if (!h->rb_order) { st = SPTIR_ERR_ALLOC; goto fail; }
-      h->device_bytes += sizeof(int32_t) * (size_t)n_groups;
       st = order_row_blocks(h->rb_chunk_ptr, cs.n_phases, cs.n_rb, max_list_len, h->rb_order, alloc, free_, actx,
                             stream, &tmp_order);
       if (st != SPTIR_OK) goto fail;
@@ -1680,11 +1695,11 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     }
     if (opt.release_canonical && with_spmm_plan) {
       // sptir_spmm reads the stream only
-      const size_t bytes = (sizeof(int32_t) + sizeof(float)) * (size_t)(h->S + T + kChunkSlots);
-      free_(h->cols, actx); free_(h->vals, actx);
+      free_(h->blobs[1], actx);
+      h->blobs[1] = nullptr;
       h->cols = nullptr; h->vals = nullptr;
+      h->device_bytes -= h->canonical_bytes;
       h->canonical_released = 1;
-      h->device_bytes -= bytes;
     }
   }
   free_(tmp.base, actx);
@@ -1692,8 +1707,6 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   if (tmp_chunks) free_(tmp_chunks, actx);
   if (tmp_place) free_(tmp_place, actx);
   if (tmp_order) free_(tmp_order, actx);
-  if (tmp_units) free_(tmp_units, actx);
-  if (tmp_row_flags) free_(tmp_row_flags, actx);
   pinned_pool().release(pinned);
   *out = h;
   return SPTIR_OK;
@@ -1705,8 +1718,6 @@ fail:
   if (tmp_chunks) free_(tmp_chunks, actx);
   if (tmp_place) free_(tmp_place, actx);
   if (tmp_order) free_(tmp_order, actx);
-  if (tmp_units) free_(tmp_units, actx);
-  if (tmp_row_flags) free_(tmp_row_flags, actx);
   pinned_pool().release(pinned);
   sptir_hyb_destroy(h);
   return st;

@@ -93,6 +93,10 @@ struct sptir_hyb {
   int32_t sweep_kb;          // rounds == 0: kilobytes of Y one sweep over the launches may touch
   int32_t canonical_released;
   size_t device_bytes;
+  // The device arrays above are parts of at most kHybBlobs allocations: [0] the index arrays whose sizes the
+  // bucket totals fix, [1] cols and vals (can be released on their own), [2] the SpMM plan.
+  void* blobs[3];
+  size_t canonical_bytes;  // size of blobs[1]
   sptir_alloc_fn alloc;
   sptir_free_fn free_;
   void* alloc_ctx;
