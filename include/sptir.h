@@ -136,6 +136,8 @@ typedef struct {
   int32_t n_row_blocks;
   int32_t parts_per_launch; /* column partitions one chunk list sweeps */
   int64_t device_bytes;     /* device memory the handle owns */
+  int32_t full_rows;        /* 1: sptir_spmm uses feature tiles of 128 floats where feat and alignment allow */
+  int32_t reserved;
 } sptir_hyb_info_t;
 
 /*
@@ -189,6 +191,11 @@ typedef struct {
                                  (sptir_hyb_build takes it from its histogram); 0: unknown, taken to be short.
                                  Rounds are chosen when it is below 16: Y round trips then cost more than the
                                  wavefronts of a round lose by drifting apart */
+  int32_t full_rows;          /* 0: chosen; 1: a wavefront gathers whole 512-byte runs of a row of X (one feature
+                                 tile of 128 floats, 32 lanes per entry) wherever feat is a multiple of 128 and X, Y
+                                 are 16-byte aligned, instead of one 128-byte line per entry and feature tile with
+                                 the tiles bound to XCDs; 2: never.  Never chosen: it measured slower on every
+                                 workload tried (the option stays so that the comparison can be repeated) */
 } sptir_build_options_t;
 
 sptir_status_t sptir_hyb_build_ex(const sptir_csr_t* csr, int32_t n_col_parts, int32_t max_bucket_log2,
@@ -234,6 +241,7 @@ typedef struct sptir_launch_plan {
   int32_t tiles_per_sweep;   /* feature tiles one sweep over the launches covers */
   int32_t n_sweeps;
   int32_t rounds;            /* 1: the chunk lists run in rounds and Y is written once */
+  int32_t full_rows;         /* 1: feature tiles of 128 floats (see sptir_build_options_t.full_rows) */
 } sptir_launch_plan_t;
 
 sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_slots, int32_t n_col_parts,

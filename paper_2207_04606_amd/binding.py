@@ -54,14 +54,16 @@ class _Info(ctypes.Structure):
                 ("n_heavy_pieces", ctypes.c_int64), ("n_heavy_items", ctypes.c_int64), ("n_heavy_nnz", ctypes.c_int64),
                 ("heavy_len", ctypes.c_int32), ("n_heavy_lists", ctypes.c_int32), ("values_per_row", ctypes.c_int32),
                 ("compact_stream", ctypes.c_int32), ("n_row_blocks", ctypes.c_int32),
-                ("parts_per_launch", ctypes.c_int32), ("device_bytes", ctypes.c_int64)]
+                ("parts_per_launch", ctypes.c_int32), ("device_bytes", ctypes.c_int64),
+                ("full_rows", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class _BuildOptions(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_int32), ("feat_hint", ctypes.c_int32), ("row_block", ctypes.c_int32),
                 ("parts_per_launch", ctypes.c_int32), ("rounds", ctypes.c_int32), ("wide_stream", ctypes.c_int32),
                 ("heavy_len", ctypes.c_int32), ("sweep_kb", ctypes.c_int32), ("release_canonical", ctypes.c_int32),
-                ("no_spmm_plan", ctypes.c_int32), ("keep_values", ctypes.c_int32), ("light_piece_len", ctypes.c_int32)]
+                ("no_spmm_plan", ctypes.c_int32), ("keep_values", ctypes.c_int32), ("light_piece_len", ctypes.c_int32),
+                ("full_rows", ctypes.c_int32)]
 
 
 def _options(options):
@@ -81,7 +83,8 @@ def _options(options):
 class _LaunchPlan(ctypes.Structure):
     _fields_ = [("row_block", ctypes.c_int32), ("parts_per_launch", ctypes.c_int32), ("n_launches", ctypes.c_int32),
                 ("compact_stream", ctypes.c_int32), ("n_feature_tiles", ctypes.c_int32),
-                ("tiles_per_sweep", ctypes.c_int32), ("n_sweeps", ctypes.c_int32), ("rounds", ctypes.c_int32)]
+                ("tiles_per_sweep", ctypes.c_int32), ("n_sweeps", ctypes.c_int32), ("rounds", ctypes.c_int32),
+                ("full_rows", ctypes.c_int32)]
 
 
 class _PlanInfo(ctypes.Structure):

@@ -86,6 +86,7 @@ sptir_status_t sptir_hyb_info(const sptir_hyb_t* h, sptir_hyb_info_t* out) {
   o.values_per_row = h->row_val ? 1 : 0;
   o.compact_stream = h->compact_stream; o.n_row_blocks = h->n_row_blocks; o.parts_per_launch = h->parts_per_phase;
   o.device_bytes = (int64_t)h->device_bytes;
+  o.full_rows = h->full_rows;
   *out = o;
   return SPTIR_OK;
 }
@@ -160,7 +161,7 @@ extern "C" sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int6
   if (opt.feat_hint == 0) opt.feat_hint = feat;
   const sptir::LaunchShape ls = sptir::decide_launch_shape(n_rows, n_cols, n_col_parts, w, stored_slots, opt);
   int vec, lg;
-  sptir::lane_shape(feat, true, true, &vec, &lg);
+  sptir::lane_shape(feat, true, true, ls.full_rows != 0, &vec, &lg);
   const int tile = vec * lg;
   sptir_launch_plan_t o;
   o.row_block = 1 << ls.log2_row_block;
@@ -173,6 +174,7 @@ extern "C" sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int6
                                                          opt.sweep_kb > 0 ? opt.sweep_kb : 160 * 1024);
   o.n_sweeps = (o.n_feature_tiles + o.tiles_per_sweep - 1) / o.tiles_per_sweep;
   o.rounds = ls.rounds;
+  o.full_rows = ls.full_rows;
   *out = o;
   return SPTIR_OK;
 }

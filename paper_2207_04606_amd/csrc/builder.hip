@@ -1109,9 +1109,13 @@ sptir_status_t device_exclusive_scan(int32_t* data, int64_t n, int32_t* seq_base
 }
 size_t scan_room(int64_t n) { return (size_t)((n + kScanSeq - 1) / kScanSeq) * kScanSeq; }
 
-int log2_row_block_setting(int32_t n_rows, bool rounds, const sptir_build_options_t& opt) {
+int log2_row_block_setting(int32_t n_rows, bool rounds, bool full_rows, const sptir_build_options_t& opt) {
   long v = opt.row_block;
-  if (v < 8 || v > 256 || (v & (v - 1))) {
+  if ((v < 8 || v > 256 || (v & (v - 1))) && full_rows) {
+    // 16 rows x 512 bytes: the same 8 KB of LDS per wavefront as 64 rows of a 128-byte tile
+    v = 16;
+    while (v > 8 && n_rows / v < 1024) v >>= 1;
+  } else if (v < 8 || v > 256 || (v & (v - 1))) {
     // A wavefront walks the list of one row block alone and keeps the block's tile of Y in LDS:
     // 64 rows x 128 bytes = 8 KB next to its 4 KB (6 KB) chunk ring allow 12 wavefronts per CU.  Measured on
     // the two large graphs with a launch per partition: 32 rows cost 3 % (more lists, each rounded up to whole
@@ -1188,7 +1192,12 @@ LaunchShape decide_launch_shape(int32_t n_rows, int32_t n_cols, int32_t c, int32
   //  of 37 entries, 1.11 -> 1.39 ms.)
   const bool short_pieces = opt.light_piece_len == 0 || opt.light_piece_len < 16;
   ls.rounds = opt.rounds == 1 ? 1 : opt.rounds == 2 ? 0 : (matter && !parts_given && short_pieces ? 1 : 0);
-  ls.log2_row_block = log2_row_block_setting(n_rows, ls.rounds != 0, opt);
+  // Whole 512-byte runs of X per entry: only when asked for.  Measured at feat = 128 against the 128-byte tiles
+  // bound to XCDs: 7 entries per row 0.108 -> 0.151 ms, 4.5 per row 0.037 -> 0.090 ms, 300 per row
+  // 1.09 -> 1.66 ms.  Two lane groups instead of eight meet every queue four times per chunk, so partial sums go
+  // through LDS at every step, and every XCD's L2 then sees all of X instead of a quarter of it.
+  ls.full_rows = opt.full_rows == 1 ? 1 : 0;
+  ls.log2_row_block = log2_row_block_setting(n_rows, ls.rounds != 0, ls.full_rows != 0, opt);
   if (ls.rounds) ls.parts_per_phase = c;
   else if (parts_given) ls.parts_per_phase = opt.parts_per_launch;
   else ls.parts_per_phase = matter ? (int32_t)fit : c;
@@ -1214,7 +1223,7 @@ extern "C" sptir_status_t sptir_hyb_build_ex(const sptir_csr_t* csr, int32_t n_c
   if (opt.row_block != 0 && (opt.row_block < 8 || opt.row_block > 256 || (opt.row_block & (opt.row_block - 1))))
     return SPTIR_ERR_INVALID_ARG;
   if (opt.parts_per_launch < 0 || opt.rounds < 0 || opt.rounds > 2 || opt.heavy_len < 0 || opt.sweep_kb < 0 ||
-      opt.feat_hint < 0)
+      opt.feat_hint < 0 || opt.full_rows < 0 || opt.full_rows > 2)
     return SPTIR_ERR_INVALID_ARG;
   return sptir::hyb_build_impl(csr, n_col_parts, max_bucket_log2, opt, stream_, out);
 }
@@ -1404,6 +1413,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     cs.ppg = ls.parts_per_phase; cs.log2_rb = ls.log2_row_block; cs.n_phases = ls.n_phases;
     h->compact_stream = ls.compact;
     h->rounds = ls.rounds;
+    h->full_rows = ls.full_rows;
     // Every row has one value for all its entries (a row-normalised adjacency matrix, say): the stream
     // carries no values, the kernels sum rows of X and scale each row of Y once.
     const bool one_value_per_row = value_bits && csr->nnz > 0 && flags[4] == flags[5];

@@ -767,9 +767,9 @@ bool plan_tiles(int64_t n_units, Geometry* g) {
   return g->grid <= 0x7FFFFFFF;
 }
 
-bool plan(int64_t n_units, int feat, const void* X, const void* Y, Geometry* g) {
+bool plan(int64_t n_units, int feat, const void* X, const void* Y, bool full_rows, Geometry* g) {
   uintptr_t align = (uintptr_t)X | (uintptr_t)Y;
-  lane_shape(feat, (align & 15) == 0, (align & 7) == 0, &g->vec, &g->lg);
+  lane_shape(feat, (align & 15) == 0, (align & 7) == 0, full_rows, &g->vec, &g->lg);
   int tf = g->vec * g->lg;
   g->n_tiles = (feat + tf - 1) / tf;
   return plan_tiles(n_units, g);
@@ -798,7 +798,8 @@ void with_flags(bool idx32, bool wide, F&& f) {
 
 template <bool UNIT, typename F>
 void with_shape(int vec, int lg, bool idx32, bool wide, F&& f) {
-  if (vec == 4 && lg == 8) with_flags<4, 8, UNIT>(idx32, wide, f);
+  if (vec == 4 && lg == 32) with_flags<4, 32, UNIT>(idx32, wide, f);
+  else if (vec == 4 && lg == 8) with_flags<4, 8, UNIT>(idx32, wide, f);
   else if (vec == 4) with_flags<4, 4, UNIT>(idx32, wide, f);
   else if (vec == 2) with_flags<2, 16, UNIT>(idx32, wide, f);
   else with_flags<1, 32, UNIT>(idx32, wide, f);
@@ -849,8 +850,9 @@ void launch_heavy(V, const Geometry& g, hipStream_t stream, const HeavyArgs& a) 
 }  // namespace
 
 // 8 lanes x 16 bytes (one 128-byte line of X per lane group) where size and alignment allow
-void lane_shape(int32_t feat, bool aligned16, bool aligned8, int* vec, int* lg) {
-  if (feat % 4 == 0 && aligned16) { *vec = 4; *lg = feat <= 16 ? 4 : 8; }
+void lane_shape(int32_t feat, bool aligned16, bool aligned8, bool full_rows, int* vec, int* lg) {
+  if (full_rows && feat % 128 == 0 && aligned16) { *vec = 4; *lg = 32; }  // 32 lanes x 16 bytes: 512 bytes of a row
+  else if (feat % 4 == 0 && aligned16) { *vec = 4; *lg = feat <= 16 ? 4 : 8; }
   else if (feat % 2 == 0 && aligned8) { *vec = 2; *lg = 16; }
   else { *vec = 1; *lg = 32; }
 }
@@ -911,7 +913,7 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
 
   Geometry g;
   const int64_t n_units = ((int64_t)h->n_row_blocks + kHybWaves - 1) / kHybWaves;
-  if (!plan(n_units, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
+  if (!plan(n_units, feat, X, Y, h->full_rows != 0, &g)) return SPTIR_ERR_OVERFLOW;
   SpmmArgs a;
   a.stream = h->stream;
   a.X = X; a.Y = Y; a.n_rows = h->n_rows; a.n_row_blocks = h->n_row_blocks; a.log2_row_block = h->log2_row_block;
@@ -1098,7 +1100,7 @@ extern "C" sptir_status_t sptir_spmm_csr(const sptir_csr_t* csr, const float* X,
   if (x_bytes && y_bytes && overlaps(X, x_bytes, Y, y_bytes)) return SPTIR_ERR_INVALID_ARG;
   if (csr->n_rows == 0) return SPTIR_OK;
   Geometry g;
-  if (!plan(((int64_t)csr->n_rows + kCsrWaves - 1) / kCsrWaves, feat, X, Y, &g)) return SPTIR_ERR_OVERFLOW;
+  if (!plan(((int64_t)csr->n_rows + kCsrWaves - 1) / kCsrWaves, feat, X, Y, false, &g)) return SPTIR_ERR_OVERFLOW;
   CsrArgs a;
   a.indptr = csr->indptr; a.indices = csr->indices; a.values = csr->values; a.X = X; a.Y = Y;
   a.n_rows = csr->n_rows; a.feat = feat; a.n_tiles = g.n_tiles; a.map_mode = g.map_mode; a.map_param = g.map_param;

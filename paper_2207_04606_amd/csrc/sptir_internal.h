@@ -95,6 +95,7 @@ struct sptir_hyb {
   size_t device_bytes;
   // The device arrays above are parts of at most kHybBlobs allocations: [0] the index arrays whose sizes the
   // bucket totals fix, [1] cols and vals (can be released on their own), [2] the SpMM plan.
+  int32_t full_rows;        // sptir_spmm may use the 128-float tile (the row blocks are sized for it)
   void* blobs[3];
   size_t canonical_bytes;  // size of blobs[1]
   sptir_alloc_fn alloc;
@@ -122,13 +123,14 @@ struct LaunchShape {
   int32_t n_phases;         // chunk-list launches per sweep (1 when rounds)
   int32_t compact;          // 1: 8-byte stream records
   int32_t rounds;           // 1: lists sweep all partitions, launched in rounds
+  int32_t full_rows;        // 1: feature tiles of 128 floats (32 lanes per entry) where feat allows
 };
 LaunchShape decide_launch_shape(int32_t n_rows, int32_t n_cols, int32_t c, int32_t w, int64_t stored_slots,
                                 const sptir_build_options_t& opt);
 
 // Lane geometry sptir_spmm uses for `feat` when X and Y are 16-byte aligned, and the feature tiles one sweep over
 // the launches covers (spmm.hip; host code).
-void lane_shape(int32_t feat, bool aligned16, bool aligned8, int* vec, int* lg);
+void lane_shape(int32_t feat, bool aligned16, bool aligned8, bool full_rows, int* vec, int* lg);
 int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches, int sweep_kb);
 
 // rb_order[launch][i] = the row block with the i-th longest chunk list of that launch (order.hip).  Works on

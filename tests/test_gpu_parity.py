@@ -293,6 +293,7 @@ def test_spmm_on_side_stream_and_repeat(gpu_lib):
     {"wide_stream": 1}, {"parts_per_launch": 1}, {"parts_per_launch": 2, "wide_stream": 1},
     {"row_block": 8}, {"row_block": 64, "parts_per_launch": 3}, {"row_block": 128}, {"row_block": 256},
     {"rounds": 1}, {"rounds": 1, "heavy_len": 64}, {"rounds": 1, "heavy_len": 16, "wide_stream": 1},
+    {"full_rows": 1}, {"full_rows": 1, "rounds": 1, "heavy_len": 30}, {"full_rows": 1, "wide_stream": 1, "row_block": 32},
     {"rounds": 1, "row_block": 16, "heavy_len": 1}, {"rounds": 2, "parts_per_launch": 1, "heavy_len": 100},
     {"rounds": 2, "heavy_len": 5000}, {"release_canonical": 1, "heavy_len": 70}])
 def test_spmm_launch_plan_knobs(gpu_lib, knobs):
@@ -321,6 +322,7 @@ def test_spmm_launch_plan_knobs(gpu_lib, knobs):
             assert info["rounds"] == 1 and info["n_phases"] == 1
         if "row_block" in knobs:
             assert info["row_block"] == knobs["row_block"]
+        assert info["full_rows"] == int(knobs.get("full_rows", 0) == 1)
         if "heavy_len" in knobs:
             assert info["heavy_len"] == knobs["heavy_len"]
             lens = np.diff(w.indptr)   # an upper bound: a heavy piece needs a row longer than heavy_len
@@ -337,7 +339,7 @@ def test_spmm_launch_plan_knobs(gpu_lib, knobs):
 @pytest.mark.parametrize("knobs", [
     {}, {"keep_values": 1}, {"rounds": 1, "heavy_len": 64}, {"rounds": 1, "wide_stream": 1, "heavy_len": 20},
     {"rounds": 2, "parts_per_launch": 1}, {"rounds": 2, "parts_per_launch": 2, "wide_stream": 1, "heavy_len": 300},
-    {"row_block": 256}])
+    {"row_block": 256}, {"full_rows": 1, "heavy_len": 40}])
 def test_spmm_one_value_per_row(gpu_lib, knobs):
     """A matrix whose rows each repeat one value (a row-normalised adjacency matrix) is stored without values in
     the SpMM stream, and the rows of Y are scaled at the end; keep_values turns that off.  Both must meet the

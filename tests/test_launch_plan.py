@@ -24,7 +24,7 @@ def test_largest_configuration_runs_in_rounds():
     # and the lists run in rounds, Y written once
     p = sptir.sptir_launch_plan(feat=128, **SOCIAL)
     assert p == dict(row_block=128, parts_per_launch=16, n_launches=1, compact_stream=1, n_feature_tiles=4,
-                     tiles_per_sweep=4, n_sweeps=1, rounds=1)
+                     tiles_per_sweep=4, n_sweeps=1, rounds=1, full_rows=0)
     # asked for explicitly, the older plan: a launch per partition, each reading back the Y of the one before
     p = sptir.sptir_launch_plan(feat=128, options={"rounds": 2}, **SOCIAL)
     assert (p["row_block"], p["parts_per_launch"], p["n_launches"], p["rounds"]) == (64, 1, 16, 0)
@@ -94,6 +94,20 @@ def test_build_options_steer_the_plan():
     assert (p["rounds"], p["parts_per_launch"], p["n_launches"]) == (1, 4, 1)
     # the feature size hint sizes the row blocks: the query takes it from feat unless told otherwise
     assert sptir.sptir_launch_plan(feat=128, options={"feat_hint": 32}, **SOCIAL)["row_block"] == 32
+
+
+def test_full_rows_are_never_chosen_but_can_be_asked_for():
+    # a wavefront per 512-byte run of a row of X measured slower than 128-byte tiles bound to XCDs on every
+    # workload, low-degree ones included, so no size chooses it
+    for sizes in (SOCIAL, MEDIUM, TINY):
+        assert sptir.sptir_launch_plan(feat=128, **sizes)["full_rows"] == 0
+    p = sptir.sptir_launch_plan(feat=128, options={"full_rows": 1}, **MEDIUM)
+    assert (p["full_rows"], p["row_block"], p["n_feature_tiles"]) == (1, 16, 1)     # 16 rows x 512 B of LDS
+    p = sptir.sptir_launch_plan(feat=256, options={"full_rows": 1}, **MEDIUM)
+    assert (p["full_rows"], p["n_feature_tiles"]) == (1, 2)
+    # the 128-float tile needs feat to be a multiple of 128: otherwise the usual tiles, on the small row blocks
+    p = sptir.sptir_launch_plan(feat=96, options={"full_rows": 1}, **MEDIUM)
+    assert (p["full_rows"], p["row_block"], p["n_feature_tiles"]) == (1, 16, 3)
 
 
 def test_invalid_arguments():
