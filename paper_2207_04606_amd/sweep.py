@@ -72,7 +72,8 @@ def main():
                           "no_hyb_ms": round(csr_ms, 4), "no_hyb_gflops": round(flops / csr_ms / 1e6, 1),
                           "speedup": round(csr_ms / ms, 3), "launches": info["n_phases"],
                           "pad_pct_of_nnz": round(100.0 * info["n_pad_slots"] / max(info["nnz"], 1), 2),
-                          "rem_nnz": info["n_rem_nnz"], "row_block": info["row_block"]}), flush=True)
+                          "rem_nnz": info["n_rem_nnz"], "row_block": info["row_block"], "rounds": info["rounds"],
+                          "heavy_pieces": info["n_heavy_pieces"]}), flush=True)
 
     if args.only in (None, "c"):
         X = torch.from_numpy(rng.standard_normal((w.n_cols, args.feat), dtype=np.float32)).to(dev)
