@@ -192,8 +192,8 @@ typedef struct {
                                  Rounds are chosen when it is below 16: Y round trips then cost more than the
                                  wavefronts of a round lose by drifting apart */
   int32_t full_rows;          /* 0: chosen; 1: a wavefront gathers whole 512-byte runs of a row of X (one feature
-                                 tile of 128 floats, 32 lanes per entry) wherever feat is a multiple of 128 and X, Y
-                                 are 16-byte aligned, instead of one 128-byte line per entry and feature tile with
+                                 tile of 128 floats, 32 lanes per entry) wherever feat is a multiple of 128, X and Y
+                                 are 16-byte aligned and the row block has at most 64 rows, instead of one 128-byte line per entry and feature tile with
                                  the tiles bound to XCDs; 2: never.  Never chosen: it measured slower on every
                                  workload tried (the option stays so that the comparison can be repeated) */
 } sptir_build_options_t;

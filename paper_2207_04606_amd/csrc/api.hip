@@ -161,7 +161,7 @@ extern "C" sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int6
   if (opt.feat_hint == 0) opt.feat_hint = feat;
   const sptir::LaunchShape ls = sptir::decide_launch_shape(n_rows, n_cols, n_col_parts, w, stored_slots, opt);
   int vec, lg;
-  sptir::lane_shape(feat, true, true, ls.full_rows != 0, &vec, &lg);
+  sptir::lane_shape(feat, true, true, ls.full_rows != 0 && sptir::full_rows_fit(ls.log2_row_block), &vec, &lg);
   const int tile = vec * lg;
   sptir_launch_plan_t o;
   o.row_block = 1 << ls.log2_row_block;

@@ -913,7 +913,10 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
 
   Geometry g;
   const int64_t n_units = ((int64_t)h->n_row_blocks + kHybWaves - 1) / kHybWaves;
-  if (!plan(n_units, feat, X, Y, h->full_rows != 0, &g)) return SPTIR_ERR_OVERFLOW;
+  // (512-byte tiles only where a workgroup's Y tiles fit the CU's LDS: a caller who fixes large row blocks and
+  //  asks for full rows gets the 128-byte tiles)
+  static_assert(kHybWaves == 4, "full_rows_fit() counts four wavefronts per workgroup");
+  if (!plan(n_units, feat, X, Y, h->full_rows != 0 && full_rows_fit(h->log2_row_block), &g)) return SPTIR_ERR_OVERFLOW;
   SpmmArgs a;
   a.stream = h->stream;
   a.X = X; a.Y = Y; a.n_rows = h->n_rows; a.n_row_blocks = h->n_row_blocks; a.log2_row_block = h->log2_row_block;

@@ -131,6 +131,11 @@ LaunchShape decide_launch_shape(int32_t n_rows, int32_t n_cols, int32_t c, int32
 // Lane geometry sptir_spmm uses for `feat` when X and Y are 16-byte aligned, and the feature tiles one sweep over
 // the launches covers (spmm.hip; host code).
 void lane_shape(int32_t feat, bool aligned16, bool aligned8, bool full_rows, int* vec, int* lg);
+// 512-byte feature tiles need row blocks whose Y tiles (4 wavefronts x rows x 512 bytes, plus the chunk rings) fit a
+// CU's LDS: up to 64 rows.  With larger row blocks sptir_spmm uses the 128-byte tiles whatever the handle asks for.
+inline bool full_rows_fit(int log2_row_block) {
+  return (size_t)4 * (((size_t)512 << log2_row_block) + 6 * 1024) <= (size_t)159 * 1024;
+}
 int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches, int sweep_kb);
 
 // rb_order[launch][i] = the row block with the i-th longest chunk list of that launch (order.hip).  Works on

@@ -294,6 +294,7 @@ def test_spmm_on_side_stream_and_repeat(gpu_lib):
     {"row_block": 8}, {"row_block": 64, "parts_per_launch": 3}, {"row_block": 128}, {"row_block": 256},
     {"rounds": 1}, {"rounds": 1, "heavy_len": 64}, {"rounds": 1, "heavy_len": 16, "wide_stream": 1},
     {"full_rows": 1}, {"full_rows": 1, "rounds": 1, "heavy_len": 30}, {"full_rows": 1, "wide_stream": 1, "row_block": 32},
+    {"full_rows": 1, "row_block": 64}, {"full_rows": 1, "row_block": 128},
     {"rounds": 1, "row_block": 16, "heavy_len": 1}, {"rounds": 2, "parts_per_launch": 1, "heavy_len": 100},
     {"rounds": 2, "heavy_len": 5000}, {"release_canonical": 1, "heavy_len": 70}])
 def test_spmm_launch_plan_knobs(gpu_lib, knobs):

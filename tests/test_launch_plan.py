@@ -108,6 +108,11 @@ def test_full_rows_are_never_chosen_but_can_be_asked_for():
     # the 128-float tile needs feat to be a multiple of 128: otherwise the usual tiles, on the small row blocks
     p = sptir.sptir_launch_plan(feat=96, options={"full_rows": 1}, **MEDIUM)
     assert (p["full_rows"], p["row_block"], p["n_feature_tiles"]) == (1, 16, 3)
+    # ... and row blocks of at most 64 rows (4 wavefronts x rows x 512 bytes of LDS): beyond that, the usual tiles
+    p = sptir.sptir_launch_plan(feat=128, options={"full_rows": 1, "row_block": 64}, **MEDIUM)
+    assert (p["row_block"], p["n_feature_tiles"]) == (64, 1)
+    p = sptir.sptir_launch_plan(feat=128, options={"full_rows": 1, "row_block": 128}, **MEDIUM)
+    assert (p["row_block"], p["n_feature_tiles"]) == (128, 4)
 
 
 def test_invalid_arguments():
