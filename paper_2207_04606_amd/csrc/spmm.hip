@@ -299,7 +299,9 @@ constexpr int kHybBlock = 64 * kHybWaves;
 //
 // UNIT: the stream holds no values (every row of A has one value for all its entries, which the caller of the
 // walk multiplies in at the end): a real slot counts 1, any other 0.
-template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT, typename Sink>
+//
+// DEPTH: gather steps in flight per wavefront (a step is UB loads per lane; each needs UB * VEC registers).
+template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT, typename Sink, int DEPTH = 2>
 struct HybWalker {
   using S = Shape<VEC, LG>;
   static constexpr int UB = S::kSteps, CS = S::kChunk;
@@ -501,16 +503,16 @@ struct HybWalker {
     __builtin_amdgcn_sched_barrier(0);
     int m_cur[kChunksPerQuad], m_next[kChunksPerQuad];
     park(0, f_first, m_cur);
-    float xa[UB][VEC], xb[UB][VEC];
-    {
+    static_assert(DEPTH >= 2 && DEPTH <= kQuadSteps && kQuadSteps % DEPTH == 0, "steps in flight must divide a quad");
+    float x[DEPTH][UB][VEC];
+#pragma unroll
+    for (int b = 0; b < DEPTH; ++b) {
       int c[UB];
-      read_ints(slot_of(0) + first_slot(0), c);
-      issue(c, xa);
-      read_ints(slot_of(0) + first_slot(1), c);
-      issue(c, xb);
+      read_ints(slot_of(0) + first_slot(b), c);
+      issue(c, x[b]);
     }
-    // one step of quad Q: `x` holds the gathers of step s and is refilled with those of step s+2
-    auto step = [&](int Q, int s, float (&x)[UB][VEC], bool refill) {
+    // one step of quad Q: `xs` holds the gathers of step s and is refilled with those of step s + DEPTH
+    auto step = [&](int Q, int s, float (&xs)[UB][VEC], bool refill) {
       const int* st = slot_of(Q);
       int t[UB];
       float v[UB];
@@ -526,37 +528,34 @@ struct HybWalker {
       }
       int c[UB];
       if (refill) {
-        const int s2 = s + 2;
+        const int s2 = s + DEPTH;
         read_ints((s2 < kQuadSteps ? st : slot_of(Q + 1)) + first_slot(s2 & (kQuadSteps - 1)), c);
       }
-      consume(st, s, m_cur[s / SUB], v, x, t);
-      if (refill) issue(c, x);
+      consume(st, s, m_cur[s / SUB], v, xs, t);
+      if (refill) issue(c, xs);
     };
     int Q = 0;
     for (; Q + 1 < n_quads; ++Q) {
       park(Q + 1, f, m_next);
 #pragma unroll
-      for (int s = 0; s < kQuadSteps; s += 2) {
-        step(Q, s, xa, true);
+      for (int s = 0; s < kQuadSteps; ++s) {
+        step(Q, s, x[s % DEPTH], true);
         // Loads come back in issue order, so the slow request for quad Q+2 (it comes from memory, the gathers
         // from L2) delays whatever is issued after it.  Placed right behind a batch of gathers, the first
-        // loads it can delay are those of the next step, which are not needed before two more steps.
+        // loads it can delay are those of the next step, which are not needed before DEPTH more steps.
         if (s == 0) fetch(Q + 2, f);
-        step(Q, s + 1, xb, true);
       }
 #pragma unroll
       for (int i = 0; i < kChunksPerQuad; ++i) m_cur[i] = m_next[i];
     }
-    // last quad: its steps 0 and 1 are in flight, nothing follows it, and the padding chunks that round the
+    // last quad: its first DEPTH steps are in flight, nothing follows it, and the padding chunks that round the
     // list up to whole quads are neither gathered for nor multiplied
     int n_real = 0;
 #pragma unroll
     for (int i = 0; i < kChunksPerQuad; ++i) n_real += chunk_is_padding(m_cur[i]) ? 0 : SUB;
 #pragma unroll
-    for (int s = 0; s < kQuadSteps; s += 2) {
-      if (s < n_real) step(Q, s, xa, s + 2 < n_real);
-      if (s + 1 < n_real) step(Q, s + 1, xb, s + 3 < n_real);
-    }
+    for (int s = 0; s < kQuadSteps; ++s)
+      if (s < n_real) step(Q, s, x[s % DEPTH], s + DEPTH < n_real);
   }
 };
 
