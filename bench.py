@@ -291,8 +291,8 @@ def main():
         build_times.append((time.perf_counter() - t0) * 1e3)
         hyb2.destroy()
     build_ms = sorted(build_times)[1]
-    # the same with the library's device memory coming from torch's caching allocator (sptir_set_allocator):
-    # the difference is what hipMalloc / hipFree of the handle's arrays and the temporaries cost
+    # the same with the library's device memory coming from torch's caching allocator (sptir_set_allocator): the
+    # difference is what hipMalloc of the handle's arrays costs (temporaries are kept between builds either way)
     sptir.sptir_set_allocator(True)
     try:
         cached_times = []

@@ -151,6 +151,14 @@ typedef void (*sptir_free_fn)(void* ptr, void* ctx);
 sptir_status_t sptir_set_allocator(sptir_alloc_fn alloc, sptir_free_fn free_, void* ctx);
 
 /*
+ * Under the default allocator sptir_hyb_build keeps the temporary device blocks of a call (at most 8 blocks and
+ * 512 MB in all, none larger than 256 MB) for the next call instead of giving them back with hipFree, which costs more
+ * than a whole small build.  This call frees what is being kept.  Handles are not affected.  With an allocator of
+ * the caller's nothing is ever kept.
+ */
+sptir_status_t sptir_release_scratch(void);
+
+/*
  * Format decomposition CSR -> hyb(c,k) on the GPU (Section 4.2.1 bucketing
  * rule; the "copy to the new format" step of Section 3.2.1 done once, as
  * pre-processing).  Runs a validation pass, a per-(row, partition) length

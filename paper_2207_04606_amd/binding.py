@@ -113,7 +113,7 @@ class _SpmmTimes(ctypes.Structure):
                 ("n_reduce_launches", ctypes.c_int32)]
 
 
-EXPORTED_SYMBOLS = ("sptir_spmm_timed", "sptir_roof_gather", "sptir_roof_fma", "sptir_set_allocator", "sptir_hyb_build", "sptir_hyb_build_ex", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
+EXPORTED_SYMBOLS = ("sptir_spmm_timed", "sptir_roof_gather", "sptir_roof_fma", "sptir_set_allocator", "sptir_release_scratch", "sptir_hyb_build", "sptir_hyb_build_ex", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
                     "sptir_spmm_noalloc",
                     "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_sddmm_plan_build", "sptir_sddmm",
                     "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_rgms_build", "sptir_rgms", "sptir_rgms_info",
@@ -461,6 +461,15 @@ def _torch_alloc(nbytes, ctx, stream):
 @_FREE_FN
 def _torch_free(ptr, ctx):
     _torch_blocks.pop(ptr, None)
+
+
+def sptir_release_scratch() -> None:
+    """Frees the temporary device blocks the library keeps between builds under the default allocator."""
+    lib = load_library()
+    lib.sptir_release_scratch.restype = ctypes.c_int
+    st = lib.sptir_release_scratch()
+    if st != SPTIR_OK:
+        raise SptirError(st, "sptir_release_scratch")
 
 
 def sptir_set_allocator(use_torch: bool) -> None:

@@ -1290,7 +1290,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   PinnedPool::Buf pinned = pinned_pool().acquire(host.size);
   if (!pinned.p) return SPTIR_ERR_ALLOC;
   host.base = pinned.p;
-  tmp.base = (char*)alloc(tmp.size, actx, stream);
+  tmp.base = (char*)scratch_alloc(tmp.size, alloc, actx, stream);
   if (!tmp.base) { pinned_pool().release(pinned); return SPTIR_ERR_ALLOC; }
   Blob tmp2;
   void* tmp_chunks = nullptr;
@@ -1298,7 +1298,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   void* tmp_order = nullptr;
 
   sptir_hyb* h = new (std::nothrow) sptir_hyb();
-  if (!h) { free_(tmp.base, actx); pinned_pool().release(pinned); return SPTIR_ERR_ALLOC; }
+  if (!h) { scratch_free(tmp.base, free_, actx); pinned_pool().release(pinned); return SPTIR_ERR_ALLOC; }
   memset(h, 0, sizeof(*h));
   h->alloc = alloc; h->free_ = free_; h->alloc_ctx = actx;
   h->n_rows = s.n_rows; h->n_cols = s.n_cols; h->c = s.c; h->k = s.k; h->w = s.w;
@@ -1443,7 +1443,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     const size_t o_piece_of = tmp2.reserve(sizeof(int32_t) * (want_heavy ? (size_t)s.c * (size_t)s.n_rows : 1));
     const size_t o_seq_base = tmp2.reserve(sizeof(int32_t) * 2 * (scan_room(std::max<int64_t>(n_pieces + 1, s.n_rows + 1)) / kScanSeq + 2));
     const size_t o_row_flags = tmp2.reserve(sizeof(int32_t) * (want_heavy ? scan_room((int64_t)s.n_rows + 1) : 1));
-    tmp2.base = (char*)alloc(tmp2.size, actx, stream);
+    tmp2.base = (char*)scratch_alloc(tmp2.size, alloc, actx, stream);
     if (!tmp2.base) { st = SPTIR_ERR_ALLOC; goto fail; }
     int32_t* d_bounds = (int32_t*)(tmp2.base + o_bounds);
     long long* d_cell_chunks = (long long*)(tmp2.base + o_cell_chunks);
@@ -1566,7 +1566,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     // (the GPU is busy: the allocations whose sizes are known come now)
     if (with_spmm_plan) {
       const size_t bytes = sizeof(PiecePlace) * (size_t)(n_pieces ? n_pieces : 1);
-      tmp_place = alloc(bytes, actx, stream);
+      tmp_place = scratch_alloc(bytes, alloc, actx, stream);
       if (!tmp_place) { st = SPTIR_ERR_ALLOC; goto fail; }
       BUILD_HIP(hipMemsetAsync(tmp_place, 0, bytes, stream));  // len 0: not queued
     }
@@ -1620,7 +1620,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       const size_t t_end = bt.reserve(heavy ? sizeof(int32_t) * (size_t)n_units : 0);
       const size_t t_quad = bt.reserve(heavy ? sizeof(int32_t) * (size_t)(n_heavy_chunks / kChunksPerQuad + 1) : 0);
       h->blobs[2] = alloc(bc.size, actx, stream);
-      tmp_chunks = alloc(bt.size, actx, stream);
+      tmp_chunks = scratch_alloc(bt.size, alloc, actx, stream);
       if (!h->blobs[2] || !tmp_chunks) { st = SPTIR_ERR_ALLOC; goto fail; }
       h->device_bytes += bc.size;
       char* c0 = (char*)h->blobs[2];
@@ -1712,22 +1712,22 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       h->canonical_released = 1;
     }
   }
-  free_(tmp.base, actx);
-  if (tmp2.base) free_(tmp2.base, actx);
-  if (tmp_chunks) free_(tmp_chunks, actx);
-  if (tmp_place) free_(tmp_place, actx);
-  if (tmp_order) free_(tmp_order, actx);
+  scratch_free(tmp.base, free_, actx);
+  scratch_free(tmp2.base, free_, actx);
+  scratch_free(tmp_chunks, free_, actx);
+  scratch_free(tmp_place, free_, actx);
+  scratch_free(tmp_order, free_, actx);
   pinned_pool().release(pinned);
   *out = h;
   return SPTIR_OK;
 
 fail:
   (void)hipStreamSynchronize(stream);
-  free_(tmp.base, actx);
-  if (tmp2.base) free_(tmp2.base, actx);
-  if (tmp_chunks) free_(tmp_chunks, actx);
-  if (tmp_place) free_(tmp_place, actx);
-  if (tmp_order) free_(tmp_order, actx);
+  scratch_free(tmp.base, free_, actx);
+  scratch_free(tmp2.base, free_, actx);
+  scratch_free(tmp_chunks, free_, actx);
+  scratch_free(tmp_place, free_, actx);
+  scratch_free(tmp_order, free_, actx);
   pinned_pool().release(pinned);
   sptir_hyb_destroy(h);
   return st;

@@ -110,9 +110,9 @@ sptir_status_t order_row_blocks(const int64_t* rb_chunk_ptr, int32_t n_launches,
   const size_t key_bytes = (sizeof(uint32_t) * (size_t)n + 255) & ~(size_t)255;
   const size_t hist_bytes = (sizeof(int32_t) * (size_t)n_hist + 255) & ~(size_t)255;
   const size_t tot_bytes = (sizeof(int32_t) * (size_t)n_launches + 255) & ~(size_t)255;
-  char* scratch = (char*)alloc(3 * key_bytes + hist_bytes + tot_bytes, actx, stream);
+  char* scratch = (char*)scratch_alloc(3 * key_bytes + hist_bytes + tot_bytes, alloc, actx, stream);
   if (!scratch) return SPTIR_ERR_ALLOC;
-  *scratch_out = scratch;  // the caller frees it once the stream has drained
+  *scratch_out = scratch;  // the caller gives it back (scratch_free) once the stream has drained
   uint32_t* keys[2] = {(uint32_t*)scratch, (uint32_t*)(scratch + key_bytes)};
   int32_t* other_vals = (int32_t*)(scratch + 2 * key_bytes);
   int32_t* hist = (int32_t*)(scratch + 3 * key_bytes);

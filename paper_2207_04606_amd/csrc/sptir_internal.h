@@ -108,6 +108,10 @@ namespace sptir {
 // allocator currently installed (api.hip)
 void current_allocator(sptir_alloc_fn* a, sptir_free_fn* f, void** ctx);
 void* default_alloc(size_t bytes, void* ctx, void* stream);
+// Temporaries of a call: from `alloc`, or, when that is the default allocator, from a small cache of blocks that
+// earlier calls have released (api.hip).  scratch_free takes back what scratch_alloc gave.
+void* scratch_alloc(size_t bytes, sptir_alloc_fn alloc, void* actx, void* stream);
+void scratch_free(void* p, sptir_free_fn free_, void* actx);
 void default_free(void* p, void* ctx);
 
 // sptir_hyb_build_ex; `opt` is complete (defaults filled in by the caller)

@@ -111,6 +111,29 @@ def test_hyb_build_through_torch_allocator(gpu_lib):
         gpu_lib.sptir_set_allocator(False)
 
 
+def test_scratch_blocks_are_kept_and_released(gpu_lib):
+    """Under the default allocator the temporaries of a build are kept for the next one: repeated builds (the same
+    sizes, then larger and smaller ones) stay bit-exact, and sptir_release_scratch gives the blocks back (free device
+    memory does not shrink over the sequence)."""
+    gpu_lib.sptir_release_scratch()
+    free0, _ = torch.cuda.mem_get_info()
+    for n_rows, c, k in ((3000, 4, 5), (3000, 4, 5), (9000, 7, 3), (500, 2, 8), (3000, 4, 5)):
+        w = ragged_workload(n_rows, n_rows, n_rows + 100, 8, max_deg=400, long_rows=3)
+        d, hyb, got, want, info = build_both(gpu_lib, w, c, k)
+        assert_same_hyb(got, want)
+        Y = torch.empty(w.n_rows, 8, device="cuda")
+        gpu_lib.sptir_spmm(hyb, d.X, Y)
+        Yr, Sr = oracle.spmm_csr(w.n_rows, w.indptr, w.indices, w.values, w.X)
+        assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"repeated build {n_rows}")
+        hyb.destroy()
+        del d, Y
+    torch.cuda.synchronize()
+    gpu_lib.sptir_release_scratch()
+    torch.cuda.empty_cache()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free1 >= free0 - (64 << 20), f"device memory not given back: {free0} -> {free1}"
+
+
 def test_torch_allocator_on_a_side_stream(gpu_lib):
     """Build, SpMM and destroy on a side stream with the library's memory coming from torch's allocator, while the
     default stream keeps allocating, filling and freeing blocks of the sizes in play: blocks the library took
