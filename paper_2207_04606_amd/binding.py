@@ -55,7 +55,7 @@ class _Info(ctypes.Structure):
                 ("heavy_len", ctypes.c_int32), ("n_heavy_lists", ctypes.c_int32), ("values_per_row", ctypes.c_int32),
                 ("compact_stream", ctypes.c_int32), ("n_row_blocks", ctypes.c_int32),
                 ("parts_per_launch", ctypes.c_int32), ("device_bytes", ctypes.c_int64),
-                ("full_rows", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("full_rows", ctypes.c_int32), ("heavy_list_items", ctypes.c_int32)]
 
 
 class _BuildOptions(ctypes.Structure):

@@ -170,6 +170,7 @@ sptir_status_t sptir_hyb_info(const sptir_hyb_t* h, sptir_hyb_info_t* out) {
   o.compact_stream = h->compact_stream; o.n_row_blocks = h->n_row_blocks; o.parts_per_launch = h->parts_per_phase;
   o.device_bytes = (int64_t)h->device_bytes;
   o.full_rows = h->full_rows;
+  o.heavy_list_items = h->heavy_list_chunks;
   *out = o;
   return SPTIR_OK;
 }

@@ -971,11 +971,11 @@ __global__ __launch_bounds__(256) void k_pack_heavy(int64_t n_heavy_chunks, int6
 // Heavy list w covers the chunks [w*L, (w+1)*L) of the heavy sequence.  A wavefront writes a partial-sum row at
 // every piece end and one more where its list ends, so its first write goes to row (pieces that end before
 // chunk w*L) + w.
-__global__ void k_heavy_list_slots(int32_t n_lists, int32_t n_units, const int32_t* __restrict__ unit_end,
-                                   int32_t* hlist_first_slot) {
+__global__ void k_heavy_list_slots(int32_t n_lists, int32_t list_chunks, int32_t n_units,
+                                   const int32_t* __restrict__ unit_end, int32_t* hlist_first_slot) {
   const int w = blockIdx.x * blockDim.x + threadIdx.x;
   if (w >= n_lists) return;
-  const int64_t x = (int64_t)w * kHeavyListChunks * kChunkSlots;
+  const int64_t x = (int64_t)w * list_chunks * kChunkSlots;
   int lo = 0, hi = n_units;  // first unit whose real entries end beyond slot x
   while (lo < hi) {
     const int mid = lo + ((hi - lo) >> 1);
@@ -986,15 +986,16 @@ __global__ void k_heavy_list_slots(int32_t n_lists, int32_t n_units, const int32
 
 // The partial-sum rows of heavy piece number u whose real entries are the slots [e0, e1) of the heavy sequence:
 // rows u + w for every heavy list w that holds one of them (see k_heavy_list_slots).
-__device__ __forceinline__ void piece_slots(int u, int e0, int e1, int* first, int* count) {
-  const int per_list = kHeavyListChunks * kChunkSlots;
+__device__ __forceinline__ void piece_slots(int list_chunks, int u, int e0, int e1, int* first, int* count) {
+  const int per_list = list_chunks * kChunkSlots;
   const int w0 = e0 / per_list, w1 = (e1 - 1) / per_list;
   *first = u + w0;
   *count = w1 - w0 + 1;
 }
 
 // One thread per row: how many partial-sum rows the heavy pieces of the row have (row_slot_ptr before its scan)
-__global__ void k_row_slot_counts(int32_t n_rows, int32_t c, const int32_t* __restrict__ piece_of,
+__global__ void k_row_slot_counts(int32_t n_rows, int32_t c, int32_t list_chunks,
+                                  const int32_t* __restrict__ piece_of,
                                   const int32_t* __restrict__ row_len, const int32_t* __restrict__ unit_before,
                                   const int32_t* __restrict__ hent_before, int32_t* row_slot_ptr) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1005,14 +1006,15 @@ __global__ void k_row_slot_counts(int32_t n_rows, int32_t c, const int32_t* __re
       const int32_t q = piece_of[(int64_t)p * n_rows + r];
       if (q < 0 || unit_before[q + 1] == unit_before[q]) continue;
       int first, count;
-      piece_slots(unit_before[q], hent_before[q], hent_before[q] + row_len[q], &first, &count);
+      piece_slots(list_chunks, unit_before[q], hent_before[q], hent_before[q] + row_len[q], &first, &count);
       n += count;
     }
   }
   row_slot_ptr[r] = n;
 }
 
-__global__ void k_row_slot_fill(int32_t n_rows, int32_t c, const int32_t* __restrict__ piece_of,
+__global__ void k_row_slot_fill(int32_t n_rows, int32_t c, int32_t list_chunks,
+                                const int32_t* __restrict__ piece_of,
                                 const int32_t* __restrict__ row_len, const int32_t* __restrict__ unit_before,
                                 const int32_t* __restrict__ hent_before, const int32_t* __restrict__ row_slot_ptr,
                                 int32_t* row_slots) {
@@ -1023,7 +1025,7 @@ __global__ void k_row_slot_fill(int32_t n_rows, int32_t c, const int32_t* __rest
     const int32_t q = piece_of[(int64_t)p * n_rows + r];
     if (q < 0 || unit_before[q + 1] == unit_before[q]) continue;
     int first, count;
-    piece_slots(unit_before[q], hent_before[q], hent_before[q] + row_len[q], &first, &count);
+    piece_slots(list_chunks, unit_before[q], hent_before[q], hent_before[q] + row_len[q], &first, &count);
     for (int i = 0; i < count; ++i) *out++ = first + i;
   }
 }
@@ -1582,7 +1584,12 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     h->n_heavy = report2[2];
     h->heavy_chunk0 = n_chunks;
     h->n_heavy_chunks = n_heavy_chunks;
-    h->n_heavy_lists = (int32_t)((n_heavy_chunks + kHeavyListChunks - 1) / kHeavyListChunks);
+    // Chunks per heavy list: 32 where that still gives thousands of lists; a graph with few heavy chunks gets
+    // shorter lists, or its heavy launch would be a handful of wavefronts walking 32 chunks each while the GPU idles.
+    int32_t list_chunks = kHeavyListChunks;
+    while (list_chunks > kChunksPerQuad && n_heavy_chunks / list_chunks < 4096) list_chunks /= 2;
+    h->heavy_list_chunks = list_chunks;
+    h->n_heavy_lists = (int32_t)((n_heavy_chunks + list_chunks - 1) / list_chunks);
     h->n_partial_rows = h->n_heavy + h->n_heavy_lists;
     if (h->n_heavy > 0) {
       h->n_heavy_segs = 2 * s.c;
@@ -1592,7 +1599,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       for (int32_t i = 0; i <= h->n_heavy_segs; ++i)
         h->hseg_list[i] = i == h->n_heavy_segs
                               ? h->n_heavy_lists
-                              : (int32_t)((report2[5 + i] / kChunkSlots + kHeavyListChunks - 1) / kHeavyListChunks);
+                              : (int32_t)((report2[5 + i] / kChunkSlots + list_chunks - 1) / list_chunks);
     } else {
       h->row_slot_ptr = nullptr;  // (its room in the first allocation stays unused)
     }
@@ -1643,9 +1650,9 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
                          h->row_len, d_unit, d_hent, B, s.k, h->R, h->S, h->bucket_row_ptr, h->bucket_slot_ptr,
                          h->rem_ptr, cs.long_len, unit_start, unit_end, unit_slot0, quad_unit);
       hipLaunchKernelGGL(k_heavy_list_slots, dim3((unsigned)((h->n_heavy_lists + 255) / 256)), dim3(256), 0, stream,
-                         h->n_heavy_lists, n_units, unit_end, h->hlist_first_slot);
+                         h->n_heavy_lists, list_chunks, n_units, unit_end, h->hlist_first_slot);
       hipLaunchKernelGGL(k_row_slot_counts, dim3((unsigned)((s.n_rows + 256) / 256)), dim3(256), 0, stream, s.n_rows,
-                         s.c, d_piece_of, h->row_len, d_unit, d_hent, h->row_slot_ptr);
+                         s.c, list_chunks, d_piece_of, h->row_len, d_unit, d_hent, h->row_slot_ptr);
       BUILD_HIP(hipGetLastError());
       st = device_exclusive_scan(h->row_slot_ptr, (int64_t)s.n_rows + 1, d_seq_base, stream);
       if (st != SPTIR_OK) goto fail;
@@ -1656,7 +1663,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
       st = device_exclusive_scan(d_row_flags, (int64_t)s.n_rows + 1, d_seq_base, stream);
       if (st != SPTIR_OK) goto fail;
       hipLaunchKernelGGL(k_row_slot_fill, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
-                         s.c, d_piece_of, h->row_len, d_unit, d_hent, h->row_slot_ptr, h->row_slots);
+                         s.c, list_chunks, d_piece_of, h->row_len, d_unit, d_hent, h->row_slot_ptr, h->row_slots);
       hipLaunchKernelGGL(k_heavy_row_fill, dim3((unsigned)((s.n_rows + 255) / 256)), dim3(256), 0, stream, s.n_rows,
                          h->row_slot_ptr, d_row_flags, h->heavy_rows);
       hipLaunchKernelGGL(k_pick2, dim3(1), dim3(64), 0, stream, h->row_slot_ptr + s.n_rows,

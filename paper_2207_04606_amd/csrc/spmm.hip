@@ -629,6 +629,7 @@ struct HeavyArgs {
   int64_t n_chunks;            // heavy chunks (a multiple of kChunksPerQuad)
   int32_t list0;               // this launch sums lists list0 .. list0 + n_lists - 1
   int32_t n_lists;
+  int32_t list_chunks;         // chunks per list
   int32_t feat;
   int32_t feat0;               // first feature of this sweep (partial-sum rows hold kPartialFeat features)
   int32_t n_tiles;             // feature tiles of this sweep
@@ -636,7 +637,7 @@ struct HeavyArgs {
   int32_t map_param;
 };
 
-// One wavefront per (heavy list, feature tile): the list's kHeavyListChunks chunks are walked like any other
+// One wavefront per (heavy list, feature tile): the list's chunks (list_chunks of them) are walked like any other
 // list, but a finished piece goes to the next partial-sum row instead of an LDS tile, and so does, at the end,
 // what has been summed of the piece the list stops in (zeros if it stops at a piece end: every wavefront takes
 // that row, so that the row numbers follow from counting alone).
@@ -657,9 +658,9 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_heavy(HeavyArgs a) {
   const int f0 = a.feat0 + f_in_sweep;
   const bool f_active = f0 < a.feat;
   int* ring = reinterpret_cast<int*>(smem) + wave * W::kRingInts;
-  const int64_t c0 = list * kHeavyListChunks;
+  const int64_t c0 = list * a.list_chunks;
   const int64_t left = a.n_chunks - c0;
-  const int n_list = (int)(left < kHeavyListChunks ? left : kHeavyListChunks);
+  const int n_list = (int)(left < a.list_chunks ? left : a.list_chunks);
   const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
   W wk{a.X, a.stream + (size_t)(a.chunk0 + c0) * (W::kArrays * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
        (unsigned)a.feat * 4u, (unsigned)f_read * 4u,
@@ -669,30 +670,64 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_heavy(HeavyArgs a) {
   wk.sink(0, g == 0, wk.acc);
 }
 
-// Y[r, feat0 + f] += (row_val[r] *) the partial sums of row r's heavy pieces, in the order of row_slots (partition by partition):
-// one thread per (row with heavy pieces, VEC features).  Runs after the chunk-list launches have written Y.
-template <int VEC>
+// Y[r, feat0 + f] += (row_val[r] *) the partial sums of row r's heavy pieces.  SPLIT groups of (width / VEC) threads per
+// row with heavy pieces: group p takes the partial-sum rows number p, p + SPLIT, .. of the row's list (four loads in
+// flight, four running sums), the groups' sums meet in LDS and the first group adds them in group order: a fixed
+// order of additions whatever the launch, so the result is reproducible.  SPLIT = 8 serves matrices with few, long
+// heavy rows (a row of 13,000 entries cut into lists of 4 chunks has 50 partial sums), SPLIT = 1 the others.
+// Runs after the chunk-list launches have written Y.
+template <int VEC, int SPLIT>
 __global__ __launch_bounds__(256) void k_heavy_reduce(const int32_t* __restrict__ heavy_rows,
                                                       const int32_t* __restrict__ row_slot_ptr,
                                                       const int32_t* __restrict__ row_slots,
                                                       const float* __restrict__ partial,
                                                       const float* __restrict__ row_val, float* Y, int32_t n_rows,
                                                       int32_t feat, int32_t feat0, int32_t width) {
+  __shared__ float part_sum[SPLIT > 1 ? 256 * VEC : 1];
   const int per_row = width / VEC;
-  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t / per_row >= n_rows) return;  // (n_rows: rows with heavy pieces)
-  const int64_t r = heavy_rows[t / per_row];
-  const int f = (int)(t % per_row) * VEC;
-  const int b = row_slot_ptr[r], e = row_slot_ptr[r + 1];
+  const int group = per_row * SPLIT;    // threads per row (at most 256: per_row <= 32 when SPLIT > 1)
+  const int rows_per_wg = 256 / group;
+  const int local = threadIdx.x;
+  const int row_in_wg = local / group, part = (local % group) / per_row, f = (local % per_row) * VEC;
+  const int64_t row_idx = (int64_t)blockIdx.x * rows_per_wg + row_in_wg;  // (among the rows with heavy pieces)
+  const bool active = row_in_wg < rows_per_wg && row_idx < n_rows;
   float sum[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) sum[i] = 0.f;
-  for (int j = b; j < e; ++j) {
-    float v[VEC];
-    load_vec<VEC>(v, partial + (size_t)row_slots[j] * kPartialFeat + f);
+  int64_t r = 0;
+  if (active) {
+    r = heavy_rows[row_idx];
+    const int b = row_slot_ptr[r], e = row_slot_ptr[r + 1];
+    float acc[4][VEC];
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) sum[i] += v[i];
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[u][i] = 0.f;
+    for (int j = b + part; j < e; j += 4 * SPLIT) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int jj = j + u * SPLIT;
+        if (jj < e) {
+          float v[VEC];
+          load_vec<VEC>(v, partial + (size_t)row_slots[jj] * kPartialFeat + f);
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) acc[u][i] += v[i];
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) sum[i] = (acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i]);
   }
+  if constexpr (SPLIT > 1) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) part_sum[local * VEC + i] = sum[i];
+    __syncthreads();
+    if (active && part == 0)
+      for (int p = 1; p < SPLIT; ++p)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) sum[i] += part_sum[(local + p * per_row) * VEC + i];
+  }
+  if (!active || part != 0) return;
   const float scale = row_val ? row_val[r] : 1.f;  // (the heavy lists of a value-less stream sum rows of X only)
   float* y = Y + (size_t)r * (size_t)feat + feat0 + f;
   float out[VEC];
@@ -977,7 +1012,7 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
     const bool y_vec4 = feat % 4 == 0 && ((uintptr_t)Y & 15) == 0;
     HeavyArgs ha;
     ha.stream = h->stream; ha.first_slot = h->hlist_first_slot; ha.X = X; ha.partial = partial;
-    ha.chunk0 = h->heavy_chunk0; ha.n_chunks = h->n_heavy_chunks; ha.feat = feat;
+    ha.chunk0 = h->heavy_chunk0; ha.n_chunks = h->n_heavy_chunks; ha.feat = feat; ha.list_chunks = h->heavy_list_chunks;
     for (int feat0 = 0; feat0 < feat; feat0 += kPartialFeat) {
       const int width = feat - feat0 < kPartialFeat ? feat - feat0 : kPartialFeat;
       Geometry gh = g;
@@ -1001,15 +1036,20 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
         first = end;
       }
       if (timers) timers->mark(stream, LaunchTimers::kHeavy, n_heavy_launches);
-      const int64_t n_threads = (int64_t)h->n_heavy_rows * (width / (y_vec4 ? 4 : 1));
-      const dim3 grid((unsigned)((n_threads + 255) / 256)), block(256);
-      if ((n_threads + 255) / 256 > 0x7FFFFFFF) return SPTIR_ERR_OVERFLOW;
-      if (y_vec4)
-        hipLaunchKernelGGL(k_heavy_reduce<4>, grid, block, 0, stream, h->heavy_rows, h->row_slot_ptr, h->row_slots,
-                           partial, h->row_val, Y, h->n_heavy_rows, feat, feat0, width);
-      else
-        hipLaunchKernelGGL(k_heavy_reduce<1>, grid, block, 0, stream, h->heavy_rows, h->row_slot_ptr, h->row_slots,
-                           partial, h->row_val, Y, h->n_heavy_rows, feat, feat0, width);
+      const int per_row = width / (y_vec4 ? 4 : 1);
+      // few rows with heavy pieces: eight groups of threads share a row's partial sums
+      const int split = (y_vec4 && (int64_t)h->n_heavy_rows * per_row < 32768) ? 8 : 1;
+      const int rows_per_wg = 256 / (per_row * split);
+      const int64_t n_wg = ((int64_t)h->n_heavy_rows + rows_per_wg - 1) / rows_per_wg;
+      if (n_wg > 0x7FFFFFFF) return SPTIR_ERR_OVERFLOW;
+      const dim3 grid((unsigned)n_wg), block(256);
+      auto reduce = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, h->heavy_rows, h->row_slot_ptr, h->row_slots, partial,
+                           h->row_val, Y, h->n_heavy_rows, feat, feat0, width);
+      };
+      if (!y_vec4) reduce(k_heavy_reduce<1, 1>);
+      else if (split == 8) reduce(k_heavy_reduce<4, 8>);
+      else reduce(k_heavy_reduce<4, 1>);
       if (timers) timers->mark(stream, LaunchTimers::kReduce, 1);
     }
   }

@@ -34,7 +34,8 @@ constexpr int kBuildBlock = 256;  // rows per workgroup in the builder kernels
 // a wavefront each, which write one partial sum per finished piece plus one for whatever piece is unfinished where
 // the list ends.  A last launch adds a row's partial sums to Y in a fixed order.
 constexpr int kHeavyLenMax = 2048;      // largest threshold the size rules choose
-constexpr int kHeavyListChunks = 32;    // chunks per heavy list (a multiple of kChunksPerQuad; 16 and 64 measure the same)
+constexpr int kHeavyListChunks = 32;    // most chunks per heavy list (a multiple of kChunksPerQuad; on the largest graph 16
+                                        // and 64 measure the same; graphs with few heavy chunks get shorter lists)
 constexpr int kPartialFeat = 128;       // features per partial sum row: wider Y is produced in sweeps of this many
 // Compact stream records spend 8 bytes per slot instead of 12: one word holds the column relative to the first
 // column of the launch (bits 0..19), the row relative to the row block (20..26), "slot is real" (27), the chunk's
@@ -95,6 +96,7 @@ struct sptir_hyb {
   size_t device_bytes;
   // The device arrays above are parts of at most kHybBlobs allocations: [0] the index arrays whose sizes the
   // bucket totals fix, [1] cols and vals (can be released on their own), [2] the SpMM plan.
+  int32_t heavy_list_chunks;  // chunks per heavy list of this handle: 4, 8, 16 or 32
   int32_t full_rows;        // sptir_spmm may use the 128-float tile (the row blocks are sized for it)
   void* blobs[3];
   size_t canonical_bytes;  // size of blobs[1]

@@ -139,7 +139,8 @@ def decode(sptir, hyb, info, w):
         written = np.zeros(n_partial, dtype=bool)
         for wl in range(info["n_heavy_lists"]):
             cur = int(first_slot[wl])
-            for k in range(base + 32 * wl, min(base + 32 * (wl + 1), base + info["n_heavy_items"])):
+            per_list = info["heavy_list_items"]
+            for k in range(base + per_list * wl, min(base + per_list * (wl + 1), base + info["n_heavy_items"])):
                 kind, hand, real, cf, rf, flag, vb = st.chunk(k)
                 if kind == 0:
                     continue
