@@ -76,12 +76,14 @@ struct Shape {
   static constexpr int kLog2Chunk = ilog2(kChunk);
 };
 
-// LDS position of the VEC floats lane fl of a group owns in local row r of the wavefront's Y tile.  Rows are
-// rotated against each other by one lane's share, so that lane groups working on neighbouring rows
-// (the lane groups of a queue chunk may hand eight rows over at once) hit different banks.
+// LDS position of the VEC floats lane fl of a group owns in local row r of the wavefront's Y tile.  A row of 32
+// floats or more spans all 32 banks, so the lane groups of one instruction (eight may hand eight rows over at once)
+// cannot collide and the tile is stored plainly; narrower rows (16 floats: feat <= 16) are rotated against each
+// other by one lane's share, so that lane groups working on neighbouring rows hit different banks.
 template <int VEC, int LG>
 __device__ __forceinline__ int tile_index(int r, int fl) {
-  return (r * LG + ((fl + r) & (LG - 1))) * VEC;
+  if constexpr (VEC * LG >= 32) return (r * LG + fl) * VEC;
+  else return (r * LG + ((fl + r) & (LG - 1))) * VEC;
 }
 
 // Adds a finished row sum into the wavefront's Y tile; r is the row relative to the row block.  The tile is
@@ -520,7 +522,8 @@ struct HybWalker {
       if constexpr (UNIT) {
         read_ints(st + (WIDE ? kRowArray * kQuadSlots : 0) + first_slot(s), t);
 #pragma unroll
-        for (int j = 0; j < UB; ++j) v[j] = row_valid(t[j]) ? 1.f : 0.f;
+        // (compact: bit 27 says "entry"; as a float, 1 or 0)
+        for (int j = 0; j < UB; ++j) v[j] = WIDE ? (row_valid(t[j]) ? 1.f : 0.f) : (float)(((unsigned)t[j] >> 27) & 1u);
       } else {
         read_ints(st + kQuadSlots + first_slot(s), t);
 #pragma unroll
