@@ -137,7 +137,7 @@ typedef struct {
   int32_t parts_per_launch; /* column partitions one chunk list sweeps */
   int64_t device_bytes;     /* device memory the handle owns */
   int32_t full_rows;        /* 1: sptir_spmm uses feature tiles of 128 floats where feat and alignment allow */
-  int32_t heavy_list_items; /* chunks per heavy list (32, fewer when the matrix has few heavy chunks) */
+  int32_t heavy_list_items; /* chunks per heavy list (16, fewer when the matrix has few heavy chunks) */
 } sptir_hyb_info_t;
 
 /*

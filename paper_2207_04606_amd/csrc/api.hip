@@ -145,7 +145,6 @@ sptir_status_t sptir_hyb_destroy(sptir_hyb_t* h) {
   if (!h) return SPTIR_OK;
   for (void* p : h->blobs)
     if (p) h->free_(p, h->alloc_ctx);
-  free(h->hseg_list);
   delete h;
   return SPTIR_OK;
 }

@@ -822,25 +822,24 @@ constexpr int kScanSeq = 4096;  // elements per sequence of the device-wide scan
 // What the host needs to know before it can size the stream, in one array: report[0] = chunks of all lists,
 // [1] = entries of heavy pieces (the sum of the counters k_heavy_counts added to; the longest list is the maximum
 // of the counters next to them), [2] = heavy pieces, [3] = slots of the heavy sequence, [4] = chunks of the longest
-// list, [5 + i] = slots of the heavy sequence before the pieces of segment i (seg_at[i]: its first piece).
+// list.
+constexpr int kReport2 = 5;
 __global__ void k_report(const long long* totals, const long long* heavy_nnz_slots, const int32_t* unit_before,
-                         const int32_t* hent_before,
-                         int64_t n_pieces, int32_t n_segs, const int64_t* __restrict__ seg_at, long long* report) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= 5 + n_segs) return;
+                         const int32_t* hent_before, int64_t n_pieces, long long* report) {
+  const int i = threadIdx.x;
+  if (i >= kReport2) return;
   long long v;
   if (i == 0) v = totals[0];
   else if (i == 1) { v = 0; for (int slot = 0; slot < kFlagSlots; ++slot) v += heavy_nnz_slots[slot * kFlagStride]; }
   else if (i == 2) v = unit_before ? unit_before[n_pieces] : 0;
   else if (i == 3) v = hent_before ? hent_before[n_pieces] : 0;
-  else if (i == 4) {
+  else {
     v = 0;
     for (int slot = 0; slot < kFlagSlots; ++slot) {
       const long long o = heavy_nnz_slots[slot * kFlagStride + 1];
       v = o > v ? o : v;
     }
   }
-  else v = hent_before ? hent_before[seg_at[i - 5]] : 0;
   report[i] = v;
 }
 
@@ -1257,7 +1256,6 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   // ---- temporary storage: one device blob now, a second one once the cell count is known; one pinned host block
   // for everything that crosses to or from the host (pageable memory would make every small copy a blocking one)
   const size_t nbk = (size_t)(s.NB ? s.NB : 1);
-  const size_t n_segs = 2 * (size_t)s.c + 1;  // heavy segments: the ELL pieces of each partition, then its remainder pieces
   Blob tmp;
   // (flags, tot_rnnz and tot_bins lie next to each other: one copy brings them to the host)
   const size_t o_flags = tmp.size;
@@ -1270,10 +1268,9 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   const size_t o_rnnz = tmp.reserve(sizeof(int64_t) * (size_t)s.c * nbk);
   const size_t o_rnnz_base = tmp.reserve(sizeof(int64_t) * (size_t)s.c);
   const size_t o_bound = tmp.reserve(sizeof(int32_t) * (size_t)(s.c - 1) * (size_t)(s.n_rows ? s.n_rows : 1) + 16);
-  const size_t o_seg_at = tmp.reserve(sizeof(int64_t) * n_segs);
   const size_t o_totals = tmp.reserve(sizeof(long long) * 4);  // chunks of all lists; -; longest list
   const size_t o_nnz_slots = tmp.reserve(sizeof(long long) * kFlagSlots * kFlagStride);  // entries of heavy pieces
-  const size_t report2_count = 5 + n_segs;
+  const size_t report2_count = kReport2;
   const size_t o_report2 = tmp.reserve(sizeof(long long) * report2_count);
   const size_t o_report3 = tmp.reserve(sizeof(int32_t) * 2);
   const int64_t n_bound_blocks =
@@ -1285,7 +1282,6 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
   const size_t h_slot_ptr = host.reserve(sizeof(int64_t) * (size_t)(B + 1));
   const size_t h_rem_part_ptr = host.reserve(sizeof(int32_t) * (size_t)(s.c + 1));
   const size_t h_rnnz_base = host.reserve(sizeof(int64_t) * (size_t)s.c);
-  const size_t h_seg_at = host.reserve(sizeof(int64_t) * n_segs);
   const size_t h_report2 = host.reserve(sizeof(long long) * report2_count);
   const size_t h_report3 = host.reserve(sizeof(int32_t) * 4);
   const size_t h_misc = host.reserve(64);
@@ -1322,7 +1318,6 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     int64_t* d_tot_rnnz = (int64_t*)(tmp.base + o_tot_rnnz);
     int64_t* d_rnnz_base = (int64_t*)(tmp.base + o_rnnz_base);
     int32_t* d_bound = (int32_t*)(tmp.base + o_bound);
-    int64_t* d_seg_at = (int64_t*)(tmp.base + o_seg_at);
     long long* d_totals = (long long*)(tmp.base + o_totals);
     long long* d_nnz_slots = (long long*)(tmp.base + o_nnz_slots);
     long long* d_report2 = (long long*)(tmp.base + o_report2);
@@ -1548,19 +1543,10 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
                          (int32_t)n_seq, d_totals);
       BUILD_HIP(hipGetLastError());
     }
-    // one report for the host: the totals, and the slots of the heavy sequence before the pieces of every segment
-    // (the ELL pieces of partition 0 .. c-1, then their remainder pieces)
+    // one report for the host: the totals
     {
-      int64_t* seg_at = (int64_t*)(host.base + h_seg_at);
-      for (int32_t p = 0; p < s.c; ++p) {
-        seg_at[p] = row_ptr[(size_t)p * (s.k + 1)];
-        seg_at[(size_t)s.c + p] = h->R + rem_part_ptr[p];
-      }
-      seg_at[2 * (size_t)s.c] = n_pieces;
-      BUILD_HIP(hipMemcpyAsync(d_seg_at, seg_at, sizeof(int64_t) * n_segs, hipMemcpyHostToDevice, stream));
-      hipLaunchKernelGGL(k_report, dim3((unsigned)((report2_count + 255) / 256)), dim3(256), 0, stream, d_totals,
-                         d_nnz_slots, want_heavy ? d_unit : nullptr, want_heavy ? d_hent : nullptr, n_pieces, (int32_t)n_segs,
-                         d_seg_at, d_report2);
+      hipLaunchKernelGGL(k_report, dim3(1), dim3(64), 0, stream, d_totals, d_nnz_slots,
+                         want_heavy ? d_unit : nullptr, want_heavy ? d_hent : nullptr, n_pieces, d_report2);
       BUILD_HIP(hipGetLastError());
       BUILD_HIP(hipMemcpyAsync(host.base + h_report2, d_report2, sizeof(long long) * report2_count,
                                hipMemcpyDeviceToHost, stream));
@@ -1584,25 +1570,14 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     h->n_heavy = report2[2];
     h->heavy_chunk0 = n_chunks;
     h->n_heavy_chunks = n_heavy_chunks;
-    // Chunks per heavy list: 32 where that still gives thousands of lists; a graph with few heavy chunks gets
-    // shorter lists, or its heavy launch would be a handful of wavefronts walking 32 chunks each while the GPU idles.
+    // Chunks per heavy list: 16 where that still gives thousands of lists; a graph with few heavy chunks gets
+    // shorter lists, or its heavy launch would be a handful of wavefronts walking 16 chunks each while the GPU idles.
     int32_t list_chunks = kHeavyListChunks;
     while (list_chunks > kChunksPerQuad && n_heavy_chunks / list_chunks < 4096) list_chunks /= 2;
     h->heavy_list_chunks = list_chunks;
     h->n_heavy_lists = (int32_t)((n_heavy_chunks + list_chunks - 1) / list_chunks);
     h->n_partial_rows = h->n_heavy + h->n_heavy_lists;
-    if (h->n_heavy > 0) {
-      h->n_heavy_segs = 2 * s.c;
-      h->hseg_list = (int32_t*)malloc(sizeof(int32_t) * (size_t)(h->n_heavy_segs + 1));
-      if (!h->hseg_list) { st = SPTIR_ERR_ALLOC; goto fail; }
-      // the first heavy list that starts at or after the chunk in which the segment's first piece starts
-      for (int32_t i = 0; i <= h->n_heavy_segs; ++i)
-        h->hseg_list[i] = i == h->n_heavy_segs
-                              ? h->n_heavy_lists
-                              : (int32_t)((report2[5 + i] / kChunkSlots + list_chunks - 1) / list_chunks);
-    } else {
-      h->row_slot_ptr = nullptr;  // (its room in the first allocation stays unused)
-    }
+    if (h->n_heavy == 0) h->row_slot_ptr = nullptr;  // (its room in the first allocation stays unused)
     const int64_t all_chunks = n_chunks + n_heavy_chunks;
     if (h->n_partial_rows > 0x7FFFFFFF || all_chunks > 0x7FFFFFFF) { st = SPTIR_ERR_OVERFLOW; goto fail; }
     const int32_t n_units = (int32_t)h->n_heavy;

@@ -34,8 +34,9 @@ constexpr int kBuildBlock = 256;  // rows per workgroup in the builder kernels
 // a wavefront each, which write one partial sum per finished piece plus one for whatever piece is unfinished where
 // the list ends.  A last launch adds a row's partial sums to Y in a fixed order.
 constexpr int kHeavyLenMax = 2048;      // largest threshold the size rules choose
-constexpr int kHeavyListChunks = 32;    // most chunks per heavy list (a multiple of kChunksPerQuad; on the largest graph 16
-                                        // and 64 measure the same; graphs with few heavy chunks get shorter lists)
+constexpr int kHeavyListChunks = 16;    // most chunks per heavy list (a multiple of kChunksPerQuad; on the largest graph 16
+                                        // beat 32 by 2 % and 64 by 4 % of the heavy launch; graphs with few heavy
+                                        // chunks get shorter lists)
 constexpr int kPartialFeat = 128;       // features per partial sum row: wider Y is produced in sweeps of this many
 // Compact stream records spend 8 bytes per slot instead of 12: one word holds the column relative to the first
 // column of the launch (bits 0..19), the row relative to the row block (20..26), "slot is real" (27), the chunk's
@@ -77,8 +78,6 @@ struct sptir_hyb {
   int64_t heavy_chunk0;       // a multiple of kChunksPerQuad
   int32_t n_heavy_lists;
   int32_t* hlist_first_slot;  // device [n_heavy_lists]: partial-sum row the list's first write goes to
-  int32_t n_heavy_segs;       // 2c: the ELL pieces of each partition, then its remainder pieces
-  int32_t* hseg_list;         // host (malloc) [n_heavy_segs + 1]: first heavy list that starts in each segment
   int32_t* row_slot_ptr;      // device [n_rows + 1]: the partial-sum rows of row r are row_slots[row_slot_ptr[r] ..)
   int32_t* row_slots;         // device, in the order they are added to Y (partition-major)
   int32_t n_heavy_rows;       // rows with at least one heavy piece

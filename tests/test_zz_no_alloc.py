@@ -67,8 +67,8 @@ def test_noalloc_without_long_rows_and_on_named_config(gpu_lib):
 
 def test_noalloc_refuses_what_the_scratch_cannot_hold(gpu_lib):
     sptir = gpu_lib
-    # 9,000 rows of 2,100 non-zeros in one partition: 9,000 heavy pieces (+ 9,282 heavy lists) x 128 floats x 4 bytes
-    # = 9.4 MB of partial sums, more than the 8 MiB of static scratch
+    # 9,000 rows of 2,100 non-zeros in one partition: 9,000 heavy pieces (+ about 18,500 heavy lists) x 128 floats x 4 bytes
+    # = 14 MB of partial sums, more than the 8 MiB of static scratch
     deg = np.full(9000, 2100, dtype=np.int64)
     w = workloads.random_csr(9000, 8192, deg, 5, 32)
     d = upload(w)
