@@ -188,7 +188,8 @@ typedef struct {
   int32_t rounds;             /* 0: chosen; 1: rounds (see sptir_hyb_info_t.rounds); 2: one launch per group of partitions */
   int32_t wide_stream;        /* 1: always 12-byte stream records */
   int32_t heavy_len;          /* row pieces with more real entries are summed by the heavy-piece launch; 0: chosen */
-  int32_t sweep_kb;           /* rounds == 2 only: kilobytes of Y one sweep over the launches may touch; 0: 163840 */
+  int32_t sweep_kb;           /* kilobytes one sweep over the launches may touch: of Y without rounds (0: 163840),
+                                 of X in rounds (0: 131072); wider operands are taken in groups of feature tiles */
   int32_t release_canonical;  /* 1: free ELL_COL, ELL_VAL, REM_COL and REM_VAL once the SpMM stream is packed
                                  (sptir_hyb_array then reports SPTIR_ERR_UNSUPPORTED for them) */
   int32_t no_spmm_plan;       /* 1: canonical arrays only; sptir_spmm refuses the handle */
@@ -265,7 +266,9 @@ sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_
  *   feat >= 1
  * Only enqueues work on `stream` (no synchronisation, no allocation).  The
  * chunk lists run in rounds (sptir_hyb_info_t.rounds: a launch per as many row
- * blocks as the GPU holds wavefronts, Y written once) or as one launch per group
+ * blocks as the GPU holds wavefronts, Y written once; an X wider than half the
+ * memory-side cache is taken in sweeps of 128 or 256 feature columns, the heavy
+ * pieces of a sweep right after its lists) or as one launch per group
  * of column partitions (n_phases launches, each adding to what the earlier ones
  * left in Y; a Y wider than the memory-side cache is then produced in several
  * such sweeps, each over a group of feature columns).  Heavy row pieces

@@ -252,9 +252,9 @@ extern "C" sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int6
   o.n_launches = ls.n_phases;
   o.compact_stream = ls.compact;
   o.n_feature_tiles = (feat + tile - 1) / tile;
-  o.tiles_per_sweep = ls.rounds ? o.n_feature_tiles
+  o.tiles_per_sweep = ls.rounds ? sptir::round_tiles_per_sweep(o.n_feature_tiles, tile, n_cols, opt.sweep_kb)
                                 : sptir::tiles_per_sweep(o.n_feature_tiles, tile, n_rows, ls.n_phases,
-                                                         opt.sweep_kb > 0 ? opt.sweep_kb : 160 * 1024);
+                                                         opt.sweep_kb);
   o.n_sweeps = (o.n_feature_tiles + o.tiles_per_sweep - 1) / o.tiles_per_sweep;
   o.rounds = ls.rounds;
   o.full_rows = ls.full_rows;

@@ -1414,7 +1414,7 @@ sptir_status_t sptir::hyb_build_impl(const sptir_csr_t* csr, int32_t n_col_parts
     // Every row has one value for all its entries (a row-normalised adjacency matrix, say): the stream
     // carries no values, the kernels sum rows of X and scale each row of Y once.
     const bool one_value_per_row = value_bits && csr->nnz > 0 && flags[4] == flags[5];
-    h->sweep_kb = opt.sweep_kb > 0 ? opt.sweep_kb : 160 * 1024;
+    h->sweep_kb = opt.sweep_kb;  // (0: the defaults of the two sweep rules)
     cs.n_rb = (int32_t)(((int64_t)s.n_rows + (1 << cs.log2_rb) - 1) >> cs.log2_rb);
     cs.long_len = heavy_len_setting(csr->nnz, (int64_t)cs.n_phases * cs.n_rb, ls.rounds != 0, opt);
     h->heavy_len = cs.long_len;

@@ -88,15 +88,16 @@ __device__ __forceinline__ int tile_index(int r, int fl) {
 
 // Adds a finished row sum into the wavefront's Y tile; r is the row relative to the row block.  The tile is
 // private to the wavefront and a row is handed over by exactly one lane group per instruction, so a plain
-// read-add-write is enough (LDS float atomics cost several times more).
+// read-add-write is enough (LDS float atomics measured three times slower for the whole launch).  Lanes past
+// the last feature are not told apart here: the tile has a place for every lane, what they add to theirs is
+// never written to Y, and the hand-over stays free of a second test.
 template <int VEC, int LG>
 struct TileSink {
   static constexpr bool kQueues = true;  // the lists it serves hold queue chunks
   float* tile;     // [row_block][kTile] in LDS
   int fl;
-  bool f_active;
   __device__ __forceinline__ void operator()(int r, bool valid, const float (&acc)[VEC]) {
-    if (valid && f_active) {
+    if (valid) {
       float* p = tile + tile_index<VEC, LG>(r, fl);
       float t[VEC];
       load_vec<VEC>(t, p);
@@ -426,8 +427,8 @@ struct HybWalker {
       for (int j = 0; j < UB; ++j) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = fmaf(v[j], x[j][e], acc[e]);
-        if (slot_hands_over(r[j])) {
-          sink(local_row(r[j]), row_valid(r[j]), acc);
+        if (slot_hands_over(r[j])) {  // (only entries carry the flag: the slots past the end of a queue do not)
+          sink(local_row(r[j]), true, acc);
 #pragma unroll
           for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
         }
@@ -600,7 +601,7 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   const int n_list = (int)(a.rb_chunk_ptr[rb + 1] - c0);  // a multiple of kChunksPerQuad
   const int f_read = f_active ? f0 : 0;  // lanes past the last feature read a valid address, never store
   W wk{a.X, a.stream + (size_t)c0 * (W::kArrays * kChunkSlots), n_list / kChunksPerQuad, lane, g, ring,
-       (unsigned)a.feat * 4u, (unsigned)f_read * 4u, TileSink<VEC, LG>{tile, fl, f_active}, {}, {}};
+       (unsigned)a.feat * 4u, (unsigned)f_read * 4u, TileSink<VEC, LG>{tile, fl}, {}, {}};
   wk.run();
 
   // write the tile: a lane group per row, one 128-byte line per group
@@ -899,11 +900,24 @@ void lane_shape(int32_t feat, bool aligned16, bool aligned8, bool full_rows, int
 // Y a sweep touches is well below its size.  So a wide Y is produced in several sweeps, each over a group of
 // feature tiles (4 or 8, which still map whole XCDs to a tile).
 int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches, int sweep_kb) {
-  const double limit_mb = (double)sweep_kb / 1024.0;
+  const double limit_mb = (double)(sweep_kb > 0 ? sweep_kb : 160 * 1024) / 1024.0;
   if (n_launches < 2 || n_tiles % 4 != 0) return n_tiles;
   const double tile_mb = (double)n_rows * tile_floats * sizeof(float) / (1024.0 * 1024.0);
   if (tile_mb * n_tiles <= limit_mb) return n_tiles;
   if (n_tiles % 8 == 0 && tile_mb * 8 <= limit_mb) return 8;
+  return 4;
+}
+
+// Feature tiles per sweep of a call that runs in rounds: all of them while the part of X they cover stays within
+// half of the 256 MB memory-side cache (or sweep_kb kilobytes, if given), else groups of whole kPartialFeat (8 or 4 tiles of 32 floats), so that the
+// heavy pieces' partial sums follow the same sweeps.  (The largest graph at 256 features, X of 238 MB: one sweep
+// 5.54 ms, two sweeps of 128 features measured faster.)
+int round_tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_cols, int sweep_kb) {
+  if (tile_floats * 4 != kPartialFeat || n_tiles <= 4) return n_tiles;
+  const double limit_mb = (double)(sweep_kb > 0 ? sweep_kb : 128 * 1024) / 1024.0;
+  const double tile_mb = (double)n_cols * tile_floats * sizeof(float) / (1024.0 * 1024.0);
+  if (tile_mb * n_tiles <= limit_mb) return n_tiles;
+  if (tile_mb * 8 <= limit_mb) return 8;
   return 4;
 }
 
@@ -970,26 +984,81 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
   const int all_tiles = g.n_tiles;
   int n_list_launches = 0;
   if (timers) timers->mark(stream, LaunchTimers::kStart, 0);
+  // Heavy pieces: partial sums of kPartialFeat features at a time, added to the Y the lists have written, for
+  // the features feat_begin .. feat_end - 1 (feat_begin a multiple of kPartialFeat).
+  auto heavy_sweeps = [&](int feat_begin, int feat_end) -> sptir_status_t {
+    if (h->n_heavy <= 0) return SPTIR_OK;
+    const bool idx32_all = offsets_fit_32(h->n_cols, feat);
+    const int tile = g.vec * g.lg;
+    const bool y_vec4 = feat % 4 == 0 && ((uintptr_t)Y & 15) == 0;
+    HeavyArgs ha;
+    ha.stream = h->stream; ha.first_slot = h->hlist_first_slot; ha.X = X; ha.partial = partial;
+    ha.chunk0 = h->heavy_chunk0; ha.n_chunks = h->n_heavy_chunks; ha.feat = feat; ha.list_chunks = h->heavy_list_chunks;
+    for (int feat0 = feat_begin; feat0 < feat_end; feat0 += kPartialFeat) {
+      const int width = feat_end - feat0 < kPartialFeat ? feat_end - feat0 : kPartialFeat;
+      Geometry gh = g;
+      gh.n_tiles = (width + tile - 1) / tile;
+      ha.feat0 = feat0; ha.n_tiles = gh.n_tiles;
+      // The heavy chunks are in partition order and so are the lists: one launch walks them all.  Workgroups start
+      // in list order, so the wavefronts resident at any time cover a window of consecutive lists that touches one
+      // slice of X, or two while it passes a partition boundary; a launch per partition measured slower (each
+      // ended with a partly filled GPU: 1.62 ms against 1.53 on the largest graph).
+      ha.list0 = 0; ha.n_lists = h->n_heavy_lists;
+      if (!plan_tiles(((int64_t)ha.n_lists + kHybWaves - 1) / kHybWaves, &gh)) return SPTIR_ERR_OVERFLOW;
+      ha.map_mode = gh.map_mode; ha.map_param = gh.map_param;
+      with_variant(g.vec, g.lg, idx32_all, wide, unit, [&](auto v) { launch_heavy(v, gh, stream, ha); });
+      if (timers) timers->mark(stream, LaunchTimers::kHeavy, 1);
+      const int per_row = width / (y_vec4 ? 4 : 1);
+      // few rows with heavy pieces: eight groups of threads share a row's partial sums
+      const int split = (y_vec4 && (int64_t)h->n_heavy_rows * per_row < 32768) ? 8 : 1;
+      const int rows_per_wg = 256 / (per_row * split);
+      const int64_t n_wg = ((int64_t)h->n_heavy_rows + rows_per_wg - 1) / rows_per_wg;
+      if (n_wg > 0x7FFFFFFF) return SPTIR_ERR_OVERFLOW;
+      const dim3 grid((unsigned)n_wg), block(256);
+      auto reduce = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, h->heavy_rows, h->row_slot_ptr, h->row_slots, partial,
+                           h->row_val, Y, h->n_heavy_rows, feat, feat0, width);
+      };
+      if (!y_vec4) reduce(k_heavy_reduce<1, 1>);
+      else if (split == 8) reduce(k_heavy_reduce<4, 8>);
+      else reduce(k_heavy_reduce<4, 1>);
+      if (timers) timers->mark(stream, LaunchTimers::kReduce, 1);
+    }
+    return SPTIR_OK;
+  };
   if (h->rounds) {
     // Rounds: a launch takes as many row blocks, in the order of their list lengths, as the GPU holds wavefronts.
     // All of them start together, their lists are about equally long and sweep the column partitions in the same
     // order, so they stay nearly in step; the Y tiles stay in LDS from the first partition to the last.
+    // A wide X is taken in sweeps over groups of feature tiles, lists and heavy pieces of one sweep before those
+    // of the next: the gathers that miss L2 are then served by the memory-side cache instead of HBM.
     int capacity = 0;
     with_variant(g.vec, g.lg, idx32, wide, unit, [&](auto v) { capacity = resident_workgroups(v, lds_bytes); });
     if (capacity <= 0) capacity = 3 * 256;
-    int64_t per_round = (int64_t)capacity / all_tiles * kHybWaves;  // row blocks
-    if (per_round < 8 * kHybWaves) per_round = 8 * kHybWaves;
-    const int64_t n_rounds = (h->n_row_blocks + per_round - 1) / per_round;
-    per_round = ((h->n_row_blocks + n_rounds - 1) / n_rounds + 7) / 8 * 8;  // rounds of equal size
-    a.rb_chunk_ptr = h->rb_chunk_ptr; a.accumulate = 0; a.tile0 = 0;
-    for (int64_t first = 0; first < h->n_row_blocks; first += per_round) {
-      const int64_t here = h->n_row_blocks - first < per_round ? h->n_row_blocks - first : per_round;
-      a.rb_order = h->rb_order + first;
-      a.n_row_blocks = (int32_t)here;
-      if (!plan_tiles((here + kHybWaves - 1) / kHybWaves, &g)) return SPTIR_ERR_OVERFLOW;
-      a.map_mode = g.map_mode; a.map_param = g.map_param;
-      with_variant(g.vec, g.lg, idx32, wide, unit, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
-      ++n_list_launches;
+    const int tile_floats = g.vec * g.lg;
+    const int per_sweep = round_tiles_per_sweep(all_tiles, tile_floats, h->n_cols, h->sweep_kb);
+    a.rb_chunk_ptr = h->rb_chunk_ptr; a.accumulate = 0;
+    for (int tile0 = 0; tile0 < all_tiles; tile0 += per_sweep) {
+      g.n_tiles = all_tiles - tile0 < per_sweep ? all_tiles - tile0 : per_sweep;
+      a.n_tiles = g.n_tiles; a.tile0 = tile0;
+      int64_t per_round = (int64_t)capacity / g.n_tiles * kHybWaves;  // row blocks
+      if (per_round < 8 * kHybWaves) per_round = 8 * kHybWaves;
+      const int64_t n_rounds = (h->n_row_blocks + per_round - 1) / per_round;
+      per_round = ((h->n_row_blocks + n_rounds - 1) / n_rounds + 7) / 8 * 8;  // rounds of equal size
+      for (int64_t first = 0; first < h->n_row_blocks; first += per_round) {
+        const int64_t here = h->n_row_blocks - first < per_round ? h->n_row_blocks - first : per_round;
+        a.rb_order = h->rb_order + first;
+        a.n_row_blocks = (int32_t)here;
+        if (!plan_tiles((here + kHybWaves - 1) / kHybWaves, &g)) return SPTIR_ERR_OVERFLOW;
+        a.map_mode = g.map_mode; a.map_param = g.map_param;
+        with_variant(g.vec, g.lg, idx32, wide, unit, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
+        ++n_list_launches;
+      }
+      if (timers) timers->mark(stream, LaunchTimers::kLists, n_list_launches);
+      n_list_launches = 0;
+      const int feat_end = (tile0 + g.n_tiles) * tile_floats;
+      const sptir_status_t st = heavy_sweeps(tile0 * tile_floats, feat_end < feat ? feat_end : feat);
+      if (st != SPTIR_OK) return st;
     }
   } else {
     const int per_sweep = tiles_per_sweep(all_tiles, g.vec * g.lg, h->n_rows, h->n_phases, h->sweep_kb);
@@ -1007,46 +1076,10 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
       }
     }
   }
-  if (timers) timers->mark(stream, LaunchTimers::kLists, n_list_launches);
-  if (h->n_heavy > 0) {
-    // heavy pieces: partial sums of kPartialFeat features at a time, added to the Y the lists have written
-    const bool idx32_all = offsets_fit_32(h->n_cols, feat);
-    const int tile = g.vec * g.lg;
-    const bool y_vec4 = feat % 4 == 0 && ((uintptr_t)Y & 15) == 0;
-    HeavyArgs ha;
-    ha.stream = h->stream; ha.first_slot = h->hlist_first_slot; ha.X = X; ha.partial = partial;
-    ha.chunk0 = h->heavy_chunk0; ha.n_chunks = h->n_heavy_chunks; ha.feat = feat; ha.list_chunks = h->heavy_list_chunks;
-    for (int feat0 = 0; feat0 < feat; feat0 += kPartialFeat) {
-      const int width = feat - feat0 < kPartialFeat ? feat - feat0 : kPartialFeat;
-      Geometry gh = g;
-      gh.n_tiles = (width + tile - 1) / tile;
-      ha.feat0 = feat0; ha.n_tiles = gh.n_tiles;
-      // The heavy chunks are in partition order and so are the lists: one launch walks them all.  Workgroups start
-      // in list order, so the wavefronts resident at any time cover a window of consecutive lists that touches one
-      // slice of X, or two while it passes a partition boundary; a launch per partition measured slower (each
-      // ended with a partly filled GPU: 1.62 ms against 1.53 on the largest graph).
-      ha.list0 = 0; ha.n_lists = h->n_heavy_lists;
-      if (!plan_tiles(((int64_t)ha.n_lists + kHybWaves - 1) / kHybWaves, &gh)) return SPTIR_ERR_OVERFLOW;
-      ha.map_mode = gh.map_mode; ha.map_param = gh.map_param;
-      with_variant(g.vec, g.lg, idx32_all, wide, unit, [&](auto v) { launch_heavy(v, gh, stream, ha); });
-      const int n_heavy_launches = 1;
-      if (timers) timers->mark(stream, LaunchTimers::kHeavy, n_heavy_launches);
-      const int per_row = width / (y_vec4 ? 4 : 1);
-      // few rows with heavy pieces: eight groups of threads share a row's partial sums
-      const int split = (y_vec4 && (int64_t)h->n_heavy_rows * per_row < 32768) ? 8 : 1;
-      const int rows_per_wg = 256 / (per_row * split);
-      const int64_t n_wg = ((int64_t)h->n_heavy_rows + rows_per_wg - 1) / rows_per_wg;
-      if (n_wg > 0x7FFFFFFF) return SPTIR_ERR_OVERFLOW;
-      const dim3 grid((unsigned)n_wg), block(256);
-      auto reduce = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, grid, block, 0, stream, h->heavy_rows, h->row_slot_ptr, h->row_slots, partial,
-                           h->row_val, Y, h->n_heavy_rows, feat, feat0, width);
-      };
-      if (!y_vec4) reduce(k_heavy_reduce<1, 1>);
-      else if (split == 8) reduce(k_heavy_reduce<4, 8>);
-      else reduce(k_heavy_reduce<4, 1>);
-      if (timers) timers->mark(stream, LaunchTimers::kReduce, 1);
-    }
+  if (!h->rounds) {
+    if (timers) timers->mark(stream, LaunchTimers::kLists, n_list_launches);
+    const sptir_status_t st = heavy_sweeps(0, feat);
+    if (st != SPTIR_OK) return st;
   }
   SPTIR_HIP(hipGetLastError());
   return SPTIR_OK;

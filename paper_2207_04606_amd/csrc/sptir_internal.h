@@ -90,7 +90,7 @@ struct sptir_hyb {
   int32_t parts_per_phase;   // column partitions swept by one chunk list
   int32_t n_phases;
   int32_t rounds;            // 1: the lists sweep all partitions and are launched in rounds (Y written once)
-  int32_t sweep_kb;          // rounds == 0: kilobytes of Y one sweep over the launches may touch
+  int32_t sweep_kb;          // kilobytes of Y (no rounds) or X (rounds) one sweep may touch; 0: the rules' defaults
   int32_t canonical_released;
   size_t device_bytes;
   // The device arrays above are parts of at most kHybBlobs allocations: [0] the index arrays whose sizes the
@@ -142,6 +142,7 @@ inline bool full_rows_fit(int log2_row_block) {
   return (size_t)4 * (((size_t)512 << log2_row_block) + 6 * 1024) <= (size_t)159 * 1024;
 }
 int tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_rows, int n_launches, int sweep_kb);
+int round_tiles_per_sweep(int n_tiles, int tile_floats, int64_t n_cols, int sweep_kb);
 
 // rb_order[launch][i] = the row block with the i-th longest chunk list of that launch (order.hip).  Works on
 // `stream`; *scratch_out is device memory the caller frees once the stream has drained.

@@ -452,6 +452,14 @@ def test_spmm_feature_sweeps(gpu_lib, feat):
     Y = torch.full((w.n_rows, feat), float("nan"), device="cuda")
     gpu_lib.sptir_spmm(hyb3, d.X, Y)
     assert_y_close(Y.cpu().numpy(), Yr, Sr, what=f"rounds feat={feat}")
+    # and with its X (1800 rows: 0.22 MB per tile) declared too wide for one sweep: groups of 8 or 4 tiles, the
+    # heavy pieces of each group right after its lists; every sum is formed as before
+    for limit_kb in (1900, 1):
+        hyb4 = gpu_lib.sptir_hyb_build_ex(w.n_rows, w.n_cols, d.indptr, d.indices, d.values, 3, 6,
+                                          {"rounds": 1, "sweep_kb": limit_kb})
+        Y2 = torch.full((w.n_rows, feat), float("nan"), device="cuda")
+        gpu_lib.sptir_spmm(hyb4, d.X, Y2)
+        assert torch.equal(Y2, Y), f"rounds feat={feat} limit={limit_kb} KB"
 
 
 @pytest.mark.parametrize("c", [1, 2, 4, 9])

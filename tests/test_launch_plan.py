@@ -54,8 +54,15 @@ def test_wide_y_is_swept_in_groups_of_feature_tiles_without_rounds():
     assert (p["tiles_per_sweep"], p["n_sweeps"]) == (8, 2)
     # a tile count that does not split into fours is not swept
     assert sptir.sptir_launch_plan(feat=320, options=old, **SOCIAL)["n_sweeps"] == 1
-    # in rounds Y never makes a round trip, so nothing is swept
-    assert sptir.sptir_launch_plan(feat=512, **SOCIAL)["n_sweeps"] == 1
+    # in rounds Y never makes a round trip; there a sweep is what keeps its share of X (232,965 rows x 128 floats
+    # = 119 MB) within half of the memory-side cache
+    assert sptir.sptir_launch_plan(feat=128, **SOCIAL)["n_sweeps"] == 1
+    p = sptir.sptir_launch_plan(feat=256, **SOCIAL)
+    assert (p["rounds"], p["tiles_per_sweep"], p["n_sweeps"]) == (1, 4, 2)
+    assert sptir.sptir_launch_plan(feat=512, **SOCIAL)["n_sweeps"] == 4
+    small_x = dict(n_rows=60000, n_cols=60000, stored_slots=30000000, n_col_parts=16)
+    p = sptir.sptir_launch_plan(feat=512, options={"rounds": 1}, **small_x)   # 60,000 x 512 floats = 123 MB
+    assert (p["tiles_per_sweep"], p["n_sweeps"]) == (16, 1)
     assert sptir.sptir_launch_plan(feat=512, **protein)["rounds"] == 1      # (piece lengths unknown to the query)
 
 
