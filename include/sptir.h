@@ -89,7 +89,7 @@ typedef enum {
    * test can decode it and find every non-zero of A exactly once).  The chunk stream: fixed records of four
    * 64-slot chunks ("quads"), each [256 column words][256 values unless values_per_row][256 row words unless
    * compact_stream]; first the chunk lists, list (launch l, row block b) at chunks RB_CHUNK_PTR[l * n_row_blocks
-   * + b] .. [.. + 1), then from chunk n_work_items on the heavy sequence, heavy list w at its chunks 32 w ...
+   * + b] .. [.. + 1), then from chunk n_work_items on the heavy sequence, heavy list w at its chunks heavy_list_items * w ...
    * A compact column word holds the column relative to the first column of the launch in bits 0..19 (heavy
    * chunks: the column itself), bits 20..26 the row relative to the row block (heavy chunks: the slot at which a
    * piece ends in the chunk), bit 27 "the slot holds an entry", bits 28..30 the chunk kind (3: eight queues of
