@@ -272,7 +272,9 @@ sptir_status_t sptir_launch_plan(int32_t n_rows, int32_t n_cols, int64_t stored_
  * of column partitions (n_phases launches, each adding to what the earlier ones
  * left in Y; a Y wider than the memory-side cache is then produced in several
  * such sweeps, each over a group of feature columns).  Heavy row pieces
- * (n_heavy_pieces > 0) take two more launches per 128 features: their partial
+ * (n_heavy_pieces > 0) take two more launches per 128 features (one where the
+ * chunk lists are a single launch and the heavy lists the smaller part: they
+ * then share that launch): their partial
  * sums pass through scratch memory that the handle owns, so calls on one handle
  * that has heavy pieces must not overlap in time.  No atomics are used and every
  * sum has a fixed order, so two calls with the same handle and X on the same GPU

@@ -243,8 +243,8 @@ enum TileMap : int {
 };
 
 // workgroup id -> (unit, feature tile); units are row blocks (hyb) or groups of rows (CSR)
-__device__ __forceinline__ void decode_block(int map_mode, int map_param, int n_tiles, int64_t* unit, int* tile) {
-  unsigned bid = blockIdx.x;
+__device__ __forceinline__ void decode_block(unsigned bid, int map_mode, int map_param, int n_tiles, int64_t* unit,
+                                             int* tile) {
   if (map_mode == kMapTilesPerXcd) {
     unsigned q = bid >> 3, x = bid & 7;
     *tile = (int)(x + 8 * (q % (unsigned)map_param));
@@ -563,14 +563,14 @@ struct HybWalker {
   }
 };
 
+// (smem: per wavefront its [row_block][kTile] tile of Y, then its quad ring; bid: the workgroup's number)
 template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT>
-__global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
+__device__ __forceinline__ void lists_workgroup(const SpmmArgs& a, unsigned bid, float* smem) {
   using S = Shape<VEC, LG>;
   using W = HybWalker<VEC, LG, IDX32, WIDE, UNIT, TileSink<VEC, LG>>;
-  extern __shared__ __align__(16) float smem[];  // per wavefront: [row_block][kTile] tile of Y, then its quad ring
   int64_t unit;
   int tile_id;
-  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
+  decode_block(bid, a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t slot = unit * kHybWaves + wave;  // the wavefronts of a workgroup are independent of each other
@@ -623,6 +623,12 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
   }
 }
 
+template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT>
+__global__ __launch_bounds__(kHybBlock) void k_spmm_hyb(SpmmArgs a) {
+  extern __shared__ __align__(16) float smem[];
+  lists_workgroup<VEC, LG, IDX32, WIDE, UNIT>(a, blockIdx.x, smem);
+}
+
 // ------------------------------------------------------------ heavy pieces
 struct HeavyArgs {
   const int32_t* stream;       // the whole chunk stream
@@ -645,14 +651,14 @@ struct HeavyArgs {
 // list, but a finished piece goes to the next partial-sum row instead of an LDS tile, and so does, at the end,
 // what has been summed of the piece the list stops in (zeros if it stops at a piece end: every wavefront takes
 // that row, so that the row numbers follow from counting alone).
+// (smem: per wavefront its quad ring; bid: the workgroup's number among those that walk heavy lists)
 template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT>
-__global__ __launch_bounds__(kHybBlock) void k_spmm_heavy(HeavyArgs a) {
+__device__ __forceinline__ void heavy_workgroup(const HeavyArgs& a, unsigned bid, float* smem) {
   using S = Shape<VEC, LG>;
   using W = HybWalker<VEC, LG, IDX32, WIDE, UNIT, PartialSink<VEC, LG>>;
-  extern __shared__ __align__(16) float smem[];  // per wavefront: its quad ring
   int64_t unit;
   int tile_id;
-  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
+  decode_block(bid, a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   if (unit * kHybWaves + wave >= a.n_lists) return;
@@ -672,6 +678,22 @@ __global__ __launch_bounds__(kHybBlock) void k_spmm_heavy(HeavyArgs a) {
   wk.run();
   sum_groups<VEC, LG>(wk.acc, S::kGroups);
   wk.sink(0, g == 0, wk.acc);
+}
+
+template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT>
+__global__ __launch_bounds__(kHybBlock) void k_spmm_heavy(HeavyArgs a) {
+  extern __shared__ __align__(16) float smem[];
+  heavy_workgroup<VEC, LG, IDX32, WIDE, UNIT>(a, blockIdx.x, smem);
+}
+
+// Both in one launch, for a matrix whose chunk lists and heavy lists are one launch each and small: the first
+// n_heavy_workgroups workgroups (a multiple of 8, so that the others keep their place among the XCDs; those past the
+// last heavy list leave at once) walk heavy lists, the rest chunk lists, and neither waits for the other.
+template <int VEC, int LG, bool IDX32, bool WIDE, bool UNIT>
+__global__ __launch_bounds__(kHybBlock) void k_spmm_hyb_heavy(SpmmArgs a, HeavyArgs ha, unsigned n_heavy_workgroups) {
+  extern __shared__ __align__(16) float smem[];
+  if (blockIdx.x < n_heavy_workgroups) heavy_workgroup<VEC, LG, IDX32, WIDE, UNIT>(ha, blockIdx.x, smem);
+  else lists_workgroup<VEC, LG, IDX32, WIDE, UNIT>(a, blockIdx.x - n_heavy_workgroups, smem);
 }
 
 // Y[r, feat0 + f] += (row_val[r] *) the partial sums of row r's heavy pieces.  SPLIT groups of (width / VEC) threads per
@@ -762,7 +784,7 @@ __global__ __launch_bounds__(64 * kCsrWaves) void k_spmm_csr(CsrArgs a) {
   using S = Shape<VEC, LG>;
   int64_t unit;
   int tile_id;
-  decode_block(a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
+  decode_block(blockIdx.x, a.map_mode, a.map_param, a.n_tiles, &unit, &tile_id);
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int64_t row = unit * kCsrWaves + wave;
   if (row >= a.n_rows) return;
@@ -859,6 +881,19 @@ void launch_lists(V, const Geometry& g, size_t lds_bytes, hipStream_t stream, co
                               160 * 1024 - 1024);
   });
   hipLaunchKernelGGL(kernel, dim3((unsigned)g.grid), dim3(kHybBlock), lds_bytes, stream, a);
+}
+
+template <typename V>
+void launch_heavy_and_lists(V, unsigned n_heavy_workgroups, unsigned n_list_workgroups, size_t lds_bytes,
+                            hipStream_t stream, const SpmmArgs& a, const HeavyArgs& ha) {
+  auto* kernel = &k_spmm_hyb_heavy<V::vec, V::lg, V::idx32, V::wide, V::unit>;
+  static std::once_flag raised;
+  std::call_once(raised, [&] {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              160 * 1024 - 1024);
+  });
+  hipLaunchKernelGGL(kernel, dim3(n_heavy_workgroups + n_list_workgroups), dim3(kHybBlock), lds_bytes, stream, a, ha,
+                     n_heavy_workgroups);
 }
 
 // workgroups of k_spmm_hyb the GPU holds at once (0: unknown)
@@ -983,31 +1018,41 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
   const bool idx32 = offsets_fit_32(wide ? (int64_t)h->n_cols : (span < h->n_cols ? span : (int64_t)h->n_cols), feat);
   const int all_tiles = g.n_tiles;
   int n_list_launches = 0;
+  bool heavy_with_lists = false;
   if (timers) timers->mark(stream, LaunchTimers::kStart, 0);
   // Heavy pieces: partial sums of kPartialFeat features at a time, added to the Y the lists have written, for
   // the features feat_begin .. feat_end - 1 (feat_begin a multiple of kPartialFeat).
-  auto heavy_sweeps = [&](int feat_begin, int feat_end) -> sptir_status_t {
-    if (h->n_heavy <= 0) return SPTIR_OK;
-    const bool idx32_all = offsets_fit_32(h->n_cols, feat);
+  const bool idx32_all = offsets_fit_32(h->n_cols, feat);
+  // the heavy launch for the features feat0 .. feat0 + width - 1 (width <= kPartialFeat)
+  auto heavy_launch_shape = [&](int feat0, int width, HeavyArgs* ha, Geometry* gh) -> bool {
+    ha->stream = h->stream; ha->first_slot = h->hlist_first_slot; ha->X = X; ha->partial = partial;
+    ha->chunk0 = h->heavy_chunk0; ha->n_chunks = h->n_heavy_chunks; ha->feat = feat;
+    ha->list_chunks = h->heavy_list_chunks;
+    *gh = g;
     const int tile = g.vec * g.lg;
+    gh->n_tiles = (width + tile - 1) / tile;
+    ha->feat0 = feat0; ha->n_tiles = gh->n_tiles;
+    ha->list0 = 0; ha->n_lists = h->n_heavy_lists;
+    if (!plan_tiles(((int64_t)ha->n_lists + kHybWaves - 1) / kHybWaves, gh)) return false;
+    ha->map_mode = gh->map_mode; ha->map_param = gh->map_param;
+    return true;
+  };
+  auto heavy_sweeps = [&](int feat_begin, int feat_end, bool already_launched = false) -> sptir_status_t {
+    if (h->n_heavy <= 0) return SPTIR_OK;
     const bool y_vec4 = feat % 4 == 0 && ((uintptr_t)Y & 15) == 0;
-    HeavyArgs ha;
-    ha.stream = h->stream; ha.first_slot = h->hlist_first_slot; ha.X = X; ha.partial = partial;
-    ha.chunk0 = h->heavy_chunk0; ha.n_chunks = h->n_heavy_chunks; ha.feat = feat; ha.list_chunks = h->heavy_list_chunks;
     for (int feat0 = feat_begin; feat0 < feat_end; feat0 += kPartialFeat) {
       const int width = feat_end - feat0 < kPartialFeat ? feat_end - feat0 : kPartialFeat;
-      Geometry gh = g;
-      gh.n_tiles = (width + tile - 1) / tile;
-      ha.feat0 = feat0; ha.n_tiles = gh.n_tiles;
+      HeavyArgs ha;
+      Geometry gh;
       // The heavy chunks are in partition order and so are the lists: one launch walks them all.  Workgroups start
       // in list order, so the wavefronts resident at any time cover a window of consecutive lists that touches one
       // slice of X, or two while it passes a partition boundary; a launch per partition measured slower (each
       // ended with a partly filled GPU: 1.62 ms against 1.53 on the largest graph).
-      ha.list0 = 0; ha.n_lists = h->n_heavy_lists;
-      if (!plan_tiles(((int64_t)ha.n_lists + kHybWaves - 1) / kHybWaves, &gh)) return SPTIR_ERR_OVERFLOW;
-      ha.map_mode = gh.map_mode; ha.map_param = gh.map_param;
-      with_variant(g.vec, g.lg, idx32_all, wide, unit, [&](auto v) { launch_heavy(v, gh, stream, ha); });
-      if (timers) timers->mark(stream, LaunchTimers::kHeavy, 1);
+      if (!heavy_launch_shape(feat0, width, &ha, &gh)) return SPTIR_ERR_OVERFLOW;
+      if (!already_launched) {
+        with_variant(g.vec, g.lg, idx32_all, wide, unit, [&](auto v) { launch_heavy(v, gh, stream, ha); });
+        if (timers) timers->mark(stream, LaunchTimers::kHeavy, 1);
+      }
       const int per_row = width / (y_vec4 ? 4 : 1);
       // few rows with heavy pieces: eight groups of threads share a row's partial sums
       const int split = (y_vec4 && (int64_t)h->n_heavy_rows * per_row < 32768) ? 8 : 1;
@@ -1071,14 +1116,29 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
         a.rb_order = h->rb_order + (size_t)phase * h->n_row_blocks;
         a.accumulate = phase > 0;
         a.X = wide ? X : X + (size_t)phase * (size_t)span * (size_t)feat;
-        with_variant(g.vec, g.lg, idx32, wide, unit, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
+        // A matrix whose chunk lists are one launch and whose heavy lists are the smaller part runs both in one
+        // launch: the few wavefronts of the heavy lists then fill CUs the chunk lists leave idle instead of
+        // waiting for them (the largest low-degree graph: 0.104 -> see the design notes).
+        HeavyArgs ha;
+        Geometry gh;
+        if (h->n_heavy > 0 && h->n_phases == 1 && per_sweep == all_tiles && feat <= kPartialFeat &&
+            idx32 == idx32_all && heavy_launch_shape(0, feat, &ha, &gh) && gh.grid <= g.grid &&
+            (gh.grid + 7) / 8 * 8 + g.grid <= 0x7FFFFFFF) {
+          const int64_t heavy_wgs = (gh.grid + 7) / 8 * 8;
+          with_variant(g.vec, g.lg, idx32, wide, unit, [&](auto v) {
+            launch_heavy_and_lists(v, (unsigned)heavy_wgs, (unsigned)g.grid, lds_bytes, stream, a, ha);
+          });
+          heavy_with_lists = true;
+        } else {
+          with_variant(g.vec, g.lg, idx32, wide, unit, [&](auto v) { launch_lists(v, g, lds_bytes, stream, a); });
+        }
         ++n_list_launches;
       }
     }
   }
   if (!h->rounds) {
     if (timers) timers->mark(stream, LaunchTimers::kLists, n_list_launches);
-    const sptir_status_t st = heavy_sweeps(0, feat);
+    const sptir_status_t st = heavy_sweeps(0, feat, heavy_with_lists);
     if (st != SPTIR_OK) return st;
   }
   SPTIR_HIP(hipGetLastError());
