@@ -215,6 +215,15 @@ sptir_status_t sptir_hyb_build_ex(const sptir_csr_t* csr, int32_t n_col_parts, i
 int32_t sptir_default_bucket_log2(int64_t nnz, int32_t n_rows);
 
 /*
+ * Host-only query: 1 if the SpMM kernels may form the byte offset of a gathered row of X (column x feat x 4 + the
+ * lane's offset inside the row) with the 24-bit multiply and 32-bit adds, for a launch whose columns span n_cols
+ * and a feature size feat: both factors below 2^24 and the largest offset below 2^32.  0 otherwise (the kernels
+ * then use 64-bit addresses), also for arguments that make no sense.  Exposed so that the rule can be tested
+ * without a GPU.
+ */
+int32_t sptir_gather_offsets_fit_32(int64_t n_cols, int32_t feat);
+
+/*
  * Format search (the tuning rule of Section 4.2.1: try several c, keep the
  * fastest).  Builds hyb(c, k) for every c of c_candidates (host array;
  * n_candidates == 0 selects the paper's {1, 2, 4, 8, 16}), runs sptir_spmm

@@ -113,7 +113,7 @@ class _SpmmTimes(ctypes.Structure):
                 ("n_reduce_launches", ctypes.c_int32)]
 
 
-EXPORTED_SYMBOLS = ("sptir_spmm_timed", "sptir_roof_gather", "sptir_roof_fma", "sptir_set_allocator", "sptir_release_scratch", "sptir_hyb_build", "sptir_hyb_build_ex", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_spmm",
+EXPORTED_SYMBOLS = ("sptir_spmm_timed", "sptir_roof_gather", "sptir_roof_fma", "sptir_set_allocator", "sptir_release_scratch", "sptir_hyb_build", "sptir_hyb_build_ex", "sptir_hyb_search", "sptir_default_bucket_log2", "sptir_gather_offsets_fit_32", "sptir_spmm",
                     "sptir_spmm_noalloc",
                     "sptir_spmm_csr", "sptir_sddmm_csr", "sptir_sddmm_plan_build", "sptir_sddmm",
                     "sptir_sddmm_plan_info", "sptir_sddmm_plan_destroy", "sptir_rgms_build", "sptir_rgms", "sptir_rgms_info",
@@ -140,6 +140,8 @@ def load_library(path: str | None = None):
                                        ctypes.POINTER(_BuildOptions), ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
     lib.sptir_default_bucket_log2.restype = ctypes.c_int32
     lib.sptir_default_bucket_log2.argtypes = [ctypes.c_int64, ctypes.c_int32]
+    lib.sptir_gather_offsets_fit_32.restype = ctypes.c_int32
+    lib.sptir_gather_offsets_fit_32.argtypes = [ctypes.c_int64, ctypes.c_int32]
     lib.sptir_spmm.restype = ctypes.c_int
     lib.sptir_spmm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
     lib.sptir_spmm_timed.restype = ctypes.c_int
@@ -246,6 +248,10 @@ def sptir_status_string(status: int) -> str:
 
 def sptir_default_bucket_log2(nnz: int, n_rows: int) -> int:
     return int(load_library().sptir_default_bucket_log2(nnz, n_rows))
+
+
+def sptir_gather_offsets_fit_32(n_cols: int, feat: int) -> bool:
+    return bool(load_library().sptir_gather_offsets_fit_32(n_cols, feat))
 
 
 def sptir_sddmm_default_col_parts(n_rows: int, n_cols: int, nnz: int, feat_hint: int = 0) -> int:

@@ -1146,6 +1146,10 @@ static sptir_status_t spmm_on_hyb(const sptir_hyb_t* h, const float* X, float* Y
   return SPTIR_OK;
 }
 
+extern "C" int32_t sptir_gather_offsets_fit_32(int64_t n_cols, int32_t feat) {
+  return (n_cols >= 0 && feat >= 1 && offsets_fit_32(n_cols, feat)) ? 1 : 0;
+}
+
 extern "C" sptir_status_t sptir_spmm(const sptir_hyb_t* h, const float* X, float* Y, int32_t feat, void* stream_) {
   return spmm_on_hyb(h, X, Y, feat, stream_, h ? h->partial : nullptr);
 }

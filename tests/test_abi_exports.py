@@ -36,6 +36,14 @@ def test_host_only_entry_points():
     assert sptir.sptir_default_bucket_log2(8, 8) == 0
     assert sptir.sptir_default_bucket_log2(9, 8) == 1
     assert sptir.sptir_default_bucket_log2(0, 8) == 0
+    # 32-bit gather offsets: column x (feat x 4) with a 24-bit multiply, so both factors stay below 2^24 and the
+    # product below 2^32
+    fit = sptir.sptir_gather_offsets_fit_32
+    assert fit(232965, 128) and fit(232965, 512) and fit(1, 1) and fit(0, 64)
+    assert fit((1 << 24) - 1, 64) and not fit(1 << 24, 64)              # columns at the 24-bit limit
+    assert fit(16, (1 << 22) - 1) and not fit(16, 1 << 22)              # bytes per row at the 24-bit limit
+    assert fit(1 << 23, 127) and not fit(1 << 23, 128)                  # product at the 32-bit limit
+    assert not fit(-1, 64) and not fit(64, 0)
 
 
 def test_null_arguments_are_rejected_without_a_gpu():
